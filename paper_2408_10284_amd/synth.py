@@ -1,0 +1,170 @@
+"""Seeded synthetic inputs for the decode-time MoE block.
+
+This module only *draws and stores numbers*: random weights, hidden-state
+streams, storage-format rounding (bf16) and the group-quantised int4 storage
+format of the weights.  It holds none of the method's arithmetic (no gating,
+no expert evaluation, no cache policy, no dequantisation) and imports neither
+the HIP binding nor the CPU checker, so both can be fed from it.
+
+Shapes follow Mixtral-8x7B (the paper's evaluation model, Sec. 5.1): hidden
+size H, FFN size F, N experts per layer, experts stored as W1[F,H] (gate
+projection), W3[F,H] (up projection), W2[H,F] (down projection).  Values are
+random stand-ins for the trained weights and benchmark prompts, which are not
+available here.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+
+import numpy as np
+
+# ----------------------------------------------------------------------------
+# storage formats
+# ----------------------------------------------------------------------------
+
+
+def bf16_bits(a: np.ndarray) -> np.ndarray:
+    """float32 -> bfloat16 bit patterns (uint16), round-to-nearest-even."""
+    u = np.ascontiguousarray(a, dtype=np.float32).view(np.uint32)
+    lsb = (u >> np.uint32(16)) & np.uint32(1)
+    r = u + np.uint32(0x7FFF) + lsb
+    return (r >> np.uint32(16)).astype(np.uint16)
+
+
+def bf16_to_f32(bits: np.ndarray) -> np.ndarray:
+    """bfloat16 bit patterns (uint16) -> float32 (exact)."""
+    return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32)
+
+
+def bf16_round(a: np.ndarray) -> np.ndarray:
+    """float32 values rounded to the nearest bfloat16, returned as float32."""
+    return bf16_to_f32(bf16_bits(a))
+
+
+# ----------------------------------------------------------------------------
+# configurations (the five workloads of the baseline description)
+# ----------------------------------------------------------------------------
+
+
+@dataclass(frozen=True)
+class MoEShape:
+    H: int
+    F: int
+    N: int
+    L: int = 1
+    dtype: str = "f32"  # "f32" | "bf16" | "int4g64"
+
+
+TINY = MoEShape(H=512, F=1024, N=8, L=1, dtype="f32")
+MIXTRAL_LAYER = MoEShape(H=4096, F=14336, N=8, L=1, dtype="bf16")
+MIXTRAL_STACK = MoEShape(H=4096, F=14336, N=8, L=32, dtype="bf16")
+MIXTRAL_STACK_INT4 = MoEShape(H=4096, F=14336, N=8, L=32, dtype="int4g64")
+
+WEIGHT_STD = 0.02
+
+
+def _rng(*key: int) -> np.random.Generator:
+    return np.random.default_rng([int(k) for k in key])
+
+
+def router_weights(shape: MoEShape, layer: int, seed: int = 0) -> np.ndarray:
+    """W_g of one layer, [N,H] float32, N(0, 0.02^2); bf16-rounded for bf16/int4 shapes."""
+    w = _rng(seed, 1, layer).standard_normal((shape.N, shape.H), dtype=np.float32) * np.float32(WEIGHT_STD)
+    return w if shape.dtype == "f32" else bf16_round(w)
+
+
+def expert_weights(shape: MoEShape, layer: int, expert: int, seed: int = 0):
+    """(W1[F,H], W3[F,H], W2[H,F]) of one expert, float32 storage, N(0, 0.02^2).
+
+    Drawn from a generator keyed on (seed, layer, expert) so any expert can be
+    regenerated without materialising the others.  For bf16 and int4 shapes
+    the values are bf16-rounded (the int4 codes are then derived from them by
+    `quantize_int4_g64`).
+    """
+    g = _rng(seed, 2, layer, expert)
+    s = np.float32(WEIGHT_STD)
+    w1 = g.standard_normal((shape.F, shape.H), dtype=np.float32) * s
+    w3 = g.standard_normal((shape.F, shape.H), dtype=np.float32) * s
+    w2 = g.standard_normal((shape.H, shape.F), dtype=np.float32) * s
+    if shape.dtype != "f32":
+        w1, w3, w2 = bf16_round(w1), bf16_round(w3), bf16_round(w2)
+    return w1, w3, w2
+
+
+def iid_tokens(n: int, H: int, seed: int = 1, dtype: str = "f32") -> np.ndarray:
+    """n independent hidden states ~ N(0, I), [n,H] float32."""
+    x = _rng(seed, 3).standard_normal((n, H), dtype=np.float32)
+    return x if dtype == "f32" else bf16_round(x)
+
+
+def ar1_tokens(n: int, H: int, rho: float = 0.8, seed: int = 1, dtype: str = "bf16") -> np.ndarray:
+    """n hidden states following a per-element AR(1) process with N(0,1) marginals.
+
+    x_0 ~ N(0,I); x_t = rho x_{t-1} + sqrt(1-rho^2) eps_t.  Successive tokens are
+    correlated, which gives the routing locality an expert cache relies on.
+    """
+    g = _rng(seed, 4)
+    x = np.empty((n, H), dtype=np.float32)
+    x[0] = g.standard_normal(H, dtype=np.float32)
+    c = np.float32(np.sqrt(1.0 - rho * rho))
+    for t in range(1, n):
+        x[t] = np.float32(rho) * x[t - 1] + c * g.standard_normal(H, dtype=np.float32)
+    return x if dtype == "f32" else bf16_round(x)
+
+
+def ar1_streams(n_steps: int, B: int, H: int, rho: float = 0.8, seed: int = 1, dtype: str = "bf16") -> np.ndarray:
+    """B independent AR(1) streams, [n_steps,B,H] float32 (the batched workload)."""
+    out = np.empty((n_steps, B, H), dtype=np.float32)
+    for b in range(B):
+        out[:, b, :] = ar1_tokens(n_steps, H, rho, seed=seed * 1000 + b, dtype=dtype)
+    return out
+
+
+def tau_profile(L: int, lo: float = 0.15, hi: float = 0.35) -> np.ndarray:
+    """Per-layer gating thresholds tau_l = sqrt(T / S_l) for a synthetic
+    sensitivity profile in which early layers are the most sensitive (Sec. 5.5):
+    tau rises linearly from `lo` at layer 0 to `hi` at layer L-1.  float32."""
+    if L == 1:
+        return np.array([lo], dtype=np.float32)
+    return np.linspace(lo, hi, L).astype(np.float32)
+
+
+# ----------------------------------------------------------------------------
+# int4 storage format (group 64 along the reduction axis, fp16 scale + zero)
+# ----------------------------------------------------------------------------
+
+INT4_GROUP = 64
+
+
+def quantize_int4_g64(w: np.ndarray):
+    """Round-to-nearest asymmetric 4-bit storage of a [rows, cols] matrix.
+
+    Groups are 64 consecutive elements along the last axis (the axis a
+    matrix-vector product reduces over).  Per group: zero = fp16(min),
+    scale = fp16((max-min)/15), code = clamp(rint((w-zero)/scale), 0, 15) with
+    the fp16-rounded scale/zero (scale == 0 -> code 0).  Returns
+    (codes uint8 [rows, cols] with values 0..15, scale fp16 [rows, cols/64],
+    zero fp16 [rows, cols/64]).  Packing into nibbles is the consumer's
+    business (`pack_nibbles`).
+    """
+    rows, cols = w.shape
+    assert cols % INT4_GROUP == 0
+    g = np.ascontiguousarray(w, dtype=np.float32).reshape(rows, cols // INT4_GROUP, INT4_GROUP)
+    lo = g.min(axis=2)
+    hi = g.max(axis=2)
+    zero = lo.astype(np.float16)
+    scale = ((hi - lo) / np.float32(15.0)).astype(np.float16)
+    z32 = zero.astype(np.float32)[:, :, None]
+    s32 = scale.astype(np.float32)[:, :, None]
+    with np.errstate(divide="ignore", invalid="ignore"):
+        q = np.rint((g - z32) / s32)
+    q = np.where(s32 > 0, q, 0.0)
+    q = np.clip(q, 0.0, 15.0).astype(np.uint8)
+    return q.reshape(rows, cols), scale, zero
+
+
+def pack_nibbles(codes: np.ndarray) -> np.ndarray:
+    """[rows, cols] codes 0..15 -> [rows, cols/2] bytes; element 2i in the low
+    nibble, element 2i+1 in the high nibble."""
+    c = codes.reshape(codes.shape[0], -1, 2)
+    return (c[:, :, 0] | (c[:, :, 1] << 4)).astype(np.uint8)

@@ -1,0 +1,237 @@
+/*
+ * adapmoe.h - C ABI of the decode-time Mixture-of-Experts block of AdapMoE
+ * (arXiv 2408.10284) for AMD MI355X (gfx950).
+ *
+ * Per token and per layer the block runs (Alg.1 of the paper):
+ *   gate      router product, softmax, top-2 and the sensitivity-scaled
+ *             activation test that decides whether the second expert runs
+ *             (Sec. 2.1 Eq.1; Sec. 4.2 Eq.3, Eq.4, Eq.8);
+ *   predict   the following layer's gate applied to the same input (Sec. 4.3);
+ *   lookup    per-layer expert cache with LRU replacement (Sec. 4.4, Sec. 5.3);
+ *   load      on-demand copy of missing experts, host DRAM -> HBM (Alg.1);
+ *   compute   SwiGLU expert FFNs and their weighted sum (Sec. 2.1 Eq.2);
+ *   prefetch  asynchronous copy of the predicted experts of the following
+ *             layer on a side stream (Sec. 4.3, Alg.1 communication stream).
+ *
+ * Conventions
+ *   - Every function returns 0 on success or a negative ADAPMOE_E* code; no
+ *     exception or abort crosses this boundary.  adapmoe_strerror() names a
+ *     code; adapmoe_last_error() gives the text of the last failure of a context.
+ *   - "dev" pointers are device (HBM) addresses, "host" pointers are host
+ *     addresses.  The caller owns every buffer it passes.  The library borrows
+ *     it for the duration of the call, except router matrices, registered
+ *     expert images and bound device experts, which are borrowed until
+ *     adapmoe_destroy().  The library owns its cache slots, events, side
+ *     stream and small staging buffers.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).
+ *     Calls enqueue work and return; outputs are valid once the stream has
+ *     reached that point, unless stated otherwise.
+ *   - Activations and outputs: x is [B,H] in the context's activation type
+ *     (float for ADAPMOE_F32, bfloat16 bit patterns otherwise), y is [B,H]
+ *     float.  ids [B,2] int32, w [B,2] float, k [B] int32.
+ *   - The product path has no CPU fallback: without a usable GPU every compute
+ *     call fails with ADAPMOE_EHIP.
+ */
+#ifndef ADAPMOE_H
+#define ADAPMOE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  ADAPMOE_OK = 0,
+  ADAPMOE_EINVAL = -1,  /* null pointer, bad dimension, id out of range, bad slot counts */
+  ADAPMOE_ENOMEM = -2,  /* HBM or host allocation failed */
+  ADAPMOE_ENOTREG = -3, /* expert has no registered host image */
+  ADAPMOE_ENORES = -4,  /* expert FFN asked for an expert that is not resident */
+  ADAPMOE_EHIP = -5,    /* HIP runtime failure (text via adapmoe_last_error) */
+  ADAPMOE_ESTATE = -6   /* call not valid in the context's current state */
+};
+
+enum { ADAPMOE_F32 = 0, ADAPMOE_BF16 = 1, ADAPMOE_INT4G64 = 2 };
+
+typedef struct adapmoe_ctx adapmoe_ctx;
+
+typedef struct {
+  int32_t H;       /* hidden size; multiple of 512 (bf16/int4) or 256 (f32) */
+  int32_t F;       /* expert FFN size; multiple of 512 (bf16/int4) or 256 (f32) */
+  int32_t N;       /* experts per layer, 2..64 */
+  int32_t L;       /* layers */
+  int32_t dtype;   /* ADAPMOE_F32 | ADAPMOE_BF16 | ADAPMOE_INT4G64 (weights; activations f32 / bf16 / bf16) */
+  int32_t max_B;   /* largest number of tokens per call, 1..64 */
+  int32_t device;  /* HIP device ordinal */
+  int32_t trace_capacity; /* cache events kept in the ring (0 = tracing off) */
+} adapmoe_config;
+
+/* Cache event kinds (Sec. 4.4 / Alg.1; one record per demanded or predicted expert). */
+enum {
+  ADAPMOE_EV_HIT = 0,      /* demanded expert resident */
+  ADAPMOE_EV_HIT_PF = 1,   /* demanded expert resident thanks to a prefetch, first use since */
+  ADAPMOE_EV_MISS = 2,     /* demanded expert absent: loaded on demand (victim evicted if the layer was full) */
+  ADAPMOE_EV_BYPASS = 3,   /* demanded expert absent and the layer owns no slot: loaded into a spare slot */
+  ADAPMOE_EV_PF_TOUCH = 4, /* predicted expert already resident: recency refreshed */
+  ADAPMOE_EV_PF_LOAD = 5   /* predicted expert absent: copy started ahead of time */
+};
+
+typedef struct {
+  int32_t token;  /* value last given to adapmoe_set_token */
+  int32_t layer;
+  int32_t kind;   /* ADAPMOE_EV_* */
+  int32_t expert;
+  int32_t victim; /* evicted expert id or -1 */
+  int32_t slot;   /* physical slot used (informative, not part of the policy) */
+} adapmoe_event;
+
+typedef struct {
+  uint64_t tokens_gated;     /* token-layers passed through moe_layer_step */
+  uint64_t single_expert;    /* of which k == 1 */
+  uint64_t hits, hits_after_prefetch, misses, bypasses;
+  uint64_t prefetch_touches, prefetch_loads;
+  uint64_t h2d_bytes;        /* bytes copied host -> HBM (demand + prefetch) */
+  uint64_t ffn_launches;
+} adapmoe_counters_t;
+
+const char* adapmoe_strerror(int code);
+const char* adapmoe_last_error(const adapmoe_ctx* ctx);
+
+/* ---- context ------------------------------------------------------------- */
+
+/* Creates a context on cfg->device.  Allocates only small tables; expert
+ * storage comes from cache_alloc() or adapmoe_bind_expert_dev(). */
+int adapmoe_create(const adapmoe_config* cfg, adapmoe_ctx** out);
+int adapmoe_destroy(adapmoe_ctx* ctx);
+
+/* Router matrix W_g of `layer` (Eq.1): device pointer, [N,H] row-major in the
+ * activation type, borrowed until destroy. */
+int adapmoe_set_router(adapmoe_ctx* ctx, int layer, const void* Wg_dev);
+
+/* Per-layer thresholds tau_l = sqrt(T / S_l) (host, L floats), S_l being the
+ * layer's sensitivity sum diag(F): one expert runs iff (1-alpha) <= tau_l,
+ * which is Eq.8 with the square root taken on both sides. */
+int adapmoe_set_tau(adapmoe_ctx* ctx, const float* tau_host);
+
+/* ---- expert images --------------------------------------------------------- */
+
+/* Size in bytes of one packed expert image for this configuration. */
+int adapmoe_expert_bytes(const adapmoe_config* cfg, size_t* bytes_out);
+
+/* Host-side, offline: canonical matrices -> the streaming image the kernels read.
+ * W1 (gate proj.) and W3 (up proj.) are [F,H], W2 (down proj.) is [H,F], all
+ * row-major, float (ADAPMOE_F32) or bfloat16 bit patterns (ADAPMOE_BF16).
+ * Image: rows of W1 and W3 interleaved ([F][2][H]) followed by W2 ([H][F]).
+ * `out_host` must hold adapmoe_expert_bytes() bytes. */
+int adapmoe_pack_expert(const adapmoe_config* cfg, const void* W1_host, const void* W3_host,
+                        const void* W2_host, void* out_host);
+
+/* Same for ADAPMOE_INT4G64: each matrix is given as unpacked 4-bit codes
+ * (uint8 0..15, [rows,cols]) plus fp16 scale and zero per 64 consecutive
+ * elements of a row ([rows, cols/64] each); decoded weight = code*scale+zero. */
+int adapmoe_pack_expert_int4(const adapmoe_config* cfg,
+                             const uint8_t* q1, const uint16_t* s1, const uint16_t* z1,
+                             const uint8_t* q3, const uint16_t* s3, const uint16_t* z3,
+                             const uint8_t* q2, const uint16_t* s2, const uint16_t* z2,
+                             void* out_host);
+
+/* Registers the packed image of (layer, expert) held in host memory (pinned
+ * memory from hipHostMalloc gives full link rate; pageable memory works but is
+ * slow).  Borrowed until destroy; this is the source of demand loads and prefetch. */
+int adapmoe_register_expert(adapmoe_ctx* ctx, int layer, int expert, const void* image_host, size_t bytes);
+
+/* Declares that the packed image of (layer, expert) lives at `image_dev` in
+ * caller-owned HBM for the lifetime of the context: always resident, never
+ * evicted, outside the cache budget.  A layer whose N experts are all bound
+ * needs no host round trip in moe_layer_step. */
+int adapmoe_bind_expert_dev(adapmoe_ctx* ctx, int layer, int expert, const void* image_dev);
+
+/* ---- cache (Sec. 4.4) ------------------------------------------------------ */
+
+/* Pure host function: cache-size allocation by the knapsack dynamic programme
+ * of Eq.16-19 over the expected on-demand loads f_{i,t} of Eq.10-15.
+ * a[L] = single-expert probability, beta[L] = prefetch accuracy, C = total
+ * slots.  Writes t_out[L] (0 <= t <= N, sum <= C; ties go to the smallest t,
+ * two costs tie within 1e-12) and the minimum cost. */
+int cache_plan(int L, int N, int C, const double* a, const double* beta, int32_t* t_out, double* cost_out);
+
+/* Expected on-demand loads of one layer with t of N experts cached (Eq.15). */
+double cache_cost(int N, int t, double a, double beta);
+
+/* Allocates sum(slots_per_layer) + 2 expert-sized slots in HBM (the 2 spare
+ * slots serve layers that own fewer slots than experts they run) and empties
+ * every layer's LRU set.  slots_per_layer[l] in 0..N.  May be called once. */
+int cache_alloc(adapmoe_ctx* ctx, const int32_t* slots_per_layer);
+
+/* Residency query: slot_out[i] = physical slot of ids[i] in `layer`, -1 if
+ * absent, -2 if bound to caller memory.  touch != 0 also makes found entries
+ * most recently used (in the order given).  Host-only, no GPU work. */
+int cache_lookup(adapmoe_ctx* ctx, int layer, const int32_t* ids_host, int n, int32_t* slot_out, int touch);
+
+/* ---- the block's steps ------------------------------------------------------ */
+
+/* Gate of `layer` on x (Eq.1, Eq.3-4, Eq.8): one wavefront per token computes
+ * the N logits, the softmax, the two largest (ties: lower index), alpha and
+ * the test (1-alpha) <= tau_layer.  Writes ids[b] = (e1,e2), k[b] in {1,2},
+ * w[b] = (1,0) if k==1 else (alpha,1-alpha).  If pred_ids_dev/pred_k_dev are
+ * non-NULL and layer+1 < L, the same kernel also applies layer+1's router and
+ * threshold to the same x (Sec. 4.3) and writes that decision there
+ * (pred_ids [B,2], pred_k [B]); for the last layer it writes pred_k = 0. */
+int moe_gate(adapmoe_ctx* ctx, int layer, const void* x_dev, int B,
+             int32_t* ids_dev, float* w_dev, int32_t* k_dev,
+             int32_t* pred_ids_dev, int32_t* pred_k_dev, void* stream);
+
+/* y[b] = sum_{j<k[b]} w[b][j] * E_{ids[b][j]}(x[b])  (Eq.2 over the activated
+ * experts), E(x) = W2 (silu(W1 x) * (W3 x)).  Reads expert images through the
+ * context's device-side residency table; every needed expert must be resident
+ * (bound, or in a cache slot whose copy was ordered before this call on
+ * `stream`).  A non-resident expert contributes nothing and raises a device
+ * flag reported as ADAPMOE_ENORES by adapmoe_check(). */
+int moe_expert_ffn(adapmoe_ctx* ctx, int layer, const void* x_dev, int B,
+                   const int32_t* ids_dev, const float* w_dev, const int32_t* k_dev,
+                   float* y_dev, void* stream);
+
+/* Prefetch for `layer` (Sec. 4.3): for the first min(n, slots of layer) ids, in
+ * order: resident -> most recently used; absent -> evict LRU if full, start an
+ * asynchronous copy on the library's side stream.  Returns at once. */
+int moe_prefetch(adapmoe_ctx* ctx, int layer, const int32_t* ids_host, int n);
+
+/* One layer of Alg.1 for B tokens: gate + predict; (if the layer is not fully
+ * bound: bring ids to the host, demand lookup, start copies of missing
+ * experts, then the predicted experts of layer+1, on the side stream, and make
+ * `stream` wait for the demanded copies only); expert FFNs + combine into y.
+ * With B > 1 the demanded set is the union over tokens in token order. */
+int moe_layer_step(adapmoe_ctx* ctx, int layer, const void* x_dev, int B, float* y_dev, void* stream);
+
+/* Residual wiring used between blocks by multi-layer runs (not from the paper):
+ * h[b] += gamma * y[b] (skipped if y_dev is NULL), then
+ * x[b] = h[b] / sqrt(mean(h[b]^2) + 1e-6) stored in the activation type.
+ * h [B,H] float, y [B,H] float, x [B,H]. */
+int moe_residual_rmsnorm(adapmoe_ctx* ctx, float* h_dev, const float* y_dev, float gamma,
+                         void* x_dev, int B, void* stream);
+
+/* ---- bookkeeping ------------------------------------------------------------- */
+
+int adapmoe_set_token(adapmoe_ctx* ctx, int token);
+/* Copies up to cap oldest unread events into buf and removes them from the ring. */
+int adapmoe_trace_read(adapmoe_ctx* ctx, adapmoe_event* buf, size_t cap, size_t* n_out);
+int adapmoe_counters(adapmoe_ctx* ctx, adapmoe_counters_t* out);
+/* Last gate decision brought to the host by moe_layer_step on a non-bound layer
+ * (ids [B,2], k [B], pred_ids [B,2], pred_k [B]); any pointer may be NULL. */
+int adapmoe_last_decision(adapmoe_ctx* ctx, int32_t* ids, int32_t* k, int32_t* pred_ids, int32_t* pred_k, int B);
+/* Waits for all work of the context (both streams given so far) and reports
+ * device-side flags: ADAPMOE_ENORES if an FFN met a non-resident expert. */
+int adapmoe_check(adapmoe_ctx* ctx, void* stream);
+
+/* Kernel timing with HIP events on the launch stream: when on, every launch of
+ * the expert-FFN kernels is bracketed by event records.  adapmoe_profile_read
+ * synchronises and returns, per kernel class (0 = gate/up GEMV, 1 = down GEMV,
+ * 2 = gate), the number of launches and their summed duration in ms, then resets. */
+int adapmoe_profile(adapmoe_ctx* ctx, int on);
+int adapmoe_profile_read(adapmoe_ctx* ctx, int kernel_class, uint64_t* launches, double* total_ms);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ADAPMOE_H */

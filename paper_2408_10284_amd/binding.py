@@ -1,0 +1,253 @@
+"""ctypes binding of libadapmoe.so: same names as the C entry points, argument
+marshalling only.  Tensors are torch tensors (device memory and streams come
+from PyTorch-ROCm); every step of the path runs inside the library's kernels.
+There is no fallback: if the library is missing or no GPU is usable, calls fail.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libadapmoe.so")
+
+OK, EINVAL, ENOMEM, ENOTREG, ENORES, EHIP, ESTATE = 0, -1, -2, -3, -4, -5, -6
+F32, BF16, INT4G64 = 0, 1, 2
+EVENT_KINDS = ("HIT", "HIT_PF", "MISS", "BYPASS", "PF_TOUCH", "PF_LOAD")
+
+
+class Config(C.Structure):
+    _fields_ = [("H", C.c_int32), ("F", C.c_int32), ("N", C.c_int32), ("L", C.c_int32),
+                ("dtype", C.c_int32), ("max_B", C.c_int32), ("device", C.c_int32),
+                ("trace_capacity", C.c_int32)]
+
+
+class Event(C.Structure):
+    _fields_ = [("token", C.c_int32), ("layer", C.c_int32), ("kind", C.c_int32),
+                ("expert", C.c_int32), ("victim", C.c_int32), ("slot", C.c_int32)]
+
+
+class Counters(C.Structure):
+    _fields_ = [(n, C.c_uint64) for n in
+                ("tokens_gated", "single_expert", "hits", "hits_after_prefetch", "misses", "bypasses",
+                 "prefetch_touches", "prefetch_loads", "h2d_bytes", "ffn_launches")]
+
+
+class AdapMoEError(RuntimeError):
+    def __init__(self, code, text):
+        super().__init__(f"adapmoe error {code}: {text}")
+        self.code = code
+
+
+_lib = None
+
+_P = C.c_void_p
+_SIGS = {
+    "adapmoe_strerror": (C.c_char_p, [C.c_int]),
+    "adapmoe_last_error": (C.c_char_p, [_P]),
+    "adapmoe_create": (C.c_int, [C.POINTER(Config), C.POINTER(_P)]),
+    "adapmoe_destroy": (C.c_int, [_P]),
+    "adapmoe_set_router": (C.c_int, [_P, C.c_int, _P]),
+    "adapmoe_set_tau": (C.c_int, [_P, C.POINTER(C.c_float)]),
+    "adapmoe_expert_bytes": (C.c_int, [C.POINTER(Config), C.POINTER(C.c_size_t)]),
+    "adapmoe_pack_expert": (C.c_int, [C.POINTER(Config), _P, _P, _P, _P]),
+    "adapmoe_pack_expert_int4": (C.c_int, [C.POINTER(Config)] + [_P] * 10),
+    "adapmoe_register_expert": (C.c_int, [_P, C.c_int, C.c_int, _P, C.c_size_t]),
+    "adapmoe_bind_expert_dev": (C.c_int, [_P, C.c_int, C.c_int, _P]),
+    "cache_plan": (C.c_int, [C.c_int, C.c_int, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double),
+                             C.POINTER(C.c_int32), C.POINTER(C.c_double)]),
+    "cache_cost": (C.c_double, [C.c_int, C.c_int, C.c_double, C.c_double]),
+    "cache_alloc": (C.c_int, [_P, C.POINTER(C.c_int32)]),
+    "cache_lookup": (C.c_int, [_P, C.c_int, C.POINTER(C.c_int32), C.c_int, C.POINTER(C.c_int32), C.c_int]),
+    "moe_gate": (C.c_int, [_P, C.c_int, _P, C.c_int, _P, _P, _P, _P, _P, _P]),
+    "moe_expert_ffn": (C.c_int, [_P, C.c_int, _P, C.c_int, _P, _P, _P, _P, _P]),
+    "moe_prefetch": (C.c_int, [_P, C.c_int, C.POINTER(C.c_int32), C.c_int]),
+    "moe_layer_step": (C.c_int, [_P, C.c_int, _P, C.c_int, _P, _P]),
+    "moe_residual_rmsnorm": (C.c_int, [_P, _P, _P, C.c_float, _P, C.c_int, _P]),
+    "adapmoe_set_token": (C.c_int, [_P, C.c_int]),
+    "adapmoe_trace_read": (C.c_int, [_P, C.POINTER(Event), C.c_size_t, C.POINTER(C.c_size_t)]),
+    "adapmoe_counters": (C.c_int, [_P, C.POINTER(Counters)]),
+    "adapmoe_last_decision": (C.c_int, [_P, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32),
+                                        C.POINTER(C.c_int32), C.c_int]),
+    "adapmoe_check": (C.c_int, [_P, _P]),
+    "adapmoe_profile": (C.c_int, [_P, C.c_int]),
+    "adapmoe_profile_read": (C.c_int, [_P, C.c_int, C.POINTER(C.c_uint64), C.POINTER(C.c_double)]),
+}
+
+
+def exported_names():
+    return sorted(_SIGS)
+
+
+def load():
+    """Loads the shared library (raises if it has not been built)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise FileNotFoundError(f"{LIB_PATH} not built: run `python -m paper_2408_10284_amd.build`")
+        lib = C.CDLL(LIB_PATH)
+        for name, (res, args) in _SIGS.items():
+            fn = getattr(lib, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = lib
+    return _lib
+
+
+def _ptr(t):
+    """Address of a torch tensor / numpy array / int / None."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    if hasattr(t, "data_ptr"):
+        return t.data_ptr()
+    return t.ctypes.data
+
+
+def _stream(s):
+    if s is None:
+        return None
+    return s.cuda_stream if hasattr(s, "cuda_stream") else int(s)
+
+
+def _chk(ctx, rc):
+    if rc != 0:
+        lib = load()
+        text = lib.adapmoe_strerror(rc).decode()
+        if ctx:
+            detail = lib.adapmoe_last_error(ctx).decode()
+            if detail:
+                text += f" ({detail})"
+        raise AdapMoEError(rc, text)
+
+
+# ---- same names as the C entry points ---------------------------------------
+
+def adapmoe_create(H, F, N, L, dtype, max_B=1, device=0, trace_capacity=0):
+    cfg = Config(H, F, N, L, dtype, max_B, device, trace_capacity)
+    ctx = _P()
+    _chk(None, load().adapmoe_create(C.byref(cfg), C.byref(ctx)))
+    return ctx, cfg
+
+
+def adapmoe_destroy(ctx):
+    _chk(None, load().adapmoe_destroy(ctx))
+
+
+def adapmoe_set_router(ctx, layer, Wg_dev):
+    _chk(ctx, load().adapmoe_set_router(ctx, layer, _ptr(Wg_dev)))
+
+
+def adapmoe_set_tau(ctx, tau):
+    arr = (C.c_float * len(tau))(*[float(t) for t in tau])
+    _chk(ctx, load().adapmoe_set_tau(ctx, arr))
+
+
+def adapmoe_expert_bytes(cfg):
+    n = C.c_size_t()
+    _chk(None, load().adapmoe_expert_bytes(C.byref(cfg), C.byref(n)))
+    return n.value
+
+
+def adapmoe_pack_expert(cfg, W1, W3, W2, out):
+    _chk(None, load().adapmoe_pack_expert(C.byref(cfg), _ptr(W1), _ptr(W3), _ptr(W2), _ptr(out)))
+
+
+def adapmoe_pack_expert_int4(cfg, q1, s1, z1, q3, s3, z3, q2, s2, z2, out):
+    _chk(None, load().adapmoe_pack_expert_int4(C.byref(cfg), *[_ptr(a) for a in (q1, s1, z1, q3, s3, z3, q2, s2, z2, out)]))
+
+
+def adapmoe_register_expert(ctx, layer, expert, image_host, nbytes):
+    _chk(ctx, load().adapmoe_register_expert(ctx, layer, expert, _ptr(image_host), nbytes))
+
+
+def adapmoe_bind_expert_dev(ctx, layer, expert, image_dev):
+    _chk(ctx, load().adapmoe_bind_expert_dev(ctx, layer, expert, _ptr(image_dev)))
+
+
+def cache_plan(L, N, Ctot, a, beta):
+    da = (C.c_double * L)(*[float(v) for v in a])
+    db = (C.c_double * L)(*[float(v) for v in beta])
+    t = (C.c_int32 * L)()
+    cost = C.c_double()
+    _chk(None, load().cache_plan(L, N, Ctot, da, db, t, C.byref(cost)))
+    return list(t), cost.value
+
+
+def cache_cost(N, t, a, beta):
+    return load().cache_cost(N, t, a, beta)
+
+
+def cache_alloc(ctx, slots_per_layer):
+    arr = (C.c_int32 * len(slots_per_layer))(*[int(v) for v in slots_per_layer])
+    _chk(ctx, load().cache_alloc(ctx, arr))
+
+
+def cache_lookup(ctx, layer, ids, touch=False):
+    n = len(ids)
+    arr = (C.c_int32 * n)(*[int(v) for v in ids])
+    out = (C.c_int32 * n)()
+    _chk(ctx, load().cache_lookup(ctx, layer, arr, n, out, 1 if touch else 0))
+    return list(out)
+
+
+def moe_gate(ctx, layer, x, B, ids, w, k, pred_ids=None, pred_k=None, stream=None):
+    _chk(ctx, load().moe_gate(ctx, layer, _ptr(x), B, _ptr(ids), _ptr(w), _ptr(k), _ptr(pred_ids), _ptr(pred_k), _stream(stream)))
+
+
+def moe_expert_ffn(ctx, layer, x, B, ids, w, k, y, stream=None):
+    _chk(ctx, load().moe_expert_ffn(ctx, layer, _ptr(x), B, _ptr(ids), _ptr(w), _ptr(k), _ptr(y), _stream(stream)))
+
+
+def moe_prefetch(ctx, layer, ids):
+    arr = (C.c_int32 * len(ids))(*[int(v) for v in ids])
+    _chk(ctx, load().moe_prefetch(ctx, layer, arr, len(ids)))
+
+
+def moe_layer_step(ctx, layer, x, B, y, stream=None):
+    _chk(ctx, load().moe_layer_step(ctx, layer, _ptr(x), B, _ptr(y), _stream(stream)))
+
+
+def moe_residual_rmsnorm(ctx, h, y, gamma, x, B, stream=None):
+    _chk(ctx, load().moe_residual_rmsnorm(ctx, _ptr(h), _ptr(y), float(gamma), _ptr(x), B, _stream(stream)))
+
+
+def adapmoe_set_token(ctx, token):
+    _chk(ctx, load().adapmoe_set_token(ctx, token))
+
+
+def adapmoe_trace_read(ctx, cap=1 << 16):
+    buf = (Event * cap)()
+    n = C.c_size_t()
+    _chk(ctx, load().adapmoe_trace_read(ctx, buf, cap, C.byref(n)))
+    return [(e.token, e.layer, EVENT_KINDS[e.kind], e.expert, e.victim, e.slot) for e in buf[: n.value]]
+
+
+def adapmoe_counters(ctx):
+    c = Counters()
+    _chk(ctx, load().adapmoe_counters(ctx, C.byref(c)))
+    return {n: getattr(c, n) for n, _ in Counters._fields_}
+
+
+def adapmoe_last_decision(ctx, B):
+    ids = (C.c_int32 * (2 * B))()
+    k = (C.c_int32 * B)()
+    pids = (C.c_int32 * (2 * B))()
+    pk = (C.c_int32 * B)()
+    _chk(ctx, load().adapmoe_last_decision(ctx, ids, k, pids, pk, B))
+    return list(ids), list(k), list(pids), list(pk)
+
+
+def adapmoe_check(ctx, stream=None):
+    _chk(ctx, load().adapmoe_check(ctx, _stream(stream)))
+
+
+def adapmoe_profile(ctx, on):
+    _chk(ctx, load().adapmoe_profile(ctx, 1 if on else 0))
+
+
+def adapmoe_profile_read(ctx, kernel_class):
+    n = C.c_uint64()
+    ms = C.c_double()
+    _chk(ctx, load().adapmoe_profile_read(ctx, kernel_class, C.byref(n), C.byref(ms)))
+    return n.value, ms.value

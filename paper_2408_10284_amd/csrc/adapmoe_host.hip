@@ -1,0 +1,807 @@
+// Host side of the library: context, expert images, per-layer LRU cache with
+// demand loads and prefetch on a side stream, the cache-size planner, and the
+// C entry points declared in include/adapmoe.h.
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <deque>
+#include <string>
+#include <vector>
+
+#include "../../include/adapmoe.h"
+#include "launch.h"
+
+using namespace adapmoe;
+
+namespace {
+
+struct Slot {
+  char* dev = nullptr;
+  hipEvent_t copy_done = nullptr;  // recorded on the side stream after the copy into the slot
+  hipEvent_t read_done = nullptr;  // recorded on the compute stream after the last FFN reading the slot
+  bool copy_pending = false;       // a copy was issued and no compute stream has been told to wait for it yet
+  bool was_read = false;
+};
+
+struct Entry {
+  int expert;
+  int slot;
+  bool by_prefetch;  // filled by a prefetch and not demanded since
+};
+
+struct LayerCache {
+  int cap = 0;
+  std::vector<Entry> order;  // front = least recently used
+  int find(int e) const {
+    for (size_t i = 0; i < order.size(); ++i)
+      if (order[i].expert == e) return (int)i;
+    return -1;
+  }
+  void touch(int pos) {
+    Entry en = order[pos];
+    order.erase(order.begin() + pos);
+    order.push_back(en);
+  }
+};
+
+struct TimedLaunch {
+  int cls;
+  hipEvent_t t0, t1;
+};
+
+}  // namespace
+
+struct adapmoe_ctx {
+  adapmoe_config cfg{};
+  size_t image_bytes = 0, w2_offset = 0;
+  bool bf16_act = false;
+  std::vector<const void*> router;
+  std::vector<float> tau;
+  std::vector<const void*> host_image;  // [L*N]
+  std::vector<const void*> bound;       // [L*N]
+  std::vector<int> bound_count;         // [L]
+  const void** d_table = nullptr;       // [L*N] device
+  int32_t* d_err = nullptr;
+  int32_t* d_dec = nullptr;             // ids[2B] k[B] pred_ids[2B] pred_k[B]
+  float* d_w = nullptr;                 // [B,2]
+  float* d_a = nullptr;                 // [B][2][F]
+  int32_t* h_dec = nullptr;             // pinned mirror of d_dec
+  hipStream_t copy_stream = nullptr;
+  LaunchCfg lc{};
+
+  bool cache_ready = false;
+  std::vector<Slot> slots;
+  std::vector<int> free_slots;
+  std::vector<LayerCache> layers;
+  std::vector<std::pair<int, const void*>> pending_pokes;  // (table index, value), applied before the next FFN
+
+  std::deque<adapmoe_event> trace;
+  adapmoe_counters_t ctr{};
+  int token = 0;
+  std::string last_error;
+
+  bool profiling = false;
+  std::vector<TimedLaunch> timed;
+  std::vector<hipEvent_t> event_pool;
+};
+
+namespace {
+
+int fail(adapmoe_ctx* c, int code, const std::string& msg) {
+  if (c) c->last_error = msg;
+  return code;
+}
+
+#define HIPCHK(ctx, call)                                                                 \
+  do {                                                                                    \
+    hipError_t e_ = (call);                                                               \
+    if (e_ != hipSuccess)                                                                 \
+      return fail((ctx), ADAPMOE_EHIP, std::string(#call) + ": " + hipGetErrorString(e_)); \
+  } while (0)
+
+bool cfg_ok(const adapmoe_config* c) {
+  if (!c) return false;
+  if (c->dtype != ADAPMOE_F32 && c->dtype != ADAPMOE_BF16) return false;
+  const int q = c->dtype == ADAPMOE_F32 ? 256 : 512;
+  if (c->H <= 0 || c->F <= 0 || c->H % q || c->F % q) return false;
+  if (c->N < 2 || c->N > 64 || c->L < 1) return false;
+  if ((size_t)2 * c->F * sizeof(float) > 160 * 1024) return false;  // a_j of two experts must fit in LDS
+  return true;
+}
+
+size_t elem_size(int dtype) { return dtype == ADAPMOE_F32 ? 4 : 2; }
+
+int env_int(const char* name, int dflt) {
+  const char* v = getenv(name);
+  if (!v || !*v) return dflt;
+  int x = atoi(v);
+  return x > 0 ? x : dflt;
+}
+
+void record(adapmoe_ctx* c, int layer, int kind, int expert, int victim, int slot) {
+  switch (kind) {
+    case ADAPMOE_EV_HIT: c->ctr.hits++; break;
+    case ADAPMOE_EV_HIT_PF: c->ctr.hits++; c->ctr.hits_after_prefetch++; break;
+    case ADAPMOE_EV_MISS: c->ctr.misses++; break;
+    case ADAPMOE_EV_BYPASS: c->ctr.bypasses++; break;
+    case ADAPMOE_EV_PF_TOUCH: c->ctr.prefetch_touches++; break;
+    case ADAPMOE_EV_PF_LOAD: c->ctr.prefetch_loads++; break;
+  }
+  if (c->cfg.trace_capacity <= 0) return;
+  if ((int)c->trace.size() >= c->cfg.trace_capacity) c->trace.pop_front();
+  c->trace.push_back(adapmoe_event{c->token, layer, kind, expert, victim, slot});
+}
+
+// Starts the copy of (layer, expert) into `slot` on the side stream.  The copy
+// waits for the last kernel that read the slot; its completion is the slot's
+// copy_done event.
+int start_copy(adapmoe_ctx* c, int layer, int expert, int slot) {
+  const void* src = c->host_image[(size_t)layer * c->cfg.N + expert];
+  if (!src) return fail(c, ADAPMOE_ENOTREG, "expert has no registered host image");
+  Slot& s = c->slots[slot];
+  if (s.was_read) HIPCHK(c, hipStreamWaitEvent(c->copy_stream, s.read_done, 0));
+  HIPCHK(c, hipMemcpyAsync(s.dev, src, c->image_bytes, hipMemcpyHostToDevice, c->copy_stream));
+  HIPCHK(c, hipEventRecord(s.copy_done, c->copy_stream));
+  s.copy_pending = true;
+  c->ctr.h2d_bytes += c->image_bytes;
+  return ADAPMOE_OK;
+}
+
+void poke_later(adapmoe_ctx* c, int layer, int expert, const void* value) {
+  c->pending_pokes.emplace_back(layer * c->cfg.N + expert, value);
+}
+
+int flush_pokes(adapmoe_ctx* c, hipStream_t s) {
+  size_t i = 0;
+  while (i < c->pending_pokes.size()) {
+    PokeArgs p{};
+    p.table = c->d_table;
+    for (p.n = 0; p.n < 4 && i < c->pending_pokes.size(); ++p.n, ++i) {
+      p.index[p.n] = c->pending_pokes[i].first;
+      p.value[p.n] = c->pending_pokes[i].second;
+    }
+    HIPCHK(c, launch_poke(p, s));
+  }
+  c->pending_pokes.clear();
+  return ADAPMOE_OK;
+}
+
+// Prefetch policy for one layer (Sec. 4.3; Alg.1 transfer set): touch or load, rank order.
+int prefetch_layer(adapmoe_ctx* c, int layer, const int32_t* ids, int n) {
+  LayerCache& lc = c->layers[layer];
+  const int N = c->cfg.N;
+  int done = 0;
+  for (int i = 0; i < n && done < lc.cap; ++i) {
+    const int e = ids[i];
+    if (e < 0 || e >= N) return fail(c, ADAPMOE_EINVAL, "prefetch: expert id out of range");
+    if (c->bound[(size_t)layer * N + e]) { ++done; continue; }  // lives in caller memory: nothing to do
+    ++done;
+    const int pos = lc.find(e);
+    if (pos >= 0) {
+      const int slot = lc.order[pos].slot;
+      lc.touch(pos);
+      record(c, layer, ADAPMOE_EV_PF_TOUCH, e, -1, slot);
+      continue;
+    }
+    int victim = -1, slot;
+    if ((int)lc.order.size() >= lc.cap) {
+      victim = lc.order.front().expert;
+      slot = lc.order.front().slot;
+      lc.order.erase(lc.order.begin());
+      poke_later(c, layer, victim, nullptr);
+    } else {
+      if (c->free_slots.empty()) return fail(c, ADAPMOE_ENOMEM, "no free cache slot");
+      slot = c->free_slots.back();
+      c->free_slots.pop_back();
+    }
+    int rc = start_copy(c, layer, e, slot);
+    if (rc) return rc;
+    lc.order.push_back(Entry{e, slot, true});
+    poke_later(c, layer, e, c->slots[slot].dev);
+    record(c, layer, ADAPMOE_EV_PF_LOAD, e, victim, slot);
+  }
+  return ADAPMOE_OK;
+}
+
+hipEvent_t get_event(adapmoe_ctx* c) {
+  if (!c->event_pool.empty()) {
+    hipEvent_t e = c->event_pool.back();
+    c->event_pool.pop_back();
+    return e;
+  }
+  hipEvent_t e = nullptr;
+  if (hipEventCreate(&e) != hipSuccess) return nullptr;
+  return e;
+}
+
+struct ScopedTimer {
+  adapmoe_ctx* c;
+  hipStream_t s;
+  TimedLaunch t{};
+  bool on;
+  ScopedTimer(adapmoe_ctx* c_, int cls, hipStream_t s_) : c(c_), s(s_), on(c_->profiling) {
+    if (!on) return;
+    t.cls = cls;
+    t.t0 = get_event(c);
+    t.t1 = get_event(c);
+    if (!t.t0 || !t.t1) { on = false; return; }
+    hipEventRecord(t.t0, s);
+  }
+  ~ScopedTimer() {
+    if (!on) return;
+    hipEventRecord(t.t1, s);
+    c->timed.push_back(t);
+  }
+};
+
+FfnArgs ffn_args(adapmoe_ctx* c, int layer, const void* x, int B, const int32_t* ids, const float* w, const int32_t* k,
+                 float* y) {
+  FfnArgs p{};
+  p.table = c->d_table + (size_t)layer * c->cfg.N;
+  p.x = x;
+  p.ids = ids;
+  p.w = w;
+  p.k = k;
+  p.a = c->d_a;
+  p.y = y;
+  p.err = c->d_err;
+  p.B = B;
+  p.H = c->cfg.H;
+  p.F = c->cfg.F;
+  p.N = c->cfg.N;
+  p.w2_offset = c->w2_offset;
+  return p;
+}
+
+int launch_ffn(adapmoe_ctx* c, int layer, const void* x, int B, const int32_t* ids, const float* w, const int32_t* k,
+               float* y, hipStream_t s) {
+  FfnArgs p = ffn_args(c, layer, x, B, ids, w, k, y);
+  {
+    ScopedTimer t(c, 0, s);
+    HIPCHK(c, launch_ffn_gateup(p, c->cfg.dtype, c->lc, s));
+  }
+  {
+    ScopedTimer t(c, 1, s);
+    HIPCHK(c, launch_ffn_down(p, c->cfg.dtype, c->lc, s));
+  }
+  c->ctr.ffn_launches++;
+  return ADAPMOE_OK;
+}
+
+int launch_gate_both(adapmoe_ctx* c, int layer, const void* x, int B, int32_t* ids, float* w, int32_t* k, int32_t* pids,
+                     int32_t* pk, hipStream_t s) {
+  if (!c->router[layer]) return fail(c, ADAPMOE_ESTATE, "router of this layer not set");
+  GateArgs g{};
+  g.x = x;
+  g.B = B;
+  g.H = c->cfg.H;
+  g.N = c->cfg.N;
+  g.Wg[0] = c->router[layer];
+  g.tau[0] = c->tau[layer];
+  g.ids[0] = ids;
+  g.k[0] = k;
+  g.w = w;
+  int routers = 1;
+  if (pids && pk) {
+    routers = 2;
+    const bool has_next = layer + 1 < c->cfg.L && c->router[layer + 1];
+    g.Wg[1] = has_next ? c->router[layer + 1] : nullptr;
+    g.tau[1] = has_next ? c->tau[layer + 1] : 0.f;
+    g.ids[1] = pids;
+    g.k[1] = pk;
+  }
+  ScopedTimer t(c, 2, s);
+  HIPCHK(c, launch_gate(g, c->bf16_act, routers, s));
+  return ADAPMOE_OK;
+}
+
+bool layer_fully_bound(const adapmoe_ctx* c, int layer) { return c->bound_count[layer] == c->cfg.N; }
+
+}  // namespace
+
+// ---------------------------------------------------------------------------
+
+extern "C" {
+
+const char* adapmoe_strerror(int code) {
+  switch (code) {
+    case ADAPMOE_OK: return "ok";
+    case ADAPMOE_EINVAL: return "invalid argument";
+    case ADAPMOE_ENOMEM: return "out of memory";
+    case ADAPMOE_ENOTREG: return "expert not registered";
+    case ADAPMOE_ENORES: return "expert not resident";
+    case ADAPMOE_EHIP: return "HIP runtime failure";
+    case ADAPMOE_ESTATE: return "invalid state for this call";
+    default: return "unknown error";
+  }
+}
+
+const char* adapmoe_last_error(const adapmoe_ctx* ctx) { return ctx ? ctx->last_error.c_str() : ""; }
+
+int adapmoe_expert_bytes(const adapmoe_config* cfg, size_t* bytes_out) {
+  if (!cfg_ok(cfg) || !bytes_out) return ADAPMOE_EINVAL;
+  *bytes_out = (size_t)3 * cfg->H * cfg->F * elem_size(cfg->dtype);
+  return ADAPMOE_OK;
+}
+
+int adapmoe_pack_expert(const adapmoe_config* cfg, const void* W1, const void* W3, const void* W2, void* out) {
+  if (!cfg_ok(cfg) || !W1 || !W3 || !W2 || !out) return ADAPMOE_EINVAL;
+  const size_t row = (size_t)cfg->H * elem_size(cfg->dtype);
+  char* o = static_cast<char*>(out);
+  for (int f = 0; f < cfg->F; ++f) {
+    memcpy(o + (size_t)(2 * f) * row, static_cast<const char*>(W1) + (size_t)f * row, row);
+    memcpy(o + (size_t)(2 * f + 1) * row, static_cast<const char*>(W3) + (size_t)f * row, row);
+  }
+  memcpy(o + (size_t)2 * cfg->F * row, W2, (size_t)cfg->H * cfg->F * elem_size(cfg->dtype));
+  return ADAPMOE_OK;
+}
+
+int adapmoe_pack_expert_int4(const adapmoe_config*, const uint8_t*, const uint16_t*, const uint16_t*, const uint8_t*,
+                             const uint16_t*, const uint16_t*, const uint8_t*, const uint16_t*, const uint16_t*, void*) {
+  return ADAPMOE_ESTATE;
+}
+
+int adapmoe_create(const adapmoe_config* cfg, adapmoe_ctx** out) {
+  if (!out) return ADAPMOE_EINVAL;
+  *out = nullptr;
+  if (!cfg_ok(cfg) || cfg->max_B < 1 || cfg->max_B > 64) return ADAPMOE_EINVAL;
+  int ndev = 0;
+  if (hipGetDeviceCount(&ndev) != hipSuccess || cfg->device < 0 || cfg->device >= ndev) return ADAPMOE_EHIP;
+  adapmoe_ctx* c = new (std::nothrow) adapmoe_ctx();
+  if (!c) return ADAPMOE_ENOMEM;
+  c->cfg = *cfg;
+  c->bf16_act = cfg->dtype != ADAPMOE_F32;
+  adapmoe_expert_bytes(cfg, &c->image_bytes);
+  c->w2_offset = (size_t)2 * cfg->F * cfg->H * elem_size(cfg->dtype);
+  const size_t LN = (size_t)cfg->L * cfg->N;
+  c->router.assign(cfg->L, nullptr);
+  c->tau.assign(cfg->L, 0.f);
+  c->host_image.assign(LN, nullptr);
+  c->bound.assign(LN, nullptr);
+  c->bound_count.assign(cfg->L, 0);
+  c->layers.resize(cfg->L);
+  c->lc.gateup_blocks = env_int("ADAPMOE_GATEUP_BLOCKS", 1024);
+  c->lc.down_blocks = env_int("ADAPMOE_DOWN_BLOCKS", 256);
+  const int B = cfg->max_B;
+  bool ok = hipSetDevice(cfg->device) == hipSuccess;
+  ok = ok && hipMalloc(&c->d_table, LN * sizeof(void*)) == hipSuccess;
+  ok = ok && hipMemset(c->d_table, 0, LN * sizeof(void*)) == hipSuccess;
+  ok = ok && hipMalloc(&c->d_err, sizeof(int32_t)) == hipSuccess;
+  ok = ok && hipMemset(c->d_err, 0, sizeof(int32_t)) == hipSuccess;
+  ok = ok && hipMalloc(&c->d_dec, (size_t)6 * B * sizeof(int32_t)) == hipSuccess;
+  ok = ok && hipMalloc(&c->d_w, (size_t)2 * B * sizeof(float)) == hipSuccess;
+  ok = ok && hipMalloc(&c->d_a, (size_t)2 * B * cfg->F * sizeof(float)) == hipSuccess;
+  ok = ok && hipHostMalloc(reinterpret_cast<void**>(&c->h_dec), (size_t)6 * B * sizeof(int32_t), hipHostMallocDefault) == hipSuccess;
+  ok = ok && hipStreamCreateWithFlags(&c->copy_stream, hipStreamNonBlocking) == hipSuccess;
+  ok = ok && ffn_kernels_init(cfg->dtype) == hipSuccess;
+  if (!ok) {
+    adapmoe_destroy(c);
+    return ADAPMOE_EHIP;
+  }
+  *out = c;
+  return ADAPMOE_OK;
+}
+
+int adapmoe_destroy(adapmoe_ctx* c) {
+  if (!c) return ADAPMOE_EINVAL;
+  hipSetDevice(c->cfg.device);
+  hipDeviceSynchronize();
+  for (Slot& s : c->slots) {
+    if (s.dev) hipFree(s.dev);
+    if (s.copy_done) hipEventDestroy(s.copy_done);
+    if (s.read_done) hipEventDestroy(s.read_done);
+  }
+  for (TimedLaunch& t : c->timed) {
+    hipEventDestroy(t.t0);
+    hipEventDestroy(t.t1);
+  }
+  for (hipEvent_t e : c->event_pool) hipEventDestroy(e);
+  if (c->copy_stream) hipStreamDestroy(c->copy_stream);
+  if (c->d_table) hipFree(c->d_table);
+  if (c->d_err) hipFree(c->d_err);
+  if (c->d_dec) hipFree(c->d_dec);
+  if (c->d_w) hipFree(c->d_w);
+  if (c->d_a) hipFree(c->d_a);
+  if (c->h_dec) hipHostFree(c->h_dec);
+  delete c;
+  return ADAPMOE_OK;
+}
+
+int adapmoe_set_router(adapmoe_ctx* c, int layer, const void* Wg_dev) {
+  if (!c || layer < 0 || layer >= c->cfg.L || !Wg_dev) return fail(c, ADAPMOE_EINVAL, "set_router: bad argument");
+  c->router[layer] = Wg_dev;
+  return ADAPMOE_OK;
+}
+
+int adapmoe_set_tau(adapmoe_ctx* c, const float* tau) {
+  if (!c || !tau) return fail(c, ADAPMOE_EINVAL, "set_tau: bad argument");
+  for (int l = 0; l < c->cfg.L; ++l) {
+    if (!(tau[l] >= 0.f)) return fail(c, ADAPMOE_EINVAL, "set_tau: threshold must be >= 0");
+    c->tau[l] = tau[l];
+  }
+  return ADAPMOE_OK;
+}
+
+int adapmoe_register_expert(adapmoe_ctx* c, int layer, int expert, const void* image_host, size_t bytes) {
+  if (!c || layer < 0 || layer >= c->cfg.L || expert < 0 || expert >= c->cfg.N || !image_host)
+    return fail(c, ADAPMOE_EINVAL, "register_expert: bad argument");
+  if (bytes != c->image_bytes) return fail(c, ADAPMOE_EINVAL, "register_expert: image size mismatch");
+  c->host_image[(size_t)layer * c->cfg.N + expert] = image_host;
+  return ADAPMOE_OK;
+}
+
+int adapmoe_bind_expert_dev(adapmoe_ctx* c, int layer, int expert, const void* image_dev) {
+  if (!c || layer < 0 || layer >= c->cfg.L || expert < 0 || expert >= c->cfg.N || !image_dev)
+    return fail(c, ADAPMOE_EINVAL, "bind_expert_dev: bad argument");
+  if ((reinterpret_cast<uintptr_t>(image_dev) & 15) != 0) return fail(c, ADAPMOE_EINVAL, "bind_expert_dev: image must be 16-byte aligned");
+  const size_t idx = (size_t)layer * c->cfg.N + expert;
+  if (c->layers[layer].find(expert) >= 0) return fail(c, ADAPMOE_ESTATE, "bind_expert_dev: expert currently cached");
+  if (!c->bound[idx]) c->bound_count[layer]++;
+  c->bound[idx] = image_dev;
+  HIPCHK(c, hipSetDevice(c->cfg.device));
+  HIPCHK(c, hipMemcpy(c->d_table + idx, &image_dev, sizeof(void*), hipMemcpyHostToDevice));
+  return ADAPMOE_OK;
+}
+
+// ---- planner (Sec. 4.4: Eq.10-15 cost, Eq.16-19 knapsack DP, traceback) -------
+
+double cache_cost(int N, int t, double a, double beta) {
+  if (N < 2 || t < 0 || t > N) return NAN;
+  const double pairs = (double)N * (N - 1);
+  const double miss1 = 1.0 - (double)t / N;                          // one given expert absent (Eq.10)
+  const double miss2 = std::max((double)(N - t) * (N - t - 1), 0.0) / pairs;  // two given experts both absent
+  const double mixed = 2.0 * (N - t) * t / pairs;                    // exactly one of two absent
+  const double one = miss1 * (1.0 - beta);                           // Eq.11
+  const double two = 2.0 * miss2 * (1.0 - beta)                      // Eq.12
+                     + miss2 * beta                                  // Eq.13
+                     + mixed * (1.0 - beta);                         // Eq.14
+  return a * one + (1.0 - a) * two;                                  // Eq.15
+}
+
+int cache_plan(int L, int N, int C, const double* a, const double* beta, int32_t* t_out, double* cost_out) {
+  if (L < 1 || N < 2 || C < 0 || !a || !beta || !t_out) return ADAPMOE_EINVAL;
+  const double tie = 1e-12;
+  std::vector<double> f((size_t)L * (N + 1));
+  for (int i = 0; i < L; ++i)
+    for (int t = 0; t <= N; ++t) f[(size_t)i * (N + 1) + t] = cache_cost(N, t, a[i], beta[i]);
+  const size_t W = (size_t)C + 1;
+  std::vector<double> best((size_t)(L + 1) * W, 0.0);  // best[i][j]: first i layers, at most j slots (Eq.19)
+  for (int i = 1; i <= L; ++i)
+    for (int j = 0; j <= C; ++j) {
+      double m = INFINITY;
+      for (int k = 0; k <= std::min(j, N); ++k)
+        m = std::min(m, best[(size_t)(i - 1) * W + (j - k)] + f[(size_t)(i - 1) * (N + 1) + k]);
+      best[(size_t)i * W + j] = m;
+    }
+  int j = C;
+  for (int i = L; i >= 1; --i) {  // traceback from the last layer, smallest slot count attaining the minimum
+    int pick = 0;
+    for (int k = 0; k <= std::min(j, N); ++k)
+      if (best[(size_t)(i - 1) * W + (j - k)] + f[(size_t)(i - 1) * (N + 1) + k] <= best[(size_t)i * W + j] + tie) {
+        pick = k;
+        break;
+      }
+    t_out[i - 1] = pick;
+    j -= pick;
+  }
+  if (cost_out) *cost_out = best[(size_t)L * W + C];
+  return ADAPMOE_OK;
+}
+
+int cache_alloc(adapmoe_ctx* c, const int32_t* slots_per_layer) {
+  if (!c || !slots_per_layer) return fail(c, ADAPMOE_EINVAL, "cache_alloc: bad argument");
+  if (c->cache_ready) return fail(c, ADAPMOE_ESTATE, "cache_alloc: already allocated");
+  size_t total = 0;
+  for (int l = 0; l < c->cfg.L; ++l) {
+    if (slots_per_layer[l] < 0 || slots_per_layer[l] > c->cfg.N) return fail(c, ADAPMOE_EINVAL, "cache_alloc: slots per layer must be in 0..N");
+    total += slots_per_layer[l];
+  }
+  total += 2;
+  HIPCHK(c, hipSetDevice(c->cfg.device));
+  c->slots.resize(total);
+  for (size_t i = 0; i < total; ++i) {
+    Slot& s = c->slots[i];
+    if (hipMalloc(reinterpret_cast<void**>(&s.dev), c->image_bytes) != hipSuccess ||
+        hipEventCreateWithFlags(&s.copy_done, hipEventDisableTiming) != hipSuccess ||
+        hipEventCreateWithFlags(&s.read_done, hipEventDisableTiming) != hipSuccess) {
+      (void)hipGetLastError();
+      for (Slot& t : c->slots) {
+        if (t.dev) hipFree(t.dev);
+        if (t.copy_done) hipEventDestroy(t.copy_done);
+        if (t.read_done) hipEventDestroy(t.read_done);
+      }
+      c->slots.clear();
+      return fail(c, ADAPMOE_ENOMEM, "cache_alloc: HBM allocation failed");
+    }
+  }
+  c->free_slots.clear();
+  for (int i = (int)total - 1; i >= 0; --i) c->free_slots.push_back(i);
+  for (int l = 0; l < c->cfg.L; ++l) {
+    c->layers[l].cap = slots_per_layer[l];
+    c->layers[l].order.clear();
+  }
+  c->cache_ready = true;
+  return ADAPMOE_OK;
+}
+
+int cache_lookup(adapmoe_ctx* c, int layer, const int32_t* ids, int n, int32_t* slot_out, int touch) {
+  if (!c || layer < 0 || layer >= c->cfg.L || !ids || !slot_out || n < 0) return fail(c, ADAPMOE_EINVAL, "cache_lookup: bad argument");
+  LayerCache& lc = c->layers[layer];
+  for (int i = 0; i < n; ++i) {
+    const int e = ids[i];
+    if (e < 0 || e >= c->cfg.N) return fail(c, ADAPMOE_EINVAL, "cache_lookup: expert id out of range");
+    if (c->bound[(size_t)layer * c->cfg.N + e]) { slot_out[i] = -2; continue; }
+    const int pos = lc.find(e);
+    if (pos < 0) { slot_out[i] = -1; continue; }
+    slot_out[i] = lc.order[pos].slot;
+    if (touch) lc.touch(pos);
+  }
+  return ADAPMOE_OK;
+}
+
+// ---- steps ------------------------------------------------------------------
+
+int moe_gate(adapmoe_ctx* c, int layer, const void* x, int B, int32_t* ids, float* w, int32_t* k, int32_t* pred_ids,
+             int32_t* pred_k, void* stream) {
+  if (!c || layer < 0 || layer >= c->cfg.L || !x || !ids || !w || !k || B < 1 || B > c->cfg.max_B)
+    return fail(c, ADAPMOE_EINVAL, "moe_gate: bad argument");
+  if ((pred_ids == nullptr) != (pred_k == nullptr)) return fail(c, ADAPMOE_EINVAL, "moe_gate: give both prediction outputs or neither");
+  return launch_gate_both(c, layer, x, B, ids, w, k, pred_ids, pred_k, static_cast<hipStream_t>(stream));
+}
+
+int moe_expert_ffn(adapmoe_ctx* c, int layer, const void* x, int B, const int32_t* ids, const float* w, const int32_t* k,
+                   float* y, void* stream) {
+  if (!c || layer < 0 || layer >= c->cfg.L || !x || !ids || !w || !k || !y || B < 1 || B > c->cfg.max_B)
+    return fail(c, ADAPMOE_EINVAL, "moe_expert_ffn: bad argument");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  int rc = flush_pokes(c, s);
+  if (rc) return rc;
+  // the ids are on the device: wait for every copy into this layer's slots that is still unannounced
+  for (Entry& en : c->layers[layer].order) {
+    Slot& sl = c->slots[en.slot];
+    if (sl.copy_pending) {
+      HIPCHK(c, hipStreamWaitEvent(s, sl.copy_done, 0));
+      sl.copy_pending = false;
+    }
+  }
+  rc = launch_ffn(c, layer, x, B, ids, w, k, y, s);
+  if (rc) return rc;
+  for (Entry& en : c->layers[layer].order) {
+    Slot& sl = c->slots[en.slot];
+    HIPCHK(c, hipEventRecord(sl.read_done, s));
+    sl.was_read = true;
+  }
+  return ADAPMOE_OK;
+}
+
+int moe_prefetch(adapmoe_ctx* c, int layer, const int32_t* ids_host, int n) {
+  if (!c || layer < 0 || layer >= c->cfg.L || !ids_host || n < 0) return fail(c, ADAPMOE_EINVAL, "moe_prefetch: bad argument");
+  if (!c->cache_ready) return fail(c, ADAPMOE_ESTATE, "moe_prefetch: cache not allocated");
+  return prefetch_layer(c, layer, ids_host, n);
+}
+
+int moe_layer_step(adapmoe_ctx* c, int layer, const void* x, int B, float* y, void* stream) {
+  if (!c || layer < 0 || layer >= c->cfg.L || !x || !y || B < 1 || B > c->cfg.max_B)
+    return fail(c, ADAPMOE_EINVAL, "moe_layer_step: bad argument");
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int N = c->cfg.N;
+  int32_t* d_ids = c->d_dec;
+  int32_t* d_k = c->d_dec + 2 * B;
+  int32_t* d_pids = c->d_dec + 3 * B;
+  int32_t* d_pk = c->d_dec + 5 * B;
+  const bool next_needs_host = layer + 1 < c->cfg.L && !layer_fully_bound(c, layer + 1) && c->cache_ready;
+  const bool host_path = !layer_fully_bound(c, layer) || next_needs_host;
+
+  int rc = launch_gate_both(c, layer, x, B, d_ids, c->d_w, d_k, host_path ? d_pids : nullptr, host_path ? d_pk : nullptr, s);
+  if (rc) return rc;
+  c->ctr.tokens_gated += B;
+
+  if (!host_path) {  // every expert of the layer lives in HBM: residency is a device-side table lookup
+    rc = flush_pokes(c, s);
+    if (rc) return rc;
+    return launch_ffn(c, layer, x, B, d_ids, c->d_w, d_k, y, s);
+  }
+  if (!c->cache_ready && !layer_fully_bound(c, layer)) return fail(c, ADAPMOE_ESTATE, "moe_layer_step: cache not allocated");
+
+  // Alg.1: the host needs E and r to decide what to transfer
+  HIPCHK(c, hipMemcpyAsync(c->h_dec, c->d_dec, (size_t)6 * B * sizeof(int32_t), hipMemcpyDeviceToHost, s));
+  HIPCHK(c, hipStreamSynchronize(s));
+  const int32_t* ids = c->h_dec;
+  const int32_t* kk = c->h_dec + 2 * B;
+  const int32_t* pids = c->h_dec + 3 * B;
+  const int32_t* pk = c->h_dec + 5 * B;
+
+  LayerCache& lc = c->layers[layer];
+  std::vector<int> used_slots;                       // slots the FFN of this step reads
+  std::vector<std::pair<int, int>> transient;        // (expert, slot) to drop right after the FFN
+  std::vector<int> demanded;                         // experts needed by this step so far
+  for (int b = 0; b < B; ++b) {
+    if (kk[b] == 1) c->ctr.single_expert++;
+    for (int j = 0; j < kk[b] && j < 2; ++j) {
+      const int e = ids[2 * b + j];
+      if (e < 0 || e >= N) return fail(c, ADAPMOE_EINVAL, "moe_layer_step: gate produced an id out of range");
+      if (c->bound[(size_t)layer * N + e]) { record(c, layer, ADAPMOE_EV_HIT, e, -1, -2); continue; }
+      bool is_transient = false;
+      for (auto& t : transient) is_transient |= (t.first == e);
+      const int pos = lc.find(e);
+      if (pos >= 0) {
+        Entry& en = lc.order[pos];
+        record(c, layer, en.by_prefetch ? ADAPMOE_EV_HIT_PF : ADAPMOE_EV_HIT, e, -1, en.slot);
+        en.by_prefetch = false;
+        used_slots.push_back(en.slot);
+        lc.touch(pos);
+        demanded.push_back(e);
+        continue;
+      }
+      if (is_transient) {  // evicted or bypassed earlier in this same step, image still in its slot
+        if (lc.cap == 0) { record(c, layer, ADAPMOE_EV_BYPASS, e, -1, -1); continue; }
+        // falls through to a regular miss below: logically it is gone
+      }
+      int victim = -1, slot = -1;
+      if (lc.cap == 0) {
+        if (c->free_slots.empty()) return fail(c, ADAPMOE_ENOMEM, "no spare slot for a bypass load");
+        slot = c->free_slots.back();
+        c->free_slots.pop_back();
+        rc = start_copy(c, layer, e, slot);
+        if (rc) return rc;
+        poke_later(c, layer, e, c->slots[slot].dev);
+        transient.emplace_back(e, slot);
+        used_slots.push_back(slot);
+        record(c, layer, ADAPMOE_EV_BYPASS, e, -1, slot);
+        continue;
+      }
+      if ((int)lc.order.size() >= lc.cap) {
+        Entry v = lc.order.front();
+        lc.order.erase(lc.order.begin());
+        victim = v.expert;
+        const bool victim_needed = std::find(demanded.begin(), demanded.end(), victim) != demanded.end();
+        if (victim_needed) {  // still read by this step's FFN: keep its image, take another slot
+          transient.emplace_back(victim, v.slot);
+          if (c->free_slots.empty()) return fail(c, ADAPMOE_ENOMEM, "no spare slot");
+          slot = c->free_slots.back();
+          c->free_slots.pop_back();
+        } else {
+          slot = v.slot;
+          poke_later(c, layer, victim, nullptr);
+        }
+      } else {
+        if (c->free_slots.empty()) return fail(c, ADAPMOE_ENOMEM, "no free cache slot");
+        slot = c->free_slots.back();
+        c->free_slots.pop_back();
+      }
+      if (is_transient) {
+        // the expert was pushed out earlier in this step and is demanded again: reuse nothing, load again
+        for (auto& t : transient)
+          if (t.first == e) t.first = -1 - e;  // its old slot is still released, but the table entry now points to the new one
+      }
+      rc = start_copy(c, layer, e, slot);
+      if (rc) return rc;
+      lc.order.push_back(Entry{e, slot, false});
+      poke_later(c, layer, e, c->slots[slot].dev);
+      used_slots.push_back(slot);
+      demanded.push_back(e);
+      record(c, layer, ADAPMOE_EV_MISS, e, victim, slot);
+    }
+  }
+
+  // predicted experts of the following layer go to the transfer queue after the demanded ones
+  if (layer + 1 < c->cfg.L && c->cache_ready) {
+    std::vector<int32_t> r;
+    for (int b = 0; b < B; ++b)
+      for (int j = 0; j < pk[b] && j < 2; ++j)
+        if (std::find(r.begin(), r.end(), pids[2 * b + j]) == r.end()) r.push_back(pids[2 * b + j]);
+    rc = prefetch_layer(c, layer + 1, r.data(), (int)r.size());
+    if (rc) return rc;
+  }
+
+  rc = flush_pokes(c, s);
+  if (rc) return rc;
+  for (int slot : used_slots) {
+    Slot& sl = c->slots[slot];
+    if (sl.copy_pending) {
+      HIPCHK(c, hipStreamWaitEvent(s, sl.copy_done, 0));
+      sl.copy_pending = false;
+    }
+  }
+  rc = launch_ffn(c, layer, x, B, d_ids, c->d_w, d_k, y, s);
+  if (rc) return rc;
+  for (int slot : used_slots) {
+    Slot& sl = c->slots[slot];
+    HIPCHK(c, hipEventRecord(sl.read_done, s));
+    sl.was_read = true;
+  }
+  for (auto& t : transient) {
+    if (t.first >= 0) poke_later(c, layer, t.first, nullptr);
+    c->free_slots.push_back(t.second);
+  }
+  if (!transient.empty()) {
+    rc = flush_pokes(c, s);
+    if (rc) return rc;
+  }
+  return ADAPMOE_OK;
+}
+
+int moe_residual_rmsnorm(adapmoe_ctx* c, float* h, const float* y, float gamma, void* x, int B, void* stream) {
+  if (!c || !h || !x || B < 1 || B > c->cfg.max_B) return fail(c, ADAPMOE_EINVAL, "moe_residual_rmsnorm: bad argument");
+  HIPCHK(c, launch_residual_rmsnorm(h, y, gamma, x, c->bf16_act, B, c->cfg.H, static_cast<hipStream_t>(stream)));
+  return ADAPMOE_OK;
+}
+
+// ---- bookkeeping ---------------------------------------------------------------
+
+int adapmoe_set_token(adapmoe_ctx* c, int token) {
+  if (!c) return ADAPMOE_EINVAL;
+  c->token = token;
+  return ADAPMOE_OK;
+}
+
+int adapmoe_trace_read(adapmoe_ctx* c, adapmoe_event* buf, size_t cap, size_t* n_out) {
+  if (!c || (!buf && cap) || !n_out) return fail(c, ADAPMOE_EINVAL, "trace_read: bad argument");
+  size_t n = std::min(cap, c->trace.size());
+  for (size_t i = 0; i < n; ++i) {
+    buf[i] = c->trace.front();
+    c->trace.pop_front();
+  }
+  *n_out = n;
+  return ADAPMOE_OK;
+}
+
+int adapmoe_counters(adapmoe_ctx* c, adapmoe_counters_t* out) {
+  if (!c || !out) return ADAPMOE_EINVAL;
+  *out = c->ctr;
+  return ADAPMOE_OK;
+}
+
+int adapmoe_last_decision(adapmoe_ctx* c, int32_t* ids, int32_t* k, int32_t* pred_ids, int32_t* pred_k, int B) {
+  if (!c || B < 1 || B > c->cfg.max_B) return fail(c, ADAPMOE_EINVAL, "last_decision: bad argument");
+  if (ids) memcpy(ids, c->h_dec, (size_t)2 * B * sizeof(int32_t));
+  if (k) memcpy(k, c->h_dec + 2 * B, (size_t)B * sizeof(int32_t));
+  if (pred_ids) memcpy(pred_ids, c->h_dec + 3 * B, (size_t)2 * B * sizeof(int32_t));
+  if (pred_k) memcpy(pred_k, c->h_dec + 5 * B, (size_t)B * sizeof(int32_t));
+  return ADAPMOE_OK;
+}
+
+int adapmoe_check(adapmoe_ctx* c, void* stream) {
+  if (!c) return ADAPMOE_EINVAL;
+  HIPCHK(c, hipStreamSynchronize(static_cast<hipStream_t>(stream)));
+  HIPCHK(c, hipStreamSynchronize(c->copy_stream));
+  int32_t flags = 0;
+  HIPCHK(c, hipMemcpy(&flags, c->d_err, sizeof(flags), hipMemcpyDeviceToHost));
+  if (flags) {
+    HIPCHK(c, hipMemset(c->d_err, 0, sizeof(int32_t)));
+    if (flags & 2) return fail(c, ADAPMOE_EINVAL, "expert FFN met an expert id out of range");
+    return fail(c, ADAPMOE_ENORES, "expert FFN met a non-resident expert");
+  }
+  return ADAPMOE_OK;
+}
+
+int adapmoe_profile(adapmoe_ctx* c, int on) {
+  if (!c) return ADAPMOE_EINVAL;
+  c->profiling = on != 0;
+  return ADAPMOE_OK;
+}
+
+int adapmoe_profile_read(adapmoe_ctx* c, int cls, uint64_t* launches, double* total_ms) {
+  if (!c || !launches || !total_ms) return fail(c, ADAPMOE_EINVAL, "profile_read: bad argument");
+  uint64_t n = 0;
+  double ms = 0.0;
+  std::vector<TimedLaunch> keep;
+  for (TimedLaunch& t : c->timed) {
+    if (t.cls != cls) { keep.push_back(t); continue; }
+    HIPCHK(c, hipEventSynchronize(t.t1));
+    float d = 0.f;
+    HIPCHK(c, hipEventElapsedTime(&d, t.t0, t.t1));
+    ms += d;
+    ++n;
+    c->event_pool.push_back(t.t0);
+    c->event_pool.push_back(t.t1);
+  }
+  c->timed.swap(keep);
+  *launches = n;
+  *total_ms = ms;
+  return ADAPMOE_OK;
+}
+
+}  // extern "C"

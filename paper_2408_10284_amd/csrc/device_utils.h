@@ -1,0 +1,109 @@
+// Device-side helpers shared by the kernels: wavefront reductions on DPP,
+// bfloat16 unpacking, 16-byte streaming loads.  gfx950 only (64-lane waves).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace adapmoe {
+
+typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
+
+constexpr int kWave = 64;
+
+// DPP controls (GCN3+ encoding)
+constexpr int kDppQuadSwap1 = 0xB1;      // quad_perm:[1,0,3,2]
+constexpr int kDppQuadSwap2 = 0x4E;      // quad_perm:[2,3,0,1]
+constexpr int kDppRowHalfMirror = 0x141;
+constexpr int kDppRowMirror = 0x140;
+
+template <int CTRL>
+__device__ __forceinline__ float dpp_f32(float v) {
+  int i = __builtin_bit_cast(int, v);
+  i = __builtin_amdgcn_update_dpp(i, i, CTRL, 0xf, 0xf, false);
+  return __builtin_bit_cast(float, i);
+}
+
+__device__ __forceinline__ float readlane_f32(float v, int lane) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
+}
+
+// Sum over the 64 lanes of a fully active wavefront; every lane gets the result.
+// Four DPP steps give each row of 16 lanes its row sum, the four row sums are
+// then read as scalars.  The order of additions is fixed, so results are
+// reproducible from run to run.
+__device__ __forceinline__ float wave_sum(float v) {
+  v += dpp_f32<kDppQuadSwap1>(v);
+  v += dpp_f32<kDppQuadSwap2>(v);
+  v += dpp_f32<kDppRowHalfMirror>(v);
+  v += dpp_f32<kDppRowMirror>(v);
+  float r0 = readlane_f32(v, 0), r1 = readlane_f32(v, 16), r2 = readlane_f32(v, 32), r3 = readlane_f32(v, 48);
+  return (r0 + r1) + (r2 + r3);
+}
+
+__device__ __forceinline__ float wave_max(float v) {
+  v = fmaxf(v, dpp_f32<kDppQuadSwap1>(v));
+  v = fmaxf(v, dpp_f32<kDppQuadSwap2>(v));
+  v = fmaxf(v, dpp_f32<kDppRowHalfMirror>(v));
+  v = fmaxf(v, dpp_f32<kDppRowMirror>(v));
+  float r0 = readlane_f32(v, 0), r1 = readlane_f32(v, 16), r2 = readlane_f32(v, 32), r3 = readlane_f32(v, 48);
+  return fmaxf(fmaxf(r0, r1), fmaxf(r2, r3));
+}
+
+// bfloat16 pair packed in a dword -> two floats (exact)
+__device__ __forceinline__ float bf16_lo(uint32_t u) { return __builtin_bit_cast(float, u << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t u) { return __builtin_bit_cast(float, u & 0xffff0000u); }
+
+// float -> bfloat16 bits, round to nearest even (NaN kept quiet)
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
+  uint32_t u = __builtin_bit_cast(uint32_t, f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+// acc += a.lo*b.lo + a.hi*b.hi for two packed bfloat16 pairs, fp32 accumulate
+__device__ __forceinline__ float dot2_bf16(uint32_t a, uint32_t b, float acc) {
+  return __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, a), __builtin_bit_cast(bf16x2_t, b), acc, false);
+}
+
+// 16-byte load of read-once data (weights): non-temporal so that the stream
+// does not displace the small reused vectors from the caches.
+__device__ __forceinline__ uint4 load_stream16(const void* p) {
+  typedef __attribute__((ext_vector_type(4))) uint32_t u32x4;
+  typedef const __attribute__((address_space(1))) u32x4* gptr_t;  // expert images always live in global memory
+  u32x4 v = __builtin_nontemporal_load((gptr_t)(uintptr_t)p);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+// Elements of type T in a 16-byte vector and the dot product of a weight
+// vector with an activation vector, for the storage types of the library.
+// Weights float32 x activations float32:
+__device__ __forceinline__ float dot16_f32(const uint4& w, const float4& x, float acc) {
+  acc = fmaf(__builtin_bit_cast(float, w.x), x.x, acc);
+  acc = fmaf(__builtin_bit_cast(float, w.y), x.y, acc);
+  acc = fmaf(__builtin_bit_cast(float, w.z), x.z, acc);
+  acc = fmaf(__builtin_bit_cast(float, w.w), x.w, acc);
+  return acc;
+}
+// Weights bfloat16 (8 per vector) x activations bfloat16 (8 per vector):
+__device__ __forceinline__ float dot16_bf16(const uint4& w, const uint4& x, float acc) {
+  acc = dot2_bf16(w.x, x.x, acc);
+  acc = dot2_bf16(w.y, x.y, acc);
+  acc = dot2_bf16(w.z, x.z, acc);
+  acc = dot2_bf16(w.w, x.w, acc);
+  return acc;
+}
+// Weights bfloat16 (8 per vector) x activations float32 (two float4):
+__device__ __forceinline__ float dot16_bf16_f32(const uint4& w, const float4& a0, const float4& a1, float acc) {
+  acc = fmaf(bf16_lo(w.x), a0.x, acc);
+  acc = fmaf(bf16_hi(w.x), a0.y, acc);
+  acc = fmaf(bf16_lo(w.y), a0.z, acc);
+  acc = fmaf(bf16_hi(w.y), a0.w, acc);
+  acc = fmaf(bf16_lo(w.z), a1.x, acc);
+  acc = fmaf(bf16_hi(w.z), a1.y, acc);
+  acc = fmaf(bf16_lo(w.w), a1.z, acc);
+  acc = fmaf(bf16_hi(w.w), a1.w, acc);
+  return acc;
+}
+
+}  // namespace adapmoe

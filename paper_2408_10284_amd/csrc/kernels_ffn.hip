@@ -1,0 +1,328 @@
+// Expert FFN for decode (one or a few tokens): weight-streaming GEMVs.
+//
+//   y = sum_{j<k} w_j * W2_j ( silu(W1_j x) * (W3_j x) )      (Sec. 2.1 Eq.2; Sec. 4.2 Eq.3-4)
+//
+// Two launches, both bound by HBM bandwidth (one multiply-add per weight read):
+//   gate/up  one wavefront per row pair (W1[f,:], W3[f,:]) of an activated
+//            expert; rows of W1 and W3 are interleaved in the image so the pair
+//            is one contiguous 2*H-element read; writes a_j[f] = w_j silu(g) u.
+//   down     one wavefront per output element y[h]: dot of W2_j[h,:] with a_j
+//            (staged in LDS) for every activated expert, summed in a fixed order.
+// Every lane reads 16 bytes per load and a wavefront reads 1 KiB contiguous.
+// No atomics: results are bit-reproducible.
+#include "device_utils.h"
+#include "launch.h"
+#include "../../include/adapmoe.h"
+
+namespace adapmoe {
+
+constexpr int kGateUpThreads = 256;
+constexpr int kDownThreads = 1024;
+constexpr int kChunkBytes = kWave * 16;  // bytes one wavefront reads per load instruction
+
+__device__ __forceinline__ float silu_f32(float g) { return g / (1.0f + expf(-g)); }
+
+// Resolves the image base pointers of the (up to two) activated experts of token b.
+__device__ __forceinline__ int resolve_experts(const FfnArgs& p, int b, const char* base[2], float w[2]) {
+  int kk = p.k[b];
+  kk = kk < 1 ? 1 : (kk > 2 ? 2 : kk);
+  for (int j = 0; j < 2; ++j) {
+    base[j] = nullptr;
+    w[j] = 0.f;
+    if (j < kk) {
+      const int e = p.ids[2 * b + j];
+      if (e < 0 || e >= p.N) {
+        if (threadIdx.x == 0) atomicOr(p.err, 2);
+      } else {
+        base[j] = static_cast<const char*>(p.table[e]);
+        w[j] = p.w[2 * b + j];
+        if (base[j] == nullptr && threadIdx.x == 0) atomicOr(p.err, 1);
+      }
+    }
+  }
+  return kk;
+}
+
+// ----------------------------------------------------------- part streaming --
+
+// Both GEMVs read, per wavefront, a known sequence of "parts": NV consecutive
+// 1 KiB runs of a matrix row (16 bytes per lane each).  Two register buffers
+// alternate: while part q is consumed, part q+1 is already in flight and part
+// q+2 is requested as soon as q's buffer is free, so a wavefront keeps NV to
+// 2*NV loads outstanding.  The steady loop has no conditional loads (those
+// would make the compiler copy the buffers); the tail is peeled.
+// next_addr() returns the lane's address of the next part in sequence,
+// consume(buf) uses the next part in sequence; both keep their own cursor.
+template <int NV>
+__device__ __forceinline__ void load_vecs(const char* p, uint4 (&buf)[NV]) {
+#pragma unroll
+  for (int c = 0; c < NV; ++c) buf[c] = load_stream16(p + (size_t)c * kChunkBytes);
+}
+
+template <int NV, class AddrFn, class ConsumeFn>
+__device__ __forceinline__ void stream_parts(int Q, AddrFn next_addr, ConsumeFn consume) {
+  if (Q <= 0) return;
+  uint4 A[NV], B[NV];
+  load_vecs<NV>(next_addr(), A);
+  if (Q > 1) load_vecs<NV>(next_addr(), B);
+  int q = 0;
+  for (; q + 3 < Q; q += 2) {
+    consume(A);
+    load_vecs<NV>(next_addr(), A);
+    consume(B);
+    load_vecs<NV>(next_addr(), B);
+  }
+  // 1, 2 or 3 parts left; A holds part q, B part q+1
+  consume(A);
+  if (q + 2 < Q) load_vecs<NV>(next_addr(), A);
+  if (q + 1 < Q) consume(B);
+  if (q + 2 < Q) consume(A);
+}
+
+// ------------------------------------------------------------------ gate/up --
+
+template <bool BF16, int NV>
+__device__ __forceinline__ float dot_x(const uint4 (&buf)[NV], const uint4* xs, int c0, int lane, float acc) {
+#pragma unroll
+  for (int c = 0; c < NV; ++c) {
+    const uint4 xv = xs[(c0 + c) * kWave + lane];
+    if (BF16) acc = dot16_bf16(buf[c], xv, acc);
+    else acc = dot16_f32(buf[c], __builtin_bit_cast(float4, xv), acc);
+  }
+  return acc;
+}
+
+// Row length not known at compile time, or an expert missing: plain loop.
+template <bool BF16>
+__device__ __forceinline__ float dot_row_generic(const char* row, const uint4* xs, int lane, int nch) {
+  float acc = 0.f;
+  for (int c = 0; c < nch; ++c) {
+    uint4 buf[1];
+    buf[0] = load_stream16(row + (size_t)c * kChunkBytes + lane * 16);
+    acc = dot_x<BF16, 1>(buf, xs, c, lane, acc);
+  }
+  return acc;
+}
+
+// Each wavefront walks over row pairs r = first, first + stride, ...; a part
+// is one row (W1[f,:] then W3[f,:], adjacent in the image).
+template <bool BF16, int NCH>
+__global__ __launch_bounds__(kGateUpThreads) void ffn_gateup_kernel(FfnArgs p) {
+  extern __shared__ uint4 xs[];  // x[b,:] in its storage type
+  const int b = blockIdx.y;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const size_t esz = BF16 ? 2 : 4;
+  const size_t row_bytes = (size_t)p.H * esz;
+  const int nch = (int)(row_bytes / kChunkBytes);
+
+  const char* base[2];
+  float wj[2];
+  const int kk = resolve_experts(p, b, base, wj);
+  const int total = kk * p.F;
+  const int stride = gridDim.x * (kGateUpThreads / kWave);
+  const int first = blockIdx.x * (kGateUpThreads / kWave) + wave;
+  float* a_out = p.a + (size_t)b * 2 * p.F;
+  const int F = p.F;
+
+  const uint4* xg = reinterpret_cast<const uint4*>(static_cast<const char*>(p.x) + (size_t)b * row_bytes);
+  for (int i = tid; i < nch * kWave; i += kGateUpThreads) xs[i] = xg[i];
+  __syncthreads();
+
+  bool all_resident = true;
+  for (int j = 0; j < kk; ++j) all_resident &= base[j] != nullptr;
+
+  if (NCH > 0 && all_resident) {
+    const int nrows = first < total ? (total - first + stride - 1) / stride : 0;
+    int ra = first, half_a = 0;  // load cursor
+    auto next_addr = [&]() -> const char* {
+      const int j = ra >= F ? 1 : 0;
+      const char* q = base[j] + ((size_t)(ra - j * F) * 2 + half_a) * row_bytes + lane * 16;
+      if (half_a) ra += stride;
+      half_a ^= 1;
+      return q;
+    };
+    int rc = first, half_c = 0;  // consume cursor
+    float g = 0.f;
+    auto consume = [&](const uint4(&buf)[NCH > 0 ? NCH : 1]) {
+      const float d = dot_x<BF16, (NCH > 0 ? NCH : 1)>(buf, xs, 0, lane, 0.f);
+      if (!half_c) {
+        g = d;
+      } else {
+        const float gs = wave_sum(g), us = wave_sum(d);
+        if (lane == 0) a_out[rc] = wj[rc >= F ? 1 : 0] * silu_f32(gs) * us;
+        rc += stride;
+      }
+      half_c ^= 1;
+    };
+    stream_parts<(NCH > 0 ? NCH : 1)>(2 * nrows, next_addr, consume);
+  } else {
+    for (int r = first; r < total; r += stride) {
+      const int j = r >= F ? 1 : 0;
+      float val = 0.f;
+      if (base[j]) {
+        const char* row = base[j] + (size_t)(r - j * F) * 2 * row_bytes;
+        const float g = wave_sum(dot_row_generic<BF16>(row, xs, lane, nch));
+        const float u = wave_sum(dot_row_generic<BF16>(row + row_bytes, xs, lane, nch));
+        val = wj[j] * silu_f32(g) * u;
+      }
+      if (lane == 0) a_out[r] = val;
+    }
+  }
+}
+
+// --------------------------------------------------------------------- down --
+
+// LDS position of a_j[f] for the bfloat16 path: a lane reads the eight values
+// matching its 16-byte weight vector as two float4; placing the two halves of
+// all 64 lanes in separate 1 KiB runs makes both reads bank-conflict free.
+__device__ __forceinline__ int lds_pos_bf16(int f4 /* float4 index, f = 4*f4 */) {
+  const int c = f4 >> 7;          // chunk of 512 elements = 128 float4
+  const int r = f4 & 127;
+  const int ln = r >> 1, half = r & 1;
+  return (c << 7) + (half << 6) + ln;
+}
+
+template <bool BF16, int NV>
+__device__ __forceinline__ float dot_a(const uint4 (&buf)[NV], const float4* aj, int c0, int lane, float acc) {
+#pragma unroll
+  for (int u = 0; u < NV; ++u) {
+    const int c = c0 + u;
+    if (BF16) acc = dot16_bf16_f32(buf[u], aj[(c << 7) + lane], aj[(c << 7) + 64 + lane], acc);
+    else acc = dot16_f32(buf[u], aj[(c << 6) + lane], acc);
+  }
+  return acc;
+}
+
+// One wavefront per output element y[h]; a part is UN vectors of a row
+// W2_j[h,:].  UN == 0 selects the plain loop (row length not a multiple of the
+// part size).  A missing expert also takes the plain loop.
+template <bool BF16, int UN>
+__global__ __launch_bounds__(kDownThreads) void ffn_down_kernel(FfnArgs p) {
+  extern __shared__ float4 as4[];  // a[j][F] of the activated experts
+  const int b = blockIdx.y;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const size_t esz = BF16 ? 2 : 4;
+  const size_t row_bytes = (size_t)p.F * esz;
+  const int nch = (int)(row_bytes / kChunkBytes);
+  const int F4 = p.F >> 2;
+  const int H = p.H;
+  constexpr int kWaves = kDownThreads / kWave;
+  constexpr int NV = UN > 0 ? UN : 1;
+
+  const char* base[2];
+  float wj[2];
+  const int kk = resolve_experts(p, b, base, wj);
+  bool all_resident = true;
+  for (int j = 0; j < kk; ++j) all_resident &= base[j] != nullptr;
+
+  const float4* ag = reinterpret_cast<const float4*>(p.a + (size_t)b * 2 * p.F);
+  for (int i = tid; i < kk * F4; i += kDownThreads) {
+    const int j = i >= F4 ? 1 : 0;
+    const int f4 = i - j * F4;
+    as4[j * F4 + (BF16 ? lds_pos_bf16(f4) : f4)] = ag[i];
+  }
+  __syncthreads();
+
+  const int first = blockIdx.x * kWaves + wave;
+  const int hstride = gridDim.x * kWaves;
+  float* y = p.y + (size_t)b * H;
+
+  if (UN > 0 && all_resident) {
+    const int nbp = nch / NV;        // parts per row of one expert
+    const int nb = kk * nbp;         // parts per output element
+    const int nrows = first < H ? (H - first + hstride - 1) / hstride : 0;
+    const char* w2[2] = {base[0] + p.w2_offset, kk > 1 ? base[1] + p.w2_offset : nullptr};
+    int ha = first, ba = 0;  // load cursor
+    auto next_addr = [&]() -> const char* {
+      const int j = ba >= nbp ? 1 : 0;
+      const char* q = w2[j] + (size_t)ha * row_bytes + (size_t)(ba - j * nbp) * NV * kChunkBytes + lane * 16;
+      if (++ba == nb) { ba = 0; ha += hstride; }
+      return q;
+    };
+    int hc = first, bc = 0;  // consume cursor
+    float acc = 0.f;
+    auto consume = [&](const uint4(&buf)[NV]) {
+      const int j = bc >= nbp ? 1 : 0;
+      acc = dot_a<BF16, NV>(buf, as4 + j * F4, (bc - j * nbp) * NV, lane, acc);
+      if (++bc == nb) {
+        const float s = wave_sum(acc);
+        if (lane == 0) y[hc] = s;
+        acc = 0.f;
+        bc = 0;
+        hc += hstride;
+      }
+    };
+    stream_parts<NV>(nrows * nb, next_addr, consume);
+  } else {
+    for (int h = first; h < H; h += hstride) {
+      float acc = 0.f;
+      for (int j = 0; j < kk; ++j) {
+        if (!base[j]) continue;
+        const char* row = base[j] + p.w2_offset + (size_t)h * row_bytes + lane * 16;
+        for (int c = 0; c < nch; ++c) {
+          uint4 buf[1];
+          buf[0] = load_stream16(row + (size_t)c * kChunkBytes);
+          acc = dot_a<BF16, 1>(buf, as4 + j * F4, c, lane, acc);
+        }
+      }
+      acc = wave_sum(acc);
+      if (lane == 0) y[h] = acc;
+    }
+  }
+}
+
+// ------------------------------------------------------------------ launch ---
+
+template <typename K>
+static hipError_t allow_big_lds(K kernel) {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+}
+
+template <bool BF16>
+static hipError_t init_down() {
+  hipError_t e;
+  if ((e = allow_big_lds(ffn_down_kernel<BF16, 7>)) != hipSuccess) return e;
+  if ((e = allow_big_lds(ffn_down_kernel<BF16, 8>)) != hipSuccess) return e;
+  if ((e = allow_big_lds(ffn_down_kernel<BF16, 4>)) != hipSuccess) return e;
+  return allow_big_lds(ffn_down_kernel<BF16, 0>);
+}
+
+hipError_t ffn_kernels_init(int dtype) { return dtype == ADAPMOE_F32 ? init_down<false>() : init_down<true>(); }
+
+template <bool BF16>
+static void launch_gateup_t(const FfnArgs& p, int nch, dim3 grid, size_t lds, hipStream_t s) {
+  dim3 block(kGateUpThreads);
+  if (nch == 8) hipLaunchKernelGGL((ffn_gateup_kernel<BF16, 8>), grid, block, lds, s, p);
+  else hipLaunchKernelGGL((ffn_gateup_kernel<BF16, 0>), grid, block, lds, s, p);
+}
+
+hipError_t launch_ffn_gateup(const FfnArgs& p, int dtype, const LaunchCfg& lc, hipStream_t s) {
+  const bool bf16 = dtype != ADAPMOE_F32;
+  const size_t row_bytes = (size_t)p.H * (bf16 ? 2 : 4);
+  const int nch = (int)(row_bytes / kChunkBytes);
+  dim3 grid(lc.gateup_blocks, p.B);
+  if (bf16) launch_gateup_t<true>(p, nch, grid, row_bytes, s);
+  else launch_gateup_t<false>(p, nch, grid, row_bytes, s);
+  return hipGetLastError();
+}
+
+template <bool BF16>
+static void launch_down_t(const FfnArgs& p, int nch, dim3 grid, size_t lds, hipStream_t s) {
+  dim3 block(kDownThreads);
+  if (nch % 7 == 0) hipLaunchKernelGGL((ffn_down_kernel<BF16, 7>), grid, block, lds, s, p);
+  else if (nch % 8 == 0) hipLaunchKernelGGL((ffn_down_kernel<BF16, 8>), grid, block, lds, s, p);
+  else if (nch % 4 == 0) hipLaunchKernelGGL((ffn_down_kernel<BF16, 4>), grid, block, lds, s, p);
+  else hipLaunchKernelGGL((ffn_down_kernel<BF16, 0>), grid, block, lds, s, p);
+}
+
+hipError_t launch_ffn_down(const FfnArgs& p, int dtype, const LaunchCfg& lc, hipStream_t s) {
+  const bool bf16 = dtype != ADAPMOE_F32;
+  const int nch = (int)((size_t)p.F * (bf16 ? 2 : 4) / kChunkBytes);
+  dim3 grid(lc.down_blocks, p.B);
+  const size_t lds = (size_t)2 * p.F * sizeof(float);
+  if (bf16) launch_down_t<true>(p, nch, grid, lds, s);
+  else launch_down_t<false>(p, nch, grid, lds, s);
+  return hipGetLastError();
+}
+
+}  // namespace adapmoe

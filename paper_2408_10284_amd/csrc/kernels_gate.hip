@@ -1,0 +1,92 @@
+// Gate kernel: router product, softmax, top-2 and the adaptive activation test
+// in one wavefront per (token, router).  Sec. 2.1 Eq.1 and Sec. 4.2 Eq.3, Eq.4,
+// Eq.8 of the AdapMoE paper; router 1 is the following layer's, applied to the
+// same input to predict its experts (Sec. 4.3).
+#include "device_utils.h"
+#include "launch.h"
+
+namespace adapmoe {
+
+template <bool BF16>
+__global__ __launch_bounds__(64) void gate_kernel(GateArgs a) {
+  const int b = blockIdx.x;
+  const int r = blockIdx.y;
+  const int lane = threadIdx.x;
+  const int N = a.N, H = a.H;
+  __shared__ float zs[64];
+
+  int32_t* ids_out = a.ids[r] + 2 * b;
+  int32_t* k_out = a.k[r] + b;
+  if (a.Wg[r] == nullptr) {  // no following layer: empty prediction
+    if (lane == 0) { ids_out[0] = -1; ids_out[1] = -1; *k_out = 0; }
+    return;
+  }
+
+  constexpr int VEC = BF16 ? 8 : 4;      // elements per 16-byte vector
+  const size_t esz = BF16 ? 2 : 4;
+  const char* xrow = static_cast<const char*>(a.x) + (size_t)b * H * esz;
+  const char* W = static_cast<const char*>(a.Wg[r]);
+
+  // z_e = sum_h x_h W_g[e,h], eight experts at a time, fp32 accumulation
+  for (int e0 = 0; e0 < N; e0 += 8) {
+    float acc[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+    for (int c = lane * VEC; c < H; c += kWave * VEC) {
+      const uint4 xv = *reinterpret_cast<const uint4*>(xrow + (size_t)c * esz);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        if (e0 + e < N) {
+          const uint4 wv = *reinterpret_cast<const uint4*>(W + ((size_t)(e0 + e) * H + c) * esz);
+          if (BF16) acc[e] = dot16_bf16(wv, xv, acc[e]);
+          else acc[e] = dot16_f32(wv, __builtin_bit_cast(float4, xv), acc[e]);
+        }
+      }
+    }
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const float s = wave_sum(acc[e]);
+      if (lane == 0 && e0 + e < N) zs[e0 + e] = s;
+    }
+  }
+  __syncthreads();
+
+  // lane e holds logit e; top-1 / top-2 by wave maximum + ballot (lowest index wins ties)
+  const bool live = lane < N;
+  const float z = live ? zs[lane] : -INFINITY;
+  const float m1 = wave_max(z);
+  const uint64_t mask1 = __builtin_amdgcn_ballot_w64(live && z == m1);
+  const int e1 = mask1 ? __builtin_ctzll(mask1) : 0;
+  const float zr = (lane == e1) ? -INFINITY : z;
+  const float m2 = wave_max(zr);
+  const uint64_t mask2 = __builtin_amdgcn_ballot_w64(live && lane != e1 && zr == m2);
+  const int e2 = mask2 ? __builtin_ctzll(mask2) : (e1 == 0 ? 1 : 0);
+
+  // full softmax over the N logits, then the two selected scores renormalised
+  const float ex = live ? expf(z - m1) : 0.f;
+  const float S = wave_sum(ex);
+  const float p1 = 1.0f / S;               // exp(m1 - m1) / S
+  const float p2 = expf(m2 - m1) / S;
+  const float alpha = p1 / (p1 + p2);
+  const float v = p2 / (p1 + p2);          // weight of the second expert, the test value
+  const int k = (v <= a.tau[r]) ? 1 : 2;   // Eq.8 with tau = sqrt(T / sum diag(F))
+
+  if (lane == 0) {
+    ids_out[0] = e1;
+    ids_out[1] = e2;
+    *k_out = k;
+    if (r == 0 && a.w != nullptr) {
+      a.w[2 * b + 0] = (k == 1) ? 1.0f : alpha;   // Eq.4 / Eq.3
+      a.w[2 * b + 1] = (k == 1) ? 0.0f : v;
+    }
+  }
+}
+
+hipError_t launch_gate(const GateArgs& a, bool bf16, int routers, hipStream_t s) {
+  dim3 grid(a.B, routers), block(64);
+  if (bf16) hipLaunchKernelGGL(gate_kernel<true>, grid, block, 0, s, a);
+  else hipLaunchKernelGGL(gate_kernel<false>, grid, block, 0, s, a);
+  return hipGetLastError();
+}
+
+}  // namespace adapmoe

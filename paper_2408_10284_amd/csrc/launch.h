@@ -1,0 +1,51 @@
+// Internal interface between the host library and the kernel translation units.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace adapmoe {
+
+struct GateArgs {
+  const void* x;        // [B,H] activation type
+  const void* Wg[2];    // router of this layer, router of the following layer (or null)
+  float tau[2];
+  int32_t* ids[2];      // [B,2] each
+  int32_t* k[2];        // [B] each
+  float* w;             // [B,2], decision of router 0 only
+  int B, H, N;
+};
+
+struct FfnArgs {
+  const void* const* table;  // residency table row of the layer: N image base pointers, null = absent
+  const void* x;             // [B,H] activation type
+  const int32_t* ids;        // [B,2]
+  const float* w;            // [B,2]
+  const int32_t* k;          // [B]
+  float* a;                  // scratch [B][2][F]: w_j * silu(W1 x) * (W3 x) per activated expert
+  float* y;                  // [B,H]
+  int32_t* err;              // device flag word (bit 0: non-resident expert, bit 1: id out of range)
+  int B, H, F, N;
+  size_t w2_offset;          // byte offset of W2 inside an expert image
+};
+
+struct LaunchCfg {
+  int gateup_blocks;  // workgroups of the gate/up GEMV (256 threads each)
+  int down_blocks;    // workgroups of the down GEMV (1024 threads each)
+};
+
+hipError_t launch_gate(const GateArgs& a, bool bf16, int routers, hipStream_t s);
+hipError_t launch_ffn_gateup(const FfnArgs& p, int dtype, const LaunchCfg& lc, hipStream_t s);
+hipError_t launch_ffn_down(const FfnArgs& p, int dtype, const LaunchCfg& lc, hipStream_t s);
+hipError_t ffn_kernels_init(int dtype);
+hipError_t launch_residual_rmsnorm(float* h, const float* y, float gamma, void* x, bool bf16, int B, int H, hipStream_t s);
+
+struct PokeArgs {
+  const void** table;   // whole device table [L*N]
+  int n;
+  int index[4];
+  const void* value[4];
+};
+hipError_t launch_poke(const PokeArgs& p, hipStream_t s);
+
+}  // namespace adapmoe

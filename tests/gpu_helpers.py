@@ -1,0 +1,71 @@
+"""Shared set-up for the GPU parity tests: synthetic layer -> packed images in HBM."""
+import numpy as np
+import torch
+
+from paper_2408_10284_amd import binding as B
+from paper_2408_10284_amd import synth
+
+
+def np_dtype_bits(shape_dtype, a):
+    """float32 array -> storage array handed to the library (float32 or bf16 bit patterns)."""
+    return a.astype(np.float32) if shape_dtype == "f32" else synth.bf16_bits(a)
+
+
+def to_dev_act(shape_dtype, a):
+    """float32 activations -> device tensor in the activation storage type."""
+    if shape_dtype == "f32":
+        return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+    bits = synth.bf16_bits(a).view(np.int16)
+    return torch.from_numpy(bits).cuda().view(torch.bfloat16).reshape(a.shape)
+
+
+class GpuLayerSet:
+    """L layers of N experts: weights from synth, packed by the library, resident in HBM
+    (bound) or registered as pinned host images."""
+
+    def __init__(self, shape, seed=0, max_B=1, trace_capacity=0, resident=True, taus=None):
+        self.shape = shape
+        dt = B.F32 if shape.dtype == "f32" else B.BF16
+        self.ctx, self.cfg = B.adapmoe_create(shape.H, shape.F, shape.N, shape.L, dt, max_B=max_B,
+                                               trace_capacity=trace_capacity)
+        self.nbytes = B.adapmoe_expert_bytes(self.cfg)
+        self.routers_f32 = []
+        self.routers_dev = []
+        self.experts_f32 = []   # [L][N] tuples (W1, W3, W2) float32, for the checker
+        self.images = []        # keeps device / pinned buffers alive
+        for l in range(shape.L):
+            wg = synth.router_weights(shape, l, seed)
+            self.routers_f32.append(wg)
+            d = to_dev_act(shape.dtype, wg)
+            self.routers_dev.append(d)
+            B.adapmoe_set_router(self.ctx, l, d)
+            row = []
+            for e in range(shape.N):
+                w1, w3, w2 = synth.expert_weights(shape, l, e, seed)
+                row.append((w1, w3, w2))
+                img = np.empty(self.nbytes, dtype=np.uint8)
+                B.adapmoe_pack_expert(self.cfg, np_dtype_bits(shape.dtype, w1), np_dtype_bits(shape.dtype, w3),
+                                      np_dtype_bits(shape.dtype, w2), img)
+                if resident:
+                    t = torch.from_numpy(img).cuda()
+                    B.adapmoe_bind_expert_dev(self.ctx, l, e, t)
+                else:
+                    t = torch.from_numpy(img).pin_memory()
+                    B.adapmoe_register_expert(self.ctx, l, e, t, self.nbytes)
+                self.images.append(t)
+            self.experts_f32.append(row)
+        self.taus = list(taus) if taus is not None else [0.2] * shape.L
+        B.adapmoe_set_tau(self.ctx, self.taus)
+
+    def close(self):
+        if self.ctx is not None:
+            torch.cuda.synchronize()
+            B.adapmoe_destroy(self.ctx)
+            self.ctx = None
+
+
+def rel_err_per_token(y, ref):
+    """max_i |y_i - ref_i| / max_i |ref_i| for each row (the floating-point bar)."""
+    y = np.asarray(y, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    return np.max(np.abs(y - ref), axis=-1) / np.max(np.abs(ref), axis=-1)

@@ -1,0 +1,282 @@
+"""GPU parity: the HIP path through the C ABI against the CPU checker, element by element."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import cache as OC
+from oracle import expert as OE
+from oracle import gate as OG
+from oracle import stack as OS
+from paper_2408_10284_amd import binding as B
+from paper_2408_10284_amd import synth
+
+from gpu_helpers import GpuLayerSet, rel_err_per_token, to_dev_act
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-5, "bf16": 2e-2}
+BAND = 1e-6        # tokens whose test value lies this close to the threshold are not compared on k
+TIE_GAP = 1e-4     # tokens whose 2nd/3rd (or 1st/2nd) logits are closer than this are not compared on ids
+
+
+def run_gate(ls, layer, X, with_pred=False):
+    n = X.shape[0]
+    xd = to_dev_act(ls.shape.dtype, X)
+    ids = torch.empty((n, 2), dtype=torch.int32, device="cuda")
+    w = torch.empty((n, 2), dtype=torch.float32, device="cuda")
+    k = torch.empty(n, dtype=torch.int32, device="cuda")
+    pids = torch.empty((n, 2), dtype=torch.int32, device="cuda") if with_pred else None
+    pk = torch.empty(n, dtype=torch.int32, device="cuda") if with_pred else None
+    mb = ls.cfg.max_B
+    for s in range(0, n, mb):
+        e = min(n, s + mb)
+        B.moe_gate(ls.ctx, layer, xd[s:e], e - s, ids[s:e], w[s:e], k[s:e],
+                   pids[s:e] if with_pred else None, pk[s:e] if with_pred else None)
+    torch.cuda.synchronize()
+    out = dict(ids=ids.cpu().numpy(), w=w.cpu().numpy(), k=k.cpu().numpy(), x_dev=xd, ids_dev=ids, w_dev=w, k_dev=k)
+    if with_pred:
+        out["pids"], out["pk"] = pids.cpu().numpy(), pk.cpu().numpy()
+    return out
+
+
+def check_gate(got_ids, got_k, got_w, ref, tau, tol_w):
+    clear_ids = (ref["gap23"] > TIE_GAP) & (ref["gap12"] > TIE_GAP)
+    assert clear_ids.mean() > 0.9
+    np.testing.assert_array_equal(got_ids[clear_ids], ref["ids"][clear_ids])
+    clear_k = clear_ids & (np.abs(ref["v"] - tau) > BAND)
+    np.testing.assert_array_equal(got_k[clear_k], ref["k"][clear_k])
+    if got_w is not None:
+        np.testing.assert_allclose(got_w[clear_k], ref["w"][clear_k], atol=tol_w)
+        np.testing.assert_allclose(got_w.sum(axis=1), 1.0, atol=1e-6)
+    return clear_k
+
+
+def run_ffn(ls, layer, g):
+    n = g["ids"].shape[0]
+    y = torch.empty((n, ls.shape.H), dtype=torch.float32, device="cuda")
+    mb = ls.cfg.max_B
+    for s in range(0, n, mb):
+        e = min(n, s + mb)
+        B.moe_expert_ffn(ls.ctx, layer, g["x_dev"][s:e], e - s, g["ids_dev"][s:e], g["w_dev"][s:e], g["k_dev"][s:e], y[s:e])
+    B.adapmoe_check(ls.ctx)
+    return y.cpu().numpy()
+
+
+# ---------------------------------------------------------------- config 1 ----
+
+@pytest.fixture(scope="module")
+def tiny():
+    ls = GpuLayerSet(synth.TINY, seed=0, max_B=8)
+    yield ls
+    ls.close()
+
+
+@pytest.mark.parametrize("tau", [0.0, 0.3, 0.45, 0.5])
+def test_tiny_fp32_gate_and_ffn(tiny, tau):
+    X = synth.iid_tokens(64, synth.TINY.H, seed=1, dtype="f32")
+    B.adapmoe_set_tau(tiny.ctx, [tau])
+    g = run_gate(tiny, 0, X)
+    ref = OG.gate_batch(X, tiny.routers_f32[0], np.float32(tau))
+    ok = check_gate(g["ids"], g["k"], g["w"], ref, tau, 1e-5)
+    if tau == 0.0:
+        assert np.all(g["k"] == 2)        # threshold 0 is fixed top-2
+    if tau == 0.5:
+        assert np.all(g["k"] == 1)        # threshold 1/2 is top-1
+        assert np.all(g["w"][:, 0] == 1.0) and np.all(g["w"][:, 1] == 0.0)
+    y = run_ffn(tiny, 0, g)
+    # expert outputs are compared on the GPU's own decision so that a token in the
+    # exclusion band still checks the FFN arithmetic
+    Yref = OE.moe_block_rows(X, tiny.experts_f32[0], g["ids"], g["w"].astype(np.float64), g["k"])
+    err = rel_err_per_token(y, Yref)
+    assert err.max() <= TOL["f32"], err.max()
+    assert ok.sum() >= 60
+
+
+def test_tiny_layer_step_matches_separate_calls(tiny):
+    X = synth.iid_tokens(16, synth.TINY.H, seed=5, dtype="f32")
+    B.adapmoe_set_tau(tiny.ctx, [0.3])
+    g = run_gate(tiny, 0, X)
+    y_sep = run_ffn(tiny, 0, g)
+    y = torch.empty((16, synth.TINY.H), dtype=torch.float32, device="cuda")
+    for s in range(0, 16, 8):
+        B.moe_layer_step(tiny.ctx, 0, g["x_dev"][s:s + 8], 8, y[s:s + 8])
+    B.adapmoe_check(tiny.ctx)
+    np.testing.assert_array_equal(y.cpu().numpy(), y_sep)   # same kernels, fixed summation order
+
+
+def test_nonresident_expert_is_reported_not_faulted():
+    shape = synth.MoEShape(H=512, F=512, N=4, L=1, dtype="f32")
+    ctx, cfg = B.adapmoe_create(shape.H, shape.F, shape.N, shape.L, B.F32)
+    try:
+        x = torch.zeros((1, 512), device="cuda")
+        ids = torch.tensor([[1, 2]], dtype=torch.int32, device="cuda")
+        w = torch.tensor([[0.6, 0.4]], device="cuda")
+        k = torch.tensor([2], dtype=torch.int32, device="cuda")
+        y = torch.full((1, 512), 7.0, device="cuda")
+        B.moe_expert_ffn(ctx, 0, x, 1, ids, w, k, y)
+        with pytest.raises(B.AdapMoEError) as ei:
+            B.adapmoe_check(ctx)
+        assert ei.value.code == B.ENORES
+        assert torch.all(y == 0)
+        B.adapmoe_check(ctx)   # flag is cleared once reported
+    finally:
+        B.adapmoe_destroy(ctx)
+
+
+# ------------------------------------------------- shapes around the tiles ----
+
+@pytest.mark.parametrize("dtype,H,F,N", [
+    ("bf16", 512, 512, 2),      # one vector run per row
+    ("bf16", 1024, 1536, 8),    # 3 runs: plain-loop down kernel
+    ("bf16", 4096, 3584, 8),    # compile-time gate/up row, 7-run down parts
+    ("bf16", 1536, 4096, 16),   # 8-run parts, two passes over experts in the gate
+    ("bf16", 2048, 2048, 5),    # 4-run parts
+    ("f32", 2048, 768, 3),      # f32 with compile-time gate/up row
+    ("f32", 256, 1792, 64),     # N = 64, 7-run parts in f32
+])
+def test_shapes_gate_and_ffn(dtype, H, F, N):
+    shape = synth.MoEShape(H=H, F=F, N=N, L=2, dtype=dtype)
+    ls = GpuLayerSet(shape, seed=3, max_B=4, taus=[0.25, 0.35])
+    try:
+        n = 22   # not a multiple of max_B
+        X = synth.ar1_tokens(n, H, 0.8, seed=2, dtype=dtype)
+        g = run_gate(ls, 0, X, with_pred=True)
+        ref = OG.gate_batch(X, ls.routers_f32[0], np.float32(0.25))
+        check_gate(g["ids"], g["k"], g["w"], ref, 0.25, 1e-5)
+        refp = OG.gate_batch(X, ls.routers_f32[1], np.float32(0.35))
+        check_gate(g["pids"], g["pk"], None, refp, 0.35, 1e-5)
+        y = run_ffn(ls, 0, g)
+        Yref = OE.moe_block_rows(X, ls.experts_f32[0], g["ids"], g["w"].astype(np.float64), g["k"])
+        err = rel_err_per_token(y, Yref)
+        assert err.max() <= TOL[dtype], err.max()
+        # last layer has no successor: empty prediction
+        g1 = run_gate(ls, 1, X, with_pred=True)
+        assert np.all(g1["pk"] == 0)
+    finally:
+        ls.close()
+
+
+def test_residual_rmsnorm():
+    for dtype in ("f32", "bf16"):
+        shape = synth.MoEShape(H=1024, F=512, N=2, L=1, dtype=dtype)
+        ctx, cfg = B.adapmoe_create(shape.H, shape.F, shape.N, 1, B.F32 if dtype == "f32" else B.BF16, max_B=4)
+        try:
+            rng = np.random.default_rng(0)
+            h = (rng.standard_normal((3, 1024)) * 3).astype(np.float32)
+            y = rng.standard_normal((3, 1024)).astype(np.float32)
+            hd, yd = torch.from_numpy(h).cuda(), torch.from_numpy(y).cuda()
+            xd = torch.empty((3, 1024), dtype=torch.float32 if dtype == "f32" else torch.bfloat16, device="cuda")
+            B.moe_residual_rmsnorm(ctx, hd, yd, 0.5, xd, 3)
+            torch.cuda.synchronize()
+            h2 = h.astype(np.float64) + 0.5 * y.astype(np.float64)
+            np.testing.assert_allclose(hd.cpu().numpy(), h2, rtol=1e-6, atol=1e-6)
+            xref = np.stack([OS.rmsnorm(r) for r in h2])
+            got = xd.float().cpu().numpy()
+            np.testing.assert_allclose(got, xref, rtol=1e-5 if dtype == "f32" else 2.0 ** -8, atol=1e-6)
+            B.moe_residual_rmsnorm(ctx, hd, None, 0.0, xd, 3)   # no update: h unchanged
+            torch.cuda.synchronize()
+            np.testing.assert_allclose(hd.cpu().numpy(), h2, rtol=1e-6, atol=1e-6)
+        finally:
+            B.adapmoe_destroy(ctx)
+
+
+# -------------------------------------------------- cache, loads, prefetch ----
+
+def _replay_trace(slots, decisions):
+    """Drive the checker's cache with the GPU run's own decisions."""
+    c = OC.ExpertCache(slots)
+    L = len(slots)
+    for (tok, l, ids, k, pids, pk) in decisions:
+        c.demand(tok, l, ids, k)
+        if l + 1 < L:
+            c.prefetch(tok, l + 1, pids[:pk])
+    return c
+
+
+@pytest.mark.parametrize("slots", [[2, 3, 1, 0], [8, 8, 8, 8], [1, 1, 1, 1], [0, 2, 0, 4]])
+def test_offloaded_stack_trace_and_outputs(slots):
+    shape = synth.MoEShape(H=512, F=1024, N=8, L=4, dtype="bf16")
+    taus = [0.2, 0.3, 0.25, 0.35]
+    ls = GpuLayerSet(shape, seed=4, max_B=1, trace_capacity=1 << 16, resident=False, taus=taus)
+    try:
+        B.cache_alloc(ls.ctx, slots)
+        n_tok, gamma = 24, 0.5
+        H0 = synth.ar1_tokens(n_tok, shape.H, 0.8, seed=9, dtype="f32") * 2.0
+        decisions = []
+        max_err = 0.0
+        for t in range(n_tok):
+            B.adapmoe_set_token(ls.ctx, t)
+            h = torch.from_numpy(H0[t:t + 1].copy()).cuda()
+            x = torch.empty((1, shape.H), dtype=torch.bfloat16, device="cuda")
+            y = torch.empty((1, shape.H), dtype=torch.float32, device="cuda")
+            B.moe_residual_rmsnorm(ls.ctx, h, None, 0.0, x, 1)
+            for l in range(shape.L):
+                B.moe_layer_step(ls.ctx, l, x, 1, y)
+                ids, k, pids, pk = B.adapmoe_last_decision(ls.ctx, 1)
+                decisions.append((t, l, ids, k[0], pids, pk[0]))
+                torch.cuda.synchronize()
+                # teacher forcing per layer: the checker evaluates the block on the GPU's own input and decision
+                xin = x.float().cpu().numpy()[0].astype(np.float64)
+                ref = OG.adaptive_gate(xin, ls.routers_f32[l], np.float32(taus[l]))
+                zs = np.sort(ref["z"])[::-1]
+                if min(zs[0] - zs[1], zs[1] - zs[2]) > TIE_GAP:
+                    assert tuple(ids) == ref["ids"]
+                    if abs(ref["v"] - taus[l]) > BAND:
+                        assert k[0] == ref["k"]
+                if l + 1 < shape.L:
+                    refp = OG.adaptive_gate(xin, ls.routers_f32[l + 1], np.float32(taus[l + 1]))
+                    zs = np.sort(refp["z"])[::-1]
+                    if min(zs[0] - zs[1], zs[1] - zs[2]) > TIE_GAP and abs(refp["v"] - taus[l + 1]) > BAND:
+                        assert list(pids[:pk[0]]) == list(refp["ids"][:refp["k"]])
+                w = (1.0, 0.0) if k[0] == 1 else (ref["alpha"], ref["v"])
+                yref = OE.moe_block(xin, ls.experts_f32[l], ids, w, k[0])
+                max_err = max(max_err, float(rel_err_per_token(y.cpu().numpy()[0], yref)))
+                B.moe_residual_rmsnorm(ls.ctx, h, y, gamma, x, 1)
+        B.adapmoe_check(ls.ctx)
+        assert max_err <= TOL["bf16"], max_err
+        sim = _replay_trace(slots, decisions)
+        got = [(t, l, kind, e, v) for (t, l, kind, e, v, _slot) in B.adapmoe_trace_read(ls.ctx)]
+        assert got == [tuple(ev) for ev in sim.events]
+        s = OC.summarise(sim.events)
+        c = B.adapmoe_counters(ls.ctx)
+        assert c["misses"] + c["bypasses"] == s["on_demand_loads"]
+        assert c["prefetch_loads"] == s["prefetch_loads"]
+        assert c["hits_after_prefetch"] == s["prefetch_useful"]
+        assert c["h2d_bytes"] == (s["on_demand_loads"] + s["prefetch_loads"]) * ls.nbytes
+        # residency reported by the library equals the checker's sets
+        for l in range(shape.L):
+            res = [e for e in range(shape.N) if B.cache_lookup(ls.ctx, l, [e])[0] >= 0]
+            assert sorted(res) == sorted(sim.resident(l))
+    finally:
+        ls.close()
+
+
+# ------------------------------------------ config 2 at full size (bench shape) ----
+
+def test_mixtral_layer_full_size():
+    """One Mixtral-8x7B-shaped layer, bf16, 256 AR(1) tokens, threshold 0.2, launched
+    the way the benchmark launches it (moe_layer_step, batch 1)."""
+    shape = synth.MIXTRAL_LAYER
+    ls = GpuLayerSet(shape, seed=0, max_B=1, taus=[0.2])
+    try:
+        X = synth.ar1_tokens(256, shape.H, 0.8, seed=1, dtype="bf16")
+        g = run_gate(ls, 0, X)
+        ref = OG.gate_batch(X, ls.routers_f32[0], np.float32(0.2))
+        clear = check_gate(g["ids"], g["k"], g["w"], ref, 0.2, 1e-5)
+        print(f"single-expert ratio {np.mean(ref['k'] == 1):.3f}, compared on k: {clear.sum()}/256, "
+              f"min gap23 {ref['gap23'].min():.2e}, min |v-tau| {np.abs(ref['v'] - 0.2).min():.2e}")
+        assert 0.05 < np.mean(ref["k"] == 1) < 0.3
+        y = torch.empty((256, shape.H), dtype=torch.float32, device="cuda")
+        for t in range(256):
+            B.moe_layer_step(ls.ctx, 0, g["x_dev"][t:t + 1], 1, y[t:t + 1])
+        B.adapmoe_check(ls.ctx)
+        yh = y.cpu().numpy()
+        sample = np.arange(0, 256, 8)
+        both = np.concatenate([sample, np.nonzero(ref["k"] == 1)[0][:4]])   # make sure k == 1 tokens are in
+        Yref = OE.moe_block_rows(X[both], ls.experts_f32[0], g["ids"][both], g["w"][both].astype(np.float64), g["k"][both])
+        err = rel_err_per_token(yh[both], Yref)
+        print(f"max rel err {err.max():.3e}")
+        assert err.max() <= TOL["bf16"]
+        assert np.all(np.isfinite(yh)) and np.all(np.abs(yh).max(axis=1) > 0)
+    finally:
+        ls.close()

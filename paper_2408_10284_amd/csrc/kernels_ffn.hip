@@ -59,12 +59,13 @@ __device__ __forceinline__ void load_vecs(const char* p, uint4 (&buf)[NV]) {
   for (int c = 0; c < NV; ++c) buf[c] = load_stream16(p + (size_t)c * kChunkBytes);
 }
 
-template <int NV, class AddrFn, class ConsumeFn>
-__device__ __forceinline__ void stream_parts(int Q, AddrFn next_addr, ConsumeFn consume) {
-  if (Q <= 0) return;
+template <int NV, class AddrFn, class ConsumeFn, class MidFn>
+__device__ __forceinline__ void stream_parts(int Q, AddrFn next_addr, ConsumeFn consume, MidFn after_first_loads) {
   uint4 A[NV], B[NV];
-  load_vecs<NV>(next_addr(), A);
+  if (Q > 0) load_vecs<NV>(next_addr(), A);
   if (Q > 1) load_vecs<NV>(next_addr(), B);
+  after_first_loads();  // e.g. staging the activation vector in LDS while the first weights travel
+  if (Q <= 0) return;
   int q = 0;
   for (; q + 3 < Q; q += 2) {
     consume(A);
@@ -125,8 +126,10 @@ __global__ __launch_bounds__(kGateUpThreads) void ffn_gateup_kernel(FfnArgs p) {
   const int F = p.F;
 
   const uint4* xg = reinterpret_cast<const uint4*>(static_cast<const char*>(p.x) + (size_t)b * row_bytes);
-  for (int i = tid; i < nch * kWave; i += kGateUpThreads) xs[i] = xg[i];
-  __syncthreads();
+  auto stage_x = [&]() {
+    for (int i = tid; i < nch * kWave; i += kGateUpThreads) xs[i] = xg[i];
+    __syncthreads();
+  };
 
   bool all_resident = true;
   for (int j = 0; j < kk; ++j) all_resident &= base[j] != nullptr;
@@ -154,8 +157,9 @@ __global__ __launch_bounds__(kGateUpThreads) void ffn_gateup_kernel(FfnArgs p) {
       }
       half_c ^= 1;
     };
-    stream_parts<(NCH > 0 ? NCH : 1)>(2 * nrows, next_addr, consume);
+    stream_parts<(NCH > 0 ? NCH : 1)>(2 * nrows, next_addr, consume, stage_x);
   } else {
+    stage_x();
     for (int r = first; r < total; r += stride) {
       const int j = r >= F ? 1 : 0;
       float val = 0.f;
@@ -216,12 +220,14 @@ __global__ __launch_bounds__(kDownThreads) void ffn_down_kernel(FfnArgs p) {
   for (int j = 0; j < kk; ++j) all_resident &= base[j] != nullptr;
 
   const float4* ag = reinterpret_cast<const float4*>(p.a + (size_t)b * 2 * p.F);
-  for (int i = tid; i < kk * F4; i += kDownThreads) {
-    const int j = i >= F4 ? 1 : 0;
-    const int f4 = i - j * F4;
-    as4[j * F4 + (BF16 ? lds_pos_bf16(f4) : f4)] = ag[i];
-  }
-  __syncthreads();
+  auto stage_a = [&]() {
+    for (int i = tid; i < kk * F4; i += kDownThreads) {
+      const int j = i >= F4 ? 1 : 0;
+      const int f4 = i - j * F4;
+      as4[j * F4 + (BF16 ? lds_pos_bf16(f4) : f4)] = ag[i];
+    }
+    __syncthreads();
+  };
 
   const int first = blockIdx.x * kWaves + wave;
   const int hstride = gridDim.x * kWaves;
@@ -252,8 +258,9 @@ __global__ __launch_bounds__(kDownThreads) void ffn_down_kernel(FfnArgs p) {
         hc += hstride;
       }
     };
-    stream_parts<NV>(nrows * nb, next_addr, consume);
+    stream_parts<NV>(nrows * nb, next_addr, consume, stage_a);
   } else {
+    stage_a();
     for (int h = first; h < H; h += hstride) {
       float acc = 0.f;
       for (int j = 0; j < kk; ++j) {

@@ -1,5 +1,6 @@
 // Gate kernel: router product, softmax, top-2 and the adaptive activation test
-// in one wavefront per (token, router).  Sec. 2.1 Eq.1 and Sec. 4.2 Eq.3, Eq.4,
+// in one workgroup per (token, router); the decision itself is taken by one
+// wavefront with DPP reductions and ballots.  Sec. 2.1 Eq.1 and Sec. 4.2 Eq.3, Eq.4,
 // Eq.8 of the AdapMoE paper; router 1 is the following layer's, applied to the
 // same input to predict its experts (Sec. 4.3).
 #include "device_utils.h"
@@ -7,18 +8,26 @@
 
 namespace adapmoe {
 
+constexpr int kGateWaves = 8;
+constexpr int kGateThreads = kGateWaves * kWave;
+
+// One workgroup per (token, router).  The H axis is cut into 1 KiB runs dealt
+// round-robin to the wavefronts, so all loads of a router matrix are in flight
+// at once (the kernel is latency-bound: 2*N*H bytes per token).  Each wavefront
+// reduces its partial logits with DPP, wavefront 0 adds the partials in a fixed
+// order and takes the decision.
 template <bool BF16>
-__global__ __launch_bounds__(64) void gate_kernel(GateArgs a) {
+__global__ __launch_bounds__(kGateThreads) void gate_kernel(GateArgs a) {
   const int b = blockIdx.x;
   const int r = blockIdx.y;
-  const int lane = threadIdx.x;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int N = a.N, H = a.H;
-  __shared__ float zs[64];
+  __shared__ float part[kGateWaves][64];
 
   int32_t* ids_out = a.ids[r] + 2 * b;
   int32_t* k_out = a.k[r] + b;
   if (a.Wg[r] == nullptr) {  // no following layer: empty prediction
-    if (lane == 0) { ids_out[0] = -1; ids_out[1] = -1; *k_out = 0; }
+    if (threadIdx.x == 0) { ids_out[0] = -1; ids_out[1] = -1; *k_out = 0; }
     return;
   }
 
@@ -27,33 +36,41 @@ __global__ __launch_bounds__(64) void gate_kernel(GateArgs a) {
   const char* xrow = static_cast<const char*>(a.x) + (size_t)b * H * esz;
   const char* W = static_cast<const char*>(a.Wg[r]);
 
-  // z_e = sum_h x_h W_g[e,h], eight experts at a time, fp32 accumulation
+  // partial z_e = sum over this wavefront's runs of x_h W_g[e,h], eight experts at a time
   for (int e0 = 0; e0 < N; e0 += 8) {
     float acc[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[e] = 0.f;
-    for (int c = lane * VEC; c < H; c += kWave * VEC) {
+    for (int c = (wave * kWave + lane) * VEC; c < H; c += kGateThreads * VEC) {
       const uint4 xv = *reinterpret_cast<const uint4*>(xrow + (size_t)c * esz);
+      uint4 wv[8];
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
+      for (int e = 0; e < 8; ++e)
+        if (e0 + e < N) wv[e] = *reinterpret_cast<const uint4*>(W + ((size_t)(e0 + e) * H + c) * esz);
+#pragma unroll
+      for (int e = 0; e < 8; ++e)
         if (e0 + e < N) {
-          const uint4 wv = *reinterpret_cast<const uint4*>(W + ((size_t)(e0 + e) * H + c) * esz);
-          if (BF16) acc[e] = dot16_bf16(wv, xv, acc[e]);
-          else acc[e] = dot16_f32(wv, __builtin_bit_cast(float4, xv), acc[e]);
+          if (BF16) acc[e] = dot16_bf16(wv[e], xv, acc[e]);
+          else acc[e] = dot16_f32(wv[e], __builtin_bit_cast(float4, xv), acc[e]);
         }
-      }
     }
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
       const float s = wave_sum(acc[e]);
-      if (lane == 0 && e0 + e < N) zs[e0 + e] = s;
+      if (lane == 0 && e0 + e < N) part[wave][e0 + e] = s;
     }
   }
   __syncthreads();
+  if (wave != 0) return;
 
   // lane e holds logit e; top-1 / top-2 by wave maximum + ballot (lowest index wins ties)
   const bool live = lane < N;
-  const float z = live ? zs[lane] : -INFINITY;
+  float z = -INFINITY;
+  if (live) {
+    z = 0.f;
+#pragma unroll
+    for (int w = 0; w < kGateWaves; ++w) z += part[w][lane];
+  }
   const float m1 = wave_max(z);
   const uint64_t mask1 = __builtin_amdgcn_ballot_w64(live && z == m1);
   const int e1 = mask1 ? __builtin_ctzll(mask1) : 0;
@@ -83,7 +100,7 @@ __global__ __launch_bounds__(64) void gate_kernel(GateArgs a) {
 }
 
 hipError_t launch_gate(const GateArgs& a, bool bf16, int routers, hipStream_t s) {
-  dim3 grid(a.B, routers), block(64);
+  dim3 grid(a.B, routers), block(kGateThreads);
   if (bf16) hipLaunchKernelGGL(gate_kernel<true>, grid, block, 0, s, a);
   else hipLaunchKernelGGL(gate_kernel<false>, grid, block, 0, s, a);
   return hipGetLastError();

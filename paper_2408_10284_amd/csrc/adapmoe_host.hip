@@ -66,7 +66,8 @@ struct adapmoe_ctx {
   int32_t* d_err = nullptr;
   int32_t* d_dec = nullptr;             // ids[2B] k[B] pred_ids[2B] pred_k[B]
   float* d_w = nullptr;                 // [B,2]
-  float* d_a = nullptr;                 // [B][2][F]
+  float* d_a = nullptr;                 // [B][2][a_stride]
+  ResolvedExperts* d_res = nullptr;     // [B] resolved experts of the last gate of moe_layer_step
   int32_t* h_dec = nullptr;             // pinned mirror of d_dec
   hipStream_t copy_stream = nullptr;
   LaunchCfg lc{};
@@ -75,7 +76,7 @@ struct adapmoe_ctx {
   std::vector<Slot> slots;
   std::vector<int> free_slots;
   std::vector<LayerCache> layers;
-  std::vector<std::pair<int, const void*>> pending_pokes;  // (table index, value), applied before the next FFN
+  std::vector<std::pair<const void**, const void*>> pending_pokes;  // (device address, value), applied before the next FFN
 
   std::deque<adapmoe_event> trace;
   adapmoe_counters_t ctr{};
@@ -103,15 +104,31 @@ int fail(adapmoe_ctx* c, int code, const std::string& msg) {
 
 bool cfg_ok(const adapmoe_config* c) {
   if (!c) return false;
-  if (c->dtype != ADAPMOE_F32 && c->dtype != ADAPMOE_BF16) return false;
-  const int q = c->dtype == ADAPMOE_F32 ? 256 : 512;
+  if (c->dtype != ADAPMOE_F32 && c->dtype != ADAPMOE_BF16 && c->dtype != ADAPMOE_INT4G64) return false;
+  const int q = c->dtype == ADAPMOE_BF16 ? 512 : 256;
   if (c->H <= 0 || c->F <= 0 || c->H % q || c->F % q) return false;
   if (c->N < 2 || c->N > 64 || c->L < 1) return false;
-  if ((size_t)2 * c->F * sizeof(float) > 160 * 1024) return false;  // a_j of two experts must fit in LDS
+  if (c->dtype == ADAPMOE_INT4G64) {
+    // a lane owns one group of 64 per block of 4096: at most 2 blocks of x and 4 blocks of a in registers
+    if (c->H > 8192 || c->F > 16384) return false;
+  } else if ((size_t)2 * c->F * sizeof(float) > 160 * 1024) {
+    return false;  // a_j of two experts must fit in LDS
+  }
   return true;
 }
 
+// bytes per element of activations and of fp32/bf16 weights
 size_t elem_size(int dtype) { return dtype == ADAPMOE_F32 ? 4 : 2; }
+
+// int4 image: bytes of one row of n weights (codes + fp16 scale/zero per 64)
+size_t i4_row_bytes(size_t n) { return n / 2 + n / 16; }
+
+// floats per (token, expert slot) of the a_j scratch
+size_t a_stride_for(const adapmoe_config& c) {
+  if (c.dtype != ADAPMOE_INT4G64) return (size_t)c.F;
+  const size_t blocks = ((size_t)c.F / 64 + 63) / 64;
+  return std::max((size_t)c.F, blocks * 2048);  // int4: blocks x 8 vectors x 64 lanes x 8 bf16
+}
 
 int env_int(const char* name, int dflt) {
   const char* v = getenv(name);
@@ -150,16 +167,20 @@ int start_copy(adapmoe_ctx* c, int layer, int expert, int slot) {
 }
 
 void poke_later(adapmoe_ctx* c, int layer, int expert, const void* value) {
-  c->pending_pokes.emplace_back(layer * c->cfg.N + expert, value);
+  c->pending_pokes.emplace_back(c->d_table + (size_t)layer * c->cfg.N + expert, value);
+}
+
+// resolved pointer of (token b, rank j) for the FFN launch of the running step
+void poke_resolved(adapmoe_ctx* c, int b, int j, const void* value) {
+  c->pending_pokes.emplace_back(&c->d_res[b].base[j], value);
 }
 
 int flush_pokes(adapmoe_ctx* c, hipStream_t s) {
   size_t i = 0;
   while (i < c->pending_pokes.size()) {
     PokeArgs p{};
-    p.table = c->d_table;
-    for (p.n = 0; p.n < 4 && i < c->pending_pokes.size(); ++p.n, ++i) {
-      p.index[p.n] = c->pending_pokes[i].first;
+    for (p.n = 0; p.n < 8 && i < c->pending_pokes.size(); ++p.n, ++i) {
+      p.addr[p.n] = c->pending_pokes[i].first;
       p.value[p.n] = c->pending_pokes[i].second;
     }
     HIPCHK(c, launch_poke(p, s));
@@ -237,14 +258,16 @@ struct ScopedTimer {
 };
 
 FfnArgs ffn_args(adapmoe_ctx* c, int layer, const void* x, int B, const int32_t* ids, const float* w, const int32_t* k,
-                 float* y) {
+                 float* y, const ResolvedExperts* res) {
   FfnArgs p{};
   p.table = c->d_table + (size_t)layer * c->cfg.N;
+  p.res = res;
   p.x = x;
   p.ids = ids;
   p.w = w;
   p.k = k;
   p.a = c->d_a;
+  p.a_stride = a_stride_for(c->cfg);
   p.y = y;
   p.err = c->d_err;
   p.B = B;
@@ -256,22 +279,23 @@ FfnArgs ffn_args(adapmoe_ctx* c, int layer, const void* x, int B, const int32_t*
 }
 
 int launch_ffn(adapmoe_ctx* c, int layer, const void* x, int B, const int32_t* ids, const float* w, const int32_t* k,
-               float* y, hipStream_t s) {
-  FfnArgs p = ffn_args(c, layer, x, B, ids, w, k, y);
+               float* y, hipStream_t s, const ResolvedExperts* res = nullptr) {
+  FfnArgs p = ffn_args(c, layer, x, B, ids, w, k, y, res);
+  const bool int4 = c->cfg.dtype == ADAPMOE_INT4G64;
   {
     ScopedTimer t(c, 0, s);
-    HIPCHK(c, launch_ffn_gateup(p, c->cfg.dtype, c->lc, s));
+    HIPCHK(c, int4 ? launch_ffn_gateup_int4(p, c->lc, s) : launch_ffn_gateup(p, c->cfg.dtype, c->lc, s));
   }
   {
     ScopedTimer t(c, 1, s);
-    HIPCHK(c, launch_ffn_down(p, c->cfg.dtype, c->lc, s));
+    HIPCHK(c, int4 ? launch_ffn_down_int4(p, c->lc, s) : launch_ffn_down(p, c->cfg.dtype, c->lc, s));
   }
   c->ctr.ffn_launches++;
   return ADAPMOE_OK;
 }
 
 int launch_gate_both(adapmoe_ctx* c, int layer, const void* x, int B, int32_t* ids, float* w, int32_t* k, int32_t* pids,
-                     int32_t* pk, hipStream_t s) {
+                     int32_t* pk, hipStream_t s, ResolvedExperts* res = nullptr) {
   if (!c->router[layer]) return fail(c, ADAPMOE_ESTATE, "router of this layer not set");
   GateArgs g{};
   g.x = x;
@@ -283,6 +307,8 @@ int launch_gate_both(adapmoe_ctx* c, int layer, const void* x, int B, int32_t* i
   g.ids[0] = ids;
   g.k[0] = k;
   g.w = w;
+  g.res = res;
+  g.table = c->d_table + (size_t)layer * c->cfg.N;
   int routers = 1;
   if (pids && pk) {
     routers = 2;
@@ -322,12 +348,13 @@ const char* adapmoe_last_error(const adapmoe_ctx* ctx) { return ctx ? ctx->last_
 
 int adapmoe_expert_bytes(const adapmoe_config* cfg, size_t* bytes_out) {
   if (!cfg_ok(cfg) || !bytes_out) return ADAPMOE_EINVAL;
-  *bytes_out = (size_t)3 * cfg->H * cfg->F * elem_size(cfg->dtype);
+  if (cfg->dtype == ADAPMOE_INT4G64) *bytes_out = (size_t)2 * cfg->F * i4_row_bytes(cfg->H) + (size_t)cfg->H * i4_row_bytes(cfg->F);
+  else *bytes_out = (size_t)3 * cfg->H * cfg->F * elem_size(cfg->dtype);
   return ADAPMOE_OK;
 }
 
 int adapmoe_pack_expert(const adapmoe_config* cfg, const void* W1, const void* W3, const void* W2, void* out) {
-  if (!cfg_ok(cfg) || !W1 || !W3 || !W2 || !out) return ADAPMOE_EINVAL;
+  if (!cfg_ok(cfg) || !W1 || !W3 || !W2 || !out || cfg->dtype == ADAPMOE_INT4G64) return ADAPMOE_EINVAL;
   const size_t row = (size_t)cfg->H * elem_size(cfg->dtype);
   char* o = static_cast<char*>(out);
   for (int f = 0; f < cfg->F; ++f) {
@@ -338,9 +365,50 @@ int adapmoe_pack_expert(const adapmoe_config* cfg, const void* W1, const void* W
   return ADAPMOE_OK;
 }
 
-int adapmoe_pack_expert_int4(const adapmoe_config*, const uint8_t*, const uint16_t*, const uint16_t*, const uint8_t*,
-                             const uint16_t*, const uint16_t*, const uint8_t*, const uint16_t*, const uint16_t*, void*) {
-  return ADAPMOE_ESTATE;
+// One row of n 4-bit codes -> the streaming row format: blocks of up to 64
+// groups, each block stored as [first 16 bytes of every group][second 16 bytes
+// of every group]; inside a dword, nibble s (s < 4) is element 2s and nibble
+// s+4 is element 2s+1 of the dword's 8 elements; then (scale, zero) per group.
+static void pack_row_int4(const uint8_t* q, const uint16_t* sc, const uint16_t* zr, size_t n, char* out) {
+  const size_t G = n / 64;
+  for (size_t blk = 0; blk * 64 < G; ++blk) {
+    const size_t nb = std::min<size_t>(64, G - blk * 64);
+    char* cb = out + blk * 2048;
+    for (size_t l = 0; l < nb; ++l) {
+      const uint8_t* gq = q + (blk * 64 + l) * 64;
+      for (int half = 0; half < 2; ++half) {
+        uint32_t* dst = reinterpret_cast<uint32_t*>(cb + half * nb * 16 + l * 16);
+        for (int d = 0; d < 4; ++d) {
+          const uint8_t* e = gq + half * 32 + d * 8;
+          uint32_t w = 0;
+          for (int sft = 0; sft < 4; ++sft) {
+            w |= (uint32_t)(e[2 * sft] & 15) << (4 * sft);
+            w |= (uint32_t)(e[2 * sft + 1] & 15) << (4 * sft + 16);
+          }
+          dst[d] = w;
+        }
+      }
+    }
+  }
+  uint32_t* sz = reinterpret_cast<uint32_t*>(out + n / 2);
+  for (size_t g = 0; g < G; ++g) sz[g] = (uint32_t)sc[g] | ((uint32_t)zr[g] << 16);
+}
+
+int adapmoe_pack_expert_int4(const adapmoe_config* cfg, const uint8_t* q1, const uint16_t* s1, const uint16_t* z1,
+                             const uint8_t* q3, const uint16_t* s3, const uint16_t* z3, const uint8_t* q2,
+                             const uint16_t* s2, const uint16_t* z2, void* out) {
+  if (!cfg_ok(cfg) || cfg->dtype != ADAPMOE_INT4G64 || !q1 || !s1 || !z1 || !q3 || !s3 || !z3 || !q2 || !s2 || !z2 || !out)
+    return ADAPMOE_EINVAL;
+  const size_t H = cfg->H, F = cfg->F;
+  const size_t rbH = i4_row_bytes(H), rbF = i4_row_bytes(F);
+  char* o = static_cast<char*>(out);
+  for (size_t f = 0; f < F; ++f) {
+    pack_row_int4(q1 + f * H, s1 + f * (H / 64), z1 + f * (H / 64), H, o + (2 * f) * rbH);
+    pack_row_int4(q3 + f * H, s3 + f * (H / 64), z3 + f * (H / 64), H, o + (2 * f + 1) * rbH);
+  }
+  char* o2 = o + 2 * F * rbH;
+  for (size_t h = 0; h < H; ++h) pack_row_int4(q2 + h * F, s2 + h * (F / 64), z2 + h * (F / 64), F, o2 + h * rbF);
+  return ADAPMOE_OK;
 }
 
 int adapmoe_create(const adapmoe_config* cfg, adapmoe_ctx** out) {
@@ -372,7 +440,9 @@ int adapmoe_create(const adapmoe_config* cfg, adapmoe_ctx** out) {
   ok = ok && hipMemset(c->d_err, 0, sizeof(int32_t)) == hipSuccess;
   ok = ok && hipMalloc(&c->d_dec, (size_t)6 * B * sizeof(int32_t)) == hipSuccess;
   ok = ok && hipMalloc(&c->d_w, (size_t)2 * B * sizeof(float)) == hipSuccess;
-  ok = ok && hipMalloc(&c->d_a, (size_t)2 * B * cfg->F * sizeof(float)) == hipSuccess;
+  ok = ok && hipMalloc(&c->d_a, (size_t)2 * B * a_stride_for(*cfg) * sizeof(float)) == hipSuccess;
+  ok = ok && hipMalloc(&c->d_res, (size_t)B * sizeof(ResolvedExperts)) == hipSuccess;
+  ok = ok && hipMemset(c->d_res, 0, (size_t)B * sizeof(ResolvedExperts)) == hipSuccess;
   ok = ok && hipHostMalloc(reinterpret_cast<void**>(&c->h_dec), (size_t)6 * B * sizeof(int32_t), hipHostMallocDefault) == hipSuccess;
   ok = ok && hipStreamCreateWithFlags(&c->copy_stream, hipStreamNonBlocking) == hipSuccess;
   ok = ok && ffn_kernels_init(cfg->dtype) == hipSuccess;
@@ -404,6 +474,7 @@ int adapmoe_destroy(adapmoe_ctx* c) {
   if (c->d_dec) hipFree(c->d_dec);
   if (c->d_w) hipFree(c->d_w);
   if (c->d_a) hipFree(c->d_a);
+  if (c->d_res) hipFree(c->d_res);
   if (c->h_dec) hipHostFree(c->h_dec);
   delete c;
   return ADAPMOE_OK;
@@ -594,14 +665,15 @@ int moe_layer_step(adapmoe_ctx* c, int layer, const void* x, int B, float* y, vo
   const bool next_needs_host = layer + 1 < c->cfg.L && !layer_fully_bound(c, layer + 1) && c->cache_ready;
   const bool host_path = !layer_fully_bound(c, layer) || next_needs_host;
 
-  int rc = launch_gate_both(c, layer, x, B, d_ids, c->d_w, d_k, host_path ? d_pids : nullptr, host_path ? d_pk : nullptr, s);
+  int rc = launch_gate_both(c, layer, x, B, d_ids, c->d_w, d_k, host_path ? d_pids : nullptr, host_path ? d_pk : nullptr, s,
+                            c->d_res);
   if (rc) return rc;
   c->ctr.tokens_gated += B;
 
   if (!host_path) {  // every expert of the layer lives in HBM: residency is a device-side table lookup
     rc = flush_pokes(c, s);
     if (rc) return rc;
-    return launch_ffn(c, layer, x, B, d_ids, c->d_w, d_k, y, s);
+    return launch_ffn(c, layer, x, B, d_ids, c->d_w, d_k, y, s, c->d_res);
   }
   if (!c->cache_ready && !layer_fully_bound(c, layer)) return fail(c, ADAPMOE_ESTATE, "moe_layer_step: cache not allocated");
 
@@ -622,7 +694,11 @@ int moe_layer_step(adapmoe_ctx* c, int layer, const void* x, int B, float* y, vo
     for (int j = 0; j < kk[b] && j < 2; ++j) {
       const int e = ids[2 * b + j];
       if (e < 0 || e >= N) return fail(c, ADAPMOE_EINVAL, "moe_layer_step: gate produced an id out of range");
-      if (c->bound[(size_t)layer * N + e]) { record(c, layer, ADAPMOE_EV_HIT, e, -1, -2); continue; }
+      if (c->bound[(size_t)layer * N + e]) {
+        record(c, layer, ADAPMOE_EV_HIT, e, -1, -2);
+        poke_resolved(c, b, j, c->bound[(size_t)layer * N + e]);
+        continue;
+      }
       bool is_transient = false;
       for (auto& t : transient) is_transient |= (t.first == e);
       const int pos = lc.find(e);
@@ -631,12 +707,18 @@ int moe_layer_step(adapmoe_ctx* c, int layer, const void* x, int B, float* y, vo
         record(c, layer, en.by_prefetch ? ADAPMOE_EV_HIT_PF : ADAPMOE_EV_HIT, e, -1, en.slot);
         en.by_prefetch = false;
         used_slots.push_back(en.slot);
+        poke_resolved(c, b, j, c->slots[en.slot].dev);
         lc.touch(pos);
         demanded.push_back(e);
         continue;
       }
       if (is_transient) {  // evicted or bypassed earlier in this same step, image still in its slot
-        if (lc.cap == 0) { record(c, layer, ADAPMOE_EV_BYPASS, e, -1, -1); continue; }
+        if (lc.cap == 0) {
+          for (auto& t : transient)
+            if (t.first == e) poke_resolved(c, b, j, c->slots[t.second].dev);
+          record(c, layer, ADAPMOE_EV_BYPASS, e, -1, -1);
+          continue;
+        }
         // falls through to a regular miss below: logically it is gone
       }
       int victim = -1, slot = -1;
@@ -649,6 +731,7 @@ int moe_layer_step(adapmoe_ctx* c, int layer, const void* x, int B, float* y, vo
         poke_later(c, layer, e, c->slots[slot].dev);
         transient.emplace_back(e, slot);
         used_slots.push_back(slot);
+        poke_resolved(c, b, j, c->slots[slot].dev);
         record(c, layer, ADAPMOE_EV_BYPASS, e, -1, slot);
         continue;
       }
@@ -681,6 +764,7 @@ int moe_layer_step(adapmoe_ctx* c, int layer, const void* x, int B, float* y, vo
       lc.order.push_back(Entry{e, slot, false});
       poke_later(c, layer, e, c->slots[slot].dev);
       used_slots.push_back(slot);
+      poke_resolved(c, b, j, c->slots[slot].dev);
       demanded.push_back(e);
       record(c, layer, ADAPMOE_EV_MISS, e, victim, slot);
     }
@@ -705,7 +789,7 @@ int moe_layer_step(adapmoe_ctx* c, int layer, const void* x, int B, float* y, vo
       sl.copy_pending = false;
     }
   }
-  rc = launch_ffn(c, layer, x, B, d_ids, c->d_w, d_k, y, s);
+  rc = launch_ffn(c, layer, x, B, d_ids, c->d_w, d_k, y, s, c->d_res);
   if (rc) return rc;
   for (int slot : used_slots) {
     Slot& sl = c->slots[slot];

@@ -75,6 +75,16 @@ __device__ __forceinline__ uint4 load_stream16(const void* p) {
   return make_uint4(v.x, v.y, v.z, v.w);
 }
 
+__device__ __forceinline__ uint32_t load_stream4(const void* p) {
+  typedef const __attribute__((address_space(1))) uint32_t* gptr_t;
+  return __builtin_nontemporal_load((gptr_t)(uintptr_t)p);
+}
+
+// fp16 bit pattern -> float
+__device__ __forceinline__ float half_bits_to_float(uint32_t h) {
+  return (float)__builtin_bit_cast(_Float16, (uint16_t)h);
+}
+
 // Elements of type T in a 16-byte vector and the dot product of a weight
 // vector with an activation vector, for the storage types of the library.
 // Weights float32 x activations float32:

@@ -12,74 +12,13 @@
 // No atomics: results are bit-reproducible.
 #include "device_utils.h"
 #include "launch.h"
+#include "stream_parts.h"
 #include "../../include/adapmoe.h"
 
 namespace adapmoe {
 
 constexpr int kGateUpThreads = 256;
 constexpr int kDownThreads = 1024;
-constexpr int kChunkBytes = kWave * 16;  // bytes one wavefront reads per load instruction
-
-__device__ __forceinline__ float silu_f32(float g) { return g / (1.0f + expf(-g)); }
-
-// Resolves the image base pointers of the (up to two) activated experts of token b.
-__device__ __forceinline__ int resolve_experts(const FfnArgs& p, int b, const char* base[2], float w[2]) {
-  int kk = p.k[b];
-  kk = kk < 1 ? 1 : (kk > 2 ? 2 : kk);
-  for (int j = 0; j < 2; ++j) {
-    base[j] = nullptr;
-    w[j] = 0.f;
-    if (j < kk) {
-      const int e = p.ids[2 * b + j];
-      if (e < 0 || e >= p.N) {
-        if (threadIdx.x == 0) atomicOr(p.err, 2);
-      } else {
-        base[j] = static_cast<const char*>(p.table[e]);
-        w[j] = p.w[2 * b + j];
-        if (base[j] == nullptr && threadIdx.x == 0) atomicOr(p.err, 1);
-      }
-    }
-  }
-  return kk;
-}
-
-// ----------------------------------------------------------- part streaming --
-
-// Both GEMVs read, per wavefront, a known sequence of "parts": NV consecutive
-// 1 KiB runs of a matrix row (16 bytes per lane each).  Two register buffers
-// alternate: while part q is consumed, part q+1 is already in flight and part
-// q+2 is requested as soon as q's buffer is free, so a wavefront keeps NV to
-// 2*NV loads outstanding.  The steady loop has no conditional loads (those
-// would make the compiler copy the buffers); the tail is peeled.
-// next_addr() returns the lane's address of the next part in sequence,
-// consume(buf) uses the next part in sequence; both keep their own cursor.
-template <int NV>
-__device__ __forceinline__ void load_vecs(const char* p, uint4 (&buf)[NV]) {
-#pragma unroll
-  for (int c = 0; c < NV; ++c) buf[c] = load_stream16(p + (size_t)c * kChunkBytes);
-}
-
-template <int NV, class AddrFn, class ConsumeFn, class MidFn>
-__device__ __forceinline__ void stream_parts(int Q, AddrFn next_addr, ConsumeFn consume, MidFn after_first_loads) {
-  uint4 A[NV], B[NV];
-  if (Q > 0) load_vecs<NV>(next_addr(), A);
-  if (Q > 1) load_vecs<NV>(next_addr(), B);
-  after_first_loads();  // e.g. staging the activation vector in LDS while the first weights travel
-  if (Q <= 0) return;
-  int q = 0;
-  for (; q + 3 < Q; q += 2) {
-    consume(A);
-    load_vecs<NV>(next_addr(), A);
-    consume(B);
-    load_vecs<NV>(next_addr(), B);
-  }
-  // 1, 2 or 3 parts left; A holds part q, B part q+1
-  consume(A);
-  if (q + 2 < Q) load_vecs<NV>(next_addr(), A);
-  if (q + 1 < Q) consume(B);
-  if (q + 2 < Q) consume(A);
-}
-
 // ------------------------------------------------------------------ gate/up --
 
 template <bool BF16, int NV>
@@ -122,7 +61,7 @@ __global__ __launch_bounds__(kGateUpThreads) void ffn_gateup_kernel(FfnArgs p) {
   const int total = kk * p.F;
   const int stride = gridDim.x * (kGateUpThreads / kWave);
   const int first = blockIdx.x * (kGateUpThreads / kWave) + wave;
-  float* a_out = p.a + (size_t)b * 2 * p.F;
+  float* a_out = p.a + (size_t)b * 2 * p.a_stride;
   const int F = p.F;
 
   const uint4* xg = reinterpret_cast<const uint4*>(static_cast<const char*>(p.x) + (size_t)b * row_bytes);
@@ -152,7 +91,7 @@ __global__ __launch_bounds__(kGateUpThreads) void ffn_gateup_kernel(FfnArgs p) {
         g = d;
       } else {
         const float gs = wave_sum(g), us = wave_sum(d);
-        if (lane == 0) a_out[rc] = wj[rc >= F ? 1 : 0] * silu_f32(gs) * us;
+        if (lane == 0) a_out[(rc >= F ? p.a_stride - F : 0) + rc] = wj[rc >= F ? 1 : 0] * silu_f32(gs) * us;
         rc += stride;
       }
       half_c ^= 1;
@@ -169,7 +108,7 @@ __global__ __launch_bounds__(kGateUpThreads) void ffn_gateup_kernel(FfnArgs p) {
         const float u = wave_sum(dot_row_generic<BF16>(row + row_bytes, xs, lane, nch));
         val = wj[j] * silu_f32(g) * u;
       }
-      if (lane == 0) a_out[r] = val;
+      if (lane == 0) a_out[(size_t)j * p.a_stride + (r - j * F)] = val;
     }
   }
 }
@@ -219,12 +158,13 @@ __global__ __launch_bounds__(kDownThreads) void ffn_down_kernel(FfnArgs p) {
   bool all_resident = true;
   for (int j = 0; j < kk; ++j) all_resident &= base[j] != nullptr;
 
-  const float4* ag = reinterpret_cast<const float4*>(p.a + (size_t)b * 2 * p.F);
+  const float4* ag = reinterpret_cast<const float4*>(p.a + (size_t)b * 2 * p.a_stride);
+  const int S4 = (int)(p.a_stride >> 2);
   auto stage_a = [&]() {
     for (int i = tid; i < kk * F4; i += kDownThreads) {
       const int j = i >= F4 ? 1 : 0;
       const int f4 = i - j * F4;
-      as4[j * F4 + (BF16 ? lds_pos_bf16(f4) : f4)] = ag[i];
+      as4[j * F4 + (BF16 ? lds_pos_bf16(f4) : f4)] = ag[j * S4 + f4];
     }
     __syncthreads();
   };
@@ -294,7 +234,10 @@ static hipError_t init_down() {
   return allow_big_lds(ffn_down_kernel<BF16, 0>);
 }
 
-hipError_t ffn_kernels_init(int dtype) { return dtype == ADAPMOE_F32 ? init_down<false>() : init_down<true>(); }
+hipError_t ffn_kernels_init(int dtype) {
+  if (dtype == ADAPMOE_INT4G64) return hipSuccess;
+  return dtype == ADAPMOE_F32 ? init_down<false>() : init_down<true>();
+}
 
 template <bool BF16>
 static void launch_gateup_t(const FfnArgs& p, int nch, dim3 grid, size_t lds, hipStream_t s) {

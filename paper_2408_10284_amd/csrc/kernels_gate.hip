@@ -92,9 +92,20 @@ __global__ __launch_bounds__(kGateThreads) void gate_kernel(GateArgs a) {
     ids_out[0] = e1;
     ids_out[1] = e2;
     *k_out = k;
+    const float w0 = (k == 1) ? 1.0f : alpha, w1 = (k == 1) ? 0.0f : v;   // Eq.4 / Eq.3
     if (r == 0 && a.w != nullptr) {
-      a.w[2 * b + 0] = (k == 1) ? 1.0f : alpha;   // Eq.4 / Eq.3
-      a.w[2 * b + 1] = (k == 1) ? 0.0f : v;
+      a.w[2 * b + 0] = w0;
+      a.w[2 * b + 1] = w1;
+    }
+    if (r == 0 && a.res != nullptr) {
+      ResolvedExperts out;
+      out.base[0] = a.table[e1];
+      out.base[1] = (k == 2) ? a.table[e2] : nullptr;
+      out.w[0] = w0;
+      out.w[1] = w1;
+      out.k = k;
+      out.pad = 0;
+      a.res[b] = out;
     }
   }
 }

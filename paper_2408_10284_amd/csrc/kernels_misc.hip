@@ -44,11 +44,11 @@ hipError_t launch_residual_rmsnorm(float* h, const float* y, float gamma, void* 
   return hipGetLastError();
 }
 
-// table[index[i]] = value[i]: residency changes are ordered on the compute
-// stream with the kernels that read the table.
+// *addr[i] = value[i]: residency changes (table entries, resolved expert
+// pointers) are ordered on the compute stream with the kernels that read them.
 __global__ void poke_kernel(PokeArgs p) {
   const int i = threadIdx.x;
-  if (i < p.n) p.table[p.index[i]] = p.value[i];
+  if (i < p.n) *p.addr[i] = p.value[i];
 }
 
 hipError_t launch_poke(const PokeArgs& p, hipStream_t s) {

@@ -6,6 +6,17 @@
 
 namespace adapmoe {
 
+// What the gate leaves for the expert kernels of the same token: the image
+// base pointers of the activated experts (already looked up in the residency
+// table), their weights and k, so that the FFN kernels need one small load
+// instead of a chain of three dependent ones.
+struct ResolvedExperts {
+  const void* base[2];
+  float w[2];
+  int32_t k;
+  int32_t pad;
+};
+
 struct GateArgs {
   const void* x;        // [B,H] activation type
   const void* Wg[2];    // router of this layer, router of the following layer (or null)
@@ -13,16 +24,20 @@ struct GateArgs {
   int32_t* ids[2];      // [B,2] each
   int32_t* k[2];        // [B] each
   float* w;             // [B,2], decision of router 0 only
+  ResolvedExperts* res; // [B] or null; written for router 0 from `table`
+  const void* const* table;  // residency table row of the layer (N pointers), used with res
   int B, H, N;
 };
 
 struct FfnArgs {
   const void* const* table;  // residency table row of the layer: N image base pointers, null = absent
+  const ResolvedExperts* res;  // [B] resolved by the gate (then ids/w/k/table are not read) or null
   const void* x;             // [B,H] activation type
   const int32_t* ids;        // [B,2]
   const float* w;            // [B,2]
   const int32_t* k;          // [B]
-  float* a;                  // scratch [B][2][F]: w_j * silu(W1 x) * (W3 x) per activated expert
+  float* a;                  // scratch [B][2][a_stride]: w_j * silu(W1 x) * (W3 x) per activated expert
+  size_t a_stride;           // floats per (token, expert slot) in the scratch, >= F
   float* y;                  // [B,H]
   int32_t* err;              // device flag word (bit 0: non-resident expert, bit 1: id out of range)
   int B, H, F, N;
@@ -38,13 +53,14 @@ hipError_t launch_gate(const GateArgs& a, bool bf16, int routers, hipStream_t s)
 hipError_t launch_ffn_gateup(const FfnArgs& p, int dtype, const LaunchCfg& lc, hipStream_t s);
 hipError_t launch_ffn_down(const FfnArgs& p, int dtype, const LaunchCfg& lc, hipStream_t s);
 hipError_t ffn_kernels_init(int dtype);
+hipError_t launch_ffn_gateup_int4(const FfnArgs& p, const LaunchCfg& lc, hipStream_t s);
+hipError_t launch_ffn_down_int4(const FfnArgs& p, const LaunchCfg& lc, hipStream_t s);
 hipError_t launch_residual_rmsnorm(float* h, const float* y, float gamma, void* x, bool bf16, int B, int H, hipStream_t s);
 
-struct PokeArgs {
-  const void** table;   // whole device table [L*N]
+struct PokeArgs {   // up to 8 pointer-sized stores, ordered on the stream
   int n;
-  int index[4];
-  const void* value[4];
+  const void** addr[8];
+  const void* value[8];
 };
 hipError_t launch_poke(const PokeArgs& p, hipStream_t s);
 

@@ -1,0 +1,105 @@
+// Shared by the expert-FFN kernels: the two-buffer part streamer, expert
+// resolution through the residency table, SiLU.
+#pragma once
+#include "device_utils.h"
+#include "launch.h"
+
+namespace adapmoe {
+
+constexpr int kChunkBytes = kWave * 16;  // bytes one wavefront reads per load instruction
+
+__device__ __forceinline__ float silu_f32(float g) { return g / (1.0f + expf(-g)); }
+
+// Resolves the image base pointers of the (up to two) activated experts of
+// token b: from the record the gate left (one load) or, for callers that bring
+// their own ids/w/k, through the residency table.
+__device__ __forceinline__ int resolve_experts(const FfnArgs& p, int b, const char* base[2], float w[2]) {
+  if (p.res != nullptr) {
+    const ResolvedExperts r = p.res[b];
+    const int kk = r.k < 1 ? 1 : (r.k > 2 ? 2 : r.k);
+    for (int j = 0; j < 2; ++j) {
+      base[j] = j < kk ? static_cast<const char*>(r.base[j]) : nullptr;
+      w[j] = j < kk ? r.w[j] : 0.f;
+      if (j < kk && base[j] == nullptr && threadIdx.x == 0) atomicOr(p.err, 1);
+    }
+    return kk;
+  }
+  int kk = p.k[b];
+  kk = kk < 1 ? 1 : (kk > 2 ? 2 : kk);
+  for (int j = 0; j < 2; ++j) {
+    base[j] = nullptr;
+    w[j] = 0.f;
+    if (j < kk) {
+      const int e = p.ids[2 * b + j];
+      if (e < 0 || e >= p.N) {
+        if (threadIdx.x == 0) atomicOr(p.err, 2);
+      } else {
+        base[j] = static_cast<const char*>(p.table[e]);
+        w[j] = p.w[2 * b + j];
+        if (base[j] == nullptr && threadIdx.x == 0) atomicOr(p.err, 1);
+      }
+    }
+  }
+  return kk;
+}
+
+// ----------------------------------------------------------- part streaming --
+
+// Both GEMVs read, per wavefront, a known sequence of "parts": NV consecutive
+// 1 KiB runs of a matrix row (16 bytes per lane each).  Two register buffers
+// alternate: while part q is consumed, part q+1 is already in flight and part
+// q+2 is requested as soon as q's buffer is free, so a wavefront keeps NV to
+// 2*NV loads outstanding.  The steady loop has no conditional loads (those
+// would make the compiler copy the buffers); the tail is peeled.
+// next_addr() returns the lane's address of the next part in sequence,
+// consume(buf) uses the next part in sequence; both keep their own cursor.
+template <int NV>
+__device__ __forceinline__ void load_vecs(const char* p, uint4 (&buf)[NV]) {
+#pragma unroll
+  for (int c = 0; c < NV; ++c) buf[c] = load_stream16(p + (size_t)c * kChunkBytes);
+}
+
+template <int NV, class AddrFn, class ConsumeFn, class MidFn>
+__device__ __forceinline__ void stream_parts(int Q, AddrFn next_addr, ConsumeFn consume, MidFn after_first_loads) {
+  uint4 A[NV], B[NV];
+  if (Q > 0) load_vecs<NV>(next_addr(), A);
+  if (Q > 1) load_vecs<NV>(next_addr(), B);
+  after_first_loads();  // e.g. staging the activation vector in LDS while the first weights travel
+  if (Q <= 0) return;
+  int q = 0;
+  for (; q + 3 < Q; q += 2) {
+    consume(A);
+    load_vecs<NV>(next_addr(), A);
+    consume(B);
+    load_vecs<NV>(next_addr(), B);
+  }
+  // 1, 2 or 3 parts left; A holds part q, B part q+1
+  consume(A);
+  if (q + 2 < Q) load_vecs<NV>(next_addr(), A);
+  if (q + 1 < Q) consume(B);
+  if (q + 2 < Q) consume(A);
+}
+
+// Same pipeline for parts that are not a plain run of vectors: load_next(buf)
+// fills a buffer with the next part in sequence.
+template <class Buf, class LoadFn, class ConsumeFn, class MidFn>
+__device__ __forceinline__ void stream_bufs(int Q, LoadFn load_next, ConsumeFn consume, MidFn after_first_loads) {
+  Buf A, B;
+  if (Q > 0) load_next(A);
+  if (Q > 1) load_next(B);
+  after_first_loads();
+  if (Q <= 0) return;
+  int q = 0;
+  for (; q + 3 < Q; q += 2) {
+    consume(A);
+    load_next(A);
+    consume(B);
+    load_next(B);
+  }
+  consume(A);
+  if (q + 2 < Q) load_next(A);
+  if (q + 1 < Q) consume(B);
+  if (q + 2 < Q) consume(A);
+}
+
+}  // namespace adapmoe

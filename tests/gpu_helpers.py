@@ -2,6 +2,7 @@
 import numpy as np
 import torch
 
+from oracle.expert import decode_int4 as OE_decode
 from paper_2408_10284_amd import binding as B
 from paper_2408_10284_amd import synth
 
@@ -25,7 +26,7 @@ class GpuLayerSet:
 
     def __init__(self, shape, seed=0, max_B=1, trace_capacity=0, resident=True, taus=None):
         self.shape = shape
-        dt = B.F32 if shape.dtype == "f32" else B.BF16
+        dt = {"f32": B.F32, "bf16": B.BF16, "int4g64": B.INT4G64}[shape.dtype]
         self.ctx, self.cfg = B.adapmoe_create(shape.H, shape.F, shape.N, shape.L, dt, max_B=max_B,
                                                trace_capacity=trace_capacity)
         self.nbytes = B.adapmoe_expert_bytes(self.cfg)
@@ -42,10 +43,19 @@ class GpuLayerSet:
             row = []
             for e in range(shape.N):
                 w1, w3, w2 = synth.expert_weights(shape, l, e, seed)
-                row.append((w1, w3, w2))
                 img = np.empty(self.nbytes, dtype=np.uint8)
-                B.adapmoe_pack_expert(self.cfg, np_dtype_bits(shape.dtype, w1), np_dtype_bits(shape.dtype, w3),
-                                      np_dtype_bits(shape.dtype, w2), img)
+                if shape.dtype == "int4g64":
+                    qs = [synth.quantize_int4_g64(m) for m in (w1, w3, w2)]
+                    args = []
+                    for (q, sc, zr) in qs:
+                        args += [q, sc.view(np.uint16), zr.view(np.uint16)]
+                    B.adapmoe_pack_expert_int4(self.cfg, *args, img)
+                    # the checker sees the same codes, scales and zeros, decoded by its own routine
+                    row.append(tuple(OE_decode(q, sc, zr) for (q, sc, zr) in qs))
+                else:
+                    row.append((w1, w3, w2))
+                    B.adapmoe_pack_expert(self.cfg, np_dtype_bits(shape.dtype, w1), np_dtype_bits(shape.dtype, w3),
+                                          np_dtype_bits(shape.dtype, w2), img)
                 if resident:
                     t = torch.from_numpy(img).cuda()
                     B.adapmoe_bind_expert_dev(self.ctx, l, e, t)

@@ -94,3 +94,54 @@ def test_planner_argument_errors(lib):
     assert lib.cache_plan(2, 1, 4, a, a, t, None) == B.EINVAL
     assert lib.cache_plan(2, 8, -1, a, a, t, None) == B.EINVAL
     assert lib.cache_plan(2, 8, 4, None, a, t, None) == B.EINVAL
+
+
+def _decode_int4_row(row_bytes, n):
+    """Independent reader of the documented int4 row format -> (codes[n], scale[n/64], zero[n/64])."""
+    G = n // 64
+    codes = np.zeros(n, dtype=np.uint8)
+    raw = np.frombuffer(row_bytes, dtype=np.uint8)
+    for g in range(G):
+        blk, l = divmod(g, 64)
+        nb = min(64, G - blk * 64)
+        for half in range(2):
+            off = blk * 2048 + half * nb * 16 + l * 16
+            dwords = raw[off:off + 16].view(np.uint32)
+            for d in range(4):
+                w = int(dwords[d])
+                for s in range(4):
+                    codes[g * 64 + half * 32 + d * 8 + 2 * s] = (w >> (4 * s)) & 15
+                    codes[g * 64 + half * 32 + d * 8 + 2 * s + 1] = (w >> (4 * s + 16)) & 15
+    sz = raw[n // 2: n // 2 + 4 * G].view(np.uint16).reshape(G, 2)
+    return codes, sz[:, 0].copy(), sz[:, 1].copy()
+
+
+def test_pack_int4_layout(lib):
+    H, F = 512, 4352     # W2 rows: 68 groups = one block of 64 + one of 4
+    cfg = B.Config(H, F, 2, 1, B.INT4G64, 1, 0, 0)
+    nbytes = B.adapmoe_expert_bytes(cfg)
+    assert nbytes == 3 * H * F * 9 // 16
+    rng = np.random.default_rng(1)
+    mats = []
+    for (r, c) in ((F, H), (F, H), (H, F)):
+        mats.append((rng.integers(0, 16, (r, c), dtype=np.uint8),
+                     rng.integers(0, 65536, (r, c // 64), dtype=np.uint16),
+                     rng.integers(0, 65536, (r, c // 64), dtype=np.uint16)))
+    out = np.zeros(nbytes, dtype=np.uint8)
+    B.adapmoe_pack_expert_int4(cfg, *[a for m in mats for a in m], out)
+    rbH, rbF = H // 2 + H // 16, F // 2 + F // 16
+    for f in (0, 1, 77, F - 1):
+        for which, m in ((0, mats[0]), (1, mats[1])):
+            row = out[(2 * f + which) * rbH:(2 * f + which + 1) * rbH].tobytes()
+            q, s, z = _decode_int4_row(row, H)
+            np.testing.assert_array_equal(q, m[0][f])
+            np.testing.assert_array_equal(s, m[1][f])
+            np.testing.assert_array_equal(z, m[2][f])
+    base = 2 * F * rbH
+    for h in (0, 5, H - 1):
+        q, s, z = _decode_int4_row(out[base + h * rbF: base + (h + 1) * rbF].tobytes(), F)
+        np.testing.assert_array_equal(q, mats[2][0][h])
+        np.testing.assert_array_equal(s, mats[2][1][h])
+        np.testing.assert_array_equal(z, mats[2][2][h])
+    # Mixtral-shaped int4 expert: 9/16 byte per weight
+    assert B.adapmoe_expert_bytes(B.Config(4096, 14336, 8, 32, B.INT4G64, 1, 0, 0)) == 99090432

@@ -14,7 +14,7 @@ from gpu_helpers import GpuLayerSet, rel_err_per_token, to_dev_act
 
 pytestmark = pytest.mark.gpu
 
-TOL = {"f32": 1e-5, "bf16": 2e-2}
+TOL = {"f32": 1e-5, "bf16": 2e-2, "int4g64": 2e-2}
 BAND = 1e-6        # tokens whose test value lies this close to the threshold are not compared on k
 TIE_GAP = 1e-4     # tokens whose 2nd/3rd (or 1st/2nd) logits are closer than this are not compared on ids
 
@@ -133,6 +133,10 @@ def test_nonresident_expert_is_reported_not_faulted():
     ("bf16", 2048, 2048, 5),    # 4-run parts
     ("f32", 2048, 768, 3),      # f32 with compile-time gate/up row
     ("f32", 256, 1792, 64),     # N = 64, 7-run parts in f32
+    ("int4g64", 4096, 1024, 4),   # one full block of 64 groups per x row, 16 groups per W2 row
+    ("int4g64", 512, 4352, 8),    # 8 groups per x row, W2 rows of 68 groups = one full block + 4 groups
+    ("int4g64", 6144, 256, 3),    # x rows of 96 groups: two blocks, the second half full
+    ("int4g64", 256, 14336, 2),   # W2 rows of 224 groups: 3 full blocks + half a block
 ])
 def test_shapes_gate_and_ffn(dtype, H, F, N):
     shape = synth.MoEShape(H=H, F=F, N=N, L=2, dtype=dtype)

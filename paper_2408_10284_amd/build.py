@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libadapmoe.so")
-SOURCES = ["adapmoe_host.hip", "kernels_gate.hip", "kernels_ffn.hip", "kernels_int4.hip", "kernels_misc.hip"]
+SOURCES = ["adapmoe_host.hip", "kernels_gate.hip", "kernels_ffn.hip", "kernels_int4.hip", "kernels_batched.hip", "kernels_misc.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fno-gpu-rdc",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wall", "-Wno-unused-command-line-argument", "-Wno-unused-value"]

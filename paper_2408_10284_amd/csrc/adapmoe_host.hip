@@ -68,6 +68,14 @@ struct adapmoe_ctx {
   float* d_w = nullptr;                 // [B,2]
   float* d_a = nullptr;                 // [B][2][a_stride]
   ResolvedExperts* d_res = nullptr;     // [B] resolved experts of the last gate of moe_layer_step
+  // batched path scratch (bf16, max_B > 1)
+  int32_t* d_bkt_count = nullptr;
+  int32_t* d_bkt_tok = nullptr;
+  float* d_bkt_w = nullptr;
+  const void** d_bkt_base = nullptr;
+  uint16_t* d_xop = nullptr;
+  uint16_t* d_ahi = nullptr;
+  uint16_t* d_alo = nullptr;
   int32_t* h_dec = nullptr;             // pinned mirror of d_dec
   hipStream_t copy_stream = nullptr;
   LaunchCfg lc{};
@@ -280,6 +288,46 @@ FfnArgs ffn_args(adapmoe_ctx* c, int layer, const void* x, int B, const int32_t*
 
 int launch_ffn(adapmoe_ctx* c, int layer, const void* x, int B, const int32_t* ids, const float* w, const int32_t* k,
                float* y, hipStream_t s, const ResolvedExperts* res = nullptr) {
+  if (c->cfg.dtype == ADAPMOE_BF16 && B >= c->lc.batch_min && c->d_xop) {
+    // several tokens: bucket by expert, stream every touched expert once (grouped GEMM on the matrix cores)
+    const size_t esz = 2;
+    for (int b0 = 0; b0 < B; b0 += 16) {
+      BatchArgs q{};
+      q.table = c->d_table + (size_t)layer * c->cfg.N;
+      q.x = static_cast<const char*>(x) + (size_t)b0 * c->cfg.H * esz;
+      q.ids = ids + 2 * b0;
+      q.w = w + 2 * b0;
+      q.k = k + b0;
+      q.y = y + (size_t)b0 * c->cfg.H;
+      q.err = c->d_err;
+      q.B = std::min(16, B - b0);
+      q.H = c->cfg.H;
+      q.F = c->cfg.F;
+      q.N = c->cfg.N;
+      q.w2_offset = c->w2_offset;
+      q.bkt_count = c->d_bkt_count;
+      q.bkt_tok = c->d_bkt_tok;
+      q.bkt_w = c->d_bkt_w;
+      q.bkt_base = c->d_bkt_base;
+      q.xop = c->d_xop;
+      q.a_hi = c->d_ahi;
+      q.a_lo = c->d_alo;
+      {
+        ScopedTimer t(c, 3, s);
+        HIPCHK(c, launch_bucket_gather(q, s));
+      }
+      {
+        ScopedTimer t(c, 4, s);
+        HIPCHK(c, launch_grouped_gateup(q, s));
+      }
+      {
+        ScopedTimer t(c, 5, s);
+        HIPCHK(c, launch_grouped_down(q, s));
+      }
+    }
+    c->ctr.ffn_launches++;
+    return ADAPMOE_OK;
+  }
   FfnArgs p = ffn_args(c, layer, x, B, ids, w, k, y, res);
   const bool int4 = c->cfg.dtype == ADAPMOE_INT4G64;
   {
@@ -432,6 +480,7 @@ int adapmoe_create(const adapmoe_config* cfg, adapmoe_ctx** out) {
   c->layers.resize(cfg->L);
   c->lc.gateup_blocks = env_int("ADAPMOE_GATEUP_BLOCKS", 1024);
   c->lc.down_blocks = env_int("ADAPMOE_DOWN_BLOCKS", 256);
+  c->lc.batch_min = env_int("ADAPMOE_BATCH_MIN", 4);
   const int B = cfg->max_B;
   bool ok = hipSetDevice(cfg->device) == hipSuccess;
   ok = ok && hipMalloc(&c->d_table, LN * sizeof(void*)) == hipSuccess;
@@ -444,6 +493,17 @@ int adapmoe_create(const adapmoe_config* cfg, adapmoe_ctx** out) {
   ok = ok && hipMalloc(&c->d_res, (size_t)B * sizeof(ResolvedExperts)) == hipSuccess;
   ok = ok && hipMemset(c->d_res, 0, (size_t)B * sizeof(ResolvedExperts)) == hipSuccess;
   ok = ok && hipHostMalloc(reinterpret_cast<void**>(&c->h_dec), (size_t)6 * B * sizeof(int32_t), hipHostMallocDefault) == hipSuccess;
+  if (cfg->dtype == ADAPMOE_BF16 && B > 1) {
+    const size_t N = cfg->N;
+    ok = ok && hipMalloc(&c->d_bkt_count, N * sizeof(int32_t)) == hipSuccess;
+    ok = ok && hipMalloc(&c->d_bkt_tok, N * 16 * sizeof(int32_t)) == hipSuccess;
+    ok = ok && hipMalloc(&c->d_bkt_w, N * 16 * sizeof(float)) == hipSuccess;
+    ok = ok && hipMalloc(&c->d_bkt_base, N * sizeof(void*)) == hipSuccess;
+    ok = ok && hipMalloc(&c->d_xop, N * (size_t)cfg->H * 16 * 2) == hipSuccess;
+    ok = ok && hipMalloc(&c->d_ahi, N * (size_t)cfg->F * 16 * 2) == hipSuccess;
+    ok = ok && hipMalloc(&c->d_alo, N * (size_t)cfg->F * 16 * 2) == hipSuccess;
+    ok = ok && batched_kernels_init() == hipSuccess;
+  }
   ok = ok && hipStreamCreateWithFlags(&c->copy_stream, hipStreamNonBlocking) == hipSuccess;
   ok = ok && ffn_kernels_init(cfg->dtype) == hipSuccess;
   if (!ok) {
@@ -475,6 +535,13 @@ int adapmoe_destroy(adapmoe_ctx* c) {
   if (c->d_w) hipFree(c->d_w);
   if (c->d_a) hipFree(c->d_a);
   if (c->d_res) hipFree(c->d_res);
+  if (c->d_bkt_count) hipFree(c->d_bkt_count);
+  if (c->d_bkt_tok) hipFree(c->d_bkt_tok);
+  if (c->d_bkt_w) hipFree(c->d_bkt_w);
+  if (c->d_bkt_base) hipFree(c->d_bkt_base);
+  if (c->d_xop) hipFree(c->d_xop);
+  if (c->d_ahi) hipFree(c->d_ahi);
+  if (c->d_alo) hipFree(c->d_alo);
   if (c->h_dec) hipHostFree(c->h_dec);
   delete c;
   return ADAPMOE_OK;

@@ -1,0 +1,304 @@
+// Batched decode (several tokens per step): the activated (token, expert)
+// pairs are bucketed by expert and every touched expert is streamed from HBM
+// once, as a grouped GEMM on the matrix cores
+//
+//   A_e[f, n] = w_n silu(W1_e[f,:] . x_n) (W3_e[f,:] . x_n)     n over the tokens of bucket e
+//   y_n      += W2_e A_e[:, n]                                   (Sec. 2.1 Eq.2 per token)
+//
+// with v_mfma_f32_16x16x32_bf16: 16 weight rows x 32 reduction elements per
+// instruction against up to 16 tokens.  The work is still bound by HBM (each
+// weight is used for at most 16 multiply-adds), so the layout follows the
+// weight stream: a wavefront owns 16 rows and walks the reduction axis; the
+// token-side operand (x, or A split into two bfloat16 terms so that it keeps
+// fp32 accuracy) is small, lives in global memory in MFMA operand order and is
+// staged through LDS slab by slab for all wavefronts of the workgroup.
+//
+// Operand order: for reduction step s (32 elements) lane l = 16 q + n holds the
+// 8 elements k = 32 s + 8 q + i of token column n.
+#include "../../include/adapmoe.h"
+#include "stream_parts.h"
+
+namespace adapmoe {
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
+typedef __attribute__((ext_vector_type(4))) float f32x4_t;
+
+constexpr int kBTok = 16;            // token columns of one MFMA
+constexpr int kBThreads = 256;       // 4 wavefronts, 16 rows each
+constexpr int kBWaves = kBThreads / kWave;
+constexpr int kDownRT = 2;           // row tiles per wavefront in the down GEMM (H must be a multiple of 128)
+
+__device__ __forceinline__ f32x4_t mfma16(const uint4& a, const uint4& b, f32x4_t c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+}
+
+// ------------------------------------------------------------------ buckets --
+
+// Every workgroup recomputes the (tiny) bucket lists, workgroup (0,0) publishes
+// them; then the grid gathers x into operand order per expert and clears y.
+// grid = (H/32/4, N): workgroup (i, e) writes 4 reduction steps of expert e.
+__global__ __launch_bounds__(kBThreads) void bucket_gather_kernel(BatchArgs p) {
+  __shared__ int s_count[64];
+  __shared__ int s_tok[64][kBTok];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int e_mine = blockIdx.y;
+  if (tid < 64) {
+    // lane l < 2B is the pair (token l/2, rank l%2)
+    const int b = lane >> 1, j = lane & 1;
+    int e = -1;
+    float w = 0.f;
+    if (b < p.B) {
+      int kk = p.k[b];
+      kk = kk < 1 ? 1 : (kk > 2 ? 2 : kk);
+      if (j < kk) {
+        e = p.ids[2 * b + j];
+        w = p.w[2 * b + j];
+        if (e < 0 || e >= p.N) {
+          e = -1;
+          if (blockIdx.x == 0 && blockIdx.y == 0) atomicOr(p.err, 2);
+        }
+      }
+    }
+    for (int ex = 0; ex < p.N; ++ex) {
+      const uint64_t m = __builtin_amdgcn_ballot_w64(e == ex);
+      const int rank = __builtin_popcountll(m & ((1ull << lane) - 1));
+      const bool resident = p.table[ex] != nullptr;
+      if (m && !resident && lane == 0 && blockIdx.x == 0 && blockIdx.y == 0) atomicOr(p.err, 1);
+      if (lane == 0) s_count[ex] = resident ? __builtin_popcountll(m) : 0;
+      if (e == ex && resident) {
+        s_tok[ex][rank] = b;
+        if (blockIdx.x == 0 && blockIdx.y == 0) {
+          p.bkt_tok[ex * kBTok + rank] = b;
+          p.bkt_w[ex * kBTok + rank] = w;
+        }
+      }
+    }
+    if (blockIdx.x == 0 && blockIdx.y == 0 && lane < p.N) {
+      p.bkt_count[lane] = s_count[lane];
+      p.bkt_base[lane] = p.table[lane];
+    }
+  }
+  __syncthreads();
+
+  // clear this workgroup's share of y
+  {
+    const int nwg = gridDim.x * gridDim.y, wg = blockIdx.y * gridDim.x + blockIdx.x;
+    const int total4 = p.B * p.H / 4;
+    float4* y4 = reinterpret_cast<float4*>(p.y);
+    for (int i = wg * kBThreads + tid; i < total4; i += nwg * kBThreads) y4[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+  }
+
+  // gather x: 4 reduction steps = 256 lane slots of 16 bytes, one per thread
+  const int cnt = s_count[e_mine];
+  if (cnt == 0) return;
+  const int step = blockIdx.x * 4 + (tid >> 6);
+  if (step * 32 >= p.H) return;
+  const int n = lane & 15, q = lane >> 4;
+  uint4 v = make_uint4(0, 0, 0, 0);
+  if (n < cnt) {
+    const uint16_t* xr = static_cast<const uint16_t*>(p.x) + (size_t)s_tok[e_mine][n] * p.H;
+    v = *reinterpret_cast<const uint4*>(xr + step * 32 + q * 8);
+  }
+  reinterpret_cast<uint4*>(p.xop)[((size_t)e_mine * (p.H / 32) + step) * 64 + lane] = v;
+}
+
+// -------------------------------------------------------------- grouped GEMM --
+
+// C[16 rows per wavefront, 16 tokens] += W[rows, :] . Bop, reduction in slabs of
+// KS steps (KS * 64 bytes of every row).  NMAT = 2 reads two interleaved
+// matrices (W1 and W3 rows of the same index, gate/up); NTERM = 2 multiplies by
+// two operand arrays (hi and lo halves of A) and adds.
+// Weight path: coalesced 16-byte loads (32 lanes cover the slab's contiguous
+// KS*64 bytes of one row, an instruction covers two rows), two slabs in flight
+// in registers; at use the slab is turned into MFMA operand order through a
+// wavefront-private LDS tile whose rows are padded by 16 bytes so that the
+// operand reads (16 rows x 16 bytes per pass) hit all banks once.
+// Token operand: staged in LDS slab by slab by the whole workgroup.
+template <int NMAT, int RT>
+struct WSlab {
+  uint4 a[NMAT][RT][8];   // instruction i of matrix t, row tile rt: rows 16 rt + 2i, 16 rt + 2i + 1
+};
+
+template <int KS>
+constexpr int wtile_row_bytes() { return KS * 64 + 16; }
+
+template <int KS, int NMAT, int NTERM>
+constexpr size_t grouped_lds_bytes() {
+  return (size_t)KS * 64 * NTERM * 16 + (size_t)kBWaves * NMAT * 16 * wtile_row_bytes<KS>();
+}
+
+// RT = row tiles of 16 per wavefront (they share the token operand and the LDS tile).
+template <int KS, int NMAT, int NTERM, int RT, class Epilogue>
+__device__ __forceinline__ void grouped_gemm_tile_loop(const char* wbase, size_t row_stride, size_t mat_stride, int nsteps,
+                                                       int ntiles_rows, int tile0, int tile_stride,
+                                                       const uint4* bop0, const uint4* bop1, uint4* lds, Epilogue epilogue) {
+  static_assert(KS * 64 == 32 * 16, "a slab row must be 32 lanes x 16 bytes");
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int m = lane & 15, q = lane >> 4;
+  const int nslabs = nsteps / KS;
+  constexpr int kSlabVecs = KS * 64 * NTERM;            // 16-byte vectors of one operand slab
+  constexpr int kVecsPerThread = kSlabVecs / kBThreads;
+  constexpr int kRowB = wtile_row_bytes<KS>();
+  char* wt = reinterpret_cast<char*>(lds + kSlabVecs) + (size_t)wave * NMAT * 16 * kRowB;   // this wavefront's tile(s)
+  char* wt_store = wt + (lane >> 5) * kRowB + (lane & 31) * 16;    // where this lane's loaded pieces go (row 2i + lane/32)
+  const char* wt_read = wt + m * kRowB + q * 16;                   // operand read: row m, bytes 64 s + 16 q
+
+  for (int tile = tile0; tile < ntiles_rows; tile += tile_stride) {
+    const int row0 = (tile * kBWaves + wave) * 16 * RT;
+    const char* wsrc = wbase + (size_t)(row0 + (lane >> 5)) * row_stride + (lane & 31) * 16;
+    f32x4_t acc[RT][NMAT];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+      for (int t = 0; t < NMAT; ++t) acc[rt][t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+
+    int sa = 0;
+    auto load_next = [&](WSlab<NMAT, RT>& buf) {
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt)
+#pragma unroll
+        for (int t = 0; t < NMAT; ++t)
+#pragma unroll
+          for (int i = 0; i < 8; ++i)
+            buf.a[t][rt][i] = load_stream16(wsrc + t * mat_stride + (size_t)(16 * rt + 2 * i) * row_stride + (size_t)sa * KS * 64);
+      ++sa;
+    };
+    int sc = 0;
+    uint4 stage[kVecsPerThread];
+    auto fetch_operand = [&](int slab) {
+#pragma unroll
+      for (int v = 0; v < kVecsPerThread; ++v) {
+        const int idx = v * kBThreads + tid;              // vector index inside the slab: [term][step][lane]
+        const int term = idx / (KS * 64), r = idx - term * (KS * 64);
+        const uint4* src = term == 0 ? bop0 : bop1;
+        stage[v] = src[(size_t)slab * KS * 64 + r];
+      }
+    };
+    auto consume = [&](const WSlab<NMAT, RT>& buf) {
+      __syncthreads();                                    // everyone is done with the previous slab in LDS
+#pragma unroll
+      for (int v = 0; v < kVecsPerThread; ++v) lds[v * kBThreads + tid] = stage[v];
+      __syncthreads();
+      if (sc + 1 < nslabs) fetch_operand(sc + 1);
+#pragma unroll
+      for (int rt = 0; rt < RT; ++rt) {
+        // the wavefront's own LDS tile: written and read by this wavefront only, program order suffices
+#pragma unroll
+        for (int t = 0; t < NMAT; ++t)
+#pragma unroll
+          for (int i = 0; i < 8; ++i)
+            *reinterpret_cast<uint4*>(wt_store + (size_t)t * 16 * kRowB + (size_t)(2 * i) * kRowB) = buf.a[t][rt][i];
+#pragma unroll
+        for (int s = 0; s < KS; ++s) {
+          uint4 a[NMAT];
+#pragma unroll
+          for (int t = 0; t < NMAT; ++t) a[t] = *reinterpret_cast<const uint4*>(wt_read + (size_t)t * 16 * kRowB + s * 64);
+#pragma unroll
+          for (int term = 0; term < NTERM; ++term) {
+            const uint4 b = lds[(term * KS + s) * 64 + lane];
+#pragma unroll
+            for (int t = 0; t < NMAT; ++t) acc[rt][t] = mfma16(a[t], b, acc[rt][t]);
+          }
+        }
+      }
+      ++sc;
+    };
+    fetch_operand(0);
+    stream_bufs<WSlab<NMAT, RT>>(nslabs, load_next, consume, [] {});
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) epilogue(row0 + 16 * rt, acc[rt]);
+  }
+}
+
+// gate/up: rows f of W1 and W3 (interleaved in the image), reduction over H
+template <int KS>
+__global__ __launch_bounds__(kBThreads) void grouped_gateup_mfma_kernel(BatchArgs p) {
+  extern __shared__ uint4 lds[];
+  const int e = blockIdx.y;
+  const int cnt = p.bkt_count[e];
+  if (cnt == 0) return;
+  const char* base = static_cast<const char*>(p.bkt_base[e]);
+  const int lane = threadIdx.x & 63, n = lane & 15, q = lane >> 4;
+  const float wn = n < cnt ? p.bkt_w[e * kBTok + n] : 0.f;
+  const size_t row_bytes = (size_t)p.H * 2;
+  uint16_t* ahi = p.a_hi + (size_t)e * p.F * kBTok;
+  uint16_t* alo = p.a_lo + (size_t)e * p.F * kBTok;
+  auto epilogue = [&](int f0, const f32x4_t (&acc)[2]) {
+    // lane holds rows f0 + 4 q + r (r = 0..3) of token column n; A goes out in the operand
+    // order of the down GEMM (reduction index f), split into hi + lo bfloat16
+    uint16_t hi[4], lo[4];
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const float v = wn * silu_f32(acc[0][r]) * acc[1][r];
+      const uint32_t h = __builtin_bit_cast(uint32_t, v) & 0xffff0000u;   // truncated high part, v - hi is exact
+      hi[r] = (uint16_t)(h >> 16);
+      lo[r] = f32_to_bf16_bits(v - __builtin_bit_cast(float, h));
+    }
+    const int f = f0 + 4 * q;                              // first of the lane's four consecutive rows
+    const size_t pos = ((size_t)(f >> 5) * 64 + ((f >> 3) & 3) * 16 + n) * 8 + (f & 7);
+    *reinterpret_cast<uint2*>(ahi + pos) = make_uint2(hi[0] | ((uint32_t)hi[1] << 16), hi[2] | ((uint32_t)hi[3] << 16));
+    *reinterpret_cast<uint2*>(alo + pos) = make_uint2(lo[0] | ((uint32_t)lo[1] << 16), lo[2] | ((uint32_t)lo[3] << 16));
+  };
+  const uint4* xop = reinterpret_cast<const uint4*>(p.xop) + (size_t)e * (p.H / 32) * 64;
+  grouped_gemm_tile_loop<KS, 2, 1, 1>(base, 2 * row_bytes, row_bytes, p.H / 32, p.F / (16 * kBWaves), blockIdx.x, gridDim.x,
+                                   xop, xop, lds, epilogue);
+}
+
+// down: rows h of W2, reduction over F, result added into y of the bucket's tokens
+template <int KS>
+__global__ __launch_bounds__(kBThreads) void grouped_down_mfma_kernel(BatchArgs p) {
+  extern __shared__ uint4 lds[];
+  const int e = blockIdx.y;
+  const int cnt = p.bkt_count[e];
+  if (cnt == 0) return;
+  const char* base = static_cast<const char*>(p.bkt_base[e]) + p.w2_offset;
+  const int lane = threadIdx.x & 63, n = lane & 15, q = lane >> 4;
+  const int tok = n < cnt ? p.bkt_tok[e * kBTok + n] : -1;
+  auto epilogue = [&](int h0, const f32x4_t (&acc)[1]) {
+    if (tok < 0) return;
+    float* yr = p.y + (size_t)tok * p.H + h0 + 4 * q;
+    // a token receives at most two contributions (its two experts) onto a cleared row:
+    // the sum does not depend on their order
+#pragma unroll
+    for (int r = 0; r < 4; ++r) atomicAdd(yr + r, acc[0][r]);
+  };
+  const uint4* ahi = reinterpret_cast<const uint4*>(p.a_hi) + (size_t)e * (p.F / 32) * 64;
+  const uint4* alo = reinterpret_cast<const uint4*>(p.a_lo) + (size_t)e * (p.F / 32) * 64;
+  grouped_gemm_tile_loop<KS, 1, 2, kDownRT>(base, (size_t)p.F * 2, 0, p.F / 32, p.H / (16 * kBWaves * kDownRT), blockIdx.x, gridDim.x, ahi, alo, lds,
+                                   epilogue);
+}
+
+// ------------------------------------------------------------------ launch ---
+
+constexpr int kGateUpKS = 8;
+constexpr int kDownKS = 8;
+
+hipError_t batched_kernels_init() {
+  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(grouped_gateup_mfma_kernel<kGateUpKS>),
+                                     hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+  if (e != hipSuccess) return e;
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(grouped_down_mfma_kernel<kDownKS>),
+                             hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+}
+
+hipError_t launch_bucket_gather(const BatchArgs& p, hipStream_t s) {
+  dim3 grid((p.H / 32 + 3) / 4, p.N), block(kBThreads);
+  hipLaunchKernelGGL(bucket_gather_kernel, grid, block, 0, s, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_grouped_gateup(const BatchArgs& p, hipStream_t s) {
+  dim3 grid(p.F / (16 * kBWaves), p.N), block(kBThreads);
+  constexpr size_t lds = grouped_lds_bytes<kGateUpKS, 2, 1>();
+  hipLaunchKernelGGL(grouped_gateup_mfma_kernel<kGateUpKS>, grid, block, lds, s, p);
+  return hipGetLastError();
+}
+
+hipError_t launch_grouped_down(const BatchArgs& p, hipStream_t s) {
+  dim3 grid(p.H / (16 * kBWaves * kDownRT), p.N), block(kBThreads);
+  constexpr size_t lds = grouped_lds_bytes<kDownKS, 1, 2>();
+  hipLaunchKernelGGL(grouped_down_mfma_kernel<kDownKS>, grid, block, lds, s, p);
+  return hipGetLastError();
+}
+
+}  // namespace adapmoe

@@ -44,9 +44,31 @@ struct FfnArgs {
   size_t w2_offset;          // byte offset of W2 inside an expert image
 };
 
+// Batched path (several tokens, experts streamed once each on the matrix cores)
+struct BatchArgs {
+  const void* const* table;  // residency table row of the layer
+  const void* x;             // [B,H] bfloat16
+  const int32_t* ids;        // [B,2]
+  const float* w;            // [B,2]
+  const int32_t* k;          // [B]
+  float* y;                  // [B,H], cleared then accumulated
+  int32_t* err;
+  int B, H, F, N;
+  size_t w2_offset;
+  // scratch owned by the context
+  int32_t* bkt_count;        // [N] tokens per expert
+  int32_t* bkt_tok;          // [N][16] token index
+  float* bkt_w;              // [N][16] routing weight
+  const void** bkt_base;     // [N] image base pointer
+  uint16_t* xop;             // [N][H/32][64][8] x of the bucket's tokens in MFMA operand order
+  uint16_t* a_hi;            // [N][F/32][64][8] A in operand order, high bfloat16 part
+  uint16_t* a_lo;            //                                      low part
+};
+
 struct LaunchCfg {
   int gateup_blocks;  // workgroups of the gate/up GEMV (256 threads each)
   int down_blocks;    // workgroups of the down GEMV (1024 threads each)
+  int batch_min;      // smallest number of tokens per call that takes the batched (MFMA) path
 };
 
 hipError_t launch_gate(const GateArgs& a, bool bf16, int routers, hipStream_t s);
@@ -55,6 +77,10 @@ hipError_t launch_ffn_down(const FfnArgs& p, int dtype, const LaunchCfg& lc, hip
 hipError_t ffn_kernels_init(int dtype);
 hipError_t launch_ffn_gateup_int4(const FfnArgs& p, const LaunchCfg& lc, hipStream_t s);
 hipError_t launch_ffn_down_int4(const FfnArgs& p, const LaunchCfg& lc, hipStream_t s);
+hipError_t batched_kernels_init();
+hipError_t launch_bucket_gather(const BatchArgs& p, hipStream_t s);
+hipError_t launch_grouped_gateup(const BatchArgs& p, hipStream_t s);
+hipError_t launch_grouped_down(const BatchArgs& p, hipStream_t s);
 hipError_t launch_residual_rmsnorm(float* h, const float* y, float gamma, void* x, bool bf16, int B, int H, hipStream_t s);
 
 struct PokeArgs {   // up to 8 pointer-sized stores, ordered on the stream

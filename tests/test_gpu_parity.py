@@ -284,3 +284,42 @@ def test_mixtral_layer_full_size():
         assert np.all(np.isfinite(yh)) and np.all(np.abs(yh).max(axis=1) > 0)
     finally:
         ls.close()
+
+
+# ------------------------------------------------ batched path (MFMA grouped GEMM) ----
+
+@pytest.mark.parametrize("H,F,N,Bt,tau", [
+    (512, 512, 8, 16, 0.25),     # one slab of x, smallest shapes
+    (1024, 1536, 8, 16, 0.25),   # several row tiles and slabs
+    (2048, 1024, 2, 16, 0.0),    # N = 2, threshold 0: every token in both buckets (16 tokens per expert)
+    (1024, 2048, 8, 5, 0.3),     # partly filled token tile
+    (1024, 1024, 16, 13, 0.5),   # threshold 1/2: one expert per token, many empty buckets
+    (512, 1024, 8, 40, 0.25),    # more than 16 tokens: processed in groups of 16
+])
+def test_batched_path(H, F, N, Bt, tau):
+    shape = synth.MoEShape(H=H, F=F, N=N, L=1, dtype="bf16")
+    ls = GpuLayerSet(shape, seed=7, max_B=Bt, taus=[tau])
+    try:
+        X = synth.ar1_tokens(Bt, H, 0.5, seed=11, dtype="bf16")
+        g = run_gate(ls, 0, X)
+        ref = OG.gate_batch(X, ls.routers_f32[0], np.float32(tau))
+        check_gate(g["ids"], g["k"], g["w"], ref, tau, 1e-5)
+        y = run_ffn(ls, 0, g)                     # one call with Bt tokens -> batched kernels
+        Yref = OE.moe_block_rows(X, ls.experts_f32[0], g["ids"], g["w"].astype(np.float64), g["k"])
+        err = rel_err_per_token(y, Yref)
+        assert err.max() <= TOL["bf16"], err.max()
+        # the per-token GEMV path gives the same numbers up to summation order and the
+        # two-term bfloat16 split of the intermediate activation
+        y1 = torch.empty((Bt, H), dtype=torch.float32, device="cuda")
+        for t in range(Bt):
+            B.moe_expert_ffn(ls.ctx, 0, g["x_dev"][t:t + 1], 1, g["ids_dev"][t:t + 1], g["w_dev"][t:t + 1], g["k_dev"][t:t + 1], y1[t:t + 1])
+        B.adapmoe_check(ls.ctx)
+        d = rel_err_per_token(y, y1.cpu().numpy())
+        assert d.max() <= 1e-4, d.max()
+        # layer_step with the same batch takes the same path
+        y2 = torch.empty((Bt, H), dtype=torch.float32, device="cuda")
+        B.moe_layer_step(ls.ctx, 0, g["x_dev"], Bt, y2)
+        B.adapmoe_check(ls.ctx)
+        np.testing.assert_array_equal(y2.cpu().numpy(), y)
+    finally:
+        ls.close()

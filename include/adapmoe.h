@@ -159,9 +159,9 @@ int cache_plan(int L, int N, int C, const double* a, const double* beta, int32_t
 /* Expected on-demand loads of one layer with t of N experts cached (Eq.15). */
 double cache_cost(int N, int t, double a, double beta);
 
-/* Allocates sum(slots_per_layer) + 2 expert-sized slots in HBM (the 2 spare
- * slots serve layers that own fewer slots than experts they run) and empties
- * every layer's LRU set.  slots_per_layer[l] in 0..N.  May be called once. */
+/* Allocates sum(slots_per_layer) + 2*max_B expert-sized slots in HBM (the spare
+ * slots serve layers that own fewer slots than the experts one step runs) and
+ * empties every layer's LRU set.  slots_per_layer[l] in 0..N.  May be called once. */
 int cache_alloc(adapmoe_ctx* ctx, const int32_t* slots_per_layer);
 
 /* Residency query: slot_out[i] = physical slot of ids[i] in `layer`, -1 if
@@ -210,6 +210,13 @@ int moe_layer_step(adapmoe_ctx* ctx, int layer, const void* x_dev, int B, float*
  * h [B,H] float, y [B,H] float, x [B,H]. */
 int moe_residual_rmsnorm(adapmoe_ctx* ctx, float* h_dev, const float* y_dev, float gamma,
                          void* x_dev, int B, void* stream);
+
+/* One token step through all L layers with the wiring above (not from the
+ * paper): for l = 0..L-1: x = norm(h) (h first updated with gamma*y of the layer
+ * before), moe_layer_step(l, x) -> y; finally h += gamma*y of the last layer.
+ * h [B,H] float is updated in place; x [B,H] (activation type) and y [B,H]
+ * float are work buffers owned by the caller.  Sets the trace token to `token`. */
+int moe_stack_token(adapmoe_ctx* ctx, int token, float* h_dev, void* x_dev, float* y_dev, int B, float gamma, void* stream);
 
 /* ---- bookkeeping ------------------------------------------------------------- */
 

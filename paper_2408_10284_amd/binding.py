@@ -64,6 +64,7 @@ _SIGS = {
     "moe_prefetch": (C.c_int, [_P, C.c_int, C.POINTER(C.c_int32), C.c_int]),
     "moe_layer_step": (C.c_int, [_P, C.c_int, _P, C.c_int, _P, _P]),
     "moe_residual_rmsnorm": (C.c_int, [_P, _P, _P, C.c_float, _P, C.c_int, _P]),
+    "moe_stack_token": (C.c_int, [_P, C.c_int, _P, _P, _P, C.c_int, C.c_float, _P]),
     "adapmoe_set_token": (C.c_int, [_P, C.c_int]),
     "adapmoe_trace_read": (C.c_int, [_P, C.POINTER(Event), C.c_size_t, C.POINTER(C.c_size_t)]),
     "adapmoe_counters": (C.c_int, [_P, C.POINTER(Counters)]),
@@ -210,6 +211,10 @@ def moe_layer_step(ctx, layer, x, B, y, stream=None):
 
 def moe_residual_rmsnorm(ctx, h, y, gamma, x, B, stream=None):
     _chk(ctx, load().moe_residual_rmsnorm(ctx, _ptr(h), _ptr(y), float(gamma), _ptr(x), B, _stream(stream)))
+
+
+def moe_stack_token(ctx, token, h, x, y, B, gamma, stream=None):
+    _chk(ctx, load().moe_stack_token(ctx, token, _ptr(h), _ptr(x), _ptr(y), B, float(gamma), _stream(stream)))
 
 
 def adapmoe_set_token(ctx, token):

@@ -636,7 +636,7 @@ int cache_alloc(adapmoe_ctx* c, const int32_t* slots_per_layer) {
     if (slots_per_layer[l] < 0 || slots_per_layer[l] > c->cfg.N) return fail(c, ADAPMOE_EINVAL, "cache_alloc: slots per layer must be in 0..N");
     total += slots_per_layer[l];
   }
-  total += 2;
+  total += 2 * (size_t)c->cfg.max_B;  // spare slots: what one step may read beyond the layers' own slots
   HIPCHK(c, hipSetDevice(c->cfg.device));
   c->slots.resize(total);
   for (size_t i = 0; i < total; ++i) {
@@ -877,6 +877,20 @@ int moe_layer_step(adapmoe_ctx* c, int layer, const void* x, int B, float* y, vo
 int moe_residual_rmsnorm(adapmoe_ctx* c, float* h, const float* y, float gamma, void* x, int B, void* stream) {
   if (!c || !h || !x || B < 1 || B > c->cfg.max_B) return fail(c, ADAPMOE_EINVAL, "moe_residual_rmsnorm: bad argument");
   HIPCHK(c, launch_residual_rmsnorm(h, y, gamma, x, c->bf16_act, B, c->cfg.H, static_cast<hipStream_t>(stream)));
+  return ADAPMOE_OK;
+}
+
+int moe_stack_token(adapmoe_ctx* c, int token, float* h, void* x, float* y, int B, float gamma, void* stream) {
+  if (!c || !h || !x || !y || B < 1 || B > c->cfg.max_B) return fail(c, ADAPMOE_EINVAL, "moe_stack_token: bad argument");
+  c->token = token;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  for (int l = 0; l < c->cfg.L; ++l) {
+    HIPCHK(c, launch_residual_rmsnorm(h, l > 0 ? y : nullptr, gamma, x, c->bf16_act, B, c->cfg.H, s));
+    int rc = moe_layer_step(c, l, x, B, y, stream);
+    if (rc) return rc;
+  }
+  // last residual update (x is rewritten with the normalised final state, unused)
+  HIPCHK(c, launch_residual_rmsnorm(h, y, gamma, x, c->bf16_act, B, c->cfg.H, s));
   return ADAPMOE_OK;
 }
 

@@ -168,3 +168,37 @@ def pack_nibbles(codes: np.ndarray) -> np.ndarray:
     nibble, element 2i+1 in the high nibble."""
     c = codes.reshape(codes.shape[0], -1, 2)
     return (c[:, :, 0] | (c[:, :, 1] << 4)).astype(np.uint8)
+
+
+# ----------------------------------------------------------------------------
+# large stacks: expert images drawn on the GPU
+# ----------------------------------------------------------------------------
+# With i.i.d. weights the packed image of an expert is itself an i.i.d. array,
+# so the multi-layer workloads (hundreds of experts, ~90 GB) draw each image
+# directly, keyed on (seed, layer, expert), instead of drawing three matrices
+# and packing them.  `unpack_image_bf16` recovers the canonical matrices of an
+# image for the checker: rows of W1 and W3 interleaved ([F][2][H]), then W2
+# ([H][F]).
+
+
+def expert_image_bf16_torch(shape: MoEShape, layer: int, expert: int, seed: int = 0, device: str = "cuda"):
+    """bfloat16 tensor [3*H*F] ~ N(0, 0.02^2): the image of expert (layer, expert)."""
+    import torch
+    g = torch.Generator(device=device)
+    g.manual_seed((int(seed) * 1000003 + int(layer)) * 1009 + int(expert))
+    n = 3 * shape.H * shape.F
+    return (torch.randn(n, device=device, generator=g, dtype=torch.float32) * WEIGHT_STD).to(torch.bfloat16)
+
+
+def router_bf16_torch(shape: MoEShape, layer: int, seed: int = 0, device: str = "cuda"):
+    import torch
+    g = torch.Generator(device=device)
+    g.manual_seed((int(seed) * 1000003 + int(layer)) * 1009 + 977)
+    return (torch.randn((shape.N, shape.H), device=device, generator=g, dtype=torch.float32) * WEIGHT_STD).to(torch.bfloat16)
+
+
+def unpack_image_bf16(bits: np.ndarray, H: int, F: int):
+    """uint16 image [3*H*F] -> (W1[F,H], W3[F,H], W2[H,F]) float32."""
+    gu = bits[: 2 * F * H].reshape(F, 2, H)
+    w2 = bits[2 * F * H:].reshape(H, F)
+    return bf16_to_f32(gu[:, 0, :]), bf16_to_f32(gu[:, 1, :]), bf16_to_f32(w2)

@@ -323,3 +323,105 @@ def test_batched_path(H, F, N, Bt, tau):
         np.testing.assert_array_equal(y2.cpu().numpy(), y)
     finally:
         ls.close()
+
+
+# ---------------------------------------- offloaded stack at the real expert size ----
+
+def test_mixtral_offloaded_stack_full_size():
+    """Mixtral-8x7B-shaped experts (352 MB each) in pinned host memory, 3 layers with
+    2, 1 and 0 cache slots: every layer step is checked against the checker on the
+    GPU's own layer input (teacher forcing), the cache trace by replay."""
+    shape = synth.MoEShape(4096, 14336, 8, 3, "bf16")
+    slots, taus, gamma, n_tok = [2, 1, 0], [0.2, 0.25, 0.3], 0.3, 6
+    ctx, cfg = B.adapmoe_create(shape.H, shape.F, shape.N, shape.L, B.BF16, max_B=1, trace_capacity=4096)
+    nbytes = B.adapmoe_expert_bytes(cfg)
+    host, routers, routers_f32 = {}, [], []
+    unpacked = {}
+
+    def expert_mats(l, e):     # canonical float32 matrices of an image, for the checker
+        if (l, e) not in unpacked:
+            bits = host[(l, e)].view(torch.int16).numpy().view(np.uint16)
+            unpacked[(l, e)] = synth.unpack_image_bf16(bits, shape.H, shape.F)
+        return unpacked[(l, e)]
+
+    try:
+        for l in range(shape.L):
+            r = synth.router_bf16_torch(shape, l, seed=5)
+            routers.append(r)
+            routers_f32.append(r.float().cpu().numpy())
+            B.adapmoe_set_router(ctx, l, r)
+            for e in range(shape.N):
+                img = synth.expert_image_bf16_torch(shape, l, e, seed=5)
+                h = torch.empty(img.numel(), dtype=torch.bfloat16, pin_memory=True)
+                h.copy_(img)
+                host[(l, e)] = h
+                B.adapmoe_register_expert(ctx, l, e, h, nbytes)
+        torch.cuda.synchronize()
+        B.adapmoe_set_tau(ctx, taus)
+        B.cache_alloc(ctx, slots)
+        H0 = synth.ar1_tokens(n_tok, shape.H, 0.8, seed=3, dtype="f32")
+        decisions, max_err = [], 0.0
+        x = torch.empty((1, shape.H), dtype=torch.bfloat16, device="cuda")
+        y = torch.empty((1, shape.H), dtype=torch.float32, device="cuda")
+        for t in range(n_tok):
+            B.adapmoe_set_token(ctx, t)
+            h = torch.from_numpy(H0[t:t + 1].copy()).cuda()
+            for l in range(shape.L):
+                B.moe_residual_rmsnorm(ctx, h, y if l > 0 else None, gamma, x, 1)
+                B.moe_layer_step(ctx, l, x, 1, y)
+                ids, k, pids, pk = B.adapmoe_last_decision(ctx, 1)
+                decisions.append((t, l, ids, k[0], pids, pk[0]))
+                torch.cuda.synchronize()
+                xin = x.float().cpu().numpy()[0].astype(np.float64)
+                ref = OG.adaptive_gate(xin, routers_f32[l], np.float32(taus[l]))
+                zs = np.sort(ref["z"])[::-1]
+                if min(zs[0] - zs[1], zs[1] - zs[2]) > TIE_GAP:
+                    assert tuple(ids) == ref["ids"]
+                    if abs(ref["v"] - taus[l]) > BAND:
+                        assert k[0] == ref["k"]
+                w = (1.0, 0.0) if k[0] == 1 else (ref["alpha"], ref["v"])
+                yref = OE.combine(ids, w, k[0], lambda e: OE.expert_ffn(xin, *expert_mats(l, e)))
+                max_err = max(max_err, float(rel_err_per_token(y.cpu().numpy()[0], yref)))
+        B.adapmoe_check(ctx)
+        print(f"max rel err over {n_tok * shape.L} layer steps: {max_err:.3e}")
+        assert max_err <= TOL["bf16"]
+        sim = _replay_trace(slots, decisions)
+        got = [(t, l, kind, e, v) for (t, l, kind, e, v, _s) in B.adapmoe_trace_read(ctx)]
+        assert got == [tuple(ev) for ev in sim.events]
+        c = B.adapmoe_counters(ctx)
+        s = OC.summarise(sim.events)
+        assert c["h2d_bytes"] == (s["on_demand_loads"] + s["prefetch_loads"]) * nbytes
+    finally:
+        torch.cuda.synchronize()
+        B.adapmoe_destroy(ctx)
+
+
+def test_stack_token_equals_manual_loop():
+    shape = synth.MoEShape(H=512, F=1024, N=8, L=4, dtype="bf16")
+    taus = [0.2, 0.3, 0.25, 0.35]
+    outs = []
+    for mode in ("manual", "stack"):
+        ls = GpuLayerSet(shape, seed=4, max_B=2, trace_capacity=1 << 12, resident=False, taus=taus)
+        try:
+            B.cache_alloc(ls.ctx, [2, 3, 1, 0])
+            H0 = synth.ar1_tokens(8, shape.H, 0.8, seed=9, dtype="f32").reshape(4, 2, shape.H)
+            x = torch.empty((2, shape.H), dtype=torch.bfloat16, device="cuda")
+            y = torch.empty((2, shape.H), dtype=torch.float32, device="cuda")
+            hs = []
+            for t in range(4):
+                h = torch.from_numpy(H0[t].copy()).cuda()
+                if mode == "stack":
+                    B.moe_stack_token(ls.ctx, t, h, x, y, 2, 0.5)
+                else:
+                    B.adapmoe_set_token(ls.ctx, t)
+                    for l in range(shape.L):
+                        B.moe_residual_rmsnorm(ls.ctx, h, y if l > 0 else None, 0.5, x, 2)
+                        B.moe_layer_step(ls.ctx, l, x, 2, y)
+                    B.moe_residual_rmsnorm(ls.ctx, h, y, 0.5, x, 2)
+                B.adapmoe_check(ls.ctx)
+                hs.append(h.cpu().numpy())
+            outs.append((np.stack(hs), B.adapmoe_trace_read(ls.ctx)))
+        finally:
+            ls.close()
+    np.testing.assert_array_equal(outs[0][0], outs[1][0])
+    assert outs[0][1] == outs[1][1]

@@ -234,7 +234,9 @@ int adapmoe_check(adapmoe_ctx* ctx, void* stream);
 /* Kernel timing with HIP events on the launch stream: when on, every launch of
  * the expert-FFN kernels is bracketed by event records.  adapmoe_profile_read
  * synchronises and returns, per kernel class (0 = gate/up GEMV, 1 = down GEMV,
- * 2 = gate), the number of launches and their summed duration in ms, then resets. */
+ * 2 = gate), the number of launches and their summed duration in ms, then resets.
+ * Further classes: 3 bucket/gather, 4 grouped gate/up GEMM, 5 grouped down GEMM
+ * (batched path), 6 fused single-token FFN (gate/up + down in one launch). */
 int adapmoe_profile(adapmoe_ctx* ctx, int on);
 int adapmoe_profile_read(adapmoe_ctx* ctx, int kernel_class, uint64_t* launches, double* total_ms);
 

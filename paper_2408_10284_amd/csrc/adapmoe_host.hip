@@ -7,6 +7,7 @@
 #include <cstdlib>
 #include <cstring>
 #include <deque>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -68,6 +69,8 @@ struct adapmoe_ctx {
   float* d_w = nullptr;                 // [B,2]
   float* d_a = nullptr;                 // [B][2][a_stride]
   ResolvedExperts* d_res = nullptr;     // [B] resolved experts of the last gate of moe_layer_step
+  unsigned* d_fused_counter = nullptr;  // arrival counter of the fused kernel's grid barrier (only grows)
+  unsigned fused_seq = 0;               // fused launches so far
   // batched path scratch (bf16, max_B > 1)
   int32_t* d_bkt_count = nullptr;
   int32_t* d_bkt_tok = nullptr;
@@ -97,6 +100,29 @@ struct adapmoe_ctx {
 };
 
 namespace {
+
+// Two fused kernels must never share the device: each keeps every compute unit
+// until all of its workgroups have arrived at its barrier.  Launches on one
+// stream are ordered anyway; a launch on another stream (or from another
+// context) first waits for everything enqueued so far on the stream of the
+// previous fused launch.
+std::mutex g_fused_mu;
+hipStream_t g_fused_last_stream = nullptr;
+bool g_fused_any = false;
+hipEvent_t g_fused_event = nullptr;
+
+hipError_t fused_serialise(hipStream_t s) {
+  std::lock_guard<std::mutex> lk(g_fused_mu);
+  if (g_fused_any && g_fused_last_stream != s) {
+    hipError_t e;
+    if (!g_fused_event && (e = hipEventCreateWithFlags(&g_fused_event, hipEventDisableTiming)) != hipSuccess) return e;
+    if ((e = hipEventRecord(g_fused_event, g_fused_last_stream)) != hipSuccess) return e;
+    if ((e = hipStreamWaitEvent(s, g_fused_event, 0)) != hipSuccess) return e;
+  }
+  g_fused_any = true;
+  g_fused_last_stream = s;
+  return hipSuccess;
+}
 
 int fail(adapmoe_ctx* c, int code, const std::string& msg) {
   if (c) c->last_error = msg;
@@ -141,8 +167,9 @@ size_t a_stride_for(const adapmoe_config& c) {
 int env_int(const char* name, int dflt) {
   const char* v = getenv(name);
   if (!v || !*v) return dflt;
-  int x = atoi(v);
-  return x > 0 ? x : dflt;
+  char* end = nullptr;
+  long x = strtol(v, &end, 10);
+  return (end != v && x >= 0) ? (int)x : dflt;
 }
 
 void record(adapmoe_ctx* c, int layer, int kind, int expert, int victim, int slot) {
@@ -329,6 +356,18 @@ int launch_ffn(adapmoe_ctx* c, int layer, const void* x, int B, const int32_t* i
     return ADAPMOE_OK;
   }
   FfnArgs p = ffn_args(c, layer, x, B, ids, w, k, y, res);
+  if (B == 1 && res != nullptr && c->lc.fused_blocks > 0) {
+    // residency of the activated experts is established by the caller (moe_layer_step)
+    FusedSync sy{c->d_fused_counter, (c->fused_seq + 1) * (unsigned)c->lc.fused_blocks, 4000000u};
+    HIPCHK(c, fused_serialise(s));
+    {
+      ScopedTimer t(c, 6, s);
+      HIPCHK(c, launch_ffn_fused(p, c->cfg.dtype, sy, c->lc.fused_blocks, s));
+    }
+    c->fused_seq++;
+    c->ctr.ffn_launches++;
+    return ADAPMOE_OK;
+  }
   const bool int4 = c->cfg.dtype == ADAPMOE_INT4G64;
   {
     ScopedTimer t(c, 0, s);
@@ -481,6 +520,7 @@ int adapmoe_create(const adapmoe_config* cfg, adapmoe_ctx** out) {
   c->lc.gateup_blocks = env_int("ADAPMOE_GATEUP_BLOCKS", 1024);
   c->lc.down_blocks = env_int("ADAPMOE_DOWN_BLOCKS", 256);
   c->lc.batch_min = env_int("ADAPMOE_BATCH_MIN", 4);
+  c->lc.fused_blocks = 0;
   const int B = cfg->max_B;
   bool ok = hipSetDevice(cfg->device) == hipSuccess;
   ok = ok && hipMalloc(&c->d_table, LN * sizeof(void*)) == hipSuccess;
@@ -506,6 +546,20 @@ int adapmoe_create(const adapmoe_config* cfg, adapmoe_ctx** out) {
   }
   ok = ok && hipStreamCreateWithFlags(&c->copy_stream, hipStreamNonBlocking) == hipSuccess;
   ok = ok && ffn_kernels_init(cfg->dtype) == hipSuccess;
+  if (ok && cfg->dtype != ADAPMOE_INT4G64 && env_int("ADAPMOE_FUSED", 0) == 1) {
+    // Opt-in (ADAPMOE_FUSED=1): single-token steps run both GEMVs in one launch with a grid-wide
+    // barrier in between.  Measured slower than two launches on MI355X (123 vs 105 us per
+    // Mixtral-shaped step): 256 workgroups each pay an L2 write-back and an L2 invalidate at the
+    // barrier, where a kernel boundary pays one of each for the whole device.
+    int cap = 0;
+    const hipError_t fe = ffn_fused_init(cfg->dtype);
+    if (fe == hipSuccess) cap = ffn_fused_capacity(cfg->dtype, cfg->H, cfg->F, cfg->device);
+    if (getenv("ADAPMOE_VERBOSE")) fprintf(stderr, "adapmoe: fused init %s, capacity %d\n", hipGetErrorString(fe), cap);
+    if (cap > 0 && hipMalloc(&c->d_fused_counter, sizeof(unsigned)) == hipSuccess &&
+        hipMemset(c->d_fused_counter, 0, sizeof(unsigned)) == hipSuccess)
+      c->lc.fused_blocks = cap;
+    (void)hipGetLastError();  // a shape the fused kernel does not take is not an error of the context
+  }
   if (!ok) {
     adapmoe_destroy(c);
     return ADAPMOE_EHIP;
@@ -535,6 +589,7 @@ int adapmoe_destroy(adapmoe_ctx* c) {
   if (c->d_w) hipFree(c->d_w);
   if (c->d_a) hipFree(c->d_a);
   if (c->d_res) hipFree(c->d_res);
+  if (c->d_fused_counter) hipFree(c->d_fused_counter);
   if (c->d_bkt_count) hipFree(c->d_bkt_count);
   if (c->d_bkt_tok) hipFree(c->d_bkt_tok);
   if (c->d_bkt_w) hipFree(c->d_bkt_w);
@@ -936,6 +991,7 @@ int adapmoe_check(adapmoe_ctx* c, void* stream) {
   HIPCHK(c, hipMemcpy(&flags, c->d_err, sizeof(flags), hipMemcpyDeviceToHost));
   if (flags) {
     HIPCHK(c, hipMemset(c->d_err, 0, sizeof(int32_t)));
+    if (flags & 4) return fail(c, ADAPMOE_EHIP, "fused FFN kernel: grid barrier timed out (device shared with another long-running kernel?)");
     if (flags & 2) return fail(c, ADAPMOE_EINVAL, "expert FFN met an expert id out of range");
     return fail(c, ADAPMOE_ENORES, "expert FFN met a non-resident expert");
   }

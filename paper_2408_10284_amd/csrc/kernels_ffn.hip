@@ -10,6 +10,8 @@
 //            (staged in LDS) for every activated expert, summed in a fixed order.
 // Every lane reads 16 bytes per load and a wavefront reads 1 KiB contiguous.
 // No atomics: results are bit-reproducible.
+#include <cstdio>
+#include <cstdlib>
 #include "device_utils.h"
 #include "launch.h"
 #include "stream_parts.h"
@@ -218,6 +220,144 @@ __global__ __launch_bounds__(kDownThreads) void ffn_down_kernel(FfnArgs p) {
   }
 }
 
+// -------------------------------------------------------------------- fused --
+
+// Both GEMVs of one token in a single launch.  The grid is one workgroup of 16
+// wavefronts per compute unit, all co-resident; between the two phases every
+// workgroup passes a grid-wide barrier (a counter in global memory), and the
+// first W2 loads are already in flight while it waits, so the HBM stream does
+// not drain between gate/up and down.  The barrier wait is bounded: a
+// workgroup that does not see all arrivals within `spin_limit` polls raises
+// error bit 2 and goes on, so the kernel always terminates.
+// Requirements checked by the launcher: one token, H row of 8 vector runs,
+// W2 rows a multiple of UN runs, grid <= number of compute units.
+constexpr int kFusedThreads = 1024;
+
+__device__ __forceinline__ void grid_barrier(const FusedSync& sy, int* s_ok, int32_t* err) {
+  __syncthreads();  // this workgroup's a_j stores are issued
+  if (threadIdx.x == 0) {
+    // one thread per workgroup does the cache maintenance: release (write back what the
+    // workgroup stored), arrive, poll without cache maintenance, acquire (drop stale lines
+    // of this compute unit's L1 and this XCD's L2) before the workgroup reads a_j
+    __hip_atomic_fetch_add(sy.counter, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+    unsigned spins = 0;
+    int ok = 1;
+    while ((int)(__hip_atomic_load(sy.counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - sy.target) < 0) {
+      if (++spins > sy.spin_limit) {
+        ok = 0;
+        atomicOr(err, 4);
+        break;
+      }
+      __builtin_amdgcn_s_sleep(1);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    *s_ok = ok;
+  }
+  __syncthreads();
+}
+
+template <bool BF16, int UN>
+__global__ __launch_bounds__(kFusedThreads) void ffn_fused_kernel(FfnArgs p, FusedSync sy) {
+  extern __shared__ uint4 smem[];  // x row, then a[j][F]
+  __shared__ int s_ok;
+  constexpr int NCH = 8;
+  constexpr int kWaves = kFusedThreads / kWave;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const size_t esz = BF16 ? 2 : 4;
+  const int H = p.H, F = p.F;
+
+  const char* base[2];
+  float wj[2];
+  const int kk = resolve_experts(p, 0, base, wj);
+  for (int j = 0; j < kk; ++j)
+    if (base[j] == nullptr) {
+      // flagged by resolve_experts; the same for every workgroup, so nobody waits at the barrier,
+      // but the arrival is still counted to keep the counter in step with the launch number
+      if (tid == 0) __hip_atomic_fetch_add(sy.counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      return;
+    }
+
+  const int first = blockIdx.x * kWaves + wave;
+  const int stride = gridDim.x * kWaves;
+
+  // ---- phase 1: a_j[f] = w_j silu(W1_j[f,:] x) (W3_j[f,:] x)
+  {
+    const size_t row_bytes = (size_t)H * esz;
+    uint4* xs = smem;
+    const uint4* xg = reinterpret_cast<const uint4*>(p.x);
+    auto stage_x = [&]() {
+      for (int i = tid; i < NCH * kWave; i += kFusedThreads) xs[i] = xg[i];
+      __syncthreads();
+    };
+    const int total = kk * F;
+    const int nrows = first < total ? (total - first + stride - 1) / stride : 0;
+    int ra = first, half_a = 0;
+    auto next_addr = [&]() -> const char* {
+      const int j = ra >= F ? 1 : 0;
+      const char* q = base[j] + ((size_t)(ra - j * F) * 2 + half_a) * row_bytes + lane * 16;
+      if (half_a) ra += stride;
+      half_a ^= 1;
+      return q;
+    };
+    int rc = first, half_c = 0;
+    float g = 0.f;
+    auto consume = [&](const uint4(&buf)[NCH]) {
+      const float d = dot_x<BF16, NCH>(buf, xs, 0, lane, 0.f);
+      if (!half_c) {
+        g = d;
+      } else {
+        const float gs = wave_sum(g), us = wave_sum(d);
+        if (lane == 0) p.a[(rc >= F ? p.a_stride - F : 0) + rc] = wj[rc >= F ? 1 : 0] * silu_f32(gs) * us;
+        rc += stride;
+      }
+      half_c ^= 1;
+    };
+    stream_parts<NCH>(2 * nrows, next_addr, consume, stage_x);
+  }
+
+  // ---- phase 2: y[h] = sum_j W2_j[h,:] a_j
+  {
+    const size_t row_bytes = (size_t)F * esz;
+    const int nch = (int)(row_bytes / kChunkBytes);
+    const int F4 = F >> 2, S4 = (int)(p.a_stride >> 2);
+    float4* as4 = reinterpret_cast<float4*>(smem + NCH * kWave);
+    const float4* ag = reinterpret_cast<const float4*>(p.a);
+    auto barrier_and_stage_a = [&]() {
+      grid_barrier(sy, &s_ok, p.err);
+      for (int i = tid; i < kk * F4; i += kFusedThreads) {
+        const int j = i >= F4 ? 1 : 0;
+        const int f4 = i - j * F4;
+        as4[j * F4 + (BF16 ? lds_pos_bf16(f4) : f4)] = ag[j * S4 + f4];
+      }
+      __syncthreads();
+    };
+    const int nbp = nch / UN, nb = kk * nbp;
+    const int nrows = first < H ? (H - first + stride - 1) / stride : 0;
+    const char* w2[2] = {base[0] + p.w2_offset, kk > 1 ? base[1] + p.w2_offset : nullptr};
+    int ha = first, ba = 0;
+    auto next_addr = [&]() -> const char* {
+      const int j = ba >= nbp ? 1 : 0;
+      const char* q = w2[j] + (size_t)ha * row_bytes + (size_t)(ba - j * nbp) * UN * kChunkBytes + lane * 16;
+      if (++ba == nb) { ba = 0; ha += stride; }
+      return q;
+    };
+    int hc = first, bc = 0;
+    float acc = 0.f;
+    auto consume = [&](const uint4(&buf)[UN]) {
+      const int j = bc >= nbp ? 1 : 0;
+      acc = dot_a<BF16, UN>(buf, as4 + j * F4, (bc - j * nbp) * UN, lane, acc);
+      if (++bc == nb) {
+        const float sum = wave_sum(acc);
+        if (lane == 0) p.y[hc] = sum;
+        acc = 0.f;
+        bc = 0;
+        hc += stride;
+      }
+    };
+    stream_parts<UN>(nrows * nb, next_addr, consume, barrier_and_stage_a);
+  }
+}
+
 // ------------------------------------------------------------------ launch ---
 
 template <typename K>
@@ -273,6 +413,61 @@ hipError_t launch_ffn_down(const FfnArgs& p, int dtype, const LaunchCfg& lc, hip
   if (bf16) launch_down_t<true>(p, nch, grid, lds, s);
   else launch_down_t<false>(p, nch, grid, lds, s);
   return hipGetLastError();
+}
+
+// the fused kernel also has a few bytes of static LDS, which count against the 160 KiB
+constexpr size_t kFusedMaxDynLds = 160 * 1024 - 256;
+
+// Fused launch; returns hipErrorNotSupported when the shape does not fit the fused kernel.
+template <bool BF16>
+static hipError_t launch_fused_t(const FfnArgs& p, const FusedSync& sy, int grid_blocks, hipStream_t s) {
+  const size_t esz = BF16 ? 2 : 4;
+  const int nch_up = (int)((size_t)p.H * esz / kChunkBytes);
+  const int nch_dn = (int)((size_t)p.F * esz / kChunkBytes);
+  const size_t lds = (size_t)p.H * esz + (size_t)2 * p.F * sizeof(float);
+  if (p.B != 1 || nch_up != 8 || lds > kFusedMaxDynLds) return hipErrorNotSupported;
+  dim3 grid(grid_blocks), block(kFusedThreads);
+  if (nch_dn % 7 == 0) hipLaunchKernelGGL((ffn_fused_kernel<BF16, 7>), grid, block, lds, s, p, sy);
+  else if (nch_dn % 8 == 0) hipLaunchKernelGGL((ffn_fused_kernel<BF16, 8>), grid, block, lds, s, p, sy);
+  else return hipErrorNotSupported;
+  return hipGetLastError();
+}
+
+hipError_t launch_ffn_fused(const FfnArgs& p, int dtype, const FusedSync& sy, int grid_blocks, hipStream_t s) {
+  return dtype == ADAPMOE_F32 ? launch_fused_t<false>(p, sy, grid_blocks, s) : launch_fused_t<true>(p, sy, grid_blocks, s);
+}
+
+// Number of workgroups of the fused kernel that are guaranteed to be resident at once
+// for this shape (one per compute unit), or 0 if the shape does not fit.
+int ffn_fused_capacity(int dtype, int H, int F, int device) {
+  const bool bf16 = dtype != ADAPMOE_F32;
+  const size_t esz = bf16 ? 2 : 4;
+  const size_t lds = (size_t)H * esz + (size_t)2 * F * sizeof(float);
+  const int nch_up = (int)((size_t)H * esz / kChunkBytes), nch_dn = (int)((size_t)F * esz / kChunkBytes);
+  if (nch_up != 8 || lds > kFusedMaxDynLds || (nch_dn % 7 != 0 && nch_dn % 8 != 0)) return 0;
+  int cus = 0, per_cu = 0;
+  if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess) return 0;
+  const void* k = nch_dn % 7 == 0 ? (bf16 ? reinterpret_cast<const void*>(ffn_fused_kernel<true, 7>) : reinterpret_cast<const void*>(ffn_fused_kernel<false, 7>))
+                                  : (bf16 ? reinterpret_cast<const void*>(ffn_fused_kernel<true, 8>) : reinterpret_cast<const void*>(ffn_fused_kernel<false, 8>));
+  const hipError_t oe = hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, k, kFusedThreads, lds);
+  if (getenv("ADAPMOE_VERBOSE")) fprintf(stderr, "adapmoe: fused occupancy query %s: %d per CU, %d CUs, lds %zu\n", hipGetErrorString(oe), per_cu, cus, lds);
+  if (oe != hipSuccess || per_cu < 1) return 0;
+  return cus;
+}
+
+template <typename K>
+static hipError_t allow_fused_lds(K kernel) {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFusedMaxDynLds);
+}
+
+hipError_t ffn_fused_init(int dtype) {
+  hipError_t e;
+  if (dtype == ADAPMOE_F32) {
+    if ((e = allow_fused_lds(ffn_fused_kernel<false, 7>)) != hipSuccess) return e;
+    return allow_fused_lds(ffn_fused_kernel<false, 8>);
+  }
+  if ((e = allow_fused_lds(ffn_fused_kernel<true, 7>)) != hipSuccess) return e;
+  return allow_fused_lds(ffn_fused_kernel<true, 8>);
 }
 
 }  // namespace adapmoe

@@ -65,16 +65,28 @@ struct BatchArgs {
   uint16_t* a_lo;            //                                      low part
 };
 
+// Grid-wide barrier of the fused FFN kernel: a counter that only grows; launch n
+// waits until it reaches n * grid size.
+struct FusedSync {
+  unsigned* counter;
+  unsigned target;
+  unsigned spin_limit;
+};
+
 struct LaunchCfg {
   int gateup_blocks;  // workgroups of the gate/up GEMV (256 threads each)
   int down_blocks;    // workgroups of the down GEMV (1024 threads each)
   int batch_min;      // smallest number of tokens per call that takes the batched (MFMA) path
+  int fused_blocks;   // workgroups of the fused single-token FFN kernel (0 = fused path off)
 };
 
 hipError_t launch_gate(const GateArgs& a, bool bf16, int routers, hipStream_t s);
 hipError_t launch_ffn_gateup(const FfnArgs& p, int dtype, const LaunchCfg& lc, hipStream_t s);
 hipError_t launch_ffn_down(const FfnArgs& p, int dtype, const LaunchCfg& lc, hipStream_t s);
 hipError_t ffn_kernels_init(int dtype);
+hipError_t ffn_fused_init(int dtype);
+int ffn_fused_capacity(int dtype, int H, int F, int device);
+hipError_t launch_ffn_fused(const FfnArgs& p, int dtype, const FusedSync& sy, int grid_blocks, hipStream_t s);
 hipError_t launch_ffn_gateup_int4(const FfnArgs& p, const LaunchCfg& lc, hipStream_t s);
 hipError_t launch_ffn_down_int4(const FfnArgs& p, const LaunchCfg& lc, hipStream_t s);
 hipError_t batched_kernels_init();

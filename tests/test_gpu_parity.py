@@ -425,3 +425,42 @@ def test_stack_token_equals_manual_loop():
             ls.close()
     np.testing.assert_array_equal(outs[0][0], outs[1][0])
     assert outs[0][1] == outs[1][1]
+
+
+# ------------------------------------------------ fused single-token kernel ----
+
+@pytest.mark.parametrize("dtype,H,F", [("bf16", 4096, 3584), ("bf16", 4096, 4096), ("f32", 2048, 1792)])
+def test_fused_single_token_kernel_equals_two_kernel_path(dtype, H, F):
+    """With ADAPMOE_FUSED=1, moe_layer_step with one token runs gate/up and down in
+    one launch (grid-wide barrier in between); the sums are taken in the same order
+    as in the two-kernel path, so the outputs are bit-identical."""
+    import os
+    shape = synth.MoEShape(H=H, F=F, N=8, L=1, dtype=dtype)
+    os.environ["ADAPMOE_FUSED"] = "1"      # the fused kernel is opt-in (read when the context is created)
+    try:
+        ls = GpuLayerSet(shape, seed=2, max_B=1, taus=[0.3])
+    finally:
+        del os.environ["ADAPMOE_FUSED"]
+    try:
+        X = synth.ar1_tokens(12, H, 0.8, seed=6, dtype=dtype)
+        g = run_gate(ls, 0, X)
+        assert 2 in g["k"]
+        y_two = run_ffn(ls, 0, g)
+        y = torch.empty((12, H), dtype=torch.float32, device="cuda")
+        c0 = B.adapmoe_counters(ls.ctx)
+        for rep in range(3):        # repeated launches: the barrier counter keeps growing
+            for t in range(12):
+                B.moe_layer_step(ls.ctx, 0, g["x_dev"][t:t + 1], 1, y[t:t + 1])
+            B.adapmoe_check(ls.ctx)
+            np.testing.assert_array_equal(y.cpu().numpy(), y_two)
+        Yref = OE.moe_block_rows(X, ls.experts_f32[0], g["ids"], g["w"].astype(np.float64), g["k"])
+        assert rel_err_per_token(y.cpu().numpy(), Yref).max() <= TOL[dtype]
+        # the fused kernel was really the one that ran
+        B.adapmoe_profile(ls.ctx, True)
+        B.moe_layer_step(ls.ctx, 0, g["x_dev"][0:1], 1, y[0:1])
+        torch.cuda.synchronize()
+        n_fused, _ = B.adapmoe_profile_read(ls.ctx, 6)
+        B.adapmoe_profile(ls.ctx, False)
+        assert n_fused == 1
+    finally:
+        ls.close()

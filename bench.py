@@ -178,6 +178,7 @@ def bench_layer(args):
 
     cpu = cpu_baseline_layer(args, shape, X, wg, experts, tau, dt == B.INT4G64) if args.cpu_seconds > 0 else None
     gu_name = "ffn_gateup_int4_kernel" if dt == B.INT4G64 else "ffn_gateup_kernel"
+    traffic = measured_traffic(gu_name) if args.workload == "mixtral_layer_bf16" else None
     out = {
         "metric": METRIC, "value": round(steps / elapsed, 2), "unit": "tokens/s (one MoE layer, batch 1)",
         "n_gpus": 1, "steps": steps, "warmup": warmup,
@@ -189,7 +190,7 @@ def bench_layer(args):
                    "mean_k": round(float(ks.mean()), 4), "single_expert_ratio": round(float((ks == 1).mean()), 4),
                    "expert_bytes": nbytes, "setup_s": round(t_setup, 1)},
         "roofline": {"bound": "hbm", "kernel": gu_name, "achieved": round(gu_gbs, 1), "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": round(gu_gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                     "unit": "GB/s", "frac": round(gu_gbs / HBM_PEAK_GBS, 4), "traffic": traffic,
                      "avg_us": round(ms_gu / max(n_gu, 1) * 1e3, 2), "launches": n_gu,
                      "bytes_per_launch": round(bytes_gu / max(n_gu, 1))},
         "kernels": {"down": {"achieved_GBs": round(dn_gbs, 1), "frac": round(dn_gbs / HBM_PEAK_GBS, 4),
@@ -203,6 +204,21 @@ def bench_layer(args):
     torch.cuda.synchronize()
     B.adapmoe_destroy(ctx)
     return out
+
+
+def measured_traffic(kernel):
+    """HBM bytes per launch (read + write) of `kernel` from the committed rocprofv3 --pmc summary
+    of this workload (FETCH_SIZE and WRITE_SIZE scaled by a plain copy), or None."""
+    path = os.path.join(ROOT, "profiles", "pmc_traffic.json")
+    try:
+        with open(path) as f:
+            data = json.load(f)
+        for name, v in data["kernels"].items():
+            if kernel + "<" in name or kernel + "(" in name:
+                return round(v["fetch_bytes_per_launch"] + v["write_bytes_per_launch"])
+    except (OSError, KeyError, ValueError):
+        pass
+    return None
 
 
 def cpu_baseline_layer(args, shape, X, wg, experts, tau, int4):

@@ -517,7 +517,7 @@ int adapmoe_create(const adapmoe_config* cfg, adapmoe_ctx** out) {
   c->bound.assign(LN, nullptr);
   c->bound_count.assign(cfg->L, 0);
   c->layers.resize(cfg->L);
-  c->lc.gateup_blocks = env_int("ADAPMOE_GATEUP_BLOCKS", 1024);
+  c->lc.gateup_blocks = env_int("ADAPMOE_GATEUP_BLOCKS", cfg->dtype == ADAPMOE_INT4G64 ? 1024 : 512);  // measured best on MI355X
   c->lc.down_blocks = env_int("ADAPMOE_DOWN_BLOCKS", 256);
   c->lc.batch_min = env_int("ADAPMOE_BATCH_MIN", 4);
   c->lc.fused_blocks = 0;

@@ -15,6 +15,7 @@
 //
 // Operand order: for reduction step s (32 elements) lane l = 16 q + n holds the
 // 8 elements k = 32 s + 8 q + i of token column n.
+#include <cstdlib>
 #include "../../include/adapmoe.h"
 #include "stream_parts.h"
 
@@ -122,13 +123,15 @@ struct WSlab {
 template <int KS>
 constexpr int wtile_row_bytes() { return KS * 64 + 16; }
 
-template <int KS, int NMAT, int NTERM>
+// DB = 2: the token operand slab is double-buffered in LDS (one barrier per slab instead of two;
+// measured 5 % slower on MI355X for the down GEMM, so both GEMMs use DB = 1)
+template <int KS, int NMAT, int NTERM, int NW, int DB>
 constexpr size_t grouped_lds_bytes() {
-  return (size_t)KS * 64 * NTERM * 16 + (size_t)kBWaves * NMAT * 16 * wtile_row_bytes<KS>();
+  return (size_t)DB * KS * 64 * NTERM * 16 + (size_t)NW * NMAT * 16 * wtile_row_bytes<KS>();
 }
 
 // RT = row tiles of 16 per wavefront (they share the token operand and the LDS tile).
-template <int KS, int NMAT, int NTERM, int RT, class Epilogue>
+template <int KS, int NMAT, int NTERM, int RT, int NW, int DB, class Epilogue>
 __device__ __forceinline__ void grouped_gemm_tile_loop(const char* wbase, size_t row_stride, size_t mat_stride, int nsteps,
                                                        int ntiles_rows, int tile0, int tile_stride,
                                                        const uint4* bop0, const uint4* bop1, uint4* lds, Epilogue epilogue) {
@@ -136,15 +139,17 @@ __device__ __forceinline__ void grouped_gemm_tile_loop(const char* wbase, size_t
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int m = lane & 15, q = lane >> 4;
   const int nslabs = nsteps / KS;
+  constexpr int kThreads = NW * kWave;
   constexpr int kSlabVecs = KS * 64 * NTERM;            // 16-byte vectors of one operand slab
-  constexpr int kVecsPerThread = kSlabVecs / kBThreads;
+  constexpr int kVecsPerThread = kSlabVecs / kThreads;
+  static_assert(kSlabVecs % kThreads == 0, "operand slab must divide evenly over the workgroup");
   constexpr int kRowB = wtile_row_bytes<KS>();
-  char* wt = reinterpret_cast<char*>(lds + kSlabVecs) + (size_t)wave * NMAT * 16 * kRowB;   // this wavefront's tile(s)
+  char* wt = reinterpret_cast<char*>(lds + DB * kSlabVecs) + (size_t)wave * NMAT * 16 * kRowB;   // this wavefront's tile(s)
   char* wt_store = wt + (lane >> 5) * kRowB + (lane & 31) * 16;    // where this lane's loaded pieces go (row 2i + lane/32)
   const char* wt_read = wt + m * kRowB + q * 16;                   // operand read: row m, bytes 64 s + 16 q
 
   for (int tile = tile0; tile < ntiles_rows; tile += tile_stride) {
-    const int row0 = (tile * kBWaves + wave) * 16 * RT;
+    const int row0 = (tile * NW + wave) * 16 * RT;
     const char* wsrc = wbase + (size_t)(row0 + (lane >> 5)) * row_stride + (lane & 31) * 16;
     f32x4_t acc[RT][NMAT];
 #pragma unroll
@@ -168,16 +173,19 @@ __device__ __forceinline__ void grouped_gemm_tile_loop(const char* wbase, size_t
     auto fetch_operand = [&](int slab) {
 #pragma unroll
       for (int v = 0; v < kVecsPerThread; ++v) {
-        const int idx = v * kBThreads + tid;              // vector index inside the slab: [term][step][lane]
+        const int idx = v * kThreads + tid;                // vector index inside the slab: [term][step][lane]
         const int term = idx / (KS * 64), r = idx - term * (KS * 64);
         const uint4* src = term == 0 ? bop0 : bop1;
         stage[v] = src[(size_t)slab * KS * 64 + r];
       }
     };
     auto consume = [&](const WSlab<NMAT, RT>& buf) {
-      __syncthreads();                                    // everyone is done with the previous slab in LDS
+      // single buffer: wait until everyone is done with the previous slab; double buffer: the
+      // other half was last read two slabs ago and every wavefront has passed a barrier since
+      uint4* bslab = lds + (DB == 2 ? (sc & 1) * kSlabVecs : 0);
+      if (DB == 1) __syncthreads();
 #pragma unroll
-      for (int v = 0; v < kVecsPerThread; ++v) lds[v * kBThreads + tid] = stage[v];
+      for (int v = 0; v < kVecsPerThread; ++v) bslab[v * kThreads + tid] = stage[v];
       __syncthreads();
       if (sc + 1 < nslabs) fetch_operand(sc + 1);
 #pragma unroll
@@ -195,7 +203,7 @@ __device__ __forceinline__ void grouped_gemm_tile_loop(const char* wbase, size_t
           for (int t = 0; t < NMAT; ++t) a[t] = *reinterpret_cast<const uint4*>(wt_read + (size_t)t * 16 * kRowB + s * 64);
 #pragma unroll
           for (int term = 0; term < NTERM; ++term) {
-            const uint4 b = lds[(term * KS + s) * 64 + lane];
+            const uint4 b = bslab[(term * KS + s) * 64 + lane];
 #pragma unroll
             for (int t = 0; t < NMAT; ++t) acc[rt][t] = mfma16(a[t], b, acc[rt][t]);
           }
@@ -240,13 +248,13 @@ __global__ __launch_bounds__(kBThreads) void grouped_gateup_mfma_kernel(BatchArg
     *reinterpret_cast<uint2*>(alo + pos) = make_uint2(lo[0] | ((uint32_t)lo[1] << 16), lo[2] | ((uint32_t)lo[3] << 16));
   };
   const uint4* xop = reinterpret_cast<const uint4*>(p.xop) + (size_t)e * (p.H / 32) * 64;
-  grouped_gemm_tile_loop<KS, 2, 1, 1>(base, 2 * row_bytes, row_bytes, p.H / 32, p.F / (16 * kBWaves), blockIdx.x, gridDim.x,
+  grouped_gemm_tile_loop<KS, 2, 1, 1, kBWaves, 1>(base, 2 * row_bytes, row_bytes, p.H / 32, p.F / (16 * kBWaves), blockIdx.x, gridDim.x,
                                    xop, xop, lds, epilogue);
 }
 
 // down: rows h of W2, reduction over F, result added into y of the bucket's tokens
-template <int KS>
-__global__ __launch_bounds__(kBThreads) void grouped_down_mfma_kernel(BatchArgs p) {
+template <int KS, int RT, int NW>
+__global__ __launch_bounds__(NW * kWave) void grouped_down_mfma_kernel(BatchArgs p) {
   extern __shared__ uint4 lds[];
   const int e = blockIdx.y;
   const int cnt = p.bkt_count[e];
@@ -264,7 +272,7 @@ __global__ __launch_bounds__(kBThreads) void grouped_down_mfma_kernel(BatchArgs 
   };
   const uint4* ahi = reinterpret_cast<const uint4*>(p.a_hi) + (size_t)e * (p.F / 32) * 64;
   const uint4* alo = reinterpret_cast<const uint4*>(p.a_lo) + (size_t)e * (p.F / 32) * 64;
-  grouped_gemm_tile_loop<KS, 1, 2, kDownRT>(base, (size_t)p.F * 2, 0, p.F / 32, p.H / (16 * kBWaves * kDownRT), blockIdx.x, gridDim.x, ahi, alo, lds,
+  grouped_gemm_tile_loop<KS, 1, 2, RT, NW, 1>(base, (size_t)p.F * 2, 0, p.F / 32, p.H / (16 * NW * RT), blockIdx.x, gridDim.x, ahi, alo, lds,
                                    epilogue);
 }
 
@@ -277,7 +285,10 @@ hipError_t batched_kernels_init() {
   hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(grouped_gateup_mfma_kernel<kGateUpKS>),
                                      hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
   if (e != hipSuccess) return e;
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(grouped_down_mfma_kernel<kDownKS>),
+  e = hipFuncSetAttribute(reinterpret_cast<const void*>(grouped_down_mfma_kernel<kDownKS, 2, 4>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+  if (e != hipSuccess) return e;
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(grouped_down_mfma_kernel<kDownKS, 1, 8>),
                              hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
 }
 
@@ -289,15 +300,23 @@ hipError_t launch_bucket_gather(const BatchArgs& p, hipStream_t s) {
 
 hipError_t launch_grouped_gateup(const BatchArgs& p, hipStream_t s) {
   dim3 grid(p.F / (16 * kBWaves), p.N), block(kBThreads);
-  constexpr size_t lds = grouped_lds_bytes<kGateUpKS, 2, 1>();
+  constexpr size_t lds = grouped_lds_bytes<kGateUpKS, 2, 1, kBWaves, 1>();
   hipLaunchKernelGGL(grouped_gateup_mfma_kernel<kGateUpKS>, grid, block, lds, s, p);
   return hipGetLastError();
 }
 
 hipError_t launch_grouped_down(const BatchArgs& p, hipStream_t s) {
-  dim3 grid(p.H / (16 * kBWaves * kDownRT), p.N), block(kBThreads);
-  constexpr size_t lds = grouped_lds_bytes<kDownKS, 1, 2>();
-  hipLaunchKernelGGL(grouped_down_mfma_kernel<kDownKS>, grid, block, lds, s, p);
+  // 8 wavefronts x 16 rows per workgroup measured 3 % faster than 4 x 32 (ADAPMOE_BDOWN_WIDE=0 selects the latter)
+  static const bool wide = getenv("ADAPMOE_BDOWN_WIDE") == nullptr || atoi(getenv("ADAPMOE_BDOWN_WIDE")) != 0;
+  if (wide) {
+    dim3 grid(p.H / 128, p.N), block(512);
+    constexpr size_t lds = grouped_lds_bytes<kDownKS, 1, 2, 8, 1>();
+    hipLaunchKernelGGL((grouped_down_mfma_kernel<kDownKS, 1, 8>), grid, block, lds, s, p);
+  } else {
+    dim3 grid(p.H / 128, p.N), block(256);
+    constexpr size_t lds = grouped_lds_bytes<kDownKS, 1, 2, 4, 1>();
+    hipLaunchKernelGGL((grouped_down_mfma_kernel<kDownKS, 2, 4>), grid, block, lds, s, p);
+  }
   return hipGetLastError();
 }
 

@@ -46,6 +46,7 @@ def parse():
                     choices=["mixtral_layer_bf16", "mixtral_layer_int4", "tiny_f32", "mixtral_stack_offload", "mixtral_batched"])
     ap.add_argument("--layers", type=int, default=None, help="layers of the stack workloads (default: offload 14, batched 32)")
     ap.add_argument("--cache", type=int, default=None, help="total cache slots of the offload workload (default 2 per layer)")
+    ap.add_argument("--dtype", default="bf16", choices=["bf16", "int4"], help="expert storage of the offload workload")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference kernel for the HBM byte counters)")
     return ap.parse_args()
@@ -265,9 +266,12 @@ def build_stack(shape, seed, keep_on_device, pin_host):
         routers.append(synth.router_bf16_torch(shape, l, seed))
         drow, hrow = [], []
         for e in range(shape.N):
-            img = synth.expert_image_bf16_torch(shape, l, e, seed)
+            if shape.dtype == "int4g64":
+                img = synth.expert_image_int4_torch(shape, l, e, seed)
+            else:
+                img = synth.expert_image_bf16_torch(shape, l, e, seed)
             if pin_host:
-                h = torch.empty(img.numel(), dtype=torch.bfloat16, pin_memory=True)
+                h = torch.empty(img.numel(), dtype=img.dtype, pin_memory=True)
                 h.copy_(img)
                 hrow.append(h)
             if keep_on_device:
@@ -287,7 +291,7 @@ def profile_gate_statistics(shape, routers, images_dev, taus, h0, gamma):
 
     from paper_2408_10284_amd import binding as B
     L, N, H = shape.L, shape.N, shape.H
-    ctx, cfg = B.adapmoe_create(H, shape.F, N, L, B.BF16, max_B=1)
+    ctx, cfg = B.adapmoe_create(H, shape.F, N, L, B.INT4G64 if shape.dtype == "int4g64" else B.BF16, max_B=1)
     try:
         for l in range(L):
             B.adapmoe_set_router(ctx, l, routers[l])
@@ -346,11 +350,13 @@ def bench_stack_offload(args):
     from paper_2408_10284_amd import synth
 
     # The test machines pin at most ~46 GB of host memory (hipHostMalloc fails beyond), so the
-    # default is 14 layers = 112 experts = 39.5 GB with the cache-to-experts ratio of the 32-layer
-    # workload (2 slots per layer, 25 %); --layers 32 needs a box that can pin 90 GB.
-    L = args.layers or 14
-    shape = synth.MoEShape(4096, 14336, 8, L, "bf16")
-    C = args.cache if args.cache is not None else 2 * L
+    # bf16 default is 14 layers = 112 experts = 39.5 GB with the cache-to-experts ratio of the 32-layer
+    # workload (2 slots per layer, 25 %); --layers 32 needs a box that can pin 90 GB.  The int4
+    # workload (25.4 GB) runs all 32 layers with 128 slots.
+    int4 = args.dtype == "int4"
+    L = args.layers or (32 if int4 else 14)
+    shape = synth.MoEShape(4096, 14336, 8, L, "int4g64" if int4 else "bf16")
+    C = args.cache if args.cache is not None else (4 * L if int4 else 2 * L)
     steps = args.steps if args.steps is not None else 48
     warmup = args.warmup if args.warmup is not None else 16
     gamma = 0.3
@@ -363,7 +369,7 @@ def bench_stack_offload(args):
     del images_dev
     torch.cuda.empty_cache()
 
-    ctx, cfg = B.adapmoe_create(shape.H, shape.F, shape.N, L, B.BF16, max_B=1, trace_capacity=0)
+    ctx, cfg = B.adapmoe_create(shape.H, shape.F, shape.N, L, B.INT4G64 if int4 else B.BF16, max_B=1, trace_capacity=0)
     nbytes = B.adapmoe_expert_bytes(cfg)
     for l in range(L):
         B.adapmoe_set_router(ctx, l, routers[l])
@@ -400,7 +406,7 @@ def bench_stack_offload(args):
     torch.cuda.synchronize()
     r0 = time.perf_counter()
     for i in range(8):
-        buf.view(torch.bfloat16).copy_(images_host[i % L][i % shape.N], non_blocking=True)
+        buf.view(images_host[0][0].dtype).copy_(images_host[i % L][i % shape.N], non_blocking=True)
     torch.cuda.synchronize()
     link_gbs = 8 * nbytes / (time.perf_counter() - r0) / 1e9
 
@@ -408,8 +414,8 @@ def bench_stack_offload(args):
         "metric": METRIC, "value": round(steps / elapsed, 3), "unit": f"tokens/s ({L}-layer stack, batch 1, offloaded experts)",
         "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(elapsed / steps * 1e3, 3),
         "us_per_layer": round(elapsed / steps / L * 1e6, 1),
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
-        "config": {"workload": f"mixtral_stack_offload: H=4096 F=14336 N=8 L={L}, {L * 8} experts ({L * 8 * nbytes / 1e9:.1f} GB) in pinned "
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
+        "config": {"workload": f"mixtral_stack_offload ({args.dtype}): H=4096 F=14336 N=8 L={L}, {L * 8} experts ({L * 8 * nbytes / 1e9:.1f} GB) in pinned "
                                f"host memory, cache of {C} slots sized by the planner, LRU + next-layer prefetch, gamma={gamma}",
                    "slots_per_layer": slots, "planner_cost": round(plan_cost, 4),
                    "a_l_mean": round(float(a.mean()), 4), "beta_l_mean": round(float(beta[1:].mean()), 4) if L > 1 else None,

@@ -202,3 +202,103 @@ def unpack_image_bf16(bits: np.ndarray, H: int, F: int):
     gu = bits[: 2 * F * H].reshape(F, 2, H)
     w2 = bits[2 * F * H:].reshape(H, F)
     return bf16_to_f32(gu[:, 0, :]), bf16_to_f32(gu[:, 1, :]), bf16_to_f32(w2)
+
+
+# ----------------------------------------------------------------------------
+# int4 images on the GPU (same storage format and row layout as the library's
+# host-side packer; used where hundreds of experts have to be prepared)
+# ----------------------------------------------------------------------------
+
+
+def quantize_int4_g64_torch(w):
+    """torch version of `quantize_int4_g64` (same float32 arithmetic): float32
+    [rows, cols] -> (codes uint8 [rows, cols], scale fp16 [rows, cols/64], zero fp16)."""
+    import torch
+    rows, cols = w.shape
+    g = w.reshape(rows, cols // INT4_GROUP, INT4_GROUP).to(torch.float32)
+    lo = g.amin(dim=2)
+    hi = g.amax(dim=2)
+    zero = lo.to(torch.float16)
+    scale = ((hi - lo) / 15.0).to(torch.float16)
+    z32 = zero.to(torch.float32).unsqueeze(2)
+    s32 = scale.to(torch.float32).unsqueeze(2)
+    q = torch.round((g - z32) / s32)
+    q = torch.where(s32 > 0, q, torch.zeros_like(q))
+    q = q.clamp_(0.0, 15.0).to(torch.uint8)
+    return q.reshape(rows, cols), scale, zero
+
+
+def _int4_rows_torch(q, scale, zero):
+    """codes [rows, n] + scale/zero [rows, n/64] -> uint8 [rows, n/2 + n/16] in the streaming row
+    format: blocks of up to 64 groups stored as [first 16 bytes of every group][second 16 bytes];
+    inside a dword nibble s (s < 4) is element 2s and nibble s+4 is element 2s+1; then
+    (scale, zero) per group."""
+    import torch
+    rows, n = q.shape
+    G = n // INT4_GROUP
+    e = q.reshape(rows, G, 2, 4, 8)                      # [row][group][half][dword][element]
+    by = torch.stack([e[..., 0] | (e[..., 2] << 4), e[..., 4] | (e[..., 6] << 4),
+                      e[..., 1] | (e[..., 3] << 4), e[..., 5] | (e[..., 7] << 4)], dim=-1)   # 4 bytes per dword
+    by = by.reshape(rows, G, 2, 16)
+    parts = []
+    full = (G // 64) * 64
+    if full:
+        parts.append(by[:, :full].reshape(rows, full // 64, 64, 2, 16).permute(0, 1, 3, 2, 4).reshape(rows, -1))
+    if G > full:
+        parts.append(by[:, full:].permute(0, 2, 1, 3).reshape(rows, -1))
+    sz = torch.stack([scale.view(torch.int16), zero.view(torch.int16)], dim=-1).contiguous().view(torch.uint8).reshape(rows, G * 4)
+    return torch.cat(parts + [sz], dim=1)
+
+
+def int4_image_from_weights_torch(w1, w3, w2):
+    """float32 W1[F,H], W3[F,H], W2[H,F] (torch) -> uint8 image in the library's int4 layout
+    (rows of W1 and W3 interleaved, then rows of W2)."""
+    import torch
+    r1 = _int4_rows_torch(*quantize_int4_g64_torch(w1))
+    r3 = _int4_rows_torch(*quantize_int4_g64_torch(w3))
+    r2 = _int4_rows_torch(*quantize_int4_g64_torch(w2))
+    gu = torch.stack([r1, r3], dim=1).reshape(-1)
+    return torch.cat([gu, r2.reshape(-1)])
+
+
+def expert_image_int4_torch(shape: MoEShape, layer: int, expert: int, seed: int = 0, device: str = "cuda"):
+    """int4 image of expert (layer, expert): bf16 N(0, 0.02^2) weights drawn on the device, quantised
+    round-to-nearest per group of 64 and packed."""
+    import torch
+    g = torch.Generator(device=device)
+    g.manual_seed((int(seed) * 1000003 + int(layer)) * 1009 + int(expert))
+    H, F = shape.H, shape.F
+    mats = []
+    for (r, c) in ((F, H), (F, H), (H, F)):
+        w = (torch.randn((r, c), device=device, generator=g, dtype=torch.float32) * WEIGHT_STD).to(torch.bfloat16).to(torch.float32)
+        mats.append(w)
+    return int4_image_from_weights_torch(*mats)
+
+
+def decode_int4_image(img: np.ndarray, H: int, F: int):
+    """uint8 int4 image -> per matrix (codes [rows, n], scale fp16, zero fp16) for W1, W3, W2,
+    reading the documented row format (the inverse of the packers; input preparation for the checker)."""
+    def rows_of(buf, rows, n):
+        G = n // INT4_GROUP
+        rb = n // 2 + n // 16
+        a = buf.reshape(rows, rb)
+        codes = np.empty((rows, n), dtype=np.uint8)
+        for blk in range((G + 63) // 64):
+            nb = min(64, G - blk * 64)
+            blkb = a[:, blk * 2048: blk * 2048 + nb * 32].reshape(rows, 2, nb, 4, 4)      # [half][group][dword][byte]
+            # bytes of a dword: (e0|e2<<4), (e4|e6<<4), (e1|e3<<4), (e5|e7<<4)
+            el = np.empty((rows, 2, nb, 4, 8), dtype=np.uint8)
+            el[..., 0], el[..., 2] = blkb[..., 0] & 15, blkb[..., 0] >> 4
+            el[..., 4], el[..., 6] = blkb[..., 1] & 15, blkb[..., 1] >> 4
+            el[..., 1], el[..., 3] = blkb[..., 2] & 15, blkb[..., 2] >> 4
+            el[..., 5], el[..., 7] = blkb[..., 3] & 15, blkb[..., 3] >> 4
+            codes[:, blk * 4096: blk * 4096 + nb * 64] = el.transpose(0, 2, 1, 3, 4).reshape(rows, nb * 64)
+        sz = np.ascontiguousarray(a[:, n // 2:]).view(np.uint16).reshape(rows, G, 2)
+        return codes, sz[..., 0].copy().view(np.float16), sz[..., 1].copy().view(np.float16)
+
+    rbH = H // 2 + H // 16
+    gu = img[: 2 * F * rbH].reshape(F, 2, rbH)
+    m1 = rows_of(np.ascontiguousarray(gu[:, 0]), F, H)
+    m3 = rows_of(np.ascontiguousarray(gu[:, 1]), F, H)
+    m2 = rows_of(img[2 * F * rbH:], H, F)
+    return m1, m3, m2

@@ -145,3 +145,23 @@ def test_pack_int4_layout(lib):
         np.testing.assert_array_equal(z, mats[2][2][h])
     # Mixtral-shaped int4 expert: 9/16 byte per weight
     assert B.adapmoe_expert_bytes(B.Config(4096, 14336, 8, 32, B.INT4G64, 1, 0, 0)) == 99090432
+
+
+def test_int4_image_generators_match_library_packer(lib):
+    """The torch-side quantiser/packer used for large stacks produces byte-identical images to
+    quantize_int4_g64 + adapmoe_pack_expert_int4, and decode_int4_image inverts both."""
+    import torch
+    from paper_2408_10284_amd import synth
+    H, F = 512, 4352
+    cfg = B.Config(H, F, 2, 1, B.INT4G64, 1, 0, 0)
+    rng = np.random.default_rng(3)
+    ws = [synth.bf16_round((rng.standard_normal(s) * 0.02).astype(np.float32)) for s in ((F, H), (F, H), (H, F))]
+    qs = [synth.quantize_int4_g64(w) for w in ws]
+    ref = np.zeros(B.adapmoe_expert_bytes(cfg), dtype=np.uint8)
+    B.adapmoe_pack_expert_int4(cfg, *[a for (q, s, z) in qs for a in (q, s.view(np.uint16), z.view(np.uint16))], ref)
+    img = synth.int4_image_from_weights_torch(*[torch.from_numpy(w) for w in ws]).numpy()
+    np.testing.assert_array_equal(img, ref)
+    for got, (q, s, z) in zip(synth.decode_int4_image(ref, H, F), qs):
+        np.testing.assert_array_equal(got[0], q)
+        np.testing.assert_array_equal(got[1].view(np.uint16), s.view(np.uint16))
+        np.testing.assert_array_equal(got[2].view(np.uint16), z.view(np.uint16))

@@ -197,9 +197,10 @@ def _replay_trace(slots, decisions):
     return c
 
 
-@pytest.mark.parametrize("slots", [[2, 3, 1, 0], [8, 8, 8, 8], [1, 1, 1, 1], [0, 2, 0, 4]])
-def test_offloaded_stack_trace_and_outputs(slots):
-    shape = synth.MoEShape(H=512, F=1024, N=8, L=4, dtype="bf16")
+@pytest.mark.parametrize("dtype,slots", [("bf16", [2, 3, 1, 0]), ("bf16", [8, 8, 8, 8]), ("bf16", [1, 1, 1, 1]), ("bf16", [0, 2, 0, 4]),
+                                         ("int4g64", [2, 3, 1, 0]), ("int4g64", [4, 4, 4, 4])])
+def test_offloaded_stack_trace_and_outputs(dtype, slots):
+    shape = synth.MoEShape(H=512, F=1024, N=8, L=4, dtype=dtype)
     taus = [0.2, 0.3, 0.25, 0.35]
     ls = GpuLayerSet(shape, seed=4, max_B=1, trace_capacity=1 << 16, resident=False, taus=taus)
     try:
@@ -237,7 +238,7 @@ def test_offloaded_stack_trace_and_outputs(slots):
                 max_err = max(max_err, float(rel_err_per_token(y.cpu().numpy()[0], yref)))
                 B.moe_residual_rmsnorm(ls.ctx, h, y, gamma, x, 1)
         B.adapmoe_check(ls.ctx)
-        assert max_err <= TOL["bf16"], max_err
+        assert max_err <= TOL[dtype], max_err
         sim = _replay_trace(slots, decisions)
         got = [(t, l, kind, e, v) for (t, l, kind, e, v, _slot) in B.adapmoe_trace_read(ls.ctx)]
         assert got == [tuple(ev) for ev in sim.events]

@@ -339,6 +339,7 @@ int launch_ffn(adapmoe_ctx* c, int layer, const void* x, int B, const int32_t* i
       q.xop = c->d_xop;
       q.a_hi = c->d_ahi;
       q.a_lo = c->d_alo;
+      q.two_terms = c->lc.batch_two_terms;
       {
         ScopedTimer t(c, 3, s);
         HIPCHK(c, launch_bucket_gather(q, s));
@@ -349,7 +350,7 @@ int launch_ffn(adapmoe_ctx* c, int layer, const void* x, int B, const int32_t* i
       }
       {
         ScopedTimer t(c, 5, s);
-        HIPCHK(c, launch_grouped_down(q, s));
+        HIPCHK(c, launch_grouped_down(q, c->lc.batch_two_terms != 0, s));
       }
     }
     c->ctr.ffn_launches++;
@@ -520,6 +521,7 @@ int adapmoe_create(const adapmoe_config* cfg, adapmoe_ctx** out) {
   c->lc.gateup_blocks = env_int("ADAPMOE_GATEUP_BLOCKS", cfg->dtype == ADAPMOE_INT4G64 ? 1024 : 512);  // measured best on MI355X
   c->lc.down_blocks = env_int("ADAPMOE_DOWN_BLOCKS", 256);
   c->lc.batch_min = env_int("ADAPMOE_BATCH_MIN", 4);
+  c->lc.batch_two_terms = env_int("ADAPMOE_BATCH_TWO_TERMS", 0);
   c->lc.fused_blocks = 0;
   const int B = cfg->max_B;
   bool ok = hipSetDevice(cfg->device) == hipSuccess;

@@ -115,9 +115,10 @@ __global__ __launch_bounds__(kBThreads) void bucket_gather_kernel(BatchArgs p) {
 // wavefront-private LDS tile whose rows are padded by 16 bytes so that the
 // operand reads (16 rows x 16 bytes per pass) hit all banks once.
 // Token operand: staged in LDS slab by slab by the whole workgroup.
-template <int NMAT, int RT>
+template <int NMAT, int RT, int NB>
 struct WSlab {
   uint4 a[NMAT][RT][8];   // instruction i of matrix t, row tile rt: rows 16 rt + 2i, 16 rt + 2i + 1
+  uint4 b[NB > 0 ? NB : 1];  // DIRECT mode: the lane's token-operand vectors of the slab, [term][step]
 };
 
 template <int KS>
@@ -129,6 +130,8 @@ template <int KS, int NMAT, int NTERM, int NW, int DB>
 constexpr size_t grouped_lds_bytes() {
   return (size_t)DB * KS * 64 * NTERM * 16 + (size_t)NW * NMAT * 16 * wtile_row_bytes<KS>();
 }
+// DIRECT mode (DB = 0): no operand slab in LDS, every wavefront loads its operand vectors itself
+// (1 KiB contiguous per instruction, served by L2) and runs without workgroup barriers.
 
 // RT = row tiles of 16 per wavefront (they share the token operand and the LDS tile).
 template <int KS, int NMAT, int NTERM, int RT, int NW, int DB, class Epilogue>
@@ -157,8 +160,10 @@ __device__ __forceinline__ void grouped_gemm_tile_loop(const char* wbase, size_t
 #pragma unroll
       for (int t = 0; t < NMAT; ++t) acc[rt][t] = f32x4_t{0.f, 0.f, 0.f, 0.f};
 
+    constexpr bool DIRECT = DB == 0;
+    using Slab = WSlab<NMAT, RT, DIRECT ? NTERM * KS : 0>;
     int sa = 0;
-    auto load_next = [&](WSlab<NMAT, RT>& buf) {
+    auto load_next = [&](Slab& buf) {
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
@@ -166,6 +171,12 @@ __device__ __forceinline__ void grouped_gemm_tile_loop(const char* wbase, size_t
 #pragma unroll
           for (int i = 0; i < 8; ++i)
             buf.a[t][rt][i] = load_stream16(wsrc + t * mat_stride + (size_t)(16 * rt + 2 * i) * row_stride + (size_t)sa * KS * 64);
+      if constexpr (DIRECT) {
+#pragma unroll
+        for (int term = 0; term < NTERM; ++term)
+#pragma unroll
+          for (int s = 0; s < KS; ++s) buf.b[term * KS + s] = (term == 0 ? bop0 : bop1)[((size_t)sa * KS + s) * 64 + lane];
+      }
       ++sa;
     };
     int sc = 0;
@@ -179,15 +190,17 @@ __device__ __forceinline__ void grouped_gemm_tile_loop(const char* wbase, size_t
         stage[v] = src[(size_t)slab * KS * 64 + r];
       }
     };
-    auto consume = [&](const WSlab<NMAT, RT>& buf) {
+    auto consume = [&](const Slab& buf) {
       // single buffer: wait until everyone is done with the previous slab; double buffer: the
       // other half was last read two slabs ago and every wavefront has passed a barrier since
       uint4* bslab = lds + (DB == 2 ? (sc & 1) * kSlabVecs : 0);
-      if (DB == 1) __syncthreads();
+      if constexpr (!DIRECT) {
+        if (DB == 1) __syncthreads();
 #pragma unroll
-      for (int v = 0; v < kVecsPerThread; ++v) bslab[v * kThreads + tid] = stage[v];
-      __syncthreads();
-      if (sc + 1 < nslabs) fetch_operand(sc + 1);
+        for (int v = 0; v < kVecsPerThread; ++v) bslab[v * kThreads + tid] = stage[v];
+        __syncthreads();
+        if (sc + 1 < nslabs) fetch_operand(sc + 1);
+      }
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt) {
         // the wavefront's own LDS tile: written and read by this wavefront only, program order suffices
@@ -203,7 +216,7 @@ __device__ __forceinline__ void grouped_gemm_tile_loop(const char* wbase, size_t
           for (int t = 0; t < NMAT; ++t) a[t] = *reinterpret_cast<const uint4*>(wt_read + (size_t)t * 16 * kRowB + s * 64);
 #pragma unroll
           for (int term = 0; term < NTERM; ++term) {
-            const uint4 b = bslab[(term * KS + s) * 64 + lane];
+            const uint4 b = DIRECT ? buf.b[term * KS + s] : bslab[(term * KS + s) * 64 + lane];
 #pragma unroll
             for (int t = 0; t < NMAT; ++t) acc[rt][t] = mfma16(a[t], b, acc[rt][t]);
           }
@@ -211,15 +224,15 @@ __device__ __forceinline__ void grouped_gemm_tile_loop(const char* wbase, size_t
       }
       ++sc;
     };
-    fetch_operand(0);
-    stream_bufs<WSlab<NMAT, RT>>(nslabs, load_next, consume, [] {});
+    if constexpr (!DIRECT) fetch_operand(0);
+    stream_bufs<Slab>(nslabs, load_next, consume, [] {});
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) epilogue(row0 + 16 * rt, acc[rt]);
   }
 }
 
 // gate/up: rows f of W1 and W3 (interleaved in the image), reduction over H
-template <int KS>
+template <int KS, int DB>
 __global__ __launch_bounds__(kBThreads) void grouped_gateup_mfma_kernel(BatchArgs p) {
   extern __shared__ uint4 lds[];
   const int e = blockIdx.y;
@@ -238,9 +251,14 @@ __global__ __launch_bounds__(kBThreads) void grouped_gateup_mfma_kernel(BatchArg
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       const float v = wn * silu_f32(acc[0][r]) * acc[1][r];
-      const uint32_t h = __builtin_bit_cast(uint32_t, v) & 0xffff0000u;   // truncated high part, v - hi is exact
-      hi[r] = (uint16_t)(h >> 16);
-      lo[r] = f32_to_bf16_bits(v - __builtin_bit_cast(float, h));
+      if (p.two_terms) {
+        const uint32_t h = __builtin_bit_cast(uint32_t, v) & 0xffff0000u;   // truncated high part, v - hi is exact
+        hi[r] = (uint16_t)(h >> 16);
+        lo[r] = f32_to_bf16_bits(v - __builtin_bit_cast(float, h));
+      } else {
+        hi[r] = f32_to_bf16_bits(v);   // single term: round to nearest
+        lo[r] = 0;
+      }
     }
     const int f = f0 + 4 * q;                              // first of the lane's four consecutive rows
     const size_t pos = ((size_t)(f >> 5) * 64 + ((f >> 3) & 3) * 16 + n) * 8 + (f & 7);
@@ -248,12 +266,12 @@ __global__ __launch_bounds__(kBThreads) void grouped_gateup_mfma_kernel(BatchArg
     *reinterpret_cast<uint2*>(alo + pos) = make_uint2(lo[0] | ((uint32_t)lo[1] << 16), lo[2] | ((uint32_t)lo[3] << 16));
   };
   const uint4* xop = reinterpret_cast<const uint4*>(p.xop) + (size_t)e * (p.H / 32) * 64;
-  grouped_gemm_tile_loop<KS, 2, 1, 1, kBWaves, 1>(base, 2 * row_bytes, row_bytes, p.H / 32, p.F / (16 * kBWaves), blockIdx.x, gridDim.x,
+  grouped_gemm_tile_loop<KS, 2, 1, 1, kBWaves, DB>(base, 2 * row_bytes, row_bytes, p.H / 32, p.F / (16 * kBWaves), blockIdx.x, gridDim.x,
                                    xop, xop, lds, epilogue);
 }
 
 // down: rows h of W2, reduction over F, result added into y of the bucket's tokens
-template <int KS, int RT, int NW>
+template <int KS, int RT, int NW, int NTERM>
 __global__ __launch_bounds__(NW * kWave) void grouped_down_mfma_kernel(BatchArgs p) {
   extern __shared__ uint4 lds[];
   const int e = blockIdx.y;
@@ -272,7 +290,7 @@ __global__ __launch_bounds__(NW * kWave) void grouped_down_mfma_kernel(BatchArgs
   };
   const uint4* ahi = reinterpret_cast<const uint4*>(p.a_hi) + (size_t)e * (p.F / 32) * 64;
   const uint4* alo = reinterpret_cast<const uint4*>(p.a_lo) + (size_t)e * (p.F / 32) * 64;
-  grouped_gemm_tile_loop<KS, 1, 2, RT, NW, 1>(base, (size_t)p.F * 2, 0, p.F / 32, p.H / (16 * NW * RT), blockIdx.x, gridDim.x, ahi, alo, lds,
+  grouped_gemm_tile_loop<KS, 1, NTERM, RT, NW, 1>(base, (size_t)p.F * 2, 0, p.F / 32, p.H / (16 * NW * RT), blockIdx.x, gridDim.x, ahi, alo, lds,
                                    epilogue);
 }
 
@@ -281,15 +299,22 @@ __global__ __launch_bounds__(NW * kWave) void grouped_down_mfma_kernel(BatchArgs
 constexpr int kGateUpKS = 8;
 constexpr int kDownKS = 8;
 
+template <typename K>
+static hipError_t big_lds(K k) {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(k), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+}
+
 hipError_t batched_kernels_init() {
-  hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(grouped_gateup_mfma_kernel<kGateUpKS>),
-                                     hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-  if (e != hipSuccess) return e;
-  e = hipFuncSetAttribute(reinterpret_cast<const void*>(grouped_down_mfma_kernel<kDownKS, 2, 4>),
-                          hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
-  if (e != hipSuccess) return e;
-  return hipFuncSetAttribute(reinterpret_cast<const void*>(grouped_down_mfma_kernel<kDownKS, 1, 8>),
-                             hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
+  hipError_t e;
+  if ((e = big_lds(grouped_gateup_mfma_kernel<kGateUpKS, 1>)) != hipSuccess) return e;
+  if ((e = big_lds(grouped_gateup_mfma_kernel<kGateUpKS, 0>)) != hipSuccess) return e;
+  if ((e = big_lds(grouped_down_mfma_kernel<kDownKS, 1, 8, 2>)) != hipSuccess) return e;
+  return big_lds(grouped_down_mfma_kernel<kDownKS, 1, 8, 1>);
+}
+
+static int env_flag(const char* name, int dflt) {
+  const char* v = getenv(name);
+  return (v && *v) ? atoi(v) : dflt;
 }
 
 hipError_t launch_bucket_gather(const BatchArgs& p, hipStream_t s) {
@@ -299,23 +324,31 @@ hipError_t launch_bucket_gather(const BatchArgs& p, hipStream_t s) {
 }
 
 hipError_t launch_grouped_gateup(const BatchArgs& p, hipStream_t s) {
+  // gate/up: every wavefront loads its own operand vectors (no workgroup barriers), measured 10 %
+  // faster than staging them per workgroup; ADAPMOE_BDIRECT=0 selects the staged variant
+  static const int direct = env_flag("ADAPMOE_BDIRECT", 1);
   dim3 grid(p.F / (16 * kBWaves), p.N), block(kBThreads);
-  constexpr size_t lds = grouped_lds_bytes<kGateUpKS, 2, 1, kBWaves, 1>();
-  hipLaunchKernelGGL(grouped_gateup_mfma_kernel<kGateUpKS>, grid, block, lds, s, p);
+  if (direct) {
+    constexpr size_t lds = grouped_lds_bytes<kGateUpKS, 2, 1, kBWaves, 0>();
+    hipLaunchKernelGGL((grouped_gateup_mfma_kernel<kGateUpKS, 0>), grid, block, lds, s, p);
+  } else {
+    constexpr size_t lds = grouped_lds_bytes<kGateUpKS, 2, 1, kBWaves, 1>();
+    hipLaunchKernelGGL((grouped_gateup_mfma_kernel<kGateUpKS, 1>), grid, block, lds, s, p);
+  }
   return hipGetLastError();
 }
 
-hipError_t launch_grouped_down(const BatchArgs& p, hipStream_t s) {
-  // 8 wavefronts x 16 rows per workgroup measured 3 % faster than 4 x 32 (ADAPMOE_BDOWN_WIDE=0 selects the latter)
-  static const bool wide = getenv("ADAPMOE_BDOWN_WIDE") == nullptr || atoi(getenv("ADAPMOE_BDOWN_WIDE")) != 0;
-  if (wide) {
-    dim3 grid(p.H / 128, p.N), block(512);
+// down: 8 wavefronts x 16 rows per workgroup, operand slab staged in LDS (the barrier-free variant
+// and 4 x 32 rows measured slower here).  `two_terms` multiplies by A = hi + lo (fp32 accuracy);
+// otherwise by A rounded to bfloat16 only.
+hipError_t launch_grouped_down(const BatchArgs& p, bool two_terms, hipStream_t s) {
+  dim3 grid(p.H / 128, p.N), block(512);
+  if (two_terms) {
     constexpr size_t lds = grouped_lds_bytes<kDownKS, 1, 2, 8, 1>();
-    hipLaunchKernelGGL((grouped_down_mfma_kernel<kDownKS, 1, 8>), grid, block, lds, s, p);
+    hipLaunchKernelGGL((grouped_down_mfma_kernel<kDownKS, 1, 8, 2>), grid, block, lds, s, p);
   } else {
-    dim3 grid(p.H / 128, p.N), block(256);
-    constexpr size_t lds = grouped_lds_bytes<kDownKS, 1, 2, 4, 1>();
-    hipLaunchKernelGGL((grouped_down_mfma_kernel<kDownKS, 2, 4>), grid, block, lds, s, p);
+    constexpr size_t lds = grouped_lds_bytes<kDownKS, 1, 1, 8, 1>();
+    hipLaunchKernelGGL((grouped_down_mfma_kernel<kDownKS, 1, 8, 1>), grid, block, lds, s, p);
   }
   return hipGetLastError();
 }

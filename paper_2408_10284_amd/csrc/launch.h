@@ -63,6 +63,7 @@ struct BatchArgs {
   uint16_t* xop;             // [N][H/32][64][8] x of the bucket's tokens in MFMA operand order
   uint16_t* a_hi;            // [N][F/32][64][8] A in operand order, high bfloat16 part
   uint16_t* a_lo;            //                                      low part
+  int two_terms;             // 1: A = hi + lo (fp32 accuracy), 0: A rounded to bfloat16
 };
 
 // Grid-wide barrier of the fused FFN kernel: a counter that only grows; launch n
@@ -77,6 +78,7 @@ struct LaunchCfg {
   int gateup_blocks;  // workgroups of the gate/up GEMV (256 threads each)
   int down_blocks;    // workgroups of the down GEMV (1024 threads each)
   int batch_min;      // smallest number of tokens per call that takes the batched (MFMA) path
+  int batch_two_terms;  // batched path: intermediate activation as hi + lo bfloat16 (1) or bfloat16 only (0)
   int fused_blocks;   // workgroups of the fused single-token FFN kernel (0 = fused path off)
 };
 
@@ -92,7 +94,7 @@ hipError_t launch_ffn_down_int4(const FfnArgs& p, const LaunchCfg& lc, hipStream
 hipError_t batched_kernels_init();
 hipError_t launch_bucket_gather(const BatchArgs& p, hipStream_t s);
 hipError_t launch_grouped_gateup(const BatchArgs& p, hipStream_t s);
-hipError_t launch_grouped_down(const BatchArgs& p, hipStream_t s);
+hipError_t launch_grouped_down(const BatchArgs& p, bool two_terms, hipStream_t s);
 hipError_t launch_residual_rmsnorm(float* h, const float* y, float gamma, void* x, bool bf16, int B, int H, hipStream_t s);
 
 struct PokeArgs {   // up to 8 pointer-sized stores, ordered on the stream

@@ -289,6 +289,7 @@ def test_mixtral_layer_full_size():
 
 # ------------------------------------------------ batched path (MFMA grouped GEMM) ----
 
+@pytest.mark.parametrize("two_terms", [0, 1])
 @pytest.mark.parametrize("H,F,N,Bt,tau", [
     (512, 512, 8, 16, 0.25),     # one slab of x, smallest shapes
     (1024, 1536, 8, 16, 0.25),   # several row tiles and slabs
@@ -297,9 +298,17 @@ def test_mixtral_layer_full_size():
     (1024, 1024, 16, 13, 0.5),   # threshold 1/2: one expert per token, many empty buckets
     (512, 1024, 8, 40, 0.25),    # more than 16 tokens: processed in groups of 16
 ])
-def test_batched_path(H, F, N, Bt, tau):
+def test_batched_path(H, F, N, Bt, tau, two_terms):
+    """Several tokens per call: grouped GEMM on the matrix cores.  By default the intermediate
+    activation is rounded to bfloat16 before the down GEMM (as a bf16 model does); with
+    ADAPMOE_BATCH_TWO_TERMS=1 it is carried as hi + lo and matches the per-token path to 1e-4."""
+    import os
     shape = synth.MoEShape(H=H, F=F, N=N, L=1, dtype="bf16")
-    ls = GpuLayerSet(shape, seed=7, max_B=Bt, taus=[tau])
+    os.environ["ADAPMOE_BATCH_TWO_TERMS"] = str(two_terms)
+    try:
+        ls = GpuLayerSet(shape, seed=7, max_B=Bt, taus=[tau])
+    finally:
+        del os.environ["ADAPMOE_BATCH_TWO_TERMS"]
     try:
         X = synth.ar1_tokens(Bt, H, 0.5, seed=11, dtype="bf16")
         g = run_gate(ls, 0, X)
@@ -309,14 +318,13 @@ def test_batched_path(H, F, N, Bt, tau):
         Yref = OE.moe_block_rows(X, ls.experts_f32[0], g["ids"], g["w"].astype(np.float64), g["k"])
         err = rel_err_per_token(y, Yref)
         assert err.max() <= TOL["bf16"], err.max()
-        # the per-token GEMV path gives the same numbers up to summation order and the
-        # two-term bfloat16 split of the intermediate activation
         y1 = torch.empty((Bt, H), dtype=torch.float32, device="cuda")
         for t in range(Bt):
             B.moe_expert_ffn(ls.ctx, 0, g["x_dev"][t:t + 1], 1, g["ids_dev"][t:t + 1], g["w_dev"][t:t + 1], g["k_dev"][t:t + 1], y1[t:t + 1])
         B.adapmoe_check(ls.ctx)
         d = rel_err_per_token(y, y1.cpu().numpy())
-        assert d.max() <= 1e-4, d.max()
+        print(f"two_terms={two_terms}: max rel err vs checker {err.max():.2e}, vs per-token path {d.max():.2e}")
+        assert d.max() <= (1e-4 if two_terms else 4e-3), d.max()
         # layer_step with the same batch takes the same path
         y2 = torch.empty((Bt, H), dtype=torch.float32, device="cuda")
         B.moe_layer_step(ls.ctx, 0, g["x_dev"], Bt, y2)

@@ -218,6 +218,16 @@ int moe_residual_rmsnorm(adapmoe_ctx* ctx, float* h_dev, const float* y_dev, flo
  * float are work buffers owned by the caller.  Sets the trace token to `token`. */
 int moe_stack_token(adapmoe_ctx* ctx, int token, float* h_dev, void* x_dev, float* y_dev, int B, float gamma, void* stream);
 
+/* Look-ahead depth of moe_layer_step, 1..3 (default 1) (Sec. 4.3, prefetch beyond the next layer).
+ * With depth D the gate launch also applies the routers of layers l+2 .. l+D to the
+ * same input.  The prediction for layer l+d (d >= 2) is acted on only when every
+ * expert predicted for layer l+d-1 was already resident (its prefetch issued no
+ * transfer); the first depth that needs a transfer ends the look-ahead of this step.
+ * Returns ADAPMOE_EINVAL outside 1..3. */
+int adapmoe_set_lookahead(adapmoe_ctx* ctx, int depth);
+/* Prediction of depth d (1..3) of the last moe_layer_step on a non-bound layer. */
+int adapmoe_last_lookahead(adapmoe_ctx* ctx, int depth, int32_t* pred_ids, int32_t* pred_k, int B);
+
 /* ---- bookkeeping ------------------------------------------------------------- */
 
 int adapmoe_set_token(adapmoe_ctx* ctx, int token);

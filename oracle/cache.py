@@ -16,7 +16,11 @@ readings taken here:
     used after evicting the least recently used entry if the layer is full;
   * a layer with zero slots never holds anything: its demand misses are
     "bypass" loads and nothing is prefetched for it;
-  * at most min(k_hat, slots) predicted experts are prefetched, in rank order.
+  * at most min(k_hat, slots) predicted experts are prefetched, in rank order;
+  * look-ahead beyond the next layer (Sec. 4.3): the predictions for layers
+    l+1, l+2, ... are served in that order, and the one for layer l+d+1 is
+    served only if serving layer l+d loaded nothing (all its predicted experts
+    were resident; a layer without slots loads nothing either).
 
 Events are tuples (token, layer, kind, expert, victim) with victim = -1 when
 nothing was evicted.
@@ -96,6 +100,19 @@ class ExpertCache:
                 ev = (token, layer, PF_LOAD, e, victim)
             out.append(ev)
         self.events.extend(out)
+        return out
+
+    def prefetch_lookahead(self, token, layer, preds):
+        """preds[d-1] = experts predicted for layer+d (d = 1, 2, ...).  Depth d+1 is served only when
+        depth d found everything resident."""
+        out = []
+        for d, r in enumerate(preds, start=1):
+            if layer + d >= len(self.layers):
+                break
+            evs = self.prefetch(token, layer + d, r)
+            out.extend(evs)
+            if any(ev[2] == PF_LOAD for ev in evs):
+                break
         return out
 
     def resident(self, layer):

@@ -31,15 +31,17 @@ def rmsnorm(h):
 
 
 def run_stack(h0, routers, taus, expert_out, gamma, store=lambda a: a, cache=None,
-              collect_x=False):
+              collect_x=False, depth=1):
     """Run tokens h0[n] through L layers.
 
     routers[l]            W_g of layer l, [N,H]
     taus[l]               threshold of layer l
     expert_out(l, e, x)   E_e^{(l)}(x), float64 [H]
     cache                 optional oracle.cache.ExpertCache driven alongside
-    Returns dict of per (token, layer): ids, k, w, v, pred (list), h (block input
-    residual, [n,L+1,H]) and, if collect_x, x [n,L,H].
+    depth                 look-ahead: layers l+1 .. l+depth are predicted from x_l (Sec. 4.3)
+    Returns dict of per (token, layer): ids, k, w, v, pred (pred[n][l] = list predicted for
+    layer l by layer l-1), ahead (ahead[n][l][d-1] = list predicted at layer l for layer l+d),
+    h (block input residual, [n,L+1,H]) and, if collect_x, x [n,L,H].
     """
     n_tok = len(h0)
     L = len(routers)
@@ -50,6 +52,7 @@ def run_stack(h0, routers, taus, expert_out, gamma, store=lambda a: a, cache=Non
     vs = np.zeros((n_tok, L), F64)
     gap23 = np.zeros((n_tok, L), F64)
     preds = [[[] for _ in range(L)] for _ in range(n_tok)]   # preds[n][l] = predicted FOR layer l
+    ahead = [[[] for _ in range(L)] for _ in range(n_tok)]
     hs = np.zeros((n_tok, L + 1, H), F64)
     xs = np.zeros((n_tok, L, H), F64) if collect_x else None
     for n in range(n_tok):
@@ -63,17 +66,16 @@ def run_stack(h0, routers, taus, expert_out, gamma, store=lambda a: a, cache=Non
             ids[n, l], ks[n, l], ws[n, l], vs[n, l] = g["ids"], g["k"], g["w"], g["v"]
             zs = np.sort(g["z"])[::-1]
             gap23[n, l] = zs[1] - zs[2] if len(zs) > 2 else np.inf
-            r = []
-            if l + 1 < L:
-                r = G.predict_next(x, routers[l + 1], taus[l + 1])
-                preds[n][l + 1] = r
+            rs = [G.predict_next(x, routers[l + d], taus[l + d]) for d in range(1, depth + 1) if l + d < L]
+            ahead[n][l] = rs
+            if rs:
+                preds[n][l + 1] = rs[0]
             if cache is not None:
                 cache.demand(n, l, g["ids"], g["k"])
-                if l + 1 < L:
-                    cache.prefetch(n, l + 1, r)
+                cache.prefetch_lookahead(n, l, rs)
             y = np.zeros(H, F64)
             for j in range(g["k"]):
                 y += F64(g["w"][j]) * expert_out(l, int(g["ids"][j]), x)
             h = h + F64(gamma) * y
         hs[n, L] = h
-    return dict(ids=ids, k=ks, w=ws, v=vs, gap23=gap23, pred=preds, h=hs, x=xs)
+    return dict(ids=ids, k=ks, w=ws, v=vs, gap23=gap23, pred=preds, ahead=ahead, h=hs, x=xs)

@@ -65,6 +65,8 @@ _SIGS = {
     "moe_layer_step": (C.c_int, [_P, C.c_int, _P, C.c_int, _P, _P]),
     "moe_residual_rmsnorm": (C.c_int, [_P, _P, _P, C.c_float, _P, C.c_int, _P]),
     "moe_stack_token": (C.c_int, [_P, C.c_int, _P, _P, _P, C.c_int, C.c_float, _P]),
+    "adapmoe_set_lookahead": (C.c_int, [_P, C.c_int]),
+    "adapmoe_last_lookahead": (C.c_int, [_P, C.c_int, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_int]),
     "adapmoe_set_token": (C.c_int, [_P, C.c_int]),
     "adapmoe_trace_read": (C.c_int, [_P, C.POINTER(Event), C.c_size_t, C.POINTER(C.c_size_t)]),
     "adapmoe_counters": (C.c_int, [_P, C.POINTER(Counters)]),
@@ -215,6 +217,17 @@ def moe_residual_rmsnorm(ctx, h, y, gamma, x, B, stream=None):
 
 def moe_stack_token(ctx, token, h, x, y, B, gamma, stream=None):
     _chk(ctx, load().moe_stack_token(ctx, token, _ptr(h), _ptr(x), _ptr(y), B, float(gamma), _stream(stream)))
+
+
+def adapmoe_set_lookahead(ctx, depth):
+    _chk(ctx, load().adapmoe_set_lookahead(ctx, depth))
+
+
+def adapmoe_last_lookahead(ctx, depth, B):
+    pids = (C.c_int32 * (2 * B))()
+    pk = (C.c_int32 * B)()
+    _chk(ctx, load().adapmoe_last_lookahead(ctx, depth, pids, pk, B))
+    return list(pids), list(pk)
 
 
 def adapmoe_set_token(ctx, token):

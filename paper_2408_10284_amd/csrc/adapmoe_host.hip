@@ -65,7 +65,8 @@ struct adapmoe_ctx {
   std::vector<int> bound_count;         // [L]
   const void** d_table = nullptr;       // [L*N] device
   int32_t* d_err = nullptr;
-  int32_t* d_dec = nullptr;             // ids[2B] k[B] pred_ids[2B] pred_k[B]
+  int32_t* d_dec = nullptr;             // ids[2B] k[B], then per look-ahead depth d = 1..3: pred_ids[2B] pred_k[B]
+  int lookahead = 1;                    // layers ahead that are predicted and prefetched (Sec. 4.3)
   float* d_w = nullptr;                 // [B,2]
   float* d_a = nullptr;                 // [B][2][a_stride]
   ResolvedExperts* d_res = nullptr;     // [B] resolved experts of the last gate of moe_layer_step
@@ -382,8 +383,10 @@ int launch_ffn(adapmoe_ctx* c, int layer, const void* x, int B, const int32_t* i
   return ADAPMOE_OK;
 }
 
-int launch_gate_both(adapmoe_ctx* c, int layer, const void* x, int B, int32_t* ids, float* w, int32_t* k, int32_t* pids,
-                     int32_t* pk, hipStream_t s, ResolvedExperts* res = nullptr) {
+// Gate of `layer` plus, for depth d = 1..depth, the gate of layer+d on the same input (prediction).
+// pred[d-1] = {ids, k} output pointers of depth d.
+int launch_gate_both(adapmoe_ctx* c, int layer, const void* x, int B, int32_t* ids, float* w, int32_t* k,
+                     int depth, int32_t* const* pred_ids, int32_t* const* pred_k, hipStream_t s, ResolvedExperts* res = nullptr) {
   if (!c->router[layer]) return fail(c, ADAPMOE_ESTATE, "router of this layer not set");
   GateArgs g{};
   g.x = x;
@@ -397,17 +400,15 @@ int launch_gate_both(adapmoe_ctx* c, int layer, const void* x, int B, int32_t* i
   g.w = w;
   g.res = res;
   g.table = c->d_table + (size_t)layer * c->cfg.N;
-  int routers = 1;
-  if (pids && pk) {
-    routers = 2;
-    const bool has_next = layer + 1 < c->cfg.L && c->router[layer + 1];
-    g.Wg[1] = has_next ? c->router[layer + 1] : nullptr;
-    g.tau[1] = has_next ? c->tau[layer + 1] : 0.f;
-    g.ids[1] = pids;
-    g.k[1] = pk;
+  for (int d = 1; d <= depth; ++d) {
+    const bool has = layer + d < c->cfg.L && c->router[layer + d];
+    g.Wg[d] = has ? c->router[layer + d] : nullptr;
+    g.tau[d] = has ? c->tau[layer + d] : 0.f;
+    g.ids[d] = pred_ids[d - 1];
+    g.k[d] = pred_k[d - 1];
   }
   ScopedTimer t(c, 2, s);
-  HIPCHK(c, launch_gate(g, c->bf16_act, routers, s));
+  HIPCHK(c, launch_gate(g, c->bf16_act, 1 + depth, s));
   return ADAPMOE_OK;
 }
 
@@ -529,12 +530,12 @@ int adapmoe_create(const adapmoe_config* cfg, adapmoe_ctx** out) {
   ok = ok && hipMemset(c->d_table, 0, LN * sizeof(void*)) == hipSuccess;
   ok = ok && hipMalloc(&c->d_err, sizeof(int32_t)) == hipSuccess;
   ok = ok && hipMemset(c->d_err, 0, sizeof(int32_t)) == hipSuccess;
-  ok = ok && hipMalloc(&c->d_dec, (size_t)6 * B * sizeof(int32_t)) == hipSuccess;
+  ok = ok && hipMalloc(&c->d_dec, (size_t)12 * B * sizeof(int32_t)) == hipSuccess;
   ok = ok && hipMalloc(&c->d_w, (size_t)2 * B * sizeof(float)) == hipSuccess;
   ok = ok && hipMalloc(&c->d_a, (size_t)2 * B * a_stride_for(*cfg) * sizeof(float)) == hipSuccess;
   ok = ok && hipMalloc(&c->d_res, (size_t)B * sizeof(ResolvedExperts)) == hipSuccess;
   ok = ok && hipMemset(c->d_res, 0, (size_t)B * sizeof(ResolvedExperts)) == hipSuccess;
-  ok = ok && hipHostMalloc(reinterpret_cast<void**>(&c->h_dec), (size_t)6 * B * sizeof(int32_t), hipHostMallocDefault) == hipSuccess;
+  ok = ok && hipHostMalloc(reinterpret_cast<void**>(&c->h_dec), (size_t)12 * B * sizeof(int32_t), hipHostMallocDefault) == hipSuccess;
   if (cfg->dtype == ADAPMOE_BF16 && B > 1) {
     const size_t N = cfg->N;
     ok = ok && hipMalloc(&c->d_bkt_count, N * sizeof(int32_t)) == hipSuccess;
@@ -743,7 +744,9 @@ int moe_gate(adapmoe_ctx* c, int layer, const void* x, int B, int32_t* ids, floa
   if (!c || layer < 0 || layer >= c->cfg.L || !x || !ids || !w || !k || B < 1 || B > c->cfg.max_B)
     return fail(c, ADAPMOE_EINVAL, "moe_gate: bad argument");
   if ((pred_ids == nullptr) != (pred_k == nullptr)) return fail(c, ADAPMOE_EINVAL, "moe_gate: give both prediction outputs or neither");
-  return launch_gate_both(c, layer, x, B, ids, w, k, pred_ids, pred_k, static_cast<hipStream_t>(stream));
+  int32_t* pi[1] = {pred_ids};
+  int32_t* pk[1] = {pred_k};
+  return launch_gate_both(c, layer, x, B, ids, w, k, pred_ids ? 1 : 0, pi, pk, static_cast<hipStream_t>(stream));
 }
 
 int moe_expert_ffn(adapmoe_ctx* c, int layer, const void* x, int B, const int32_t* ids, const float* w, const int32_t* k,
@@ -784,13 +787,13 @@ int moe_layer_step(adapmoe_ctx* c, int layer, const void* x, int B, float* y, vo
   const int N = c->cfg.N;
   int32_t* d_ids = c->d_dec;
   int32_t* d_k = c->d_dec + 2 * B;
-  int32_t* d_pids = c->d_dec + 3 * B;
-  int32_t* d_pk = c->d_dec + 5 * B;
+  int32_t* d_pids[3] = {c->d_dec + 3 * B, c->d_dec + 6 * B, c->d_dec + 9 * B};
+  int32_t* d_pk[3] = {c->d_dec + 5 * B, c->d_dec + 8 * B, c->d_dec + 11 * B};
   const bool next_needs_host = layer + 1 < c->cfg.L && !layer_fully_bound(c, layer + 1) && c->cache_ready;
   const bool host_path = !layer_fully_bound(c, layer) || next_needs_host;
 
-  int rc = launch_gate_both(c, layer, x, B, d_ids, c->d_w, d_k, host_path ? d_pids : nullptr, host_path ? d_pk : nullptr, s,
-                            c->d_res);
+  const int depth = host_path ? c->lookahead : 0;
+  int rc = launch_gate_both(c, layer, x, B, d_ids, c->d_w, d_k, depth, d_pids, d_pk, s, c->d_res);
   if (rc) return rc;
   c->ctr.tokens_gated += B;
 
@@ -802,12 +805,10 @@ int moe_layer_step(adapmoe_ctx* c, int layer, const void* x, int B, float* y, vo
   if (!c->cache_ready && !layer_fully_bound(c, layer)) return fail(c, ADAPMOE_ESTATE, "moe_layer_step: cache not allocated");
 
   // Alg.1: the host needs E and r to decide what to transfer
-  HIPCHK(c, hipMemcpyAsync(c->h_dec, c->d_dec, (size_t)6 * B * sizeof(int32_t), hipMemcpyDeviceToHost, s));
+  HIPCHK(c, hipMemcpyAsync(c->h_dec, c->d_dec, (size_t)(3 + 3 * depth) * B * sizeof(int32_t), hipMemcpyDeviceToHost, s));
   HIPCHK(c, hipStreamSynchronize(s));
   const int32_t* ids = c->h_dec;
   const int32_t* kk = c->h_dec + 2 * B;
-  const int32_t* pids = c->h_dec + 3 * B;
-  const int32_t* pk = c->h_dec + 5 * B;
 
   LayerCache& lc = c->layers[layer];
   std::vector<int> used_slots;                       // slots the FFN of this step reads
@@ -894,14 +895,21 @@ int moe_layer_step(adapmoe_ctx* c, int layer, const void* x, int B, float* y, vo
     }
   }
 
-  // predicted experts of the following layer go to the transfer queue after the demanded ones
-  if (layer + 1 < c->cfg.L && c->cache_ready) {
-    std::vector<int32_t> r;
-    for (int b = 0; b < B; ++b)
-      for (int j = 0; j < pk[b] && j < 2; ++j)
-        if (std::find(r.begin(), r.end(), pids[2 * b + j]) == r.end()) r.push_back(pids[2 * b + j]);
-    rc = prefetch_layer(c, layer + 1, r.data(), (int)r.size());
-    if (rc) return rc;
+  // Predicted experts go to the transfer queue after the demanded ones (Alg.1).  Look-ahead
+  // (Sec. 4.3): the layer after next is served only if nothing had to be loaded for the nearer one.
+  if (c->cache_ready) {
+    for (int d = 1; d <= depth && layer + d < c->cfg.L; ++d) {
+      const int32_t* pids = c->h_dec + 3 * B * d;
+      const int32_t* pk = pids + 2 * B;
+      std::vector<int32_t> r;
+      for (int b = 0; b < B; ++b)
+        for (int j = 0; j < pk[b] && j < 2; ++j)
+          if (std::find(r.begin(), r.end(), pids[2 * b + j]) == r.end()) r.push_back(pids[2 * b + j]);
+      const uint64_t loads_before = c->ctr.prefetch_loads;
+      rc = prefetch_layer(c, layer + d, r.data(), (int)r.size());
+      if (rc) return rc;
+      if (c->ctr.prefetch_loads != loads_before) break;
+    }
   }
 
   rc = flush_pokes(c, s);
@@ -952,6 +960,19 @@ int moe_stack_token(adapmoe_ctx* c, int token, float* h, void* x, float* y, int 
 }
 
 // ---- bookkeeping ---------------------------------------------------------------
+
+int adapmoe_set_lookahead(adapmoe_ctx* c, int depth) {
+  if (!c || depth < 1 || depth > 3) return fail(c, ADAPMOE_EINVAL, "set_lookahead: depth must be 1, 2 or 3");
+  c->lookahead = depth;
+  return ADAPMOE_OK;
+}
+
+int adapmoe_last_lookahead(adapmoe_ctx* c, int depth, int32_t* pred_ids, int32_t* pred_k, int B) {
+  if (!c || depth < 1 || depth > 3 || B < 1 || B > c->cfg.max_B) return fail(c, ADAPMOE_EINVAL, "last_lookahead: bad argument");
+  if (pred_ids) memcpy(pred_ids, c->h_dec + 3 * B * depth, (size_t)2 * B * sizeof(int32_t));
+  if (pred_k) memcpy(pred_k, c->h_dec + 3 * B * depth + 2 * B, (size_t)B * sizeof(int32_t));
+  return ADAPMOE_OK;
+}
 
 int adapmoe_set_token(adapmoe_ctx* c, int token) {
   if (!c) return ADAPMOE_EINVAL;

@@ -382,7 +382,9 @@ hipError_t ffn_kernels_init(int dtype) {
 template <bool BF16>
 static void launch_gateup_t(const FfnArgs& p, int nch, dim3 grid, size_t lds, hipStream_t s) {
   dim3 block(kGateUpThreads);
-  if (nch == 8) hipLaunchKernelGGL((ffn_gateup_kernel<BF16, 8>), grid, block, lds, s, p);
+  if (nch == 8) hipLaunchKernelGGL((ffn_gateup_kernel<BF16, 8>), grid, block, lds, s, p);         // H = 4096 bf16, 2048 fp32
+  else if (nch == 12) hipLaunchKernelGGL((ffn_gateup_kernel<BF16, 12>), grid, block, lds, s, p);  // H = 6144 bf16 (8x22B)
+  else if (nch == 4) hipLaunchKernelGGL((ffn_gateup_kernel<BF16, 4>), grid, block, lds, s, p);
   else hipLaunchKernelGGL((ffn_gateup_kernel<BF16, 0>), grid, block, lds, s, p);
 }
 

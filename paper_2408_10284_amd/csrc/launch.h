@@ -19,10 +19,10 @@ struct ResolvedExperts {
 
 struct GateArgs {
   const void* x;        // [B,H] activation type
-  const void* Wg[2];    // router of this layer, router of the following layer (or null)
-  float tau[2];
-  int32_t* ids[2];      // [B,2] each
-  int32_t* k[2];        // [B] each
+  const void* Wg[4];    // router of this layer, routers of the following layers (look-ahead; null = none)
+  float tau[4];
+  int32_t* ids[4];      // [B,2] each
+  int32_t* k[4];        // [B] each
   float* w;             // [B,2], decision of router 0 only
   ResolvedExperts* res; // [B] or null; written for router 0 from `table`
   const void* const* table;  // residency table row of the layer (N pointers), used with res

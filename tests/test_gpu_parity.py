@@ -133,6 +133,8 @@ def test_nonresident_expert_is_reported_not_faulted():
     ("bf16", 2048, 2048, 5),    # 4-run parts
     ("f32", 2048, 768, 3),      # f32 with compile-time gate/up row
     ("f32", 256, 1792, 64),     # N = 64, 7-run parts in f32
+    ("bf16", 6144, 16384, 2),   # Mixtral-8x22B expert shape: 12-run gate/up rows, 32-run down rows
+    ("int4g64", 512, 16384, 2),   # W2 rows of 256 groups = 4 full blocks (8x22B FFN size)
     ("int4g64", 4096, 1024, 4),   # one full block of 64 groups per x row, 16 groups per W2 row
     ("int4g64", 512, 4352, 8),    # 8 groups per x row, W2 rows of 68 groups = one full block + 4 groups
     ("int4g64", 6144, 256, 3),    # x rows of 96 groups: two blocks, the second half full
@@ -192,7 +194,9 @@ def _replay_trace(slots, decisions):
     L = len(slots)
     for (tok, l, ids, k, pids, pk) in decisions:
         c.demand(tok, l, ids, k)
-        if l + 1 < L:
+        if isinstance(pk, (list, tuple)):      # look-ahead: one prediction per depth
+            c.prefetch_lookahead(tok, l, [p[:n] for p, n in zip(pids, pk)])
+        elif l + 1 < L:
             c.prefetch(tok, l + 1, pids[:pk])
     return c
 
@@ -252,6 +256,65 @@ def test_offloaded_stack_trace_and_outputs(dtype, slots):
         for l in range(shape.L):
             res = [e for e in range(shape.N) if B.cache_lookup(ls.ctx, l, [e])[0] >= 0]
             assert sorted(res) == sorted(sim.resident(l))
+    finally:
+        ls.close()
+
+
+@pytest.mark.parametrize("depth,slots", [(2, [3, 3, 3, 3, 3, 3]), (3, [2, 4, 1, 0, 5, 2]), (3, [8, 8, 8, 8, 8, 8])])
+def test_lookahead_prefetch_trace(depth, slots):
+    """Predictions for up to three layers ahead (Sec. 4.3): every depth's decision equals the checker's
+    gate of that layer on the same input, and the cache events equal the checker's replay of the rule
+    'go one layer further only if the nearer one needed no transfer'."""
+    shape = synth.MoEShape(H=512, F=512, N=8, L=6, dtype="bf16")
+    taus = [0.2, 0.3, 0.25, 0.35, 0.3, 0.2]
+    ls = GpuLayerSet(shape, seed=14, max_B=1, trace_capacity=1 << 16, resident=False, taus=taus)
+    try:
+        B.cache_alloc(ls.ctx, slots)
+        B.adapmoe_set_lookahead(ls.ctx, depth)
+        n_tok, gamma = 32, 0.5
+        H0 = synth.ar1_tokens(n_tok, shape.H, 0.8, seed=19, dtype="f32") * 2.0
+        decisions = []
+        for t in range(n_tok):
+            B.adapmoe_set_token(ls.ctx, t)
+            h = torch.from_numpy(H0[t:t + 1].copy()).cuda()
+            x = torch.empty((1, shape.H), dtype=torch.bfloat16, device="cuda")
+            y = torch.empty((1, shape.H), dtype=torch.float32, device="cuda")
+            B.moe_residual_rmsnorm(ls.ctx, h, None, 0.0, x, 1)
+            for l in range(shape.L):
+                B.moe_layer_step(ls.ctx, l, x, 1, y)
+                ids, k, pids1, pk1 = B.adapmoe_last_decision(ls.ctx, 1)
+                torch.cuda.synchronize()
+                xin = x.float().cpu().numpy()[0].astype(np.float64)
+                ahead_ids, ahead_k = [], []
+                for d in range(1, depth + 1):
+                    if l + d >= shape.L:
+                        break
+                    pids, pk = B.adapmoe_last_lookahead(ls.ctx, d, 1)
+                    if d == 1:
+                        assert (pids, pk) == (pids1, pk1)
+                    refp = OG.adaptive_gate(xin, ls.routers_f32[l + d], np.float32(taus[l + d]))
+                    zs = np.sort(refp["z"])[::-1]
+                    if min(zs[0] - zs[1], zs[1] - zs[2]) > TIE_GAP and abs(refp["v"] - taus[l + d]) > BAND:
+                        assert list(pids[:pk[0]]) == list(refp["ids"][:refp["k"]])
+                    ahead_ids.append(pids)
+                    ahead_k.append(pk[0])
+                decisions.append((t, l, ids, k[0], ahead_ids, ahead_k))
+                B.moe_residual_rmsnorm(ls.ctx, h, y, gamma, x, 1)
+        B.adapmoe_check(ls.ctx)
+        sim = _replay_trace(slots, decisions)
+        got = [(t, l, kind, e, v) for (t, l, kind, e, v, _slot) in B.adapmoe_trace_read(ls.ctx)]
+        assert got == [tuple(ev) for ev in sim.events]
+        # the rule did reach beyond the next layer in this run
+        sim2, deep = OC.ExpertCache(slots), 0
+        for (tok, l, ids, k, pids, pk) in decisions:
+            sim2.demand(tok, l, ids, k)
+            evs = sim2.prefetch_lookahead(tok, l, [p[:n] for p, n in zip(pids, pk)])
+            deep += sum(ev[1] > l + 1 for ev in evs)
+        assert deep > 0
+        s = OC.summarise(sim.events)
+        c = B.adapmoe_counters(ls.ctx)
+        assert c["prefetch_loads"] == s["prefetch_loads"]
+        assert c["misses"] + c["bypasses"] == s["on_demand_loads"]
     finally:
         ls.close()
 

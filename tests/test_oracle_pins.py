@@ -278,6 +278,43 @@ def test_cache_prefetch_hand_trace(golden_dir):
     assert s["on_demand_loads"] == 4 and s["prefetch_loads"] == 2 and s["prefetch_useful"] == 2
 
 
+def test_cache_lookahead_hand_trace(golden_dir):
+    g = _load(golden_dir, "cache_lookahead_trace.json")
+    c = OC.ExpertCache(g["slots"])
+    for s in g["steps"]:
+        c.demand(s["token"], s["layer"], s["demand"], s["k"])
+        c.prefetch_lookahead(s["token"], s["layer"], s["ahead"])
+    assert [list(e) for e in c.events] == g["events"]
+    assert [c.resident(l) for l in range(len(g["slots"]))] == g["final_resident"]
+
+
+def test_cache_lookahead_depth_one_is_plain_prefetch_and_deeper_never_loads_after_a_load():
+    rng = np.random.default_rng(5)
+    L, N = 5, 6
+    slots = [2, 0, 3, 1, 2]
+    a, b, d3 = OC.ExpertCache(slots), OC.ExpertCache(slots), OC.ExpertCache(slots)
+    for n in range(80):
+        for l in range(L):
+            ids = rng.choice(N, size=2, replace=False)
+            k = int(rng.integers(1, 3))
+            ahead = [list(rng.choice(N, size=int(rng.integers(1, 3)), replace=False)) for _ in range(3)]
+            a.demand(n, l, ids, k)
+            b.demand(n, l, ids, k)
+            d3.demand(n, l, ids, k)
+            if l + 1 < L:
+                a.prefetch(n, l + 1, ahead[0])
+            b.prefetch_lookahead(n, l, ahead[:1])
+            evs = d3.prefetch_lookahead(n, l, ahead)
+            # within one step: layers appear in increasing order, nothing beyond the stack, and
+            # only the deepest layer served may contain a load
+            layers = [ev[1] for ev in evs]
+            assert layers == sorted(layers) and all(l < x < L for x in layers)
+            for ev in evs:
+                if ev[2] == OC.PF_LOAD:
+                    assert ev[1] == max(layers)
+    assert a.events == b.events
+
+
 def test_cache_prefetch_against_timestamp_simulator():
     rng = np.random.default_rng(12)
     for trial in range(50):

@@ -7,7 +7,7 @@
  *             activation test that decides whether the second expert runs
  *             (Sec. 2.1 Eq.1; Sec. 4.2 Eq.3, Eq.4, Eq.8);
  *   predict   the following layer's gate applied to the same input (Sec. 4.3);
- *   lookup    per-layer expert cache with LRU replacement (Sec. 4.4, Sec. 5.3);
+ *   lookup    per-layer expert cache with LRU replacement (Sec. 4.4, Sec. 6.3);
  *   load      on-demand copy of missing experts, host DRAM -> HBM (Alg.1);
  *   compute   SwiGLU expert FFNs and their weighted sum (Sec. 2.1 Eq.2);
  *   prefetch  asynchronous copy of the predicted experts of the following
@@ -93,6 +93,7 @@ typedef struct {
   uint64_t prefetch_touches, prefetch_loads;
   uint64_t h2d_bytes;        /* bytes copied host -> HBM (demand + prefetch) */
   uint64_t ffn_launches;
+  uint64_t tiled_ffn;       /* experts evaluated tile by tile while their copy was still running */
 } adapmoe_counters_t;
 
 const char* adapmoe_strerror(int code);
@@ -217,6 +218,15 @@ int moe_residual_rmsnorm(adapmoe_ctx* ctx, float* h_dev, const float* y_dev, flo
  * h [B,H] float is updated in place; x [B,H] (activation type) and y [B,H]
  * float are work buffers owned by the caller.  Sets the trace token to `token`. */
 int moe_stack_token(adapmoe_ctx* ctx, int token, float* h_dev, void* x_dev, float* y_dev, int B, float gamma, void* stream);
+
+/* Tile-wise loading (Sec. 5, Fig.6(b) and Alg.1: tile-wise scheduling).  tiles = 0 or 1: an expert image
+ * is one copy and the expert FFN waits for all of it (default).  tiles >= 2 (at most 64): every
+ * copy is issued as `tiles` blocks of gate/up row pairs followed by tiles/2 blocks of W2 rows, each
+ * with its own event; a single-token moe_layer_step whose expert is still arriving evaluates the
+ * experts already in HBM first and then the arriving one block by block, each launch waiting only
+ * for the block it reads.  Cache decisions, events and counters are the same in both modes; outputs
+ * agree up to the order of the final additions.  Calls with B > 1 wait for whole images. */
+int adapmoe_set_tiles(adapmoe_ctx* ctx, int tiles);
 
 /* Look-ahead depth of moe_layer_step, 1..3 (default 1) (Sec. 4.3, prefetch beyond the next layer).
  * With depth D the gate launch also applies the routers of layers l+2 .. l+D to the

@@ -2,7 +2,7 @@
 (test infrastructure).
 
 The paper keeps a bounded set of experts per layer in GPU memory (Sec. 4.4),
-replaces by least-recently-used (Sec. 5.3), loads missing experts of the
+replaces by least-recently-used (Sec. 6.3), loads missing experts of the
 current layer on demand and prefetches the experts predicted for the following
 layer (Sec. 4.3, Alg.1: the transfer set is the non-resident required experts
 plus the predicted ones).  The paper does not say whether a prefetch counts as

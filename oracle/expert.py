@@ -3,7 +3,7 @@
 The MoE output is the gate-weighted sum of expert outputs (Sec. 2.1, Eq.2);
 with adaptive gating it is alpha*f1(x) + (1-alpha)*f2(x) when two experts run
 (Eq.3) and f1(x) when one runs (Eq.4).  The expert body is the evaluation
-model's (Mixtral, Sec. 5.1): a bias-free SwiGLU FFN,
+model's (Mixtral, Sec. 6.1): a bias-free SwiGLU FFN,
 E(x) = W2 . ( silu(W1 x) * (W3 x) ),  silu(g) = g / (1 + exp(-g)).
 All arithmetic is float64.
 """
@@ -72,7 +72,7 @@ def moe_block_rows(X, experts, ids, w, k):
 
 
 # ---------------------------------------------------------------------------
-# 4-bit group-quantised storage (the paper runs 4-bit experts, Sec. 5.3; this
+# 4-bit group-quantised storage (the paper runs 4-bit experts, Sec. 6.3; this
 # build's storage format is asymmetric round-to-nearest with groups of 64
 # along the reduction axis and fp16 scale / zero per group)
 # ---------------------------------------------------------------------------

@@ -30,7 +30,7 @@ class Event(C.Structure):
 class Counters(C.Structure):
     _fields_ = [(n, C.c_uint64) for n in
                 ("tokens_gated", "single_expert", "hits", "hits_after_prefetch", "misses", "bypasses",
-                 "prefetch_touches", "prefetch_loads", "h2d_bytes", "ffn_launches")]
+                 "prefetch_touches", "prefetch_loads", "h2d_bytes", "ffn_launches", "tiled_ffn")]
 
 
 class AdapMoEError(RuntimeError):
@@ -65,6 +65,7 @@ _SIGS = {
     "moe_layer_step": (C.c_int, [_P, C.c_int, _P, C.c_int, _P, _P]),
     "moe_residual_rmsnorm": (C.c_int, [_P, _P, _P, C.c_float, _P, C.c_int, _P]),
     "moe_stack_token": (C.c_int, [_P, C.c_int, _P, _P, _P, C.c_int, C.c_float, _P]),
+    "adapmoe_set_tiles": (C.c_int, [_P, C.c_int]),
     "adapmoe_set_lookahead": (C.c_int, [_P, C.c_int]),
     "adapmoe_last_lookahead": (C.c_int, [_P, C.c_int, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_int]),
     "adapmoe_set_token": (C.c_int, [_P, C.c_int]),
@@ -217,6 +218,10 @@ def moe_residual_rmsnorm(ctx, h, y, gamma, x, B, stream=None):
 
 def moe_stack_token(ctx, token, h, x, y, B, gamma, stream=None):
     _chk(ctx, load().moe_stack_token(ctx, token, _ptr(h), _ptr(x), _ptr(y), B, float(gamma), _stream(stream)))
+
+
+def adapmoe_set_tiles(ctx, tiles):
+    _chk(ctx, load().adapmoe_set_tiles(ctx, tiles))
 
 
 def adapmoe_set_lookahead(ctx, depth):

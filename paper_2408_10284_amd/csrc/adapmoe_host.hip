@@ -24,6 +24,9 @@ struct Slot {
   hipEvent_t read_done = nullptr;  // recorded on the compute stream after the last FFN reading the slot
   bool copy_pending = false;       // a copy was issued and no compute stream has been told to wait for it yet
   bool was_read = false;
+  std::vector<hipEvent_t> tile_done;  // tile-wise copies: one event per tile, in transfer order (created on first use)
+  bool tiled = false;              // the last copy into the slot was issued tile by tile
+  uint64_t copy_seq = 0;           // position of the last copy in the side stream's order
 };
 
 struct Entry {
@@ -67,6 +70,8 @@ struct adapmoe_ctx {
   int32_t* d_err = nullptr;
   int32_t* d_dec = nullptr;             // ids[2B] k[B], then per look-ahead depth d = 1..3: pred_ids[2B] pred_k[B]
   int lookahead = 1;                    // layers ahead that are predicted and prefetched (Sec. 4.3)
+  int tiles = 0;                        // > 1: expert copies are cut into tiles and a waiting FFN runs tile by tile (Alg.1)
+  uint64_t copy_seq = 0;
   float* d_w = nullptr;                 // [B,2]
   float* d_a = nullptr;                 // [B][2][a_stride]
   ResolvedExperts* d_res = nullptr;     // [B] resolved experts of the last gate of moe_layer_step
@@ -187,6 +192,35 @@ void record(adapmoe_ctx* c, int layer, int kind, int expert, int victim, int slo
   c->trace.push_back(adapmoe_event{c->token, layer, kind, expert, victim, slot});
 }
 
+// Tile-wise transfer (Sec. 5, Alg.1): the gate/up part of an image (F row pairs) is cut into
+// `tiles` blocks of rows and the W2 part (H rows) into tiles/2, all of (nearly) equal size.
+int gateup_tiles(const adapmoe_ctx* c) { return c->tiles; }
+int down_tiles(const adapmoe_ctx* c) { return std::max(1, c->tiles / 2); }
+// rows [*r0, *r1) of tile t: t < gateup_tiles counts row pairs, the others rows of W2
+void tile_rows(const adapmoe_ctx* c, int t, int* r0, int* r1) {
+  const int tg = gateup_tiles(c), td = down_tiles(c);
+  if (t < tg) {
+    *r0 = (int)((int64_t)c->cfg.F * t / tg);
+    *r1 = (int)((int64_t)c->cfg.F * (t + 1) / tg);
+  } else {
+    *r0 = (int)((int64_t)c->cfg.H * (t - tg) / td);
+    *r1 = (int)((int64_t)c->cfg.H * (t - tg + 1) / td);
+  }
+}
+void tile_bytes(const adapmoe_ctx* c, int t, size_t* b0, size_t* b1) {
+  int r0, r1;
+  tile_rows(c, t, &r0, &r1);
+  if (t < gateup_tiles(c)) {
+    const size_t pair = c->w2_offset / (size_t)c->cfg.F;
+    *b0 = pair * r0;
+    *b1 = pair * r1;
+  } else {
+    const size_t row = (c->image_bytes - c->w2_offset) / (size_t)c->cfg.H;
+    *b0 = c->w2_offset + row * r0;
+    *b1 = c->w2_offset + row * r1;
+  }
+}
+
 // Starts the copy of (layer, expert) into `slot` on the side stream.  The copy
 // waits for the last kernel that read the slot; its completion is the slot's
 // copy_done event.
@@ -195,9 +229,27 @@ int start_copy(adapmoe_ctx* c, int layer, int expert, int slot) {
   if (!src) return fail(c, ADAPMOE_ENOTREG, "expert has no registered host image");
   Slot& s = c->slots[slot];
   if (s.was_read) HIPCHK(c, hipStreamWaitEvent(c->copy_stream, s.read_done, 0));
-  HIPCHK(c, hipMemcpyAsync(s.dev, src, c->image_bytes, hipMemcpyHostToDevice, c->copy_stream));
+  s.tiled = c->tiles > 1;
+  if (s.tiled) {
+    // tiles in storage order: row-pair blocks of the interleaved W1/W3 part, then row blocks of W2
+    const int tg = gateup_tiles(c), td = down_tiles(c);
+    while ((int)s.tile_done.size() < tg + td) {
+      hipEvent_t ev = nullptr;
+      HIPCHK(c, hipEventCreateWithFlags(&ev, hipEventDisableTiming));
+      s.tile_done.push_back(ev);
+    }
+    for (int t = 0; t < tg + td; ++t) {
+      size_t b0, b1;
+      tile_bytes(c, t, &b0, &b1);
+      HIPCHK(c, hipMemcpyAsync(s.dev + b0, static_cast<const char*>(src) + b0, b1 - b0, hipMemcpyHostToDevice, c->copy_stream));
+      HIPCHK(c, hipEventRecord(s.tile_done[t], c->copy_stream));
+    }
+  } else {
+    HIPCHK(c, hipMemcpyAsync(s.dev, src, c->image_bytes, hipMemcpyHostToDevice, c->copy_stream));
+  }
   HIPCHK(c, hipEventRecord(s.copy_done, c->copy_stream));
   s.copy_pending = true;
+  s.copy_seq = ++c->copy_seq;
   c->ctr.h2d_bytes += c->image_bytes;
   return ADAPMOE_OK;
 }
@@ -311,6 +363,7 @@ FfnArgs ffn_args(adapmoe_ctx* c, int layer, const void* x, int B, const int32_t*
   p.F = c->cfg.F;
   p.N = c->cfg.N;
   p.w2_offset = c->w2_offset;
+  p.j_only = -1;
   return p;
 }
 
@@ -378,6 +431,64 @@ int launch_ffn(adapmoe_ctx* c, int layer, const void* x, int B, const int32_t* i
   {
     ScopedTimer t(c, 1, s);
     HIPCHK(c, int4 ? launch_ffn_down_int4(p, c->lc, s) : launch_ffn_down(p, c->cfg.dtype, c->lc, s));
+  }
+  c->ctr.ffn_launches++;
+  return ADAPMOE_OK;
+}
+
+// One token whose activated experts are partly still on their way (Alg.1, tile-wise scheduling):
+// experts already in HBM are evaluated first, then each arriving expert tile by tile in the order
+// the side stream delivers them; every launch waits only for the tile it reads.  rank_slot[j] is
+// the cache slot of the expert of rank j, or -1 when it lives in caller memory.
+int launch_ffn_tiled(adapmoe_ctx* c, int layer, const void* x, int kk, const int* rank_slot, float* y, hipStream_t s) {
+  const bool int4 = c->cfg.dtype == ADAPMOE_INT4G64;
+  int order[2] = {0, 1};
+  auto arrival = [&](int j) -> uint64_t {
+    if (rank_slot[j] < 0) return 0;
+    const Slot& sl = c->slots[rank_slot[j]];
+    return sl.copy_pending ? sl.copy_seq : 0;
+  };
+  if (kk > 1 && arrival(1) < arrival(0)) std::swap(order[0], order[1]);
+  auto gateup = [&](FfnArgs& p) -> int {
+    ScopedTimer t(c, 0, s);
+    HIPCHK(c, int4 ? launch_ffn_gateup_int4(p, c->lc, s) : launch_ffn_gateup(p, c->cfg.dtype, c->lc, s));
+    return ADAPMOE_OK;
+  };
+  auto down = [&](FfnArgs& p) -> int {
+    ScopedTimer t(c, 1, s);
+    HIPCHK(c, int4 ? launch_ffn_down_int4(p, c->lc, s) : launch_ffn_down(p, c->cfg.dtype, c->lc, s));
+    return ADAPMOE_OK;
+  };
+  for (int i = 0; i < kk && i < 2; ++i) {
+    const int j = order[i];
+    FfnArgs p = ffn_args(c, layer, x, 1, nullptr, nullptr, nullptr, y, c->d_res);
+    p.j_only = j;
+    p.accumulate = i > 0;
+    Slot* sl = rank_slot[j] >= 0 ? &c->slots[rank_slot[j]] : nullptr;
+    int rc;
+    if (sl && sl->copy_pending && hipEventQuery(sl->copy_done) == hipSuccess) sl->copy_pending = false;  // already landed
+    (void)hipGetLastError();  // hipErrorNotReady from the query is not an error
+    if (sl && sl->copy_pending && sl->tiled) {
+      const int tg = gateup_tiles(c), td = down_tiles(c);
+      for (int t = 0; t < tg + td; ++t) {
+        HIPCHK(c, hipStreamWaitEvent(s, sl->tile_done[t], 0));
+        tile_rows(c, t, &p.r0, &p.r1);
+        rc = t < tg ? gateup(p) : down(p);
+        if (rc) return rc;
+      }
+      sl->copy_pending = false;
+      c->ctr.tiled_ffn++;
+    } else {
+      if (sl && sl->copy_pending) {
+        HIPCHK(c, hipStreamWaitEvent(s, sl->copy_done, 0));
+        sl->copy_pending = false;
+      }
+      p.r0 = 0;
+      p.r1 = c->cfg.F;
+      if ((rc = gateup(p))) return rc;
+      p.r1 = c->cfg.H;
+      if ((rc = down(p))) return rc;
+    }
   }
   c->ctr.ffn_launches++;
   return ADAPMOE_OK;
@@ -511,7 +622,8 @@ int adapmoe_create(const adapmoe_config* cfg, adapmoe_ctx** out) {
   c->cfg = *cfg;
   c->bf16_act = cfg->dtype != ADAPMOE_F32;
   adapmoe_expert_bytes(cfg, &c->image_bytes);
-  c->w2_offset = (size_t)2 * cfg->F * cfg->H * elem_size(cfg->dtype);
+  c->w2_offset = cfg->dtype == ADAPMOE_INT4G64 ? (size_t)2 * cfg->F * i4_row_bytes(cfg->H)
+                                               : (size_t)2 * cfg->F * cfg->H * elem_size(cfg->dtype);
   const size_t LN = (size_t)cfg->L * cfg->N;
   c->router.assign(cfg->L, nullptr);
   c->tau.assign(cfg->L, 0.f);
@@ -579,6 +691,7 @@ int adapmoe_destroy(adapmoe_ctx* c) {
     if (s.dev) hipFree(s.dev);
     if (s.copy_done) hipEventDestroy(s.copy_done);
     if (s.read_done) hipEventDestroy(s.read_done);
+    for (hipEvent_t ev : s.tile_done) hipEventDestroy(ev);
   }
   for (TimedLaunch& t : c->timed) {
     hipEventDestroy(t.t0);
@@ -814,6 +927,7 @@ int moe_layer_step(adapmoe_ctx* c, int layer, const void* x, int B, float* y, vo
   std::vector<int> used_slots;                       // slots the FFN of this step reads
   std::vector<std::pair<int, int>> transient;        // (expert, slot) to drop right after the FFN
   std::vector<int> demanded;                         // experts needed by this step so far
+  int rank_slot[2] = {-1, -1};                       // slot of token 0's expert of rank j (-1: caller memory)
   for (int b = 0; b < B; ++b) {
     if (kk[b] == 1) c->ctr.single_expert++;
     for (int j = 0; j < kk[b] && j < 2; ++j) {
@@ -833,6 +947,7 @@ int moe_layer_step(adapmoe_ctx* c, int layer, const void* x, int B, float* y, vo
         en.by_prefetch = false;
         used_slots.push_back(en.slot);
         poke_resolved(c, b, j, c->slots[en.slot].dev);
+        if (b == 0) rank_slot[j] = en.slot;
         lc.touch(pos);
         demanded.push_back(e);
         continue;
@@ -840,7 +955,10 @@ int moe_layer_step(adapmoe_ctx* c, int layer, const void* x, int B, float* y, vo
       if (is_transient) {  // evicted or bypassed earlier in this same step, image still in its slot
         if (lc.cap == 0) {
           for (auto& t : transient)
-            if (t.first == e) poke_resolved(c, b, j, c->slots[t.second].dev);
+            if (t.first == e) {
+              poke_resolved(c, b, j, c->slots[t.second].dev);
+              if (b == 0) rank_slot[j] = t.second;
+            }
           record(c, layer, ADAPMOE_EV_BYPASS, e, -1, -1);
           continue;
         }
@@ -857,6 +975,7 @@ int moe_layer_step(adapmoe_ctx* c, int layer, const void* x, int B, float* y, vo
         transient.emplace_back(e, slot);
         used_slots.push_back(slot);
         poke_resolved(c, b, j, c->slots[slot].dev);
+        if (b == 0) rank_slot[j] = slot;
         record(c, layer, ADAPMOE_EV_BYPASS, e, -1, slot);
         continue;
       }
@@ -890,6 +1009,7 @@ int moe_layer_step(adapmoe_ctx* c, int layer, const void* x, int B, float* y, vo
       poke_later(c, layer, e, c->slots[slot].dev);
       used_slots.push_back(slot);
       poke_resolved(c, b, j, c->slots[slot].dev);
+      if (b == 0) rank_slot[j] = slot;
       demanded.push_back(e);
       record(c, layer, ADAPMOE_EV_MISS, e, victim, slot);
     }
@@ -914,14 +1034,21 @@ int moe_layer_step(adapmoe_ctx* c, int layer, const void* x, int B, float* y, vo
 
   rc = flush_pokes(c, s);
   if (rc) return rc;
-  for (int slot : used_slots) {
-    Slot& sl = c->slots[slot];
-    if (sl.copy_pending) {
-      HIPCHK(c, hipStreamWaitEvent(s, sl.copy_done, 0));
-      sl.copy_pending = false;
+  bool tile_path = false;
+  if (c->tiles > 1 && B == 1 && c->lc.fused_blocks == 0)
+    for (int slot : used_slots) tile_path |= c->slots[slot].copy_pending && c->slots[slot].tiled;
+  if (tile_path) {
+    rc = launch_ffn_tiled(c, layer, x, kk[0], rank_slot, y, s);
+  } else {
+    for (int slot : used_slots) {
+      Slot& sl = c->slots[slot];
+      if (sl.copy_pending) {
+        HIPCHK(c, hipStreamWaitEvent(s, sl.copy_done, 0));
+        sl.copy_pending = false;
+      }
     }
+    rc = launch_ffn(c, layer, x, B, d_ids, c->d_w, d_k, y, s, c->d_res);
   }
-  rc = launch_ffn(c, layer, x, B, d_ids, c->d_w, d_k, y, s, c->d_res);
   if (rc) return rc;
   for (int slot : used_slots) {
     Slot& sl = c->slots[slot];
@@ -960,6 +1087,13 @@ int moe_stack_token(adapmoe_ctx* c, int token, float* h, void* x, float* y, int 
 }
 
 // ---- bookkeeping ---------------------------------------------------------------
+
+int adapmoe_set_tiles(adapmoe_ctx* c, int tiles) {
+  if (!c || tiles < 0 || tiles > 64 || tiles > c->cfg.F || tiles / 2 > c->cfg.H)
+    return fail(c, ADAPMOE_EINVAL, "set_tiles: tiles must be 0..64 and not exceed the number of rows");
+  c->tiles = tiles;
+  return ADAPMOE_OK;
+}
 
 int adapmoe_set_lookahead(adapmoe_ctx* c, int depth) {
   if (!c || depth < 1 || depth > 3) return fail(c, ADAPMOE_EINVAL, "set_lookahead: depth must be 1, 2 or 3");

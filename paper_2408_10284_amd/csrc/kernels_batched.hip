@@ -27,7 +27,6 @@ typedef __attribute__((ext_vector_type(4))) float f32x4_t;
 constexpr int kBTok = 16;            // token columns of one MFMA
 constexpr int kBThreads = 256;       // 4 wavefronts, 16 rows each
 constexpr int kBWaves = kBThreads / kWave;
-constexpr int kDownRT = 2;           // row tiles per wavefront in the down GEMM (H must be a multiple of 128)
 
 __device__ __forceinline__ f32x4_t mfma16(const uint4& a, const uint4& b, f32x4_t c) {
   return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8_t, a), __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);

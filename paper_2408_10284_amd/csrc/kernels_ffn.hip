@@ -10,6 +10,7 @@
 //            (staged in LDS) for every activated expert, summed in a fixed order.
 // Every lane reads 16 bytes per load and a wavefront reads 1 KiB contiguous.
 // No atomics: results are bit-reproducible.
+#include <algorithm>
 #include <cstdio>
 #include <cstdlib>
 #include "device_utils.h"
@@ -60,11 +61,14 @@ __global__ __launch_bounds__(kGateUpThreads) void ffn_gateup_kernel(FfnArgs p) {
   const char* base[2];
   float wj[2];
   const int kk = resolve_experts(p, b, base, wj);
-  const int total = kk * p.F;
-  const int stride = gridDim.x * (kGateUpThreads / kWave);
-  const int first = blockIdx.x * (kGateUpThreads / kWave) + wave;
-  float* a_out = p.a + (size_t)b * 2 * p.a_stride;
   const int F = p.F;
+  const bool windowed = p.j_only >= 0;
+  if (windowed && p.j_only >= kk) return;
+  const int lo = windowed ? p.j_only * F + p.r0 : 0;        // rows are numbered expert-major: r = j*F + f
+  const int total = windowed ? p.j_only * F + p.r1 : kk * F;
+  const int stride = gridDim.x * (kGateUpThreads / kWave);
+  const int first = lo + blockIdx.x * (kGateUpThreads / kWave) + wave;
+  float* a_out = p.a + (size_t)b * 2 * p.a_stride;
 
   const uint4* xg = reinterpret_cast<const uint4*>(static_cast<const char*>(p.x) + (size_t)b * row_bytes);
   auto stage_x = [&]() {
@@ -73,7 +77,7 @@ __global__ __launch_bounds__(kGateUpThreads) void ffn_gateup_kernel(FfnArgs p) {
   };
 
   bool all_resident = true;
-  for (int j = 0; j < kk; ++j) all_resident &= base[j] != nullptr;
+  for (int j = 0; j < kk; ++j) all_resident &= base[j] != nullptr || (windowed && j != p.j_only);
 
   if (NCH > 0 && all_resident) {
     const int nrows = first < total ? (total - first + stride - 1) / stride : 0;
@@ -157,29 +161,35 @@ __global__ __launch_bounds__(kDownThreads) void ffn_down_kernel(FfnArgs p) {
   const char* base[2];
   float wj[2];
   const int kk = resolve_experts(p, b, base, wj);
+  const bool windowed = p.j_only >= 0;
+  if (windowed && p.j_only >= kk) return;
+  const int j0 = windowed ? p.j_only : 0;   // experts j0 .. j0 + nj - 1 take part
+  const int nj = windowed ? 1 : kk;
+  const int hlo = windowed ? p.r0 : 0, hhi = windowed ? p.r1 : H;
   bool all_resident = true;
-  for (int j = 0; j < kk; ++j) all_resident &= base[j] != nullptr;
+  for (int j = j0; j < j0 + nj; ++j) all_resident &= base[j] != nullptr;
 
   const float4* ag = reinterpret_cast<const float4*>(p.a + (size_t)b * 2 * p.a_stride);
   const int S4 = (int)(p.a_stride >> 2);
   auto stage_a = [&]() {
-    for (int i = tid; i < kk * F4; i += kDownThreads) {
-      const int j = i >= F4 ? 1 : 0;
-      const int f4 = i - j * F4;
-      as4[j * F4 + (BF16 ? lds_pos_bf16(f4) : f4)] = ag[j * S4 + f4];
+    for (int i = tid; i < nj * F4; i += kDownThreads) {
+      const int jr = i >= F4 ? 1 : 0;
+      const int f4 = i - jr * F4;
+      as4[jr * F4 + (BF16 ? lds_pos_bf16(f4) : f4)] = ag[(j0 + jr) * S4 + f4];
     }
     __syncthreads();
   };
 
-  const int first = blockIdx.x * kWaves + wave;
+  const int first = hlo + blockIdx.x * kWaves + wave;
   const int hstride = gridDim.x * kWaves;
   float* y = p.y + (size_t)b * H;
+  const bool accumulate = p.accumulate != 0;
 
   if (UN > 0 && all_resident) {
     const int nbp = nch / NV;        // parts per row of one expert
-    const int nb = kk * nbp;         // parts per output element
-    const int nrows = first < H ? (H - first + hstride - 1) / hstride : 0;
-    const char* w2[2] = {base[0] + p.w2_offset, kk > 1 ? base[1] + p.w2_offset : nullptr};
+    const int nb = nj * nbp;         // parts per output element
+    const int nrows = first < hhi ? (hhi - first + hstride - 1) / hstride : 0;
+    const char* w2[2] = {base[j0] + p.w2_offset, nj > 1 ? base[1] + p.w2_offset : nullptr};
     int ha = first, ba = 0;  // load cursor
     auto next_addr = [&]() -> const char* {
       const int j = ba >= nbp ? 1 : 0;
@@ -194,7 +204,7 @@ __global__ __launch_bounds__(kDownThreads) void ffn_down_kernel(FfnArgs p) {
       acc = dot_a<BF16, NV>(buf, as4 + j * F4, (bc - j * nbp) * NV, lane, acc);
       if (++bc == nb) {
         const float s = wave_sum(acc);
-        if (lane == 0) y[hc] = s;
+        if (lane == 0) y[hc] = accumulate ? y[hc] + s : s;
         acc = 0.f;
         bc = 0;
         hc += hstride;
@@ -203,19 +213,20 @@ __global__ __launch_bounds__(kDownThreads) void ffn_down_kernel(FfnArgs p) {
     stream_parts<NV>(nrows * nb, next_addr, consume, stage_a);
   } else {
     stage_a();
-    for (int h = first; h < H; h += hstride) {
+    for (int h = first; h < hhi; h += hstride) {
       float acc = 0.f;
-      for (int j = 0; j < kk; ++j) {
+      for (int jr = 0; jr < nj; ++jr) {
+        const int j = j0 + jr;
         if (!base[j]) continue;
         const char* row = base[j] + p.w2_offset + (size_t)h * row_bytes + lane * 16;
         for (int c = 0; c < nch; ++c) {
           uint4 buf[1];
           buf[0] = load_stream16(row + (size_t)c * kChunkBytes);
-          acc = dot_a<BF16, 1>(buf, as4 + j * F4, c, lane, acc);
+          acc = dot_a<BF16, 1>(buf, as4 + jr * F4, c, lane, acc);
         }
       }
       acc = wave_sum(acc);
-      if (lane == 0) y[h] = acc;
+      if (lane == 0) y[h] = accumulate ? y[h] + acc : acc;
     }
   }
 }
@@ -393,6 +404,7 @@ hipError_t launch_ffn_gateup(const FfnArgs& p, int dtype, const LaunchCfg& lc, h
   const size_t row_bytes = (size_t)p.H * (bf16 ? 2 : 4);
   const int nch = (int)(row_bytes / kChunkBytes);
   dim3 grid(lc.gateup_blocks, p.B);
+  if (p.j_only >= 0) grid.x = std::max(1, std::min(lc.gateup_blocks, (p.r1 - p.r0 + 3) / (kGateUpThreads / kWave)));
   if (bf16) launch_gateup_t<true>(p, nch, grid, row_bytes, s);
   else launch_gateup_t<false>(p, nch, grid, row_bytes, s);
   return hipGetLastError();
@@ -411,6 +423,7 @@ hipError_t launch_ffn_down(const FfnArgs& p, int dtype, const LaunchCfg& lc, hip
   const bool bf16 = dtype != ADAPMOE_F32;
   const int nch = (int)((size_t)p.F * (bf16 ? 2 : 4) / kChunkBytes);
   dim3 grid(lc.down_blocks, p.B);
+  if (p.j_only >= 0) grid.x = std::max(1, std::min(lc.down_blocks, (p.r1 - p.r0 + 15) / (kDownThreads / kWave)));
   const size_t lds = (size_t)2 * p.F * sizeof(float);
   if (bf16) launch_down_t<true>(p, nch, grid, lds, s);
   else launch_down_t<false>(p, nch, grid, lds, s);

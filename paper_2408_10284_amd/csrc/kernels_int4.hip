@@ -1,6 +1,6 @@
 // Expert FFN for decode with 4-bit group-quantised weights (groups of 64 along
 // the reduction axis, fp16 scale and zero per group; weight = code*scale+zero).
-// The paper runs its experts in 4 bit (Sec. 5.3); dequantisation is fused into
+// The paper runs its experts in 4 bit (Sec. 6.3); dequantisation is fused into
 // the GEMVs of Eq.2 so that only the packed image crosses HBM (9/16 byte per
 // weight).
 //
@@ -131,9 +131,10 @@ __global__ __launch_bounds__(kI4GateUpThreads) void ffn_gateup_int4_kernel(FfnAr
   const char* rbase[2];
   float rw[2];
   int rj[2];
-  int nv = 0;  // resident activated experts, rank order
+  const bool windowed = p.j_only >= 0;
+  int nv = 0;  // resident activated experts taking part, rank order
   for (int j = 0; j < kk; ++j)
-    if (base[j]) { rbase[nv] = base[j]; rw[nv] = wj[j]; rj[nv] = j; ++nv; }
+    if (base[j] && (!windowed || j == p.j_only)) { rbase[nv] = base[j]; rw[nv] = wj[j]; rj[nv] = j; ++nv; }
 
   // The lane's groups of x (bfloat16) and their sums.  x is read from global
   // memory in order (one 16-byte piece per thread) and turned through LDS:
@@ -159,9 +160,10 @@ __global__ __launch_bounds__(kI4GateUpThreads) void ffn_gateup_int4_kernel(FfnAr
     }
   };
 
-  const int total = nv * F;
+  // rows are numbered r = (index among the taking-part experts) * F + f
+  const int total = windowed ? (nv ? p.r1 : 0) : nv * F;
   const int stride = gridDim.x * (kI4GateUpThreads / kWave);
-  const int first = blockIdx.x * (kI4GateUpThreads / kWave) + wave;
+  const int first = (windowed ? p.r0 : 0) + blockIdx.x * (kI4GateUpThreads / kWave) + wave;
   const int nrows = first < total ? (total - first + stride - 1) / stride : 0;
   uint16_t* a_out = reinterpret_cast<uint16_t*>(p.a + (size_t)b * 2 * p.a_stride);
 
@@ -219,10 +221,12 @@ __global__ __launch_bounds__(kI4DownThreads) void ffn_down_int4_kernel(FfnArgs p
   int rj[2];
   int nv = 0;
   const size_t w2_off = (size_t)2 * F * i4_row_bytes(H);
+  const bool windowed = p.j_only >= 0;
   for (int j = 0; j < kk; ++j)
-    if (base[j]) { w2[nv] = base[j] + w2_off; rj[nv] = j; ++nv; }
+    if (base[j] && (!windowed || j == p.j_only)) { w2[nv] = base[j] + w2_off; rj[nv] = j; ++nv; }
 
-  const int h0 = blockIdx.x * kI4DownRows;
+  const int h0 = (windowed ? p.r0 : 0) + blockIdx.x * kI4DownRows;
+  const int hhi = windowed ? p.r1 : H;
   float acc[kI4DownRows];
 #pragma unroll
   for (int r = 0; r < kI4DownRows; ++r) acc[r] = 0.f;
@@ -264,11 +268,12 @@ __global__ __launch_bounds__(kI4DownThreads) void ffn_down_int4_kernel(FfnArgs p
     if (lane == 0) part[wave][r] = s;
   }
   __syncthreads();
-  if (threadIdx.x < kI4DownRows && h0 + threadIdx.x < H) {
+  if (threadIdx.x < kI4DownRows && h0 + threadIdx.x < hhi) {
     float y = 0.f;
 #pragma unroll
     for (int w = 0; w < kI4DownThreads / kWave; ++w) y += part[w][threadIdx.x];
-    p.y[(size_t)b * H + h0 + threadIdx.x] = y;
+    float* out = p.y + (size_t)b * H + h0 + threadIdx.x;
+    *out = p.accumulate ? *out + y : y;
   }
 }
 
@@ -276,6 +281,7 @@ __global__ __launch_bounds__(kI4DownThreads) void ffn_down_int4_kernel(FfnArgs p
 
 hipError_t launch_ffn_gateup_int4(const FfnArgs& p, const LaunchCfg& lc, hipStream_t s) {
   dim3 grid(lc.gateup_blocks, p.B), block(kI4GateUpThreads);
+  if (p.j_only >= 0) grid.x = std::max(1, std::min(lc.gateup_blocks, (p.r1 - p.r0 + 3) / (kI4GateUpThreads / kWave)));
   const int nblk = ((p.H >> 6) + 63) >> 6;
   if (nblk == 1) hipLaunchKernelGGL(ffn_gateup_int4_kernel<1>, grid, block, 1 * 8192, s, p);
   else hipLaunchKernelGGL(ffn_gateup_int4_kernel<2>, grid, block, 2 * 8192, s, p);
@@ -283,7 +289,8 @@ hipError_t launch_ffn_gateup_int4(const FfnArgs& p, const LaunchCfg& lc, hipStre
 }
 
 hipError_t launch_ffn_down_int4(const FfnArgs& p, const LaunchCfg&, hipStream_t s) {
-  dim3 grid((p.H + kI4DownRows - 1) / kI4DownRows, p.B), block(kI4DownThreads);
+  const int rows = p.j_only >= 0 ? p.r1 - p.r0 : p.H;
+  dim3 grid(std::max(1, (rows + kI4DownRows - 1) / kI4DownRows), p.B), block(kI4DownThreads);
   hipLaunchKernelGGL(ffn_down_int4_kernel, grid, block, 0, s, p);
   return hipGetLastError();
 }

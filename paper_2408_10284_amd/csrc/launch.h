@@ -42,6 +42,11 @@ struct FfnArgs {
   int32_t* err;              // device flag word (bit 0: non-resident expert, bit 1: id out of range)
   int B, H, F, N;
   size_t w2_offset;          // byte offset of W2 inside an expert image
+  // Window of a tile-wise launch (Alg.1, tile-wise scheduling): j_only >= 0 restricts the launch
+  // to the activated expert of that rank and to rows [r0, r1) of its gate/up pairs (gate/up
+  // kernels) or of W2 (down kernels); accumulate != 0 adds onto y instead of overwriting it.
+  // j_only < 0: all activated experts, all rows, overwrite.
+  int j_only, r0, r1, accumulate;
 };
 
 // Batched path (several tokens, experts streamed once each on the matrix cores)

@@ -6,7 +6,7 @@ format of the weights.  It holds none of the method's arithmetic (no gating,
 no expert evaluation, no cache policy, no dequantisation) and imports neither
 the HIP binding nor the CPU checker, so both can be fed from it.
 
-Shapes follow Mixtral-8x7B (the paper's evaluation model, Sec. 5.1): hidden
+Shapes follow Mixtral-8x7B (the paper's evaluation model, Sec. 6.1): hidden
 size H, FFN size F, N experts per layer, experts stored as W1[F,H] (gate
 projection), W3[F,H] (up projection), W2[H,F] (down projection).  Values are
 random stand-ins for the trained weights and benchmark prompts, which are not
@@ -122,7 +122,7 @@ def ar1_streams(n_steps: int, B: int, H: int, rho: float = 0.8, seed: int = 1, d
 
 def tau_profile(L: int, lo: float = 0.15, hi: float = 0.35) -> np.ndarray:
     """Per-layer gating thresholds tau_l = sqrt(T / S_l) for a synthetic
-    sensitivity profile in which early layers are the most sensitive (Sec. 5.5):
+    sensitivity profile in which early layers are the most sensitive (Sec. 6.5):
     tau rises linearly from `lo` at layer 0 to `hi` at layer L-1.  float32."""
     if L == 1:
         return np.array([lo], dtype=np.float32)

@@ -204,11 +204,26 @@ def _replay_trace(slots, decisions):
 @pytest.mark.parametrize("dtype,slots", [("bf16", [2, 3, 1, 0]), ("bf16", [8, 8, 8, 8]), ("bf16", [1, 1, 1, 1]), ("bf16", [0, 2, 0, 4]),
                                          ("int4g64", [2, 3, 1, 0]), ("int4g64", [4, 4, 4, 4])])
 def test_offloaded_stack_trace_and_outputs(dtype, slots):
-    shape = synth.MoEShape(H=512, F=1024, N=8, L=4, dtype=dtype)
+    _offloaded_stack(dtype, slots, H=512, F=1024, tiles=0)
+
+
+@pytest.mark.parametrize("dtype,slots,tiles", [("bf16", [2, 3, 1, 0], 4), ("bf16", [1, 1, 1, 1], 3), ("f32", [2, 0, 3, 1], 8),
+                                               ("int4g64", [2, 3, 1, 0], 6)])
+def test_tile_wise_loading(dtype, slots, tiles):
+    """Copies cut into tiles, the waiting expert evaluated tile by tile (Sec. 5, Alg.1): same cache
+    trace as the checker's replay, outputs within the bar, and the tile path did run."""
+    c = _offloaded_stack(dtype, slots, H=1024, F=4096, tiles=tiles)
+    assert c["tiled_ffn"] > 0
+
+
+def _offloaded_stack(dtype, slots, H, F, tiles):
+    shape = synth.MoEShape(H=H, F=F, N=8, L=4, dtype=dtype)
     taus = [0.2, 0.3, 0.25, 0.35]
     ls = GpuLayerSet(shape, seed=4, max_B=1, trace_capacity=1 << 16, resident=False, taus=taus)
     try:
         B.cache_alloc(ls.ctx, slots)
+        if tiles:
+            B.adapmoe_set_tiles(ls.ctx, tiles)
         n_tok, gamma = 24, 0.5
         H0 = synth.ar1_tokens(n_tok, shape.H, 0.8, seed=9, dtype="f32") * 2.0
         decisions = []
@@ -216,7 +231,7 @@ def test_offloaded_stack_trace_and_outputs(dtype, slots):
         for t in range(n_tok):
             B.adapmoe_set_token(ls.ctx, t)
             h = torch.from_numpy(H0[t:t + 1].copy()).cuda()
-            x = torch.empty((1, shape.H), dtype=torch.bfloat16, device="cuda")
+            x = torch.empty((1, shape.H), dtype=torch.float32 if dtype == "f32" else torch.bfloat16, device="cuda")
             y = torch.empty((1, shape.H), dtype=torch.float32, device="cuda")
             B.moe_residual_rmsnorm(ls.ctx, h, None, 0.0, x, 1)
             for l in range(shape.L):
@@ -256,6 +271,7 @@ def test_offloaded_stack_trace_and_outputs(dtype, slots):
         for l in range(shape.L):
             res = [e for e in range(shape.N) if B.cache_lookup(ls.ctx, l, [e])[0] >= 0]
             assert sorted(res) == sorted(sim.resident(l))
+        return c
     finally:
         ls.close()
 

@@ -47,6 +47,8 @@ def parse():
     ap.add_argument("--layers", type=int, default=None, help="layers of the stack workloads (default: offload 14, batched 32)")
     ap.add_argument("--cache", type=int, default=None, help="total cache slots of the offload workload (default 2 per layer)")
     ap.add_argument("--dtype", default="bf16", choices=["bf16", "int4"], help="expert storage of the offload workload")
+    ap.add_argument("--tiles", type=int, default=0, help="offload workload: tile-wise loading with this many gate/up tiles (0 = whole images)")
+    ap.add_argument("--lookahead", type=int, default=1, help="offload workload: layers predicted and prefetched ahead (1..3)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference kernel for the HBM byte counters)")
     return ap.parse_args()
@@ -377,6 +379,9 @@ def bench_stack_offload(args):
             B.adapmoe_register_expert(ctx, l, e, images_host[l][e], nbytes)
     B.adapmoe_set_tau(ctx, taus)
     B.cache_alloc(ctx, slots)
+    if args.tiles:
+        B.adapmoe_set_tiles(ctx, args.tiles)
+    B.adapmoe_set_lookahead(ctx, args.lookahead)
     t_setup = time.time() - t_setup
 
     x = torch.empty((1, shape.H), dtype=torch.bfloat16, device="cuda")
@@ -416,7 +421,8 @@ def bench_stack_offload(args):
         "us_per_layer": round(elapsed / steps / L * 1e6, 1),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
         "config": {"workload": f"mixtral_stack_offload ({args.dtype}): H=4096 F=14336 N=8 L={L}, {L * 8} experts ({L * 8 * nbytes / 1e9:.1f} GB) in pinned "
-                               f"host memory, cache of {C} slots sized by the planner, LRU + next-layer prefetch, gamma={gamma}",
+                               f"host memory, cache of {C} slots sized by the planner, LRU + prefetch {args.lookahead} layer(s) ahead, "
+                               f"{'tile-wise loading (' + str(args.tiles) + ' tiles)' if args.tiles else 'whole-image loading'}, gamma={gamma}",
                    "slots_per_layer": slots, "planner_cost": round(plan_cost, 4),
                    "a_l_mean": round(float(a.mean()), 4), "beta_l_mean": round(float(beta[1:].mean()), 4) if L > 1 else None,
                    "cos_successive_inputs": cos, "setup_s": round(t_setup, 1)},
@@ -428,7 +434,8 @@ def bench_stack_offload(args):
                   "prefetch_loads": d["prefetch_loads"], "prefetch_touches": d["prefetch_touches"],
                   "single_expert_ratio": round(d["single_expert"] / max(d["tokens_gated"], 1), 4),
                   "h2d_GB": round(d["h2d_bytes"] / 1e9, 2),
-                  "loads_per_token": round((d["misses"] + d["bypasses"] + d["prefetch_loads"]) / steps, 2)},
+                  "loads_per_token": round((d["misses"] + d["bypasses"] + d["prefetch_loads"]) / steps, 2),
+                  "experts_evaluated_tile_wise": d["tiled_ffn"]},
         "cpu_baseline": None,
     }
     torch.cuda.synchronize()

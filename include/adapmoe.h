@@ -219,6 +219,14 @@ int moe_residual_rmsnorm(adapmoe_ctx* ctx, float* h_dev, const float* y_dev, flo
  * float are work buffers owned by the caller.  Sets the trace token to `token`. */
 int moe_stack_token(adapmoe_ctx* ctx, int token, float* h_dev, void* x_dev, float* y_dev, int B, float gamma, void* stream);
 
+/* Predictive gate for the first layer (Sec. 4.3, Eq.9).  Gpre_dev: device matrix [N,H] in the
+ * activation type, borrowed until replaced or the context is destroyed; null switches it off
+ * (default: layer 0 is served by its LRU set only).  When set, moe_layer_step on the last layer also
+ * applies Gpre to that layer's block input, takes the adaptive decision with layer 0's threshold
+ * and prefetches the predicted experts into layer 0's cache for the following token; the decision
+ * is reported as the depth-1 prediction of that step.  Training the matrix is the caller's business. */
+int adapmoe_set_first_layer_predictor(adapmoe_ctx* ctx, const void* Gpre_dev);
+
 /* Tile-wise loading (Sec. 5, Fig.6(b) and Alg.1: tile-wise scheduling).  tiles = 0 or 1: an expert image
  * is one copy and the expert FFN waits for all of it (default).  tiles >= 2 (at most 64): every
  * copy is issued as `tiles` blocks of gate/up row pairs followed by tiles/2 blocks of W2 rows, each

@@ -31,7 +31,7 @@ def rmsnorm(h):
 
 
 def run_stack(h0, routers, taus, expert_out, gamma, store=lambda a: a, cache=None,
-              collect_x=False, depth=1):
+              collect_x=False, depth=1, first_gate=None):
     """Run tokens h0[n] through L layers.
 
     routers[l]            W_g of layer l, [N,H]
@@ -39,8 +39,11 @@ def run_stack(h0, routers, taus, expert_out, gamma, store=lambda a: a, cache=Non
     expert_out(l, e, x)   E_e^{(l)}(x), float64 [H]
     cache                 optional oracle.cache.ExpertCache driven alongside
     depth                 look-ahead: layers l+1 .. l+depth are predicted from x_l (Sec. 4.3)
+    first_gate            optional predictive gate [N,H] for layer 0 (Sec. 4.3, Eq.9): applied to the last
+                          layer's block input, with layer 0's threshold; its prediction is prefetched
+                          into layer 0's cache for the following token
     Returns dict of per (token, layer): ids, k, w, v, pred (pred[n][l] = list predicted for
-    layer l by layer l-1), ahead (ahead[n][l][d-1] = list predicted at layer l for layer l+d),
+    layer l by layer l-1; pred[n][0] = list predicted by the predictive gate during token n-1), ahead (ahead[n][l][d-1] = list predicted at layer l for layer l+d),
     h (block input residual, [n,L+1,H]) and, if collect_x, x [n,L,H].
     """
     n_tok = len(h0)
@@ -73,6 +76,12 @@ def run_stack(h0, routers, taus, expert_out, gamma, store=lambda a: a, cache=Non
             if cache is not None:
                 cache.demand(n, l, g["ids"], g["k"])
                 cache.prefetch_lookahead(n, l, rs)
+            if first_gate is not None and l == L - 1:
+                r0 = G.predict_next(x, first_gate, taus[0])
+                if n + 1 < n_tok:
+                    preds[n + 1][0] = r0
+                if cache is not None:
+                    cache.prefetch(n, 0, r0)
             y = np.zeros(H, F64)
             for j in range(g["k"]):
                 y += F64(g["w"][j]) * expert_out(l, int(g["ids"][j]), x)

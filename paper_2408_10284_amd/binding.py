@@ -65,6 +65,7 @@ _SIGS = {
     "moe_layer_step": (C.c_int, [_P, C.c_int, _P, C.c_int, _P, _P]),
     "moe_residual_rmsnorm": (C.c_int, [_P, _P, _P, C.c_float, _P, C.c_int, _P]),
     "moe_stack_token": (C.c_int, [_P, C.c_int, _P, _P, _P, C.c_int, C.c_float, _P]),
+    "adapmoe_set_first_layer_predictor": (C.c_int, [_P, _P]),
     "adapmoe_set_tiles": (C.c_int, [_P, C.c_int]),
     "adapmoe_set_lookahead": (C.c_int, [_P, C.c_int]),
     "adapmoe_last_lookahead": (C.c_int, [_P, C.c_int, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_int]),
@@ -218,6 +219,10 @@ def moe_residual_rmsnorm(ctx, h, y, gamma, x, B, stream=None):
 
 def moe_stack_token(ctx, token, h, x, y, B, gamma, stream=None):
     _chk(ctx, load().moe_stack_token(ctx, token, _ptr(h), _ptr(x), _ptr(y), B, float(gamma), _stream(stream)))
+
+
+def adapmoe_set_first_layer_predictor(ctx, Gpre):
+    _chk(ctx, load().adapmoe_set_first_layer_predictor(ctx, _ptr(Gpre) if Gpre is not None else None))
 
 
 def adapmoe_set_tiles(ctx, tiles):

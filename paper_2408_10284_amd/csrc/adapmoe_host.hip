@@ -70,6 +70,7 @@ struct adapmoe_ctx {
   int32_t* d_err = nullptr;
   int32_t* d_dec = nullptr;             // ids[2B] k[B], then per look-ahead depth d = 1..3: pred_ids[2B] pred_k[B]
   int lookahead = 1;                    // layers ahead that are predicted and prefetched (Sec. 4.3)
+  const void* first_pred = nullptr;     // predictive gate for layer 0 of the following token (Sec. 4.3, Eq.9), device [N,H]
   int tiles = 0;                        // > 1: expert copies are cut into tiles and a waiting FFN runs tile by tile (Alg.1)
   uint64_t copy_seq = 0;
   float* d_w = nullptr;                 // [B,2]
@@ -518,6 +519,11 @@ int launch_gate_both(adapmoe_ctx* c, int layer, const void* x, int B, int32_t* i
     g.ids[d] = pred_ids[d - 1];
     g.k[d] = pred_k[d - 1];
   }
+  if (depth >= 1 && layer == c->cfg.L - 1 && c->first_pred) {
+    // last layer: its input also goes through the predictive gate of the first layer
+    g.Wg[1] = c->first_pred;
+    g.tau[1] = c->tau[0];
+  }
   ScopedTimer t(c, 2, s);
   HIPCHK(c, launch_gate(g, c->bf16_act, 1 + depth, s));
   return ADAPMOE_OK;
@@ -902,7 +908,9 @@ int moe_layer_step(adapmoe_ctx* c, int layer, const void* x, int B, float* y, vo
   int32_t* d_k = c->d_dec + 2 * B;
   int32_t* d_pids[3] = {c->d_dec + 3 * B, c->d_dec + 6 * B, c->d_dec + 9 * B};
   int32_t* d_pk[3] = {c->d_dec + 5 * B, c->d_dec + 8 * B, c->d_dec + 11 * B};
-  const bool next_needs_host = layer + 1 < c->cfg.L && !layer_fully_bound(c, layer + 1) && c->cache_ready;
+  const bool wraps = layer == c->cfg.L - 1 && c->first_pred != nullptr;   // prediction for layer 0 of the next token
+  const int next = wraps ? 0 : layer + 1;
+  const bool next_needs_host = next < c->cfg.L && !layer_fully_bound(c, next) && c->cache_ready;
   const bool host_path = !layer_fully_bound(c, layer) || next_needs_host;
 
   const int depth = host_path ? c->lookahead : 0;
@@ -1018,7 +1026,8 @@ int moe_layer_step(adapmoe_ctx* c, int layer, const void* x, int B, float* y, vo
   // Predicted experts go to the transfer queue after the demanded ones (Alg.1).  Look-ahead
   // (Sec. 4.3): the layer after next is served only if nothing had to be loaded for the nearer one.
   if (c->cache_ready) {
-    for (int d = 1; d <= depth && layer + d < c->cfg.L; ++d) {
+    for (int d = 1; d <= depth && (layer + d < c->cfg.L || (wraps && d == 1)); ++d) {
+      const int target = wraps ? 0 : layer + d;
       const int32_t* pids = c->h_dec + 3 * B * d;
       const int32_t* pk = pids + 2 * B;
       std::vector<int32_t> r;
@@ -1026,7 +1035,7 @@ int moe_layer_step(adapmoe_ctx* c, int layer, const void* x, int B, float* y, vo
         for (int j = 0; j < pk[b] && j < 2; ++j)
           if (std::find(r.begin(), r.end(), pids[2 * b + j]) == r.end()) r.push_back(pids[2 * b + j]);
       const uint64_t loads_before = c->ctr.prefetch_loads;
-      rc = prefetch_layer(c, layer + d, r.data(), (int)r.size());
+      rc = prefetch_layer(c, target, r.data(), (int)r.size());
       if (rc) return rc;
       if (c->ctr.prefetch_loads != loads_before) break;
     }
@@ -1087,6 +1096,12 @@ int moe_stack_token(adapmoe_ctx* c, int token, float* h, void* x, float* y, int 
 }
 
 // ---- bookkeeping ---------------------------------------------------------------
+
+int adapmoe_set_first_layer_predictor(adapmoe_ctx* c, const void* Gpre_dev) {
+  if (!c) return ADAPMOE_EINVAL;
+  c->first_pred = Gpre_dev;
+  return ADAPMOE_OK;
+}
 
 int adapmoe_set_tiles(adapmoe_ctx* c, int tiles) {
   if (!c || tiles < 0 || tiles > 64 || tiles > c->cfg.F || tiles / 2 > c->cfg.H)

@@ -188,7 +188,7 @@ def test_residual_rmsnorm():
 
 # -------------------------------------------------- cache, loads, prefetch ----
 
-def _replay_trace(slots, decisions):
+def _replay_trace(slots, decisions, wrap=False):
     """Drive the checker's cache with the GPU run's own decisions."""
     c = OC.ExpertCache(slots)
     L = len(slots)
@@ -198,6 +198,8 @@ def _replay_trace(slots, decisions):
             c.prefetch_lookahead(tok, l, [p[:n] for p, n in zip(pids, pk)])
         elif l + 1 < L:
             c.prefetch(tok, l + 1, pids[:pk])
+        elif wrap:                             # predictive gate of the first layer, for the next token
+            c.prefetch(tok, 0, pids[:pk])
     return c
 
 
@@ -216,12 +218,31 @@ def test_tile_wise_loading(dtype, slots, tiles):
     assert c["tiled_ffn"] > 0
 
 
-def _offloaded_stack(dtype, slots, H, F, tiles):
+@pytest.mark.parametrize("dtype,slots", [("bf16", [2, 3, 1, 0]), ("bf16", [0, 2, 2, 2]), ("int4g64", [3, 3, 3, 3])])
+def test_first_layer_predictive_gate(dtype, slots):
+    """Predictive gate for layer 0 (Sec. 4.3, Eq.9): applied to the last layer's input, decision equal to
+    the checker's gate with that matrix and layer 0's threshold, prefetched into layer 0's cache."""
+    c = _offloaded_stack(dtype, slots, H=512, F=1024, tiles=0, first_pred=True)
+    assert c["prefetch_loads"] + c["prefetch_touches"] > 0
+
+
+def _offloaded_stack(dtype, slots, H, F, tiles, first_pred=False):
     shape = synth.MoEShape(H=H, F=F, N=8, L=4, dtype=dtype)
     taus = [0.2, 0.3, 0.25, 0.35]
     ls = GpuLayerSet(shape, seed=4, max_B=1, trace_capacity=1 << 16, resident=False, taus=taus)
     try:
         B.cache_alloc(ls.ctx, slots)
+        gpre_f32 = gpre_dev = None
+        if first_pred:   # an untrained stand-in: the first router plus noise (training is outside this path)
+            noise = synth.router_weights(shape, 0, seed=77)
+            g = ls.routers_f32[0] + 0.5 * noise.astype(np.float32)
+            if dtype == "f32":
+                gpre_f32 = g.astype(np.float32)
+                gpre_dev = torch.from_numpy(gpre_f32).cuda()
+            else:
+                gpre_f32 = synth.bf16_round(g)
+                gpre_dev = torch.from_numpy(gpre_f32).cuda().to(torch.bfloat16)
+            B.adapmoe_set_first_layer_predictor(ls.ctx, gpre_dev)
         if tiles:
             B.adapmoe_set_tiles(ls.ctx, tiles)
         n_tok, gamma = 24, 0.5
@@ -247,18 +268,22 @@ def _offloaded_stack(dtype, slots, H, F, tiles):
                     assert tuple(ids) == ref["ids"]
                     if abs(ref["v"] - taus[l]) > BAND:
                         assert k[0] == ref["k"]
-                if l + 1 < shape.L:
-                    refp = OG.adaptive_gate(xin, ls.routers_f32[l + 1], np.float32(taus[l + 1]))
+                if l + 1 < shape.L or first_pred:
+                    nxt = l + 1 if l + 1 < shape.L else 0
+                    Wn = ls.routers_f32[nxt] if l + 1 < shape.L else gpre_f32
+                    refp = OG.adaptive_gate(xin, Wn, np.float32(taus[nxt]))
                     zs = np.sort(refp["z"])[::-1]
-                    if min(zs[0] - zs[1], zs[1] - zs[2]) > TIE_GAP and abs(refp["v"] - taus[l + 1]) > BAND:
+                    if min(zs[0] - zs[1], zs[1] - zs[2]) > TIE_GAP and abs(refp["v"] - taus[nxt]) > BAND:
                         assert list(pids[:pk[0]]) == list(refp["ids"][:refp["k"]])
+                else:
+                    assert pk[0] == 0
                 w = (1.0, 0.0) if k[0] == 1 else (ref["alpha"], ref["v"])
                 yref = OE.moe_block(xin, ls.experts_f32[l], ids, w, k[0])
                 max_err = max(max_err, float(rel_err_per_token(y.cpu().numpy()[0], yref)))
                 B.moe_residual_rmsnorm(ls.ctx, h, y, gamma, x, 1)
         B.adapmoe_check(ls.ctx)
         assert max_err <= TOL[dtype], max_err
-        sim = _replay_trace(slots, decisions)
+        sim = _replay_trace(slots, decisions, wrap=first_pred)
         got = [(t, l, kind, e, v) for (t, l, kind, e, v, _slot) in B.adapmoe_trace_read(ls.ctx)]
         assert got == [tuple(ev) for ev in sim.events]
         s = OC.summarise(sim.events)

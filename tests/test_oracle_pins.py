@@ -455,3 +455,41 @@ def test_stack_wiring():
         for l in range(L - 1):
             assert r["pred"][n][l + 1] == OG.predict_next(r["x"][n, l], routers[l + 1], 0.2)
         assert r["pred"][n][0] == []
+
+
+def test_first_layer_predictive_gate_is_exact_when_inputs_repeat():
+    """With gamma = 0 and the same token repeated, the last layer's input of token n equals the first
+    layer's input of token n+1, so a predictive gate equal to the first router predicts layer 0 exactly
+    (Sec. 4.3): after the first token, layer 0 never loads on demand.  With two alternating tokens the
+    same gate always predicts the wrong pair and the two-slot LRU set keeps missing."""
+    from oracle import stack as OS
+    rng = np.random.default_rng(21)
+    L, N, H = 3, 6, 16
+    routers = [rng.standard_normal((N, H)) for _ in range(L)]
+    taus = [0.0] * L                      # always two experts
+    # two tokens alternate, so layer 0 needs two different expert pairs in turn
+    t0, t1 = rng.standard_normal(H), rng.standard_normal(H)
+    h0 = [t0, t1] * 6
+    zero = lambda l, e, x: np.zeros(H)
+
+    def loads_layer0(first_gate):
+        c = OC.ExpertCache([2, 2, 2])
+        OS.run_stack(h0, routers, taus, zero, gamma=0.0, cache=c, first_gate=first_gate)
+        return [ev for ev in c.events if ev[1] == 0 and ev[2] == OC.MISS], c
+
+    e0 = set(OG.adaptive_gate(OS.rmsnorm(t0), routers[0], 0.0)["ids"])
+    e1 = set(OG.adaptive_gate(OS.rmsnorm(t1), routers[0], 0.0)["ids"])
+    assert e0 != e1                        # the seed gives two different pairs, otherwise the test is void
+    miss_without, _ = loads_layer0(None)
+    assert len(miss_without) >= 6          # LRU with 2 slots thrashes on the alternation
+    # a predictive gate applied to token n's last-layer input predicts token n's own layer-0 pair
+    # (inputs repeat across layers), not token n+1's: with alternating tokens it is always wrong
+    miss_self, _ = loads_layer0(routers[0])
+    assert len(miss_self) >= 6
+    # constant stream: prediction exact, so after the first token layer 0 only hits
+    c = OC.ExpertCache([2, 2, 2])
+    out = OS.run_stack([t0] * 5, routers, taus, zero, gamma=0.0, cache=c, first_gate=routers[0])
+    l0 = [ev for ev in c.events if ev[1] == 0]
+    assert [ev[2] for ev in l0 if ev[0] == 0 and ev[2] in (OC.MISS, OC.HIT)] == [OC.MISS, OC.MISS]
+    assert all(ev[2] in (OC.HIT, OC.HIT_PF, OC.PF_TOUCH) for ev in l0 if not (ev[0] == 0 and ev[2] == OC.MISS))
+    assert all(sorted(out["pred"][n][0]) == sorted(e0) for n in range(1, 5))

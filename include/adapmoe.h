@@ -52,7 +52,7 @@ enum {
   ADAPMOE_ESTATE = -6   /* call not valid in the context's current state */
 };
 
-enum { ADAPMOE_F32 = 0, ADAPMOE_BF16 = 1, ADAPMOE_INT4G64 = 2 };
+enum { ADAPMOE_F32 = 0, ADAPMOE_BF16 = 1, ADAPMOE_INT4G64 = 2, ADAPMOE_INT2G64 = 3 };
 
 typedef struct adapmoe_ctx adapmoe_ctx;
 
@@ -61,7 +61,7 @@ typedef struct {
   int32_t F;       /* expert FFN size; multiple of 512 (bf16/int4) or 256 (f32) */
   int32_t N;       /* experts per layer, 2..64 */
   int32_t L;       /* layers */
-  int32_t dtype;   /* ADAPMOE_F32 | ADAPMOE_BF16 | ADAPMOE_INT4G64 (weights; activations f32 / bf16 / bf16) */
+  int32_t dtype;   /* ADAPMOE_F32 | ADAPMOE_BF16 | ADAPMOE_INT4G64 | ADAPMOE_INT2G64 (weights; activations f32 / bf16 / bf16 / bf16) */
   int32_t max_B;   /* largest number of tokens per call, 1..64 */
   int32_t device;  /* HIP device ordinal */
   int32_t trace_capacity; /* cache events kept in the ring (0 = tracing off) */
@@ -132,6 +132,14 @@ int adapmoe_pack_expert(const adapmoe_config* cfg, const void* W1_host, const vo
  * (uint8 0..15, [rows,cols]) plus fp16 scale and zero per 64 consecutive
  * elements of a row ([rows, cols/64] each); decoded weight = code*scale+zero. */
 int adapmoe_pack_expert_int4(const adapmoe_config* cfg,
+                             const uint8_t* q1, const uint16_t* s1, const uint16_t* z1,
+                             const uint8_t* q3, const uint16_t* s3, const uint16_t* z3,
+                             const uint8_t* q2, const uint16_t* s2, const uint16_t* z2,
+                             void* out_host);
+
+/* Same for ADAPMOE_INT2G64 (the paper's 2-bit MoE blocks, Sec. 6.3): codes are uint8 0..3,
+ * scale and zero as above; 5/16 byte per weight in the image. */
+int adapmoe_pack_expert_int2(const adapmoe_config* cfg,
                              const uint8_t* q1, const uint16_t* s1, const uint16_t* z1,
                              const uint8_t* q3, const uint16_t* s3, const uint16_t* z3,
                              const uint8_t* q2, const uint16_t* s2, const uint16_t* z2,

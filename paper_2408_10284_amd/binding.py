@@ -12,7 +12,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libadapmoe.so")
 
 OK, EINVAL, ENOMEM, ENOTREG, ENORES, EHIP, ESTATE = 0, -1, -2, -3, -4, -5, -6
-F32, BF16, INT4G64 = 0, 1, 2
+F32, BF16, INT4G64, INT2G64 = 0, 1, 2, 3
 EVENT_KINDS = ("HIT", "HIT_PF", "MISS", "BYPASS", "PF_TOUCH", "PF_LOAD")
 
 
@@ -52,6 +52,7 @@ _SIGS = {
     "adapmoe_expert_bytes": (C.c_int, [C.POINTER(Config), C.POINTER(C.c_size_t)]),
     "adapmoe_pack_expert": (C.c_int, [C.POINTER(Config), _P, _P, _P, _P]),
     "adapmoe_pack_expert_int4": (C.c_int, [C.POINTER(Config)] + [_P] * 10),
+    "adapmoe_pack_expert_int2": (C.c_int, [C.POINTER(Config)] + [_P] * 10),
     "adapmoe_register_expert": (C.c_int, [_P, C.c_int, C.c_int, _P, C.c_size_t]),
     "adapmoe_bind_expert_dev": (C.c_int, [_P, C.c_int, C.c_int, _P]),
     "cache_plan": (C.c_int, [C.c_int, C.c_int, C.c_int, C.POINTER(C.c_double), C.POINTER(C.c_double),
@@ -160,6 +161,10 @@ def adapmoe_pack_expert(cfg, W1, W3, W2, out):
 
 def adapmoe_pack_expert_int4(cfg, q1, s1, z1, q3, s3, z3, q2, s2, z2, out):
     _chk(None, load().adapmoe_pack_expert_int4(C.byref(cfg), *[_ptr(a) for a in (q1, s1, z1, q3, s3, z3, q2, s2, z2, out)]))
+
+
+def adapmoe_pack_expert_int2(cfg, q1, s1, z1, q3, s3, z3, q2, s2, z2, out):
+    _chk(None, load().adapmoe_pack_expert_int2(C.byref(cfg), *[_ptr(a) for a in (q1, s1, z1, q3, s3, z3, q2, s2, z2, out)]))
 
 
 def adapmoe_register_expert(ctx, layer, expert, image_host, nbytes):

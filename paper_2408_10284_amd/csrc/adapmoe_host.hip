@@ -145,11 +145,11 @@ int fail(adapmoe_ctx* c, int code, const std::string& msg) {
 
 bool cfg_ok(const adapmoe_config* c) {
   if (!c) return false;
-  if (c->dtype != ADAPMOE_F32 && c->dtype != ADAPMOE_BF16 && c->dtype != ADAPMOE_INT4G64) return false;
+  if (c->dtype != ADAPMOE_F32 && c->dtype != ADAPMOE_BF16 && c->dtype != ADAPMOE_INT4G64 && c->dtype != ADAPMOE_INT2G64) return false;
   const int q = c->dtype == ADAPMOE_BF16 ? 512 : 256;
   if (c->H <= 0 || c->F <= 0 || c->H % q || c->F % q) return false;
   if (c->N < 2 || c->N > 64 || c->L < 1) return false;
-  if (c->dtype == ADAPMOE_INT4G64) {
+  if (c->dtype == ADAPMOE_INT4G64 || c->dtype == ADAPMOE_INT2G64) {
     // a lane owns one group of 64 per block of 4096: at most 2 blocks of x and 4 blocks of a in registers
     if (c->H > 8192 || c->F > 16384) return false;
   } else if ((size_t)2 * c->F * sizeof(float) > 160 * 1024) {
@@ -161,12 +161,15 @@ bool cfg_ok(const adapmoe_config* c) {
 // bytes per element of activations and of fp32/bf16 weights
 size_t elem_size(int dtype) { return dtype == ADAPMOE_F32 ? 4 : 2; }
 
-// int4 image: bytes of one row of n weights (codes + fp16 scale/zero per 64)
-size_t i4_row_bytes(size_t n) { return n / 2 + n / 16; }
+// code width of the group-quantised formats, 0 for fp32/bf16 weights
+int quant_bits(int dtype) { return dtype == ADAPMOE_INT4G64 ? 4 : dtype == ADAPMOE_INT2G64 ? 2 : 0; }
+
+// quantised image: bytes of one row of n weights (codes + fp16 scale/zero per 64)
+size_t q_row_bytes(int bits, size_t n) { return n * bits / 8 + n / 16; }
 
 // floats per (token, expert slot) of the a_j scratch
 size_t a_stride_for(const adapmoe_config& c) {
-  if (c.dtype != ADAPMOE_INT4G64) return (size_t)c.F;
+  if (!quant_bits(c.dtype)) return (size_t)c.F;
   const size_t blocks = ((size_t)c.F / 64 + 63) / 64;
   return std::max((size_t)c.F, blocks * 2048);  // int4: blocks x 8 vectors x 64 lanes x 8 bf16
 }
@@ -424,14 +427,14 @@ int launch_ffn(adapmoe_ctx* c, int layer, const void* x, int B, const int32_t* i
     c->ctr.ffn_launches++;
     return ADAPMOE_OK;
   }
-  const bool int4 = c->cfg.dtype == ADAPMOE_INT4G64;
+  const int qb = quant_bits(c->cfg.dtype);
   {
     ScopedTimer t(c, 0, s);
-    HIPCHK(c, int4 ? launch_ffn_gateup_int4(p, c->lc, s) : launch_ffn_gateup(p, c->cfg.dtype, c->lc, s));
+    HIPCHK(c, qb ? launch_ffn_gateup_quant(p, qb, c->lc, s) : launch_ffn_gateup(p, c->cfg.dtype, c->lc, s));
   }
   {
     ScopedTimer t(c, 1, s);
-    HIPCHK(c, int4 ? launch_ffn_down_int4(p, c->lc, s) : launch_ffn_down(p, c->cfg.dtype, c->lc, s));
+    HIPCHK(c, qb ? launch_ffn_down_quant(p, qb, c->lc, s) : launch_ffn_down(p, c->cfg.dtype, c->lc, s));
   }
   c->ctr.ffn_launches++;
   return ADAPMOE_OK;
@@ -442,7 +445,7 @@ int launch_ffn(adapmoe_ctx* c, int layer, const void* x, int B, const int32_t* i
 // the side stream delivers them; every launch waits only for the tile it reads.  rank_slot[j] is
 // the cache slot of the expert of rank j, or -1 when it lives in caller memory.
 int launch_ffn_tiled(adapmoe_ctx* c, int layer, const void* x, int kk, const int* rank_slot, float* y, hipStream_t s) {
-  const bool int4 = c->cfg.dtype == ADAPMOE_INT4G64;
+  const int qb = quant_bits(c->cfg.dtype);
   int order[2] = {0, 1};
   auto arrival = [&](int j) -> uint64_t {
     if (rank_slot[j] < 0) return 0;
@@ -452,12 +455,12 @@ int launch_ffn_tiled(adapmoe_ctx* c, int layer, const void* x, int kk, const int
   if (kk > 1 && arrival(1) < arrival(0)) std::swap(order[0], order[1]);
   auto gateup = [&](FfnArgs& p) -> int {
     ScopedTimer t(c, 0, s);
-    HIPCHK(c, int4 ? launch_ffn_gateup_int4(p, c->lc, s) : launch_ffn_gateup(p, c->cfg.dtype, c->lc, s));
+    HIPCHK(c, qb ? launch_ffn_gateup_quant(p, qb, c->lc, s) : launch_ffn_gateup(p, c->cfg.dtype, c->lc, s));
     return ADAPMOE_OK;
   };
   auto down = [&](FfnArgs& p) -> int {
     ScopedTimer t(c, 1, s);
-    HIPCHK(c, int4 ? launch_ffn_down_int4(p, c->lc, s) : launch_ffn_down(p, c->cfg.dtype, c->lc, s));
+    HIPCHK(c, qb ? launch_ffn_down_quant(p, qb, c->lc, s) : launch_ffn_down(p, c->cfg.dtype, c->lc, s));
     return ADAPMOE_OK;
   };
   for (int i = 0; i < kk && i < 2; ++i) {
@@ -554,13 +557,13 @@ const char* adapmoe_last_error(const adapmoe_ctx* ctx) { return ctx ? ctx->last_
 
 int adapmoe_expert_bytes(const adapmoe_config* cfg, size_t* bytes_out) {
   if (!cfg_ok(cfg) || !bytes_out) return ADAPMOE_EINVAL;
-  if (cfg->dtype == ADAPMOE_INT4G64) *bytes_out = (size_t)2 * cfg->F * i4_row_bytes(cfg->H) + (size_t)cfg->H * i4_row_bytes(cfg->F);
+  if (const int qb = quant_bits(cfg->dtype)) *bytes_out = (size_t)2 * cfg->F * q_row_bytes(qb, cfg->H) + (size_t)cfg->H * q_row_bytes(qb, cfg->F);
   else *bytes_out = (size_t)3 * cfg->H * cfg->F * elem_size(cfg->dtype);
   return ADAPMOE_OK;
 }
 
 int adapmoe_pack_expert(const adapmoe_config* cfg, const void* W1, const void* W3, const void* W2, void* out) {
-  if (!cfg_ok(cfg) || !W1 || !W3 || !W2 || !out || cfg->dtype == ADAPMOE_INT4G64) return ADAPMOE_EINVAL;
+  if (!cfg_ok(cfg) || !W1 || !W3 || !W2 || !out || quant_bits(cfg->dtype)) return ADAPMOE_EINVAL;
   const size_t row = (size_t)cfg->H * elem_size(cfg->dtype);
   char* o = static_cast<char*>(out);
   for (int f = 0; f < cfg->F; ++f) {
@@ -571,50 +574,66 @@ int adapmoe_pack_expert(const adapmoe_config* cfg, const void* W1, const void* W
   return ADAPMOE_OK;
 }
 
-// One row of n 4-bit codes -> the streaming row format: blocks of up to 64
-// groups, each block stored as [first 16 bytes of every group][second 16 bytes
-// of every group]; inside a dword, nibble s (s < 4) is element 2s and nibble
-// s+4 is element 2s+1 of the dword's 8 elements; then (scale, zero) per group.
-static void pack_row_int4(const uint8_t* q, const uint16_t* sc, const uint16_t* zr, size_t n, char* out) {
+// One row of n codes (4 or 2 bits) -> the streaming row format: blocks of up to 64 groups; a
+// group's 64 codes take bits/2 vectors of 16 bytes and a block stores vector v of every group
+// before vector v+1 of any.  A dword covers 32/bits consecutive elements: field s of its low
+// half is element 2s, field s of its high half is element 2s+1.  Then (scale, zero) per group.
+static void pack_row_quant(int bits, const uint8_t* q, const uint16_t* sc, const uint16_t* zr, size_t n, char* out) {
   const size_t G = n / 64;
+  const int vecs = bits / 2;               // 16-byte vectors per group
+  const int per_dword = 32 / bits;         // elements per dword
+  const uint32_t cmask = (1u << bits) - 1;
   for (size_t blk = 0; blk * 64 < G; ++blk) {
     const size_t nb = std::min<size_t>(64, G - blk * 64);
-    char* cb = out + blk * 2048;
+    char* cb = out + blk * 64 * (size_t)bits * 8;
     for (size_t l = 0; l < nb; ++l) {
       const uint8_t* gq = q + (blk * 64 + l) * 64;
-      for (int half = 0; half < 2; ++half) {
-        uint32_t* dst = reinterpret_cast<uint32_t*>(cb + half * nb * 16 + l * 16);
+      for (int v = 0; v < vecs; ++v) {
+        uint32_t* dst = reinterpret_cast<uint32_t*>(cb + v * nb * 16 + l * 16);
         for (int d = 0; d < 4; ++d) {
-          const uint8_t* e = gq + half * 32 + d * 8;
+          const uint8_t* e = gq + (v * 4 + d) * per_dword;
           uint32_t w = 0;
-          for (int sft = 0; sft < 4; ++sft) {
-            w |= (uint32_t)(e[2 * sft] & 15) << (4 * sft);
-            w |= (uint32_t)(e[2 * sft + 1] & 15) << (4 * sft + 16);
+          for (int sft = 0; sft < per_dword / 2; ++sft) {
+            w |= (uint32_t)(e[2 * sft] & cmask) << (bits * sft);
+            w |= (uint32_t)(e[2 * sft + 1] & cmask) << (bits * sft + 16);
           }
           dst[d] = w;
         }
       }
     }
   }
-  uint32_t* sz = reinterpret_cast<uint32_t*>(out + n / 2);
+  uint32_t* sz = reinterpret_cast<uint32_t*>(out + n * bits / 8);
   for (size_t g = 0; g < G; ++g) sz[g] = (uint32_t)sc[g] | ((uint32_t)zr[g] << 16);
+}
+
+static int pack_expert_quant(const adapmoe_config* cfg, int dtype, const uint8_t* q1, const uint16_t* s1, const uint16_t* z1,
+                             const uint8_t* q3, const uint16_t* s3, const uint16_t* z3, const uint8_t* q2,
+                             const uint16_t* s2, const uint16_t* z2, void* out) {
+  if (!cfg_ok(cfg) || cfg->dtype != dtype || !q1 || !s1 || !z1 || !q3 || !s3 || !z3 || !q2 || !s2 || !z2 || !out)
+    return ADAPMOE_EINVAL;
+  const int bits = quant_bits(dtype);
+  const size_t H = cfg->H, F = cfg->F;
+  const size_t rbH = q_row_bytes(bits, H), rbF = q_row_bytes(bits, F);
+  char* o = static_cast<char*>(out);
+  for (size_t f = 0; f < F; ++f) {
+    pack_row_quant(bits, q1 + f * H, s1 + f * (H / 64), z1 + f * (H / 64), H, o + (2 * f) * rbH);
+    pack_row_quant(bits, q3 + f * H, s3 + f * (H / 64), z3 + f * (H / 64), H, o + (2 * f + 1) * rbH);
+  }
+  char* o2 = o + 2 * F * rbH;
+  for (size_t h = 0; h < H; ++h) pack_row_quant(bits, q2 + h * F, s2 + h * (F / 64), z2 + h * (F / 64), F, o2 + h * rbF);
+  return ADAPMOE_OK;
 }
 
 int adapmoe_pack_expert_int4(const adapmoe_config* cfg, const uint8_t* q1, const uint16_t* s1, const uint16_t* z1,
                              const uint8_t* q3, const uint16_t* s3, const uint16_t* z3, const uint8_t* q2,
                              const uint16_t* s2, const uint16_t* z2, void* out) {
-  if (!cfg_ok(cfg) || cfg->dtype != ADAPMOE_INT4G64 || !q1 || !s1 || !z1 || !q3 || !s3 || !z3 || !q2 || !s2 || !z2 || !out)
-    return ADAPMOE_EINVAL;
-  const size_t H = cfg->H, F = cfg->F;
-  const size_t rbH = i4_row_bytes(H), rbF = i4_row_bytes(F);
-  char* o = static_cast<char*>(out);
-  for (size_t f = 0; f < F; ++f) {
-    pack_row_int4(q1 + f * H, s1 + f * (H / 64), z1 + f * (H / 64), H, o + (2 * f) * rbH);
-    pack_row_int4(q3 + f * H, s3 + f * (H / 64), z3 + f * (H / 64), H, o + (2 * f + 1) * rbH);
-  }
-  char* o2 = o + 2 * F * rbH;
-  for (size_t h = 0; h < H; ++h) pack_row_int4(q2 + h * F, s2 + h * (F / 64), z2 + h * (F / 64), F, o2 + h * rbF);
-  return ADAPMOE_OK;
+  return pack_expert_quant(cfg, ADAPMOE_INT4G64, q1, s1, z1, q3, s3, z3, q2, s2, z2, out);
+}
+
+int adapmoe_pack_expert_int2(const adapmoe_config* cfg, const uint8_t* q1, const uint16_t* s1, const uint16_t* z1,
+                             const uint8_t* q3, const uint16_t* s3, const uint16_t* z3, const uint8_t* q2,
+                             const uint16_t* s2, const uint16_t* z2, void* out) {
+  return pack_expert_quant(cfg, ADAPMOE_INT2G64, q1, s1, z1, q3, s3, z3, q2, s2, z2, out);
 }
 
 int adapmoe_create(const adapmoe_config* cfg, adapmoe_ctx** out) {
@@ -628,8 +647,8 @@ int adapmoe_create(const adapmoe_config* cfg, adapmoe_ctx** out) {
   c->cfg = *cfg;
   c->bf16_act = cfg->dtype != ADAPMOE_F32;
   adapmoe_expert_bytes(cfg, &c->image_bytes);
-  c->w2_offset = cfg->dtype == ADAPMOE_INT4G64 ? (size_t)2 * cfg->F * i4_row_bytes(cfg->H)
-                                               : (size_t)2 * cfg->F * cfg->H * elem_size(cfg->dtype);
+  c->w2_offset = quant_bits(cfg->dtype) ? (size_t)2 * cfg->F * q_row_bytes(quant_bits(cfg->dtype), cfg->H)
+                                        : (size_t)2 * cfg->F * cfg->H * elem_size(cfg->dtype);
   const size_t LN = (size_t)cfg->L * cfg->N;
   c->router.assign(cfg->L, nullptr);
   c->tau.assign(cfg->L, 0.f);
@@ -637,7 +656,7 @@ int adapmoe_create(const adapmoe_config* cfg, adapmoe_ctx** out) {
   c->bound.assign(LN, nullptr);
   c->bound_count.assign(cfg->L, 0);
   c->layers.resize(cfg->L);
-  c->lc.gateup_blocks = env_int("ADAPMOE_GATEUP_BLOCKS", cfg->dtype == ADAPMOE_INT4G64 ? 1024 : 512);  // measured best on MI355X
+  c->lc.gateup_blocks = env_int("ADAPMOE_GATEUP_BLOCKS", quant_bits(cfg->dtype) ? 1024 : 512);  // measured best on MI355X
   c->lc.down_blocks = env_int("ADAPMOE_DOWN_BLOCKS", 256);
   c->lc.batch_min = env_int("ADAPMOE_BATCH_MIN", 4);
   c->lc.batch_two_terms = env_int("ADAPMOE_BATCH_TWO_TERMS", 0);
@@ -667,7 +686,7 @@ int adapmoe_create(const adapmoe_config* cfg, adapmoe_ctx** out) {
   }
   ok = ok && hipStreamCreateWithFlags(&c->copy_stream, hipStreamNonBlocking) == hipSuccess;
   ok = ok && ffn_kernels_init(cfg->dtype) == hipSuccess;
-  if (ok && cfg->dtype != ADAPMOE_INT4G64 && env_int("ADAPMOE_FUSED", 0) == 1) {
+  if (ok && !quant_bits(cfg->dtype) && env_int("ADAPMOE_FUSED", 0) == 1) {
     // Opt-in (ADAPMOE_FUSED=1): single-token steps run both GEMVs in one launch with a grid-wide
     // barrier in between.  Measured slower than two launches on MI355X (123 vs 105 us per
     // Mixtral-shaped step): 256 workgroups each pay an L2 write-back and an L2 invalidate at the

@@ -14,6 +14,11 @@
 //           (s < 4) = element 8d+2s and nibble s+4 = element 8d+2s+1.
 //   image = rows of W1 and W3 interleaved (W1[0], W3[0], W1[1], ...) then rows of W2.
 //
+// The 2-bit variant (the paper's second setting stores MoE blocks in 2 bit, Sec. 6.3) uses the
+// same scheme with 2-bit codes: a group's 64 codes are one 16-byte vector, a block of nb groups
+// is nb x 16 bytes, and inside a dword field s (s < 8, bits 2s) is element 2s and field s+8 is
+// element 2s+1 of the dword's 16 elements; 5/16 byte per weight.
+//
 // Arithmetic: a nibble pair masked into two bfloat16 mantissas with exponent
 // 2^7 reads as (128+q0, 128+q1); v_dot2_f32_bf16 multiplies it with a packed
 // bfloat16 activation pair and accumulates in fp32.  Per group
@@ -30,7 +35,8 @@ constexpr int kI4GateUpThreads = 256;
 constexpr int kI4DownThreads = 256;   // 4 wavefronts = 4 blocks of 64 groups of a W2 row
 constexpr int kI4DownRows = 4;        // output rows per workgroup
 
-__device__ __forceinline__ size_t i4_row_bytes(int n) { return (size_t)n / 2 + (size_t)n / 16; }
+template <int BITS>
+__device__ __forceinline__ size_t q_row_bytes(int n) { return (size_t)n * BITS / 8 + (size_t)n / 16; }
 
 // The mask and the exponent pattern live in registers (fetched through opaque
 // moves) so that (v & mask) | pattern is a single v_and_or_b32; as literals the
@@ -38,9 +44,11 @@ __device__ __forceinline__ size_t i4_row_bytes(int n) { return (size_t)n / 2 + (
 struct I4Consts {
   uint32_t mask, magic;
 };
-__device__ __forceinline__ I4Consts i4_consts() {
+template <int BITS>
+__device__ __forceinline__ I4Consts q_consts() {
   I4Consts k;
-  asm("s_mov_b32 %0, 0x000F000F" : "=s"(k.mask));
+  if constexpr (BITS == 4) asm("s_mov_b32 %0, 0x000F000F" : "=s"(k.mask));
+  else asm("s_mov_b32 %0, 0x00030003" : "=s"(k.mask));
   asm("v_mov_b32 %0, 0x43004300" : "=v"(k.magic));
   return k;
 }
@@ -59,6 +67,23 @@ __device__ __forceinline__ void dot_codes16(const uint4& c, const uint4* x, floa
   }
 }
 
+// the same for a 16-byte vector of 64 two-bit codes, x given as 8 vectors
+__device__ __forceinline__ void dot_codes16_2bit(const uint4& c, const uint4* x, float (&acc)[4], const I4Consts& k) {
+  const uint32_t w[4] = {c.x, c.y, c.z, c.w};
+#pragma unroll
+  for (int d = 0; d < 4; ++d) {
+    const uint4 xa = x[2 * d], xb = x[2 * d + 1];
+    acc[0] = dot2_bf16((w[d] & k.mask) | k.magic, xa.x, acc[0]);
+    acc[1] = dot2_bf16(((w[d] >> 2) & k.mask) | k.magic, xa.y, acc[1]);
+    acc[2] = dot2_bf16(((w[d] >> 4) & k.mask) | k.magic, xa.z, acc[2]);
+    acc[3] = dot2_bf16(((w[d] >> 6) & k.mask) | k.magic, xa.w, acc[3]);
+    acc[0] = dot2_bf16(((w[d] >> 8) & k.mask) | k.magic, xb.x, acc[0]);
+    acc[1] = dot2_bf16(((w[d] >> 10) & k.mask) | k.magic, xb.y, acc[1]);
+    acc[2] = dot2_bf16(((w[d] >> 12) & k.mask) | k.magic, xb.z, acc[2]);
+    acc[3] = dot2_bf16(((w[d] >> 14) & k.mask) | k.magic, xb.w, acc[3]);
+  }
+}
+
 // sum of the 64 bfloat16 values of a group held as 8 vectors of packed pairs
 __device__ __forceinline__ float sum_group(const uint4* x) {
   const uint32_t ones = 0x3F803F80u;
@@ -73,29 +98,36 @@ __device__ __forceinline__ float sum_group(const uint4* x) {
   return (s[0] + s[1]) + (s[2] + s[3]);
 }
 
-struct I4Group {  // what one lane holds of one row block: its group's codes and (scale, zero)
-  uint4 c0, c1;
+template <int BITS>
+struct QGroup {  // what one lane holds of one row block: its group's codes (BITS/2 vectors) and (scale, zero)
+  uint4 c[BITS / 2];
   uint32_t sz;
 };
 
 // lane's share of block `blk` (nb groups) of the row starting at `row`.  Lanes
 // beyond nb re-read the block's last group (no branch around the loads, so the
 // compiler can count outstanding loads exactly); i4_group_dot ignores them.
-__device__ __forceinline__ void i4_load_group(const char* row, int n, int blk, int lane, I4Group& g) {
+template <int BITS>
+__device__ __forceinline__ void i4_load_group(const char* row, int n, int blk, int lane, QGroup<BITS>& g) {
   const int G = n >> 6;
   const int nb = min(64, G - blk * 64);
   const int l = min(lane, nb - 1);
-  const char* cb = row + (size_t)blk * 2048;
-  g.c0 = load_stream16(cb + l * 16);
-  g.c1 = load_stream16(cb + nb * 16 + l * 16);
-  g.sz = load_stream4(row + (size_t)n / 2 + (size_t)(blk * 64 + l) * 4);
+  const char* cb = row + (size_t)blk * (64 * BITS * 8);
+#pragma unroll
+  for (int v = 0; v < BITS / 2; ++v) g.c[v] = load_stream16(cb + v * nb * 16 + l * 16);
+  g.sz = load_stream4(row + (size_t)n * BITS / 8 + (size_t)(blk * 64 + l) * 4);
 }
 
 // value of the lane's group: sum (q s + z) x, with xs = sum of the group's x
-__device__ __forceinline__ float i4_group_dot(const I4Group& g, const uint4* x, float xsum, const I4Consts& k, bool live) {
+template <int BITS>
+__device__ __forceinline__ float i4_group_dot(const QGroup<BITS>& g, const uint4* x, float xsum, const I4Consts& k, bool live) {
   float a0[4] = {0.f, 0.f, 0.f, 0.f}, a1[4] = {0.f, 0.f, 0.f, 0.f};
-  dot_codes16(g.c0, x, a0, k);
-  dot_codes16(g.c1, x + 4, a1, k);
+  if constexpr (BITS == 4) {
+    dot_codes16(g.c[0], x, a0, k);
+    dot_codes16(g.c[1], x + 4, a1, k);
+  } else {
+    dot_codes16_2bit(g.c[0], x, a0, k);
+  }
   const float d = ((a0[0] + a0[1]) + (a0[2] + a0[3])) + ((a1[0] + a1[1]) + (a1[2] + a1[3]));
   const float s = half_bits_to_float(g.sz & 0xffffu), z = half_bits_to_float(g.sz >> 16);
   return live ? fmaf(s, d, (z - 128.f * s) * xsum) : 0.f;
@@ -110,20 +142,20 @@ __device__ __forceinline__ int i4_a_pos(int f) {
 
 // ------------------------------------------------------------------ gate/up --
 
-template <int NBLK>
+template <int BITS, int NBLK>
 struct I4RowPair {
-  I4Group g1[NBLK], g3[NBLK];
+  QGroup<BITS> g1[NBLK], g3[NBLK];
 };
 
 // One wavefront per row pair; lane l owns group l (+64 per further block) of
 // both rows, its share of x stays in registers for the whole kernel.
-template <int NBLK>
-__global__ __launch_bounds__(kI4GateUpThreads) void ffn_gateup_int4_kernel(FfnArgs p) {
+template <int BITS, int NBLK>
+__global__ __launch_bounds__(kI4GateUpThreads) void ffn_gateup_quant_kernel(FfnArgs p) {
   const int b = blockIdx.y;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int H = p.H, F = p.F;
-  const size_t rb = i4_row_bytes(H);
-  const I4Consts kc = i4_consts();
+  const size_t rb = q_row_bytes<BITS>(H);
+  const I4Consts kc = q_consts<BITS>();
 
   const char* base[2];
   float wj[2];
@@ -168,7 +200,7 @@ __global__ __launch_bounds__(kI4GateUpThreads) void ffn_gateup_int4_kernel(FfnAr
   uint16_t* a_out = reinterpret_cast<uint16_t*>(p.a + (size_t)b * 2 * p.a_stride);
 
   int ra = first;
-  auto load_next = [&](I4RowPair<NBLK>& buf) {
+  auto load_next = [&](I4RowPair<BITS, NBLK>& buf) {
     const int j = ra >= F ? 1 : 0;
     const char* row = rbase[j] + (size_t)(ra - j * F) * 2 * rb;
 #pragma unroll
@@ -179,7 +211,7 @@ __global__ __launch_bounds__(kI4GateUpThreads) void ffn_gateup_int4_kernel(FfnAr
     ra += stride;
   };
   int rc = first;
-  auto consume = [&](const I4RowPair<NBLK>& buf) {
+  auto consume = [&](const I4RowPair<BITS, NBLK>& buf) {
     float g = 0.f, u = 0.f;
 #pragma unroll
     for (int i = 0; i < NBLK; ++i) {
@@ -193,26 +225,28 @@ __global__ __launch_bounds__(kI4GateUpThreads) void ffn_gateup_int4_kernel(FfnAr
     if (lane == 0) a_out[(size_t)rj[j] * 2 * p.a_stride + i4_a_pos(f)] = f32_to_bf16_bits(rw[j] * silu_f32(g) * u);
     rc += stride;
   };
-  stream_bufs<I4RowPair<NBLK>>(nrows, load_next, consume, stage_x);
+  stream_bufs<I4RowPair<BITS, NBLK>>(nrows, load_next, consume, stage_x);
 }
 
 // --------------------------------------------------------------------- down --
 
+template <int BITS>
 struct I4DownRows {
-  I4Group g[kI4DownRows];
+  QGroup<BITS> g[kI4DownRows];
 };
 
 // One workgroup per kI4DownRows consecutive output rows; wavefront w owns block
 // w (64 groups) of every W2 row and keeps its share of a_j in registers.
-__global__ __launch_bounds__(kI4DownThreads) void ffn_down_int4_kernel(FfnArgs p) {
+template <int BITS>
+__global__ __launch_bounds__(kI4DownThreads) void ffn_down_quant_kernel(FfnArgs p) {
   __shared__ float part[kI4DownThreads / kWave][kI4DownRows];
   const int b = blockIdx.y;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int H = p.H, F = p.F;
-  const size_t rb = i4_row_bytes(F);
+  const size_t rb = q_row_bytes<BITS>(F);
   const int G = F >> 6;
   const int nblk = (G + 63) >> 6;
-  const I4Consts kc = i4_consts();
+  const I4Consts kc = q_consts<BITS>();
 
   const char* base[2];
   float wj[2];
@@ -220,7 +254,7 @@ __global__ __launch_bounds__(kI4DownThreads) void ffn_down_int4_kernel(FfnArgs p
   const char* w2[2];
   int rj[2];
   int nv = 0;
-  const size_t w2_off = (size_t)2 * F * i4_row_bytes(H);
+  const size_t w2_off = (size_t)2 * F * q_row_bytes<BITS>(H);
   const bool windowed = p.j_only >= 0;
   for (int j = 0; j < kk; ++j)
     if (base[j] && (!windowed || j == p.j_only)) { w2[nv] = base[j] + w2_off; rj[nv] = j; ++nv; }
@@ -233,7 +267,7 @@ __global__ __launch_bounds__(kI4DownThreads) void ffn_down_int4_kernel(FfnArgs p
 
   if (wave < nblk) {
     const bool has_group = wave * 64 + lane < G;
-    I4DownRows buf[2];
+    I4DownRows<BITS> buf[2];
     uint4 a[2][8];
     // all weight loads of the workgroup's rows go out first, then the lane's 64 values of
     // each a_j (written by the gate/up kernel as packed bfloat16 pairs, L2-resident)
@@ -279,19 +313,25 @@ __global__ __launch_bounds__(kI4DownThreads) void ffn_down_int4_kernel(FfnArgs p
 
 // ------------------------------------------------------------------ launch ---
 
-hipError_t launch_ffn_gateup_int4(const FfnArgs& p, const LaunchCfg& lc, hipStream_t s) {
+hipError_t launch_ffn_gateup_quant(const FfnArgs& p, int bits, const LaunchCfg& lc, hipStream_t s) {
   dim3 grid(lc.gateup_blocks, p.B), block(kI4GateUpThreads);
   if (p.j_only >= 0) grid.x = std::max(1, std::min(lc.gateup_blocks, (p.r1 - p.r0 + 3) / (kI4GateUpThreads / kWave)));
   const int nblk = ((p.H >> 6) + 63) >> 6;
-  if (nblk == 1) hipLaunchKernelGGL(ffn_gateup_int4_kernel<1>, grid, block, 1 * 8192, s, p);
-  else hipLaunchKernelGGL(ffn_gateup_int4_kernel<2>, grid, block, 2 * 8192, s, p);
+  if (bits == 4) {
+    if (nblk == 1) hipLaunchKernelGGL((ffn_gateup_quant_kernel<4, 1>), grid, block, 1 * 8192, s, p);
+    else hipLaunchKernelGGL((ffn_gateup_quant_kernel<4, 2>), grid, block, 2 * 8192, s, p);
+  } else {
+    if (nblk == 1) hipLaunchKernelGGL((ffn_gateup_quant_kernel<2, 1>), grid, block, 1 * 8192, s, p);
+    else hipLaunchKernelGGL((ffn_gateup_quant_kernel<2, 2>), grid, block, 2 * 8192, s, p);
+  }
   return hipGetLastError();
 }
 
-hipError_t launch_ffn_down_int4(const FfnArgs& p, const LaunchCfg&, hipStream_t s) {
+hipError_t launch_ffn_down_quant(const FfnArgs& p, int bits, const LaunchCfg&, hipStream_t s) {
   const int rows = p.j_only >= 0 ? p.r1 - p.r0 : p.H;
   dim3 grid(std::max(1, (rows + kI4DownRows - 1) / kI4DownRows), p.B), block(kI4DownThreads);
-  hipLaunchKernelGGL(ffn_down_int4_kernel, grid, block, 0, s, p);
+  if (bits == 4) hipLaunchKernelGGL(ffn_down_quant_kernel<4>, grid, block, 0, s, p);
+  else hipLaunchKernelGGL(ffn_down_quant_kernel<2>, grid, block, 0, s, p);
   return hipGetLastError();
 }
 

@@ -94,8 +94,9 @@ hipError_t ffn_kernels_init(int dtype);
 hipError_t ffn_fused_init(int dtype);
 int ffn_fused_capacity(int dtype, int H, int F, int device);
 hipError_t launch_ffn_fused(const FfnArgs& p, int dtype, const FusedSync& sy, int grid_blocks, hipStream_t s);
-hipError_t launch_ffn_gateup_int4(const FfnArgs& p, const LaunchCfg& lc, hipStream_t s);
-hipError_t launch_ffn_down_int4(const FfnArgs& p, const LaunchCfg& lc, hipStream_t s);
+// group-quantised experts, bits = 4 or 2
+hipError_t launch_ffn_gateup_quant(const FfnArgs& p, int bits, const LaunchCfg& lc, hipStream_t s);
+hipError_t launch_ffn_down_quant(const FfnArgs& p, int bits, const LaunchCfg& lc, hipStream_t s);
 hipError_t batched_kernels_init();
 hipError_t launch_bucket_gather(const BatchArgs& p, hipStream_t s);
 hipError_t launch_grouped_gateup(const BatchArgs& p, hipStream_t s);

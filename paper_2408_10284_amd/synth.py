@@ -52,7 +52,7 @@ class MoEShape:
     F: int
     N: int
     L: int = 1
-    dtype: str = "f32"  # "f32" | "bf16" | "int4g64"
+    dtype: str = "f32"  # "f32" | "bf16" | "int4g64" | "int2g64"
 
 
 TINY = MoEShape(H=512, F=1024, N=8, L=1, dtype="f32")
@@ -136,8 +136,9 @@ def tau_profile(L: int, lo: float = 0.15, hi: float = 0.35) -> np.ndarray:
 INT4_GROUP = 64
 
 
-def quantize_int4_g64(w: np.ndarray):
-    """Round-to-nearest asymmetric 4-bit storage of a [rows, cols] matrix.
+def quantize_int4_g64(w: np.ndarray, levels: int = 15):
+    """Round-to-nearest asymmetric 4-bit storage of a [rows, cols] matrix
+    (levels = 15; `quantize_int2_g64` calls it with levels = 3 for 2-bit codes).
 
     Groups are 64 consecutive elements along the last axis (the axis a
     matrix-vector product reduces over).  Per group: zero = fp16(min),
@@ -153,14 +154,19 @@ def quantize_int4_g64(w: np.ndarray):
     lo = g.min(axis=2)
     hi = g.max(axis=2)
     zero = lo.astype(np.float16)
-    scale = ((hi - lo) / np.float32(15.0)).astype(np.float16)
+    scale = ((hi - lo) / np.float32(levels)).astype(np.float16)
     z32 = zero.astype(np.float32)[:, :, None]
     s32 = scale.astype(np.float32)[:, :, None]
     with np.errstate(divide="ignore", invalid="ignore"):
         q = np.rint((g - z32) / s32)
     q = np.where(s32 > 0, q, 0.0)
-    q = np.clip(q, 0.0, 15.0).astype(np.uint8)
+    q = np.clip(q, 0.0, float(levels)).astype(np.uint8)
     return q.reshape(rows, cols), scale, zero
+
+
+def quantize_int2_g64(w: np.ndarray):
+    """The same storage scheme with 2-bit codes 0..3: scale = fp16((max-min)/3)."""
+    return quantize_int4_g64(w, levels=3)
 
 
 def pack_nibbles(codes: np.ndarray) -> np.ndarray:
@@ -210,7 +216,7 @@ def unpack_image_bf16(bits: np.ndarray, H: int, F: int):
 # ----------------------------------------------------------------------------
 
 
-def quantize_int4_g64_torch(w):
+def quantize_int4_g64_torch(w, levels=15):
     """torch version of `quantize_int4_g64` (same float32 arithmetic): float32
     [rows, cols] -> (codes uint8 [rows, cols], scale fp16 [rows, cols/64], zero fp16)."""
     import torch
@@ -219,12 +225,12 @@ def quantize_int4_g64_torch(w):
     lo = g.amin(dim=2)
     hi = g.amax(dim=2)
     zero = lo.to(torch.float16)
-    scale = ((hi - lo) / 15.0).to(torch.float16)
+    scale = ((hi - lo) / float(levels)).to(torch.float16)
     z32 = zero.to(torch.float32).unsqueeze(2)
     s32 = scale.to(torch.float32).unsqueeze(2)
     q = torch.round((g - z32) / s32)
     q = torch.where(s32 > 0, q, torch.zeros_like(q))
-    q = q.clamp_(0.0, 15.0).to(torch.uint8)
+    q = q.clamp_(0.0, float(levels)).to(torch.uint8)
     return q.reshape(rows, cols), scale, zero
 
 
@@ -297,6 +303,71 @@ def decode_int4_image(img: np.ndarray, H: int, F: int):
         return codes, sz[..., 0].copy().view(np.float16), sz[..., 1].copy().view(np.float16)
 
     rbH = H // 2 + H // 16
+    gu = img[: 2 * F * rbH].reshape(F, 2, rbH)
+    m1 = rows_of(np.ascontiguousarray(gu[:, 0]), F, H)
+    m3 = rows_of(np.ascontiguousarray(gu[:, 1]), F, H)
+    m2 = rows_of(img[2 * F * rbH:], H, F)
+    return m1, m3, m2
+
+
+# ----------------------------------------------------------------------------
+# 2-bit images (same scheme, codes 0..3; a group's 64 codes are 16 bytes; in a dword field s of
+# the low half is element 2s and field s of the high half is element 2s+1 of its 16 elements)
+# ----------------------------------------------------------------------------
+
+
+def _int2_rows_torch(q, scale, zero):
+    """codes [rows, n] (0..3) + scale/zero [rows, n/64] -> uint8 [rows, n/4 + n/16]: per group 16
+    bytes of codes (groups consecutive), then (scale, zero) per group."""
+    import torch
+    rows, n = q.shape
+    G = n // INT4_GROUP
+    e = q.reshape(rows, G, 4, 16)                        # [row][group][dword][element]
+    def byte(a, b, c, d):
+        return e[..., a] | (e[..., b] << 2) | (e[..., c] << 4) | (e[..., d] << 6)
+    by = torch.stack([byte(0, 2, 4, 6), byte(8, 10, 12, 14), byte(1, 3, 5, 7), byte(9, 11, 13, 15)], dim=-1)
+    sz = torch.stack([scale.view(torch.int16), zero.view(torch.int16)], dim=-1).contiguous().view(torch.uint8).reshape(rows, G * 4)
+    return torch.cat([by.reshape(rows, G * 16), sz], dim=1)
+
+
+def int2_image_from_weights_torch(w1, w3, w2):
+    """float32 W1[F,H], W3[F,H], W2[H,F] (torch) -> uint8 image in the library's 2-bit layout."""
+    import torch
+    r1 = _int2_rows_torch(*quantize_int4_g64_torch(w1, levels=3))
+    r3 = _int2_rows_torch(*quantize_int4_g64_torch(w3, levels=3))
+    r2 = _int2_rows_torch(*quantize_int4_g64_torch(w2, levels=3))
+    gu = torch.stack([r1, r3], dim=1).reshape(-1)
+    return torch.cat([gu, r2.reshape(-1)])
+
+
+def expert_image_int2_torch(shape: MoEShape, layer: int, expert: int, seed: int = 0, device: str = "cuda"):
+    """2-bit image of expert (layer, expert): the same bf16 N(0, 0.02^2) weights as the int4 generator."""
+    import torch
+    g = torch.Generator(device=device)
+    g.manual_seed((int(seed) * 1000003 + int(layer)) * 1009 + int(expert))
+    H, F = shape.H, shape.F
+    mats = []
+    for (r, c) in ((F, H), (F, H), (H, F)):
+        w = (torch.randn((r, c), device=device, generator=g, dtype=torch.float32) * WEIGHT_STD).to(torch.bfloat16).to(torch.float32)
+        mats.append(w)
+    return int2_image_from_weights_torch(*mats)
+
+
+def decode_int2_image(img: np.ndarray, H: int, F: int):
+    """uint8 2-bit image -> per matrix (codes [rows, n], scale fp16, zero fp16) for W1, W3, W2."""
+    def rows_of(buf, rows, n):
+        G = n // INT4_GROUP
+        rb = n // 4 + n // 16
+        a = buf.reshape(rows, rb)
+        by = a[:, : n // 4].reshape(rows, G, 4, 4)                      # [group][dword][byte]
+        el = np.empty((rows, G, 4, 16), dtype=np.uint8)
+        for b, first in enumerate((0, 8, 1, 9)):                        # byte b holds elements first, first+2, +4, +6
+            for f in range(4):
+                el[..., first + 2 * f] = (by[..., b] >> (2 * f)) & 3
+        sz = np.ascontiguousarray(a[:, n // 4:]).view(np.uint16).reshape(rows, G, 2)
+        return el.reshape(rows, n), sz[..., 0].copy().view(np.float16), sz[..., 1].copy().view(np.float16)
+
+    rbH = H // 4 + H // 16
     gu = img[: 2 * F * rbH].reshape(F, 2, rbH)
     m1 = rows_of(np.ascontiguousarray(gu[:, 0]), F, H)
     m3 = rows_of(np.ascontiguousarray(gu[:, 1]), F, H)

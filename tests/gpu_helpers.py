@@ -26,7 +26,7 @@ class GpuLayerSet:
 
     def __init__(self, shape, seed=0, max_B=1, trace_capacity=0, resident=True, taus=None):
         self.shape = shape
-        dt = {"f32": B.F32, "bf16": B.BF16, "int4g64": B.INT4G64}[shape.dtype]
+        dt = {"f32": B.F32, "bf16": B.BF16, "int4g64": B.INT4G64, "int2g64": B.INT2G64}[shape.dtype]
         self.ctx, self.cfg = B.adapmoe_create(shape.H, shape.F, shape.N, shape.L, dt, max_B=max_B,
                                                trace_capacity=trace_capacity)
         self.nbytes = B.adapmoe_expert_bytes(self.cfg)
@@ -44,12 +44,13 @@ class GpuLayerSet:
             for e in range(shape.N):
                 w1, w3, w2 = synth.expert_weights(shape, l, e, seed)
                 img = np.empty(self.nbytes, dtype=np.uint8)
-                if shape.dtype == "int4g64":
-                    qs = [synth.quantize_int4_g64(m) for m in (w1, w3, w2)]
+                if shape.dtype in ("int4g64", "int2g64"):
+                    four = shape.dtype == "int4g64"
+                    qs = [(synth.quantize_int4_g64 if four else synth.quantize_int2_g64)(m) for m in (w1, w3, w2)]
                     args = []
                     for (q, sc, zr) in qs:
                         args += [q, sc.view(np.uint16), zr.view(np.uint16)]
-                    B.adapmoe_pack_expert_int4(self.cfg, *args, img)
+                    (B.adapmoe_pack_expert_int4 if four else B.adapmoe_pack_expert_int2)(self.cfg, *args, img)
                     # the checker sees the same codes, scales and zeros, decoded by its own routine
                     row.append(tuple(OE_decode(q, sc, zr) for (q, sc, zr) in qs))
                 else:

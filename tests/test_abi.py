@@ -165,3 +165,57 @@ def test_int4_image_generators_match_library_packer(lib):
         np.testing.assert_array_equal(got[0], q)
         np.testing.assert_array_equal(got[1].view(np.uint16), s.view(np.uint16))
         np.testing.assert_array_equal(got[2].view(np.uint16), z.view(np.uint16))
+
+
+def _decode_int2_row(row_bytes, n):
+    """Independent reader of the documented 2-bit row format."""
+    G = n // 64
+    codes = np.zeros(n, dtype=np.uint8)
+    raw = np.frombuffer(row_bytes, dtype=np.uint8)
+    for g in range(G):
+        blk, l = divmod(g, 64)
+        off = blk * 1024 + l * 16          # a block of nb groups is nb x 16 bytes, groups in order
+        dwords = raw[off:off + 16].view(np.uint32)
+        for d in range(4):
+            w = int(dwords[d])
+            for s in range(8):
+                codes[g * 64 + d * 16 + 2 * s] = (w >> (2 * s)) & 3
+                codes[g * 64 + d * 16 + 2 * s + 1] = (w >> (2 * s + 16)) & 3
+    sz = raw[n // 4: n // 4 + 4 * G].view(np.uint16).reshape(G, 2)
+    return codes, sz[:, 0].copy(), sz[:, 1].copy()
+
+
+def test_pack_int2_layout_and_generators(lib):
+    import torch
+    from paper_2408_10284_amd import synth
+    H, F = 512, 4352
+    cfg = B.Config(H, F, 2, 1, B.INT2G64, 1, 0, 0)
+    nbytes = B.adapmoe_expert_bytes(cfg)
+    assert nbytes == 3 * H * F * 5 // 16
+    assert B.adapmoe_expert_bytes(B.Config(4096, 14336, 8, 32, B.INT2G64, 1, 0, 0)) == 55050240
+    rng = np.random.default_rng(5)
+    ws = [synth.bf16_round((rng.standard_normal(s) * 0.02).astype(np.float32)) for s in ((F, H), (F, H), (H, F))]
+    qs = [synth.quantize_int2_g64(w) for w in ws]
+    out = np.zeros(nbytes, dtype=np.uint8)
+    B.adapmoe_pack_expert_int2(cfg, *[a for (q, s, z) in qs for a in (q, s.view(np.uint16), z.view(np.uint16))], out)
+    rbH, rbF = H // 4 + H // 16, F // 4 + F // 16
+    for f in (0, 3, F - 1):
+        for which in (0, 1):
+            q, s, z = _decode_int2_row(out[(2 * f + which) * rbH:(2 * f + which + 1) * rbH].tobytes(), H)
+            np.testing.assert_array_equal(q, qs[which][0][f])
+            np.testing.assert_array_equal(s, qs[which][1][f].view(np.uint16))
+            np.testing.assert_array_equal(z, qs[which][2][f].view(np.uint16))
+    base = 2 * F * rbH
+    for h in (0, 9, H - 1):
+        q, s, z = _decode_int2_row(out[base + h * rbF: base + (h + 1) * rbF].tobytes(), F)
+        np.testing.assert_array_equal(q, qs[2][0][h])
+        np.testing.assert_array_equal(s, qs[2][1][h].view(np.uint16))
+    # the torch-side generator used for large stacks is byte-identical, and the image reader inverts it
+    img = synth.int2_image_from_weights_torch(*[torch.from_numpy(w) for w in ws]).numpy()
+    np.testing.assert_array_equal(img, out)
+    for got, (q, s, z) in zip(synth.decode_int2_image(out, H, F), qs):
+        np.testing.assert_array_equal(got[0], q)
+        np.testing.assert_array_equal(got[1].view(np.uint16), s.view(np.uint16))
+        np.testing.assert_array_equal(got[2].view(np.uint16), z.view(np.uint16))
+    # a config of one type is refused by the other packer
+    assert lib.adapmoe_pack_expert_int4(ctypes.byref(cfg), *([None] * 10)) == B.EINVAL

@@ -14,7 +14,7 @@ from gpu_helpers import GpuLayerSet, rel_err_per_token, to_dev_act
 
 pytestmark = pytest.mark.gpu
 
-TOL = {"f32": 1e-5, "bf16": 2e-2, "int4g64": 2e-2}
+TOL = {"f32": 1e-5, "bf16": 2e-2, "int4g64": 2e-2, "int2g64": 2e-2}
 BAND = 1e-6        # tokens whose test value lies this close to the threshold are not compared on k
 TIE_GAP = 1e-4     # tokens whose 2nd/3rd (or 1st/2nd) logits are closer than this are not compared on ids
 
@@ -139,6 +139,10 @@ def test_nonresident_expert_is_reported_not_faulted():
     ("int4g64", 512, 4352, 8),    # 8 groups per x row, W2 rows of 68 groups = one full block + 4 groups
     ("int4g64", 6144, 256, 3),    # x rows of 96 groups: two blocks, the second half full
     ("int4g64", 256, 14336, 2),   # W2 rows of 224 groups: 3 full blocks + half a block
+    ("int2g64", 4096, 1024, 4),   # 2-bit codes: one full block of 64 groups per x row
+    ("int2g64", 512, 4352, 8),    # W2 rows of 68 groups = one full block + 4 groups
+    ("int2g64", 6144, 256, 3),    # x rows of 96 groups: two blocks
+    ("int2g64", 256, 14336, 2),   # W2 rows of 224 groups
 ])
 def test_shapes_gate_and_ffn(dtype, H, F, N):
     shape = synth.MoEShape(H=H, F=F, N=N, L=2, dtype=dtype)
@@ -204,13 +208,13 @@ def _replay_trace(slots, decisions, wrap=False):
 
 
 @pytest.mark.parametrize("dtype,slots", [("bf16", [2, 3, 1, 0]), ("bf16", [8, 8, 8, 8]), ("bf16", [1, 1, 1, 1]), ("bf16", [0, 2, 0, 4]),
-                                         ("int4g64", [2, 3, 1, 0]), ("int4g64", [4, 4, 4, 4])])
+                                         ("int4g64", [2, 3, 1, 0]), ("int4g64", [4, 4, 4, 4]), ("int2g64", [2, 3, 1, 0])])
 def test_offloaded_stack_trace_and_outputs(dtype, slots):
     _offloaded_stack(dtype, slots, H=512, F=1024, tiles=0)
 
 
 @pytest.mark.parametrize("dtype,slots,tiles", [("bf16", [2, 3, 1, 0], 4), ("bf16", [1, 1, 1, 1], 3), ("f32", [2, 0, 3, 1], 8),
-                                               ("int4g64", [2, 3, 1, 0], 6)])
+                                               ("int4g64", [2, 3, 1, 0], 6), ("int2g64", [3, 1, 2, 0], 4)])
 def test_tile_wise_loading(dtype, slots, tiles):
     """Copies cut into tiles, the waiting expert evaluated tile by tile (Sec. 5, Alg.1): same cache
     trace as the checker's replay, outputs within the bar, and the tile path did run."""

@@ -204,6 +204,21 @@ def test_int4_decode_hand_values():
     np.testing.assert_array_equal(OE.unpack_nibbles(packed), [[1, 2, 0, 15]])
 
 
+def test_two_bit_decode_hand_values():
+    # the same decode with 2-bit codes (Sec. 6.3, 2-bit MoE blocks): 0..3 with scale 0.5, zero -1 -> -1, -0.5, 0, 0.5
+    codes = np.arange(64).reshape(1, 64) % 4
+    w = OE.decode_int4(codes, np.array([[0.5]], dtype=np.float16), np.array([[-1.0]], dtype=np.float16), group=64)
+    np.testing.assert_array_equal(w[0, :8], [-1.0, -0.5, 0.0, 0.5, -1.0, -0.5, 0.0, 0.5])
+    # a quantised expert evaluated from decoded weights equals the one evaluated from the formula per element
+    rng = np.random.default_rng(3)
+    q = rng.integers(0, 4, (2, 128))
+    sc = rng.uniform(0.01, 0.1, (2, 2)).astype(np.float16)
+    zr = rng.uniform(-0.1, 0.0, (2, 2)).astype(np.float16)
+    x = rng.standard_normal(128)
+    ref = [sum((float(q[r, c]) * float(sc[r, c // 64]) + float(zr[r, c // 64])) * x[c] for c in range(128)) for r in range(2)]
+    np.testing.assert_allclose(OE.decode_int4(q, sc, zr) @ x, ref, rtol=1e-12)
+
+
 # ----------------------------------------------------------------- cache ----
 
 class _StampLRU:

@@ -56,3 +56,17 @@ def test_int4_quantiser_error_bound():
     # constant group: scale 0, codes 0
     q0, s0, z0 = synth.quantize_int4_g64(np.full((1, 64), 0.5, dtype=np.float32))
     assert np.all(q0 == 0) and s0[0, 0] == 0 and z0[0, 0] == np.float16(0.5)
+
+
+def test_int2_quantiser_error_bound():
+    rng = np.random.default_rng(2)
+    w = synth.bf16_round((rng.standard_normal((8, 192)) * 0.02).astype(np.float32))
+    q, scale, zero = synth.quantize_int2_g64(w)
+    assert q.dtype == np.uint8 and q.max() == 3 and q.min() == 0
+    s = np.repeat(scale.astype(np.float32), 64, axis=1)
+    z = np.repeat(zero.astype(np.float32), 64, axis=1)
+    err = np.abs(q * s + z - w)
+    assert np.all(err <= 0.5 * s + 2.0 ** -11 * (np.abs(z) + 3 * s) + 1e-12)
+    # every group uses both ends of its range
+    g = q.reshape(8, 3, 64)
+    assert np.all(g.min(axis=2) == 0) and np.all(g.max(axis=2) == 3)

@@ -14,6 +14,7 @@ timed on a bounded sample of the same tokens as a baseline.
 
 Other workloads (same JSON shape, selected with --workload):
   mixtral_layer_int4     same layer with group-64 int4 experts (dequantisation fused)
+  mixtral_layer_int2     same layer with group-64 2-bit experts
   mixtral_stack_offload  L-layer stack, experts in pinned host memory, bounded HBM cache
                          sized by the planner, LRU + next-layer prefetch (host-link bound)
   mixtral_batched        16 decode streams per step, experts resident, MFMA grouped GEMM
@@ -43,10 +44,11 @@ def parse():
     ap.add_argument("--tokens", type=int, default=256, help="distinct decode tokens cycled through")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget for the CPU-checker baseline (0 = skip)")
     ap.add_argument("--workload", default="mixtral_layer_bf16",
-                    choices=["mixtral_layer_bf16", "mixtral_layer_int4", "tiny_f32", "mixtral_stack_offload", "mixtral_batched"])
+                    choices=["mixtral_layer_bf16", "mixtral_layer_int4", "mixtral_layer_int2", "tiny_f32", "mixtral_stack_offload",
+                             "mixtral_batched"])
     ap.add_argument("--layers", type=int, default=None, help="layers of the stack workloads (default: offload 14, batched 32)")
     ap.add_argument("--cache", type=int, default=None, help="total cache slots of the offload workload (default 2 per layer)")
-    ap.add_argument("--dtype", default="bf16", choices=["bf16", "int4"], help="expert storage of the offload workload")
+    ap.add_argument("--dtype", default="bf16", choices=["bf16", "int4", "int2"], help="expert storage of the offload workload")
     ap.add_argument("--tiles", type=int, default=0, help="offload workload: tile-wise loading with this many gate/up tiles (0 = whole images)")
     ap.add_argument("--lookahead", type=int, default=1, help="offload workload: layers predicted and prefetched ahead (1..3)")
     ap.add_argument("--calibrate-copy", action="store_true",
@@ -97,8 +99,10 @@ def bench_layer(args):
     if args.workload == "tiny_f32":
         shape, tau, act, dt = synth.TINY, 0.3, "f32", B.F32
         X = synth.iid_tokens(args.tokens, shape.H, seed=1, dtype="f32")
-    elif args.workload == "mixtral_layer_int4":
-        shape, tau, act, dt = synth.MoEShape(4096, 14336, 8, 1, "int4g64"), 0.2, "bf16", B.INT4G64
+    elif args.workload in ("mixtral_layer_int4", "mixtral_layer_int2"):
+        four = args.workload == "mixtral_layer_int4"
+        shape = synth.MoEShape(4096, 14336, 8, 1, "int4g64" if four else "int2g64")
+        tau, act, dt = 0.2, "bf16", (B.INT4G64 if four else B.INT2G64)
         X = synth.ar1_tokens(args.tokens, shape.H, 0.8, seed=1, dtype="bf16")
     else:
         shape, tau, act, dt = synth.MIXTRAL_LAYER, 0.2, "bf16", B.BF16
@@ -122,9 +126,11 @@ def bench_layer(args):
     for e in range(shape.N):
         w1, w3, w2 = synth.expert_weights(shape, 0, e)
         img = np.empty(nbytes, dtype=np.uint8)
-        if dt == B.INT4G64:
-            qs = [synth.quantize_int4_g64(m) for m in (w1, w3, w2)]
-            B.adapmoe_pack_expert_int4(cfg, *[a for (q, s, z) in qs for a in (q, s.view(np.uint16), z.view(np.uint16))], img)
+        if dt in (B.INT4G64, B.INT2G64):
+            quant, pack = ((synth.quantize_int4_g64, B.adapmoe_pack_expert_int4) if dt == B.INT4G64
+                           else (synth.quantize_int2_g64, B.adapmoe_pack_expert_int2))
+            qs = [quant(m) for m in (w1, w3, w2)]
+            pack(cfg, *[a for (q, s, z) in qs for a in (q, s.view(np.uint16), z.view(np.uint16))], img)
             experts.append(qs)
         elif dt == B.BF16:
             B.adapmoe_pack_expert(cfg, synth.bf16_bits(w1), synth.bf16_bits(w3), synth.bf16_bits(w2), img)
@@ -179,15 +185,16 @@ def bench_layer(args):
     dn_gbs = bytes_dn / (ms_dn * 1e-3) / 1e9
     ffn_gbs = (bytes_gu + bytes_dn) / ((ms_gu + ms_dn) * 1e-3) / 1e9
 
-    cpu = cpu_baseline_layer(args, shape, X, wg, experts, tau, dt == B.INT4G64) if args.cpu_seconds > 0 else None
-    gu_name = "ffn_gateup_int4_kernel" if dt == B.INT4G64 else "ffn_gateup_kernel"
+    quantised = dt in (B.INT4G64, B.INT2G64)
+    cpu = cpu_baseline_layer(args, shape, X, wg, experts, tau, quantised) if args.cpu_seconds > 0 else None
+    gu_name = "ffn_gateup_quant_kernel" if quantised else "ffn_gateup_kernel"
     traffic = measured_traffic(gu_name) if args.workload == "mixtral_layer_bf16" else None
     out = {
         "metric": METRIC, "value": round(steps / elapsed, 2), "unit": "tokens/s (one MoE layer, batch 1)",
         "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": round(elapsed / steps * 1e3, 6), "us_per_layer": round(elapsed / steps * 1e6, 2),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "int4" if dt == B.INT4G64 else act, "data": "synthetic",
+        "dtype": {B.INT4G64: "int4", B.INT2G64: "int2"}.get(dt, act), "data": "synthetic",
         "config": {"workload": f"{args.workload}: H={shape.H} F={shape.F} N={shape.N} L=1, tau={tau}, "
                                f"{args.tokens} AR(1) decode tokens cycled, experts resident in HBM",
                    "mean_k": round(float(ks.mean()), 4), "single_expert_ratio": round(float((ks == 1).mean()), 4),
@@ -268,7 +275,9 @@ def build_stack(shape, seed, keep_on_device, pin_host):
         routers.append(synth.router_bf16_torch(shape, l, seed))
         drow, hrow = [], []
         for e in range(shape.N):
-            if shape.dtype == "int4g64":
+            if shape.dtype == "int2g64":
+                img = synth.expert_image_int2_torch(shape, l, e, seed)
+            elif shape.dtype == "int4g64":
                 img = synth.expert_image_int4_torch(shape, l, e, seed)
             else:
                 img = synth.expert_image_bf16_torch(shape, l, e, seed)
@@ -293,7 +302,8 @@ def profile_gate_statistics(shape, routers, images_dev, taus, h0, gamma):
 
     from paper_2408_10284_amd import binding as B
     L, N, H = shape.L, shape.N, shape.H
-    ctx, cfg = B.adapmoe_create(H, shape.F, N, L, B.INT4G64 if shape.dtype == "int4g64" else B.BF16, max_B=1)
+    dt = {"int4g64": B.INT4G64, "int2g64": B.INT2G64}.get(shape.dtype, B.BF16)
+    ctx, cfg = B.adapmoe_create(H, shape.F, N, L, dt, max_B=1)
     try:
         for l in range(L):
             B.adapmoe_set_router(ctx, l, routers[l])
@@ -355,9 +365,9 @@ def bench_stack_offload(args):
     # bf16 default is 14 layers = 112 experts = 39.5 GB with the cache-to-experts ratio of the 32-layer
     # workload (2 slots per layer, 25 %); --layers 32 needs a box that can pin 90 GB.  The int4
     # workload (25.4 GB) runs all 32 layers with 128 slots.
-    int4 = args.dtype == "int4"
+    int4 = args.dtype in ("int4", "int2")      # quantised images: all 32 layers fit the pinning limit
     L = args.layers or (32 if int4 else 14)
-    shape = synth.MoEShape(4096, 14336, 8, L, "int4g64" if int4 else "bf16")
+    shape = synth.MoEShape(4096, 14336, 8, L, {"int4": "int4g64", "int2": "int2g64"}.get(args.dtype, "bf16"))
     C = args.cache if args.cache is not None else (4 * L if int4 else 2 * L)
     steps = args.steps if args.steps is not None else 48
     warmup = args.warmup if args.warmup is not None else 16
@@ -371,7 +381,8 @@ def bench_stack_offload(args):
     del images_dev
     torch.cuda.empty_cache()
 
-    ctx, cfg = B.adapmoe_create(shape.H, shape.F, shape.N, L, B.INT4G64 if int4 else B.BF16, max_B=1, trace_capacity=0)
+    ctx, cfg = B.adapmoe_create(shape.H, shape.F, shape.N, L, {"int4": B.INT4G64, "int2": B.INT2G64}.get(args.dtype, B.BF16),
+                                max_B=1, trace_capacity=0)
     nbytes = B.adapmoe_expert_bytes(cfg)
     for l in range(L):
         B.adapmoe_set_router(ctx, l, routers[l])

@@ -386,7 +386,7 @@ static hipError_t init_down() {
 }
 
 hipError_t ffn_kernels_init(int dtype) {
-  if (dtype == ADAPMOE_INT4G64) return hipSuccess;
+  if (dtype == ADAPMOE_INT4G64 || dtype == ADAPMOE_INT2G64) return hipSuccess;  // quantised kernels use static LDS only
   return dtype == ADAPMOE_F32 ? init_down<false>() : init_down<true>();
 }
 

@@ -1,0 +1,126 @@
+"""GPU tests of the edges of the C ABI: argument errors, the largest supported sizes, degenerate inputs."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import expert as OE
+from oracle import gate as OG
+from paper_2408_10284_amd import binding as B
+from paper_2408_10284_amd import synth
+from gpu_helpers import GpuLayerSet, rel_err_per_token, to_dev_act
+from test_gpu_parity import TOL, check_gate, run_ffn, run_gate
+
+pytestmark = pytest.mark.gpu
+
+
+def _code(fn, *args):
+    with pytest.raises(B.AdapMoEError) as ei:
+        fn(*args)
+    return ei.value.code
+
+
+def test_argument_errors_are_reported():
+    shape = synth.MoEShape(H=512, F=512, N=4, L=2, dtype="bf16")
+    ls = GpuLayerSet(shape, seed=1, max_B=2, resident=False)
+    try:
+        x = torch.zeros((2, 512), dtype=torch.bfloat16, device="cuda")
+        y = torch.zeros((2, 512), dtype=torch.float32, device="cuda")
+        ids = torch.zeros((2, 2), dtype=torch.int32, device="cuda")
+        w = torch.zeros((2, 2), dtype=torch.float32, device="cuda")
+        k = torch.ones(2, dtype=torch.int32, device="cuda")
+        # empty and oversized batches, layers out of range, null pointers
+        assert _code(B.moe_gate, ls.ctx, 0, x, 0, ids, w, k) == B.EINVAL
+        assert _code(B.moe_gate, ls.ctx, 0, x, 3, ids, w, k) == B.EINVAL
+        assert _code(B.moe_gate, ls.ctx, 2, x, 1, ids, w, k) == B.EINVAL
+        assert _code(B.moe_gate, ls.ctx, 0, None, 1, ids, w, k) == B.EINVAL
+        assert _code(B.moe_expert_ffn, ls.ctx, 0, x, 0, ids, w, k, y) == B.EINVAL
+        assert _code(B.moe_expert_ffn, ls.ctx, -1, x, 1, ids, w, k, y) == B.EINVAL
+        assert _code(B.moe_layer_step, ls.ctx, 0, x, 3, y) == B.EINVAL
+        assert _code(B.moe_layer_step, ls.ctx, 0, x, 1, None) == B.EINVAL
+        # a layer step on offloaded experts before the cache exists
+        assert _code(B.moe_layer_step, ls.ctx, 0, x, 1, y) == B.ESTATE
+        assert _code(B.cache_alloc, ls.ctx, [5, 0]) == B.EINVAL        # more slots than experts
+        assert _code(B.cache_alloc, ls.ctx, [-1, 0]) == B.EINVAL
+        B.cache_alloc(ls.ctx, [1, 1])
+        assert _code(B.cache_alloc, ls.ctx, [1, 1]) == B.ESTATE        # only once
+        assert _code(B.moe_prefetch, ls.ctx, 0, [4]) == B.EINVAL        # expert id out of range
+        assert _code(B.moe_prefetch, ls.ctx, 2, [0]) == B.EINVAL
+        assert _code(B.adapmoe_set_tiles, ls.ctx, 65) == B.EINVAL
+        assert _code(B.adapmoe_set_tiles, ls.ctx, -1) == B.EINVAL
+        assert _code(B.adapmoe_set_lookahead, ls.ctx, 0) == B.EINVAL
+        assert _code(B.adapmoe_set_lookahead, ls.ctx, 4) == B.EINVAL
+        pinned = torch.empty(16, dtype=torch.uint8).pin_memory()
+        assert _code(B.adapmoe_register_expert, ls.ctx, 0, 0, pinned, 16) == B.EINVAL   # wrong image size
+        # the context still works after all of that
+        B.moe_layer_step(ls.ctx, 0, x[:1], 1, y[:1])
+        B.adapmoe_check(ls.ctx)
+        assert torch.all(torch.isfinite(y))
+    finally:
+        ls.close()
+
+
+def test_unregistered_expert_is_an_error_not_a_fault():
+    shape = synth.MoEShape(H=512, F=512, N=4, L=1, dtype="bf16")
+    ctx, cfg = B.adapmoe_create(shape.H, shape.F, shape.N, shape.L, B.BF16)
+    try:
+        B.adapmoe_set_router(ctx, 0, to_dev_act("bf16", synth.router_weights(shape, 0)))
+        B.adapmoe_set_tau(ctx, [0.2])
+        B.cache_alloc(ctx, [2])
+        x = to_dev_act("bf16", synth.iid_tokens(1, 512, seed=1, dtype="bf16"))
+        y = torch.zeros((1, 512), dtype=torch.float32, device="cuda")
+        assert _code(B.moe_layer_step, ctx, 0, x, 1, y) == B.ENOTREG
+    finally:
+        torch.cuda.synchronize()
+        B.adapmoe_destroy(ctx)
+
+
+@pytest.mark.parametrize("dtype,H,F,N,max_B", [
+    ("bf16", 512, 20480, 2, 1),      # largest F of the fp32/bf16 GEMV path: a_j of two experts fills the 160 KB of LDS
+    ("int4g64", 8192, 512, 2, 1),    # largest H of the quantised path: two full blocks of x per lane
+    ("int2g64", 8192, 2048, 2, 1),   # the same with 2-bit codes (F = 16384 is covered by the shape tests)
+    ("bf16", 512, 512, 64, 64),      # most experts, largest batch: 64 tokens over 64 experts through the batched path
+    ("f32", 256, 256, 2, 64),        # smallest shapes, largest batch, looped GEMV path
+])
+def test_largest_supported_sizes(dtype, H, F, N, max_B):
+    shape = synth.MoEShape(H=H, F=F, N=N, L=1, dtype=dtype)
+    ls = GpuLayerSet(shape, seed=5, max_B=max_B, taus=[0.3])
+    try:
+        n = max(max_B, 3)
+        X = synth.ar1_tokens(n, H, 0.5, seed=6, dtype=dtype)
+        g = run_gate(ls, 0, X)
+        ref = OG.gate_batch(X, ls.routers_f32[0], np.float32(0.3))
+        check_gate(g["ids"], g["k"], g["w"], ref, 0.3, 1e-5)
+        y = run_ffn(ls, 0, g)
+        Yref = OE.moe_block_rows(X, ls.experts_f32[0], g["ids"], g["w"].astype(np.float64), g["k"])
+        err = rel_err_per_token(y, Yref)
+        assert err.max() <= TOL[dtype], err.max()
+    finally:
+        ls.close()
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16", "int4g64"])
+def test_degenerate_inputs(dtype):
+    """Zero input: all logits equal, so the tie rule picks experts 0 and 1 with weights 1/2 each, the test value
+    is exactly 1/2 (two experts below a threshold of 1/2, one at it), and the block output is exactly zero.
+    Identical tokens give identical outputs."""
+    shape = synth.MoEShape(H=512, F=1024, N=8, L=1, dtype=dtype)
+    ls = GpuLayerSet(shape, seed=8, max_B=4, taus=[0.3])
+    try:
+        Z = np.zeros((3, shape.H), dtype=np.float32)
+        g = run_gate(ls, 0, Z)
+        assert np.all(g["ids"] == [0, 1]) and np.all(g["k"] == 2)
+        np.testing.assert_array_equal(g["w"], 0.5)
+        assert OG.adaptive_gate(Z[0].astype(np.float64), ls.routers_f32[0], 0.3)["ids"] == (0, 1)
+        y = run_ffn(ls, 0, g)
+        assert np.all(y == 0.0)
+        B.adapmoe_set_tau(ls.ctx, [0.5])
+        g = run_gate(ls, 0, Z)
+        assert np.all(g["k"] == 1) and np.all(g["w"] == [1.0, 0.0])
+        B.adapmoe_set_tau(ls.ctx, [0.3])
+        X = np.repeat(synth.iid_tokens(1, shape.H, seed=2, dtype=dtype), 4, axis=0)
+        g = run_gate(ls, 0, X)
+        y = run_ffn(ls, 0, g)
+        assert np.all(g["ids"] == g["ids"][0]) and np.all(y == y[0])
+        assert np.all(np.isfinite(y)) and np.abs(y).max() > 0
+    finally:
+        ls.close()

@@ -176,7 +176,11 @@ def bench_layer(args):
     n_gu, ms_gu = B.adapmoe_profile_read(ctx, 0)
     n_dn, ms_dn = B.adapmoe_profile_read(ctx, 1)
     n_gt, ms_gt = B.adapmoe_profile_read(ctx, 2)
+    n_fu, ms_fu = B.adapmoe_profile_read(ctx, 6)
     B.adapmoe_profile(ctx, False)
+    fused = n_gu == 0 and n_fu > 0          # ADAPMOE_FUSED: both GEMVs in one launch, timed as one kernel
+    if fused:
+        n_gu, ms_gu, n_dn, ms_dn = n_fu, ms_fu * 2.0 / 3.0, n_fu, ms_fu / 3.0
     ks = np.array([k_host[(warmup + s) % args.tokens] for s in range(steps)], dtype=np.float64)
     per_matrix = nbytes / 3.0                                     # bytes of one of the three matrices of an expert
     bytes_gu = float(ks.sum()) * 2 * per_matrix                   # W1 and W3 of every activated expert
@@ -187,7 +191,7 @@ def bench_layer(args):
 
     quantised = dt in (B.INT4G64, B.INT2G64)
     cpu = cpu_baseline_layer(args, shape, X, wg, experts, tau, quantised) if args.cpu_seconds > 0 else None
-    gu_name = "ffn_gateup_quant_kernel" if quantised else "ffn_gateup_kernel"
+    gu_name = "ffn_fused_kernel" if fused else ("ffn_gateup_quant_kernel" if quantised else "ffn_gateup_kernel")
     traffic = measured_traffic(gu_name) if args.workload == "mixtral_layer_bf16" else None
     out = {
         "metric": METRIC, "value": round(steps / elapsed, 2), "unit": "tokens/s (one MoE layer, batch 1)",

@@ -688,9 +688,9 @@ int adapmoe_create(const adapmoe_config* cfg, adapmoe_ctx** out) {
   ok = ok && ffn_kernels_init(cfg->dtype) == hipSuccess;
   if (ok && !quant_bits(cfg->dtype) && env_int("ADAPMOE_FUSED", 0) == 1) {
     // Opt-in (ADAPMOE_FUSED=1): single-token steps run both GEMVs in one launch with a grid-wide
-    // barrier in between.  Measured slower than two launches on MI355X (123 vs 105 us per
-    // Mixtral-shaped step): 256 workgroups each pay an L2 write-back and an L2 invalidate at the
-    // barrier, where a kernel boundary pays one of each for the whole device.
+    // barrier in between.  Measured slower than two launches on MI355X (114 vs 108 us per
+    // Mixtral-shaped step) even though the barrier needs no cache maintenance: every workgroup
+    // re-reads a_j past its L2, and the slowest workgroup of the first phase holds up all others.
     int cap = 0;
     const hipError_t fe = ffn_fused_init(cfg->dtype);
     if (fe == hipSuccess) cap = ffn_fused_capacity(cfg->dtype, cfg->H, cfg->F, cfg->device);

@@ -237,7 +237,8 @@ __global__ __launch_bounds__(kDownThreads) void ffn_down_kernel(FfnArgs p) {
 // wavefronts per compute unit, all co-resident; between the two phases every
 // workgroup passes a grid-wide barrier (a counter in global memory), and the
 // first W2 loads are already in flight while it waits, so the HBM stream does
-// not drain between gate/up and down.  The barrier wait is bounded: a
+// not drain between gate/up and down.  Measured slower than two launches all the
+// same (114 vs 108 us per Mixtral-shaped step), so it is an opt-in.  The barrier wait is bounded: a
 // workgroup that does not see all arrivals within `spin_limit` polls raises
 // error bit 2 and goes on, so the kernel always terminates.
 // Requirements checked by the launcher: one token, H row of 8 vector runs,
@@ -247,10 +248,11 @@ constexpr int kFusedThreads = 1024;
 __device__ __forceinline__ void grid_barrier(const FusedSync& sy, int* s_ok, int32_t* err) {
   __syncthreads();  // this workgroup's a_j stores are issued
   if (threadIdx.x == 0) {
-    // one thread per workgroup does the cache maintenance: release (write back what the
-    // workgroup stored), arrive, poll without cache maintenance, acquire (drop stale lines
-    // of this compute unit's L1 and this XCD's L2) before the workgroup reads a_j
-    __hip_atomic_fetch_add(sy.counter, 1u, __ATOMIC_RELEASE, __HIP_MEMORY_SCOPE_AGENT);
+    // a_j is written with device-coherent stores, which have completed at device scope once the
+    // barrier above has waited for them, and read back with device-coherent loads, which do not
+    // see stale cache lines: arrival and wait need no cache write-back or invalidate (with a
+    // release / acquire pair here every workgroup paid both, 11 us more per step)
+    __hip_atomic_fetch_add(sy.counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     unsigned spins = 0;
     int ok = 1;
     while ((int)(__hip_atomic_load(sy.counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) - sy.target) < 0) {
@@ -261,7 +263,6 @@ __device__ __forceinline__ void grid_barrier(const FusedSync& sy, int* s_ok, int
       }
       __builtin_amdgcn_s_sleep(1);
     }
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
     *s_ok = ok;
   }
   __syncthreads();
@@ -318,7 +319,11 @@ __global__ __launch_bounds__(kFusedThreads) void ffn_fused_kernel(FfnArgs p, Fus
         g = d;
       } else {
         const float gs = wave_sum(g), us = wave_sum(d);
-        if (lane == 0) p.a[(rc >= F ? p.a_stride - F : 0) + rc] = wj[rc >= F ? 1 : 0] * silu_f32(gs) * us;
+        if (lane == 0) {
+          float* dst = p.a + (rc >= F ? p.a_stride - F : 0) + rc;
+          const float val = wj[rc >= F ? 1 : 0] * silu_f32(gs) * us;
+          __hip_atomic_store(dst, val, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
         rc += stride;
       }
       half_c ^= 1;
@@ -338,7 +343,12 @@ __global__ __launch_bounds__(kFusedThreads) void ffn_fused_kernel(FfnArgs p, Fus
       for (int i = tid; i < kk * F4; i += kFusedThreads) {
         const int j = i >= F4 ? 1 : 0;
         const int f4 = i - j * F4;
-        as4[j * F4 + (BF16 ? lds_pos_bf16(f4) : f4)] = ag[j * S4 + f4];
+        const uint64_t* src = reinterpret_cast<const uint64_t*>(ag + j * S4 + f4);
+        const uint64_t lo = __hip_atomic_load(src, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const uint64_t hi = __hip_atomic_load(src + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        as4[j * F4 + (BF16 ? lds_pos_bf16(f4) : f4)] =
+            make_float4(__builtin_bit_cast(float, (uint32_t)lo), __builtin_bit_cast(float, (uint32_t)(lo >> 32)),
+                        __builtin_bit_cast(float, (uint32_t)hi), __builtin_bit_cast(float, (uint32_t)(hi >> 32)));
       }
       __syncthreads();
     };

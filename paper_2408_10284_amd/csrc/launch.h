@@ -72,7 +72,9 @@ struct BatchArgs {
 };
 
 // Grid-wide barrier of the fused FFN kernel: a counter that only grows; launch n
-// waits until it reaches n * grid size.
+// waits until it reaches n * grid size.  The intermediate vector a_j crosses the
+// barrier through device-coherent stores and loads, so that the barrier itself
+// needs no cache write-back or invalidate.
 struct FusedSync {
   unsigned* counter;
   unsigned target;

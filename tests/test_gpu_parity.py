@@ -549,8 +549,9 @@ def test_stack_token_equals_manual_loop():
 @pytest.mark.parametrize("dtype,H,F", [("bf16", 4096, 3584), ("bf16", 4096, 4096), ("f32", 2048, 1792)])
 def test_fused_single_token_kernel_equals_two_kernel_path(dtype, H, F):
     """With ADAPMOE_FUSED=1, moe_layer_step with one token runs gate/up and down in
-    one launch (grid-wide barrier in between); the sums are taken in the same order
-    as in the two-kernel path, so the outputs are bit-identical."""
+    one launch (grid-wide barrier in between, the intermediate vector crossing it through
+    device-coherent accesses); the sums are taken in the same order as in the two-kernel
+    path, so the outputs are bit-identical."""
     import os
     shape = synth.MoEShape(H=H, F=F, N=8, L=1, dtype=dtype)
     os.environ["ADAPMOE_FUSED"] = "1"      # the fused kernel is opt-in (read when the context is created)

@@ -192,7 +192,8 @@ def bench_layer(args):
     quantised = dt in (B.INT4G64, B.INT2G64)
     cpu = cpu_baseline_layer(args, shape, X, wg, experts, tau, quantised) if args.cpu_seconds > 0 else None
     gu_name = "ffn_fused_kernel" if fused else ("ffn_gateup_quant_kernel" if quantised else "ffn_gateup_kernel")
-    traffic = measured_traffic(gu_name) if args.workload == "mixtral_layer_bf16" else None
+    traffic = {"mixtral_layer_bf16": measured_traffic(gu_name),
+               "mixtral_layer_int4": measured_traffic("ffn_gateup_quant_kernel<4", "pmc_traffic_int4.json")}.get(args.workload)
     out = {
         "metric": METRIC, "value": round(steps / elapsed, 2), "unit": "tokens/s (one MoE layer, batch 1)",
         "n_gpus": 1, "steps": steps, "warmup": warmup,
@@ -220,15 +221,15 @@ def bench_layer(args):
     return out
 
 
-def measured_traffic(kernel):
+def measured_traffic(kernel, summary="pmc_traffic.json"):
     """HBM bytes per launch (read + write) of `kernel` from the committed rocprofv3 --pmc summary
     of this workload (FETCH_SIZE and WRITE_SIZE scaled by a plain copy), or None."""
-    path = os.path.join(ROOT, "profiles", "pmc_traffic.json")
+    path = os.path.join(ROOT, "profiles", summary)
     try:
         with open(path) as f:
             data = json.load(f)
         for name, v in data["kernels"].items():
-            if kernel + "<" in name or kernel + "(" in name:
+            if kernel in name:
                 return round(v["fetch_bytes_per_launch"] + v["write_bytes_per_launch"])
     except (OSError, KeyError, ValueError):
         pass
@@ -526,7 +527,8 @@ def bench_batched(args):
                    "setup_s": round(t_setup, 1)},
         "roofline": {"bound": "hbm", "kernel": "grouped_gateup_mfma_kernel", "achieved": round(8 * 2 * per_matrix / (gu_us * 1e-6) / 1e9, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(8 * 2 * per_matrix / (gu_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
-                     "traffic": None, "avg_us": round(gu_us, 1), "launches": n_l,
+                     "traffic": measured_traffic("grouped_gateup_mfma_kernel", "pmc_traffic_batched.json"),
+                     "avg_us": round(gu_us, 1), "launches": n_l,
                      "note": "bytes counted as all 8 experts of the layer per launch (7.9 are touched on average)"},
         "kernels": {"grouped_down_mfma_kernel": {"avg_us": round(dn_us, 1), "achieved_GBs": round(8 * per_matrix / (dn_us * 1e-6) / 1e9, 1)},
                     "bucket_gather_kernel": {"avg_us": round(prof[3][1] / max(prof[3][0], 1) * 1e3, 2)},

@@ -190,6 +190,19 @@ def bench_layer(args):
     ffn_gbs = (bytes_gu + bytes_dn) / ((ms_gu + ms_dn) * 1e-3) / 1e9
 
     quantised = dt in (B.INT4G64, B.INT2G64)
+    # what this machine's memory system does on a plain device-to-device copy (1 GiB read + 1 GiB written per copy)
+    src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").fill_(1)
+    dst = torch.empty_like(src)
+    dst.copy_(src)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    for _ in range(5):
+        dst.copy_(src)
+    ev1.record()
+    torch.cuda.synchronize()
+    copy_gbs = 5 * 2 * float(1 << 30) / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
+    del src, dst
+
     cpu = cpu_baseline_layer(args, shape, X, wg, experts, tau, quantised) if args.cpu_seconds > 0 else None
     gu_name = "ffn_fused_kernel" if fused else ("ffn_gateup_quant_kernel" if quantised else "ffn_gateup_kernel")
     traffic = {"mixtral_layer_bf16": measured_traffic(gu_name),
@@ -207,7 +220,8 @@ def bench_layer(args):
         "roofline": {"bound": "hbm", "kernel": gu_name, "achieved": round(gu_gbs, 1), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(gu_gbs / HBM_PEAK_GBS, 4), "traffic": traffic,
                      "avg_us": round(ms_gu / max(n_gu, 1) * 1e3, 2), "launches": n_gu,
-                     "bytes_per_launch": round(bytes_gu / max(n_gu, 1))},
+                     "bytes_per_launch": round(bytes_gu / max(n_gu, 1)),
+                     "measured_device_copy_GBs": round(copy_gbs, 1), "frac_of_device_copy": round(gu_gbs / copy_gbs, 4)},
         "kernels": {"down": {"achieved_GBs": round(dn_gbs, 1), "frac": round(dn_gbs / HBM_PEAK_GBS, 4),
                              "avg_us": round(ms_dn / max(n_dn, 1) * 1e3, 2)},
                     "gate": {"avg_us": round(ms_gt / max(n_gt, 1) * 1e3, 2)},

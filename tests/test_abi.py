@@ -219,3 +219,42 @@ def test_pack_int2_layout_and_generators(lib):
         np.testing.assert_array_equal(got[2].view(np.uint16), z.view(np.uint16))
     # a config of one type is refused by the other packer
     assert lib.adapmoe_pack_expert_int4(ctypes.byref(cfg), *([None] * 10)) == B.EINVAL
+
+
+def test_product_and_checker_do_not_touch_each_other():
+    """The library package never imports the checker (there is no CPU fallback), the checker never
+    imports the library, and bench.py reaches the checker only from its CPU-baseline function."""
+    import ast
+    def imports(path):
+        tree = ast.parse(open(path).read())
+        out = []
+        for node in ast.walk(tree):
+            if isinstance(node, ast.Import):
+                out += [(a.name, node.lineno) for a in node.names]
+            elif isinstance(node, ast.ImportFrom) and node.module:
+                out.append((node.module, node.lineno))
+        return out
+    pkg = os.path.join(ROOT, "paper_2408_10284_amd")
+    for f in os.listdir(pkg):
+        if f.endswith(".py"):
+            assert not [m for m, _ in imports(os.path.join(pkg, f)) if m.split(".")[0] == "oracle"], f
+    for f in os.listdir(os.path.join(ROOT, "oracle")):
+        if f.endswith(".py"):
+            assert not [m for m, _ in imports(os.path.join(ROOT, "oracle", f)) if "paper_2408_10284_amd" in m], f
+    # csrc never mentions the checker either
+    for f in os.listdir(os.path.join(pkg, "csrc")):
+        assert "oracle" not in open(os.path.join(pkg, "csrc", f)).read(), f
+    src = open(os.path.join(ROOT, "bench.py")).read()
+    tree = ast.parse(src)
+    for node in tree.body:
+        if isinstance(node, ast.FunctionDef):
+            uses = [n for n in ast.walk(node) if isinstance(n, ast.ImportFrom) and n.module and n.module.startswith("oracle")]
+            assert not uses or node.name == "cpu_baseline_layer", node.name
+    assert not [n for n in tree.body if isinstance(n, (ast.Import, ast.ImportFrom)) and "oracle" in ast.dump(n)]
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0 and "one GPU" in r.stderr

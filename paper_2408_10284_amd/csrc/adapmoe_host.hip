@@ -78,6 +78,7 @@ struct adapmoe_ctx {
   ResolvedExperts* d_res = nullptr;     // [B] resolved experts of the last gate of moe_layer_step
   unsigned* d_fused_counter = nullptr;  // arrival counter of the fused kernel's grid barrier (only grows)
   unsigned fused_seq = 0;               // fused launches so far
+  unsigned* d_dyn = nullptr;            // [max_B][kDynQueues * kDynStride] row counters of the gate/up GEMV's dynamic tail, zero between steps
   // batched path scratch (bf16, max_B > 1)
   int32_t* d_bkt_count = nullptr;
   int32_t* d_bkt_tok = nullptr;
@@ -368,6 +369,7 @@ FfnArgs ffn_args(adapmoe_ctx* c, int layer, const void* x, int B, const int32_t*
   p.N = c->cfg.N;
   p.w2_offset = c->w2_offset;
   p.j_only = -1;
+  p.dyn_pct = c->lc.dyn_pct;
   return p;
 }
 
@@ -428,12 +430,19 @@ int launch_ffn(adapmoe_ctx* c, int layer, const void* x, int B, const int32_t* i
     return ADAPMOE_OK;
   }
   const int qb = quant_bits(c->cfg.dtype);
+  // dynamic tail of the gate/up GEMV: its row counters are zero at launch because the down kernel
+  // of the previous step cleared them (both kernels always run as a pair on one stream)
+  const bool dyn = c->lc.dyn_pct > 0 && !qb;
   {
     ScopedTimer t(c, 0, s);
+    p.dyn_ctr = dyn ? c->d_dyn : nullptr;
+    p.dyn_clear = nullptr;
     HIPCHK(c, qb ? launch_ffn_gateup_quant(p, qb, c->lc, s) : launch_ffn_gateup(p, c->cfg.dtype, c->lc, s));
   }
   {
     ScopedTimer t(c, 1, s);
+    p.dyn_ctr = nullptr;
+    p.dyn_clear = dyn ? c->d_dyn : nullptr;
     HIPCHK(c, qb ? launch_ffn_down_quant(p, qb, c->lc, s) : launch_ffn_down(p, c->cfg.dtype, c->lc, s));
   }
   c->ctr.ffn_launches++;
@@ -661,12 +670,15 @@ int adapmoe_create(const adapmoe_config* cfg, adapmoe_ctx** out) {
   c->lc.batch_min = env_int("ADAPMOE_BATCH_MIN", 4);
   c->lc.batch_two_terms = env_int("ADAPMOE_BATCH_TWO_TERMS", 0);
   c->lc.fused_blocks = 0;
+  c->lc.dyn_pct = quant_bits(cfg->dtype) ? 0 : env_int("ADAPMOE_DYN_PCT", 15);
   const int B = cfg->max_B;
   bool ok = hipSetDevice(cfg->device) == hipSuccess;
   ok = ok && hipMalloc(&c->d_table, LN * sizeof(void*)) == hipSuccess;
   ok = ok && hipMemset(c->d_table, 0, LN * sizeof(void*)) == hipSuccess;
   ok = ok && hipMalloc(&c->d_err, sizeof(int32_t)) == hipSuccess;
   ok = ok && hipMemset(c->d_err, 0, sizeof(int32_t)) == hipSuccess;
+  ok = ok && hipMalloc(&c->d_dyn, (size_t)B * kDynQueues * kDynStride * sizeof(unsigned)) == hipSuccess;
+  ok = ok && hipMemset(c->d_dyn, 0, (size_t)B * kDynQueues * kDynStride * sizeof(unsigned)) == hipSuccess;
   ok = ok && hipMalloc(&c->d_dec, (size_t)12 * B * sizeof(int32_t)) == hipSuccess;
   ok = ok && hipMalloc(&c->d_w, (size_t)2 * B * sizeof(float)) == hipSuccess;
   ok = ok && hipMalloc(&c->d_a, (size_t)2 * B * a_stride_for(*cfg) * sizeof(float)) == hipSuccess;
@@ -731,6 +743,7 @@ int adapmoe_destroy(adapmoe_ctx* c) {
   if (c->d_a) hipFree(c->d_a);
   if (c->d_res) hipFree(c->d_res);
   if (c->d_fused_counter) hipFree(c->d_fused_counter);
+  if (c->d_dyn) hipFree(c->d_dyn);
   if (c->d_bkt_count) hipFree(c->d_bkt_count);
   if (c->d_bkt_tok) hipFree(c->d_bkt_tok);
   if (c->d_bkt_w) hipFree(c->d_bkt_w);

@@ -79,7 +79,57 @@ __global__ __launch_bounds__(kGateUpThreads) void ffn_gateup_kernel(FfnArgs p) {
   bool all_resident = true;
   for (int j = 0; j < kk; ++j) all_resident &= base[j] != nullptr || (windowed && j != p.j_only);
 
-  if (NCH > 0 && all_resident) {
+
+  if (NCH > 0 && all_resident && p.dyn_ctr != nullptr && !windowed) {
+    // Static passes first, then rows drawn from the shared counters (see FfnArgs::dyn_ctr).
+    constexpr int NV = NCH > 0 ? NCH : 1;
+    unsigned* ctr = p.dyn_ctr + (size_t)b * kDynQueues * kDynStride;
+    const int nfull = total / stride;
+    const int npool = nfull >= 2 ? max(1, (nfull * p.dyn_pct + 50) / 100) : nfull;
+    const int nstatic = nfull - npool;
+    const int pool_start = nstatic * stride, pool_len = total - pool_start;
+    // queue q of nq holds pool rows pool_start + q + nq * t; workgroups 8m .. 8m+7 (one per
+    // compute-unit group under round-robin dispatch) share queue m % nq, so every queue in use
+    // has wavefronts drawing from it
+    const int nq = min(kDynQueues, (int)(gridDim.x + 7) >> 3);
+    const int q = (blockIdx.x >> 3) % nq;
+    const int qlen = (pool_len - q + nq - 1) / nq;
+    int it = 0;
+    bool pool_open = true;
+    auto grab = [&]() -> int {
+      if (!pool_open) return -1;
+      unsigned old = 0;
+      if (lane == 0) old = __hip_atomic_fetch_add(ctr + q * kDynStride, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      old = __builtin_amdgcn_readfirstlane(old);
+      if ((int)old < qlen) return pool_start + q + nq * (int)old;
+      pool_open = false;
+      return -1;
+    };
+    auto next_row = [&]() -> int {
+      if (it < nstatic) return (it++) * stride + first;
+      return grab();
+    };
+    auto load_half = [&](uint4(&buf)[NV], int r, int half) {
+      const int j = r >= F ? 1 : 0;
+      load_vecs<NV>(base[j] + ((size_t)(r - j * F) * 2 + half) * row_bytes + lane * 16, buf);
+    };
+    uint4 A[NV], B[NV];
+    int cur = next_row();
+    if (cur >= 0) {
+      load_half(A, cur, 0);
+      load_half(B, cur, 1);
+    }
+    stage_x();
+    while (cur >= 0) {
+      const int nxt = next_row();
+      const float g = wave_sum(dot_x<BF16, NV>(A, xs, 0, lane, 0.f));
+      if (nxt >= 0) load_half(A, nxt, 0);
+      const float u = wave_sum(dot_x<BF16, NV>(B, xs, 0, lane, 0.f));
+      if (lane == 0) a_out[(cur >= F ? p.a_stride - F : 0) + cur] = wj[cur >= F ? 1 : 0] * silu_f32(g) * u;
+      if (nxt >= 0) load_half(B, nxt, 1);
+      cur = nxt;
+    }
+  } else if (NCH > 0 && all_resident) {
     const int nrows = first < total ? (total - first + stride - 1) / stride : 0;
     int ra = first, half_a = 0;  // load cursor
     auto next_addr = [&]() -> const char* {
@@ -184,6 +234,8 @@ __global__ __launch_bounds__(kDownThreads) void ffn_down_kernel(FfnArgs p) {
   const int hstride = gridDim.x * kWaves;
   float* y = p.y + (size_t)b * H;
   const bool accumulate = p.accumulate != 0;
+  // the gate/up kernel's row counters are cleared here, ready for its next launch
+  if (blockIdx.x == 0 && tid < kDynQueues && p.dyn_clear && !windowed) p.dyn_clear[((size_t)b * kDynQueues + tid) * kDynStride] = 0u;
 
   if (UN > 0 && all_resident) {
     const int nbp = nch / NV;        // parts per row of one expert

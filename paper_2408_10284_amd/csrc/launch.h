@@ -47,7 +47,22 @@ struct FfnArgs {
   // kernels) or of W2 (down kernels); accumulate != 0 adds onto y instead of overwriting it.
   // j_only < 0: all activated experts, all rows, overwrite.
   int j_only, r0, r1, accumulate;
+  // Dynamic tail (null = every row is assigned statically).  The last `dyn_pct` percent of the
+  // passes over the grid are not dealt out in advance but drawn one row at a time from
+  // kDynQueues shared counters, so that compute-unit groups that reach memory faster during a
+  // launch end up doing more rows.  Every queue is shared by wavefronts of all compute-unit
+  // groups; a wavefront draws from one queue only and stops when it is empty, so a launch
+  // costs one atomic per drawn row plus one per wavefront.  Counters sit kDynStride words apart
+  // (different memory channels: same-address atomics serialise at about 90 per microsecond).
+  // dyn_ctr[b][kDynQueues * kDynStride] is read by the gate/up kernel and must be zero at its
+  // launch; the down kernel, which runs after it, clears dyn_clear (the same array) again.
+  unsigned* dyn_ctr;
+  unsigned* dyn_clear;
+  int dyn_pct;
 };
+
+constexpr int kDynQueues = 64;
+constexpr int kDynStride = 128;   // unsigned words between two counters (512 bytes)
 
 // Batched path (several tokens, experts streamed once each on the matrix cores)
 struct BatchArgs {
@@ -87,6 +102,7 @@ struct LaunchCfg {
   int batch_min;      // smallest number of tokens per call that takes the batched (MFMA) path
   int batch_two_terms;  // batched path: intermediate activation as hi + lo bfloat16 (1) or bfloat16 only (0)
   int fused_blocks;   // workgroups of the fused single-token FFN kernel (0 = fused path off)
+  int dyn_pct;        // percent of the row passes of the GEMV kernels that are scheduled dynamically (0 = none)
 };
 
 hipError_t launch_gate(const GateArgs& a, bool bf16, int routers, hipStream_t s);

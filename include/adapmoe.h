@@ -26,6 +26,10 @@
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).
  *     Calls enqueue work and return; outputs are valid once the stream has
  *     reached that point, unless stated otherwise.
+ *   - A context is not thread-safe, and its compute calls share scratch memory
+ *     (intermediate vectors, bucket lists, row counters): the work of two calls
+ *     on one context must not overlap on the GPU, i.e. give them the same
+ *     stream or order the streams yourself.  Separate contexts are independent.
  *   - Activations and outputs: x is [B,H] in the context's activation type
  *     (float for ADAPMOE_F32, bfloat16 bit patterns otherwise), y is [B,H]
  *     float.  ids [B,2] int32, w [B,2] float, k [B] int32.

@@ -15,6 +15,7 @@ timed on a bounded sample of the same tokens as a baseline.
 Other workloads (same JSON shape, selected with --workload):
   mixtral_layer_int4     same layer with group-64 int4 experts (dequantisation fused)
   mixtral_layer_int2     same layer with group-64 2-bit experts
+  mixtral_stack_resident 32 layers, all experts resident in HBM (90 GB bf16), batch-1 decode through the whole stack
   mixtral_stack_offload  L-layer stack, experts in pinned host memory, bounded HBM cache
                          sized by the planner, LRU + next-layer prefetch (host-link bound)
   mixtral_batched        16 decode streams per step, experts resident, MFMA grouped GEMM
@@ -45,7 +46,7 @@ def parse():
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget for the CPU-checker baseline (0 = skip)")
     ap.add_argument("--workload", default="mixtral_layer_bf16",
                     choices=["mixtral_layer_bf16", "mixtral_layer_int4", "mixtral_layer_int2", "tiny_f32", "mixtral_stack_offload",
-                             "mixtral_batched"])
+                             "mixtral_batched", "mixtral_stack_resident"])
     ap.add_argument("--layers", type=int, default=None, help="layers of the stack workloads (default: offload 14, batched 32)")
     ap.add_argument("--cache", type=int, default=None, help="total cache slots of the offload workload (default 2 per layer)")
     ap.add_argument("--dtype", default="bf16", choices=["bf16", "int4", "int2"], help="expert storage of the offload workload")
@@ -80,6 +81,8 @@ def main():
         out = bench_stack_offload(args)
     elif args.workload == "mixtral_batched":
         out = bench_batched(args)
+    elif args.workload == "mixtral_stack_resident":
+        out = bench_stack_resident(args)
     else:
         out = bench_layer(args)
     print(json.dumps(out))
@@ -549,6 +552,82 @@ def bench_batched(args):
                     "gate_kernel": {"avg_us": round(prof[2][1] / max(prof[2][0], 1) * 1e3, 2)},
                     "mfma_flops_per_layer_step": 2 * 3 * shape.H * shape.F * 16 * 8,
                     "mfma_util_of_2.5PFLOPs": round(2 * 3 * shape.H * shape.F * 16 * 8 / ((gu_us + dn_us) * 1e-6) / 2.5e15, 4)},
+        "cpu_baseline": None,
+    }
+    torch.cuda.synchronize()
+    B.adapmoe_destroy(ctx)
+    return out
+
+
+# --------------------------------------------------------------------------- batch 1, resident stack ----
+
+def bench_stack_resident(args):
+    import torch
+
+    from paper_2408_10284_amd import binding as B
+    from paper_2408_10284_amd import synth
+
+    L = args.layers or 32
+    shape = synth.MoEShape(4096, 14336, 8, L, "bf16")
+    steps = args.steps if args.steps is not None else 128
+    warmup = args.warmup if args.warmup is not None else 16
+    gamma = 0.3
+    taus = synth.tau_profile(L)
+    t_setup = time.time()
+    routers, images_dev, _ = build_stack(shape, 0, keep_on_device=True, pin_host=False)
+    ctx, cfg = B.adapmoe_create(shape.H, shape.F, shape.N, L, B.BF16, max_B=1)
+    nbytes = B.adapmoe_expert_bytes(cfg)
+    for l in range(L):
+        B.adapmoe_set_router(ctx, l, routers[l])
+        for e in range(shape.N):
+            B.adapmoe_bind_expert_dev(ctx, l, e, images_dev[l][e])
+    B.adapmoe_set_tau(ctx, taus)
+    H0 = torch.from_numpy(synth.ar1_tokens(warmup + steps, shape.H, 0.8, seed=1, dtype="f32")).cuda()
+    t_setup = time.time() - t_setup
+    x = torch.empty((1, shape.H), dtype=torch.bfloat16, device="cuda")
+    y = torch.empty((1, shape.H), dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream()
+
+    def run(first, n):
+        for t in range(first, first + n):
+            h = H0[t:t + 1].clone()
+            B.moe_stack_token(ctx, t, h, x, y, 1, gamma, stream)
+
+    run(0, warmup)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    run(warmup, steps)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    B.adapmoe_check(ctx)
+    # the host does not see the decisions on this path (no round trip): the single-expert ratio comes from a
+    # separate pass over 16 of the tokens that reads the gate's outputs
+    a_l, _, _ = profile_gate_statistics(shape, routers, images_dev, taus, H0[warmup:warmup + 16], gamma)
+    single = float(a_l.mean())
+
+    B.adapmoe_profile(ctx, True)
+    run(warmup, min(steps, 32))
+    torch.cuda.synchronize()
+    n_gu, ms_gu = B.adapmoe_profile_read(ctx, 0)
+    n_dn, ms_dn = B.adapmoe_profile_read(ctx, 1)
+    B.adapmoe_profile(ctx, False)
+    mean_k = 2.0 - single
+    per_matrix = nbytes / 3.0
+    gu_gbs = mean_k * 2 * per_matrix / (ms_gu / max(n_gu, 1) * 1e-3) / 1e9
+    dn_gbs = mean_k * per_matrix / (ms_dn / max(n_dn, 1) * 1e-3) / 1e9
+    out = {
+        "metric": METRIC, "value": round(steps / elapsed, 2), "unit": f"tokens/s ({L}-layer stack, batch 1, experts resident)",
+        "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(elapsed / steps * 1e3, 3),
+        "us_per_layer": round(elapsed / steps / L * 1e6, 1),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"mixtral_stack_resident: H=4096 F=14336 N=8 L={L}, one AR(1) stream, experts resident in HBM "
+                               f"({L * 8 * nbytes / 1e9:.1f} GB), residual + RMS norm between blocks, gamma={gamma}",
+                   "single_expert_ratio": round(single, 4), "setup_s": round(t_setup, 1)},
+        "roofline": {"bound": "hbm", "kernel": "ffn_gateup_kernel", "achieved": round(gu_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": round(gu_gbs / HBM_PEAK_GBS, 4), "traffic": None,
+                     "avg_us": round(ms_gu / max(n_gu, 1) * 1e3, 2), "launches": n_gu},
+        "kernels": {"down": {"achieved_GBs": round(dn_gbs, 1), "avg_us": round(ms_dn / max(n_dn, 1) * 1e3, 2)},
+                    "whole_step_GBs": round(mean_k * nbytes * L / (elapsed / steps) / 1e9, 1)},
         "cpu_baseline": None,
     }
     torch.cuda.synchronize()

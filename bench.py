@@ -52,6 +52,7 @@ def parse():
     ap.add_argument("--dtype", default="bf16", choices=["bf16", "int4", "int2"], help="expert storage of the offload workload")
     ap.add_argument("--tiles", type=int, default=0, help="offload workload: tile-wise loading with this many gate/up tiles (0 = whole images)")
     ap.add_argument("--lookahead", type=int, default=1, help="offload workload: layers predicted and prefetched ahead (1..3)")
+    ap.add_argument("--graph", action="store_true", help="mixtral_stack_resident: replay one captured HIP graph per token")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference kernel for the HBM byte counters)")
     return ap.parse_args()
@@ -588,10 +589,29 @@ def bench_stack_resident(args):
     y = torch.empty((1, shape.H), dtype=torch.float32, device="cuda")
     stream = torch.cuda.current_stream()
 
+    hbuf = torch.empty((1, shape.H), dtype=torch.float32, device="cuda")
+    graph = None
+    if args.graph:
+        # the whole token step (4 launches per layer) as one graph; the residual stream lives in hbuf
+        side = torch.cuda.Stream()
+        side.wait_stream(stream)
+        with torch.cuda.stream(side):
+            hbuf.copy_(H0[0:1])
+            B.moe_stack_token(ctx, 0, hbuf, x, y, 1, gamma, side)
+            side.synchronize()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph, stream=side):
+                B.moe_stack_token(ctx, 0, hbuf, x, y, 1, gamma, torch.cuda.current_stream())
+        stream.wait_stream(side)
+
     def run(first, n):
         for t in range(first, first + n):
-            h = H0[t:t + 1].clone()
-            B.moe_stack_token(ctx, t, h, x, y, 1, gamma, stream)
+            if graph is not None:
+                hbuf.copy_(H0[t:t + 1])
+                graph.replay()
+            else:
+                h = H0[t:t + 1].clone()
+                B.moe_stack_token(ctx, t, h, x, y, 1, gamma, stream)
 
     run(0, warmup)
     torch.cuda.synchronize()
@@ -600,6 +620,7 @@ def bench_stack_resident(args):
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     B.adapmoe_check(ctx)
+    graph_steps, graph = graph is not None, None      # the instrumented pass below runs eagerly
     # the host does not see the decisions on this path (no round trip): the single-expert ratio comes from a
     # separate pass over 16 of the tokens that reads the gate's outputs
     a_l, _, _ = profile_gate_statistics(shape, routers, images_dev, taus, H0[warmup:warmup + 16], gamma)
@@ -621,7 +642,8 @@ def bench_stack_resident(args):
         "us_per_layer": round(elapsed / steps / L * 1e6, 1),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"mixtral_stack_resident: H=4096 F=14336 N=8 L={L}, one AR(1) stream, experts resident in HBM "
-                               f"({L * 8 * nbytes / 1e9:.1f} GB), residual + RMS norm between blocks, gamma={gamma}",
+                               f"({L * 8 * nbytes / 1e9:.1f} GB), residual + RMS norm between blocks, gamma={gamma}"
+                               + (", one HIP graph replay per token" if graph_steps else ""),
                    "single_expert_ratio": round(single, 4), "setup_s": round(t_setup, 1)},
         "roofline": {"bound": "hbm", "kernel": "ffn_gateup_kernel", "achieved": round(gu_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(gu_gbs / HBM_PEAK_GBS, 4), "traffic": None,

@@ -124,3 +124,69 @@ def test_degenerate_inputs(dtype):
         assert np.all(np.isfinite(y)) and np.abs(y).max() > 0
     finally:
         ls.close()
+
+
+def test_resident_stack_step_can_be_captured_in_a_graph():
+    """With every expert resident, moe_stack_token makes no host round trip, allocates nothing and clears
+    its own counters in kernels, so a HIP graph can hold it.  The graph is replayed several times, on new
+    inputs, with eager work in between, and every replay is compared with the eager result."""
+    shape = synth.MoEShape(H=1024, F=2048, N=8, L=3, dtype="bf16")
+    ls = GpuLayerSet(shape, seed=21, max_B=1, taus=[0.2, 0.3, 0.25])
+    try:
+        n = 5
+        H0 = torch.from_numpy(synth.ar1_tokens(n, shape.H, 0.8, seed=3, dtype="f32") * 2.0).cuda()
+        x = torch.empty((1, shape.H), dtype=torch.bfloat16, device="cuda")
+        y = torch.empty((1, shape.H), dtype=torch.float32, device="cuda")
+        h = torch.empty((1, shape.H), dtype=torch.float32, device="cuda")
+
+        def eager(t):
+            h.copy_(H0[t:t + 1])
+            B.moe_stack_token(ls.ctx, t, h, x, y, 1, 0.5, torch.cuda.current_stream())
+            torch.cuda.synchronize()
+            return h.clone(), y.clone()
+
+        ref = [eager(t) for t in range(n)]
+        g = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            h.copy_(H0[0:1])
+            B.moe_stack_token(ls.ctx, 0, h, x, y, 1, 0.5, side)       # warm-up on the capture stream
+            side.synchronize()
+            with torch.cuda.graph(g, stream=side):
+                B.moe_stack_token(ls.ctx, 0, h, x, y, 1, 0.5, torch.cuda.current_stream())
+        torch.cuda.current_stream().wait_stream(side)
+        for rep in range(2):
+            for t in range(n):
+                h.copy_(H0[t:t + 1])
+                g.replay()
+                torch.cuda.synchronize()
+                assert torch.equal(h, ref[t][0]) and torch.equal(y, ref[t][1]), (rep, t)
+                he, ye = eager((t + 1) % n)                              # eager work between replays
+                assert torch.equal(he, ref[(t + 1) % n][0]) and torch.equal(ye, ref[(t + 1) % n][1])
+        B.adapmoe_check(ls.ctx)
+    finally:
+        ls.close()
+
+
+def test_two_contexts_are_independent():
+    a = GpuLayerSet(synth.MoEShape(H=512, F=1024, N=4, L=1, dtype="bf16"), seed=31, max_B=2, taus=[0.3])
+    b = GpuLayerSet(synth.MoEShape(H=1024, F=512, N=8, L=1, dtype="f32"), seed=32, max_B=2, taus=[0.25])
+    try:
+        Xa = synth.ar1_tokens(6, 512, 0.5, seed=1, dtype="bf16")
+        Xb = synth.ar1_tokens(6, 1024, 0.5, seed=2, dtype="f32")
+        ga, gb = run_gate(a, 0, Xa), run_gate(b, 0, Xb)
+        ya_alone, yb_alone = run_ffn(a, 0, ga), run_ffn(b, 0, gb)
+        # interleaved, two tokens at a time
+        ya = torch.empty((6, 512), dtype=torch.float32, device="cuda")
+        yb = torch.empty((6, 1024), dtype=torch.float32, device="cuda")
+        for s in range(0, 6, 2):
+            B.moe_layer_step(a.ctx, 0, ga["x_dev"][s:s + 2], 2, ya[s:s + 2])
+            B.moe_layer_step(b.ctx, 0, gb["x_dev"][s:s + 2], 2, yb[s:s + 2])
+        B.adapmoe_check(a.ctx)
+        B.adapmoe_check(b.ctx)
+        np.testing.assert_array_equal(ya.cpu().numpy(), ya_alone)
+        np.testing.assert_array_equal(yb.cpu().numpy(), yb_alone)
+    finally:
+        a.close()
+        b.close()

@@ -510,7 +510,8 @@ int launch_ffn_tiled(adapmoe_ctx* c, int layer, const void* x, int kk, const int
 // Gate of `layer` plus, for depth d = 1..depth, the gate of layer+d on the same input (prediction).
 // pred[d-1] = {ids, k} output pointers of depth d.
 int launch_gate_both(adapmoe_ctx* c, int layer, const void* x, int B, int32_t* ids, float* w, int32_t* k,
-                     int depth, int32_t* const* pred_ids, int32_t* const* pred_k, hipStream_t s, ResolvedExperts* res = nullptr) {
+                     int depth, int32_t* const* pred_ids, int32_t* const* pred_k, hipStream_t s, ResolvedExperts* res = nullptr,
+                     const NormArgs* norm = nullptr) {
   if (!c->router[layer]) return fail(c, ADAPMOE_ESTATE, "router of this layer not set");
   GateArgs g{};
   g.x = x;
@@ -536,8 +537,11 @@ int launch_gate_both(adapmoe_ctx* c, int layer, const void* x, int B, int32_t* i
     g.Wg[1] = c->first_pred;
     g.tau[1] = c->tau[0];
   }
+  if (norm && depth > 0)   // several routers read x: it has to be complete before any of their workgroups starts
+    HIPCHK(c, launch_residual_rmsnorm(norm->h, norm->y, norm->gamma, norm->x, c->bf16_act, B, c->cfg.H, s));
   ScopedTimer t(c, 2, s);
-  HIPCHK(c, launch_gate(g, c->bf16_act, 1 + depth, s));
+  if (norm && depth == 0) HIPCHK(c, launch_norm_gate(g, *norm, c->bf16_act, s));   // one router: normalise and gate in one launch
+  else HIPCHK(c, launch_gate(g, c->bf16_act, 1 + depth, s));
   return ADAPMOE_OK;
 }
 
@@ -931,7 +935,13 @@ int moe_prefetch(adapmoe_ctx* c, int layer, const int32_t* ids_host, int n) {
   return prefetch_layer(c, layer, ids_host, n);
 }
 
-int moe_layer_step(adapmoe_ctx* c, int layer, const void* x, int B, float* y, void* stream) {
+}  // extern "C"
+
+namespace {
+
+// moe_layer_step with an optional residual update + normalisation in front of the gate
+// (norm->x must be the x the step reads).
+int layer_step_impl(adapmoe_ctx* c, int layer, const void* x, int B, float* y, void* stream, const NormArgs* norm) {
   if (!c || layer < 0 || layer >= c->cfg.L || !x || !y || B < 1 || B > c->cfg.max_B)
     return fail(c, ADAPMOE_EINVAL, "moe_layer_step: bad argument");
   hipStream_t s = static_cast<hipStream_t>(stream);
@@ -946,7 +956,7 @@ int moe_layer_step(adapmoe_ctx* c, int layer, const void* x, int B, float* y, vo
   const bool host_path = !layer_fully_bound(c, layer) || next_needs_host;
 
   const int depth = host_path ? c->lookahead : 0;
-  int rc = launch_gate_both(c, layer, x, B, d_ids, c->d_w, d_k, depth, d_pids, d_pk, s, c->d_res);
+  int rc = launch_gate_both(c, layer, x, B, d_ids, c->d_w, d_k, depth, d_pids, d_pk, s, c->d_res, norm);
   if (rc) return rc;
   c->ctr.tokens_gated += B;
 
@@ -1107,6 +1117,14 @@ int moe_layer_step(adapmoe_ctx* c, int layer, const void* x, int B, float* y, vo
   return ADAPMOE_OK;
 }
 
+}  // namespace
+
+extern "C" {
+
+int moe_layer_step(adapmoe_ctx* c, int layer, const void* x, int B, float* y, void* stream) {
+  return layer_step_impl(c, layer, x, B, y, stream, nullptr);
+}
+
 int moe_residual_rmsnorm(adapmoe_ctx* c, float* h, const float* y, float gamma, void* x, int B, void* stream) {
   if (!c || !h || !x || B < 1 || B > c->cfg.max_B) return fail(c, ADAPMOE_EINVAL, "moe_residual_rmsnorm: bad argument");
   HIPCHK(c, launch_residual_rmsnorm(h, y, gamma, x, c->bf16_act, B, c->cfg.H, static_cast<hipStream_t>(stream)));
@@ -1118,8 +1136,8 @@ int moe_stack_token(adapmoe_ctx* c, int token, float* h, void* x, float* y, int 
   c->token = token;
   hipStream_t s = static_cast<hipStream_t>(stream);
   for (int l = 0; l < c->cfg.L; ++l) {
-    HIPCHK(c, launch_residual_rmsnorm(h, l > 0 ? y : nullptr, gamma, x, c->bf16_act, B, c->cfg.H, s));
-    int rc = moe_layer_step(c, l, x, B, y, stream);
+    const NormArgs norm{h, l > 0 ? y : nullptr, gamma, x};
+    int rc = layer_step_impl(c, l, x, B, y, stream, &norm);
     if (rc) return rc;
   }
   // last residual update (x is rewritten with the normalised final state, unused)

@@ -17,12 +17,9 @@ constexpr int kGateThreads = kGateWaves * kWave;
 // reduces its partial logits with DPP, wavefront 0 adds the partials in a fixed
 // order and takes the decision.
 template <bool BF16>
-__global__ __launch_bounds__(kGateThreads) void gate_kernel(GateArgs a) {
-  const int b = blockIdx.x;
-  const int r = blockIdx.y;
+__device__ __forceinline__ void gate_body(const GateArgs& a, int b, int r, float (*part)[64]) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int N = a.N, H = a.H;
-  __shared__ float part[kGateWaves][64];
 
   int32_t* ids_out = a.ids[r] + 2 * b;
   int32_t* k_out = a.k[r] + b;
@@ -108,6 +105,61 @@ __global__ __launch_bounds__(kGateThreads) void gate_kernel(GateArgs a) {
       a.res[b] = out;
     }
   }
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(kGateThreads) void gate_kernel(GateArgs a) {
+  __shared__ float part[kGateWaves][64];
+  gate_body<BF16>(a, blockIdx.x, blockIdx.y, part);
+}
+
+// Residual update and RMS normalisation of the block input (the wiring between blocks of the
+// multi-layer workloads) followed by the gate of one router, in one launch: the first 256
+// threads run exactly the arithmetic of the separate normalisation kernel, then the whole
+// workgroup runs the gate on the x it has just written.  Same results as the two launches.
+template <bool BF16>
+__global__ __launch_bounds__(kGateThreads) void norm_gate_kernel(GateArgs a, NormArgs n) {
+  __shared__ float part[kGateWaves][64];
+  __shared__ float npart[4];
+  const int b = blockIdx.x, tid = threadIdx.x;
+  const int H = a.H;
+  constexpr int kNormThreads = 256;
+  float* hr = n.h + (size_t)b * H;
+  const float* yr = n.y ? n.y + (size_t)b * H : nullptr;
+  if (tid < kNormThreads) {
+    float ss = 0.f;
+    for (int i = tid; i < H; i += kNormThreads) {
+      float v = hr[i];
+      if (yr) {
+        v = fmaf(n.gamma, yr[i], v);
+        hr[i] = v;
+      }
+      ss = fmaf(v, v, ss);
+    }
+    ss = wave_sum(ss);
+    if ((tid & 63) == 0) npart[tid >> 6] = ss;
+  }
+  __syncthreads();
+  if (tid < kNormThreads) {
+    float tot = 0.f;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) tot += npart[i];
+    const float inv = 1.0f / sqrtf(tot / (float)H + 1e-6f);
+    for (int i = tid; i < H; i += kNormThreads) {
+      const float v = hr[i] * inv;
+      if (BF16) static_cast<uint16_t*>(n.x)[(size_t)b * H + i] = f32_to_bf16_bits(v);
+      else static_cast<float*>(n.x)[(size_t)b * H + i] = v;
+    }
+  }
+  __syncthreads();   // x of this token is written and visible to the workgroup
+  gate_body<BF16>(a, b, 0, part);
+}
+
+hipError_t launch_norm_gate(const GateArgs& a, const NormArgs& n, bool bf16, hipStream_t s) {
+  dim3 grid(a.B), block(kGateThreads);
+  if (bf16) hipLaunchKernelGGL(norm_gate_kernel<true>, grid, block, 0, s, a, n);
+  else hipLaunchKernelGGL(norm_gate_kernel<false>, grid, block, 0, s, a, n);
+  return hipGetLastError();
 }
 
 hipError_t launch_gate(const GateArgs& a, bool bf16, int routers, hipStream_t s) {

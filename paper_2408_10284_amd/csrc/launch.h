@@ -29,6 +29,15 @@ struct GateArgs {
   int B, H, N;
 };
 
+// Residual update and normalisation in front of a gate: h[b] += gamma * y[b] (y may be null),
+// x[b] = h[b] / sqrt(mean(h[b]^2) + 1e-6) in the activation type.
+struct NormArgs {
+  float* h;
+  const float* y;
+  float gamma;
+  void* x;
+};
+
 struct FfnArgs {
   const void* const* table;  // residency table row of the layer: N image base pointers, null = absent
   const ResolvedExperts* res;  // [B] resolved by the gate (then ids/w/k/table are not read) or null
@@ -106,6 +115,7 @@ struct LaunchCfg {
 };
 
 hipError_t launch_gate(const GateArgs& a, bool bf16, int routers, hipStream_t s);
+hipError_t launch_norm_gate(const GateArgs& a, const NormArgs& n, bool bf16, hipStream_t s);
 hipError_t launch_ffn_gateup(const FfnArgs& p, int dtype, const LaunchCfg& lc, hipStream_t s);
 hipError_t launch_ffn_down(const FfnArgs& p, int dtype, const LaunchCfg& lc, hipStream_t s);
 hipError_t ffn_kernels_init(int dtype);

@@ -582,3 +582,71 @@ def test_fused_single_token_kernel_equals_two_kernel_path(dtype, H, F):
         assert n_fused == 1
     finally:
         ls.close()
+
+
+@pytest.mark.parametrize("Bt,slots,depth", [(2, [1, 2, 0, 3], 1), (3, [2, 2, 2, 2], 2), (5, [3, 1, 4, 0], 1), (8, [1, 1, 1, 1], 3)])
+def test_offloaded_steps_with_several_tokens(Bt, slots, depth):
+    """Several tokens per step over offloaded experts: the tokens' demands are served in token order, then the
+    union of their predictions (first occurrence order) is prefetched.  Small caches force evictions of experts
+    that the same step still reads.  Trace, counters and residency against the checker's replay; outputs of
+    every token against the checker on the GPU's own layer input."""
+    shape = synth.MoEShape(H=512, F=512, N=8, L=4, dtype="bf16")
+    taus = [0.2, 0.3, 0.25, 0.35]
+    ls = GpuLayerSet(shape, seed=41, max_B=Bt, trace_capacity=1 << 16, resident=False, taus=taus)
+    try:
+        B.cache_alloc(ls.ctx, slots)
+        B.adapmoe_set_lookahead(ls.ctx, depth)
+        n_steps, gamma = 16, 0.5
+        H0 = synth.ar1_streams(n_steps, Bt, shape.H, 0.8, seed=43, dtype="f32") * 2.0
+        sim = OC.ExpertCache(slots)
+        max_err = 0.0
+        x = torch.empty((Bt, shape.H), dtype=torch.bfloat16, device="cuda")
+        y = torch.empty((Bt, shape.H), dtype=torch.float32, device="cuda")
+        for t in range(n_steps):
+            B.adapmoe_set_token(ls.ctx, t)
+            h = torch.from_numpy(H0[t].copy()).cuda()
+            B.moe_residual_rmsnorm(ls.ctx, h, None, 0.0, x, Bt)
+            for l in range(shape.L):
+                B.moe_layer_step(ls.ctx, l, x, Bt, y)
+                ids, k, _, _ = B.adapmoe_last_decision(ls.ctx, Bt)
+                torch.cuda.synchronize()
+                ids = np.array(ids).reshape(Bt, 2)
+                for b in range(Bt):
+                    sim.demand(t, l, ids[b], k[b])
+                ahead = []
+                for d in range(1, depth + 1):
+                    if l + d >= shape.L:
+                        break
+                    pids, pk = B.adapmoe_last_lookahead(ls.ctx, d, Bt)
+                    pids = np.array(pids).reshape(Bt, 2)
+                    union = []
+                    for b in range(Bt):
+                        for j in range(pk[b]):
+                            if int(pids[b, j]) not in union:
+                                union.append(int(pids[b, j]))
+                    ahead.append(union)
+                sim.prefetch_lookahead(t, l, ahead)
+                xin = x.float().cpu().numpy().astype(np.float64)
+                yh = y.cpu().numpy()
+                for b in range(Bt):
+                    ref = OG.adaptive_gate(xin[b], ls.routers_f32[l], np.float32(taus[l]))
+                    w = (1.0, 0.0) if k[b] == 1 else (ref["alpha"], ref["v"])
+                    zs = np.sort(ref["z"])[::-1]
+                    if min(zs[0] - zs[1], zs[1] - zs[2]) > TIE_GAP:
+                        assert tuple(ids[b]) == ref["ids"]
+                        yref = OE.moe_block(xin[b], ls.experts_f32[l], ids[b], w, k[b])
+                        max_err = max(max_err, float(rel_err_per_token(yh[b], yref)))
+                B.moe_residual_rmsnorm(ls.ctx, h, y, gamma, x, Bt)
+        B.adapmoe_check(ls.ctx)
+        assert max_err <= TOL["bf16"], max_err
+        got = [(t, l, kind, e, v) for (t, l, kind, e, v, _slot) in B.adapmoe_trace_read(ls.ctx)]
+        assert got == [tuple(ev) for ev in sim.events]
+        s = OC.summarise(sim.events)
+        c = B.adapmoe_counters(ls.ctx)
+        assert c["misses"] + c["bypasses"] == s["on_demand_loads"]
+        assert c["prefetch_loads"] == s["prefetch_loads"]
+        for l in range(shape.L):
+            res = [e for e in range(shape.N) if B.cache_lookup(ls.ctx, l, [e])[0] >= 0]
+            assert sorted(res) == sorted(sim.resident(l))
+    finally:
+        ls.close()

@@ -190,3 +190,28 @@ def test_two_contexts_are_independent():
     finally:
         a.close()
         b.close()
+
+
+@pytest.mark.parametrize("blocks,pct", [(40, 50), (7, 100), (1000, 15), (512, 0)])
+def test_dynamic_tail_with_odd_grids(blocks, pct):
+    """The gate/up kernel's dynamic tail must cover every row exactly once for any grid size and pool share
+    (grids that are no multiple of 8 workgroups, fewer workgroups than queues, everything in the pool)."""
+    import os
+    shape = synth.MoEShape(H=4096, F=1536, N=4, L=1, dtype="bf16")     # compile-time row length, 2 F no multiple of most grids
+    os.environ["ADAPMOE_GATEUP_BLOCKS"] = str(blocks)
+    os.environ["ADAPMOE_DYN_PCT"] = str(pct)
+    try:
+        ls = GpuLayerSet(shape, seed=51, max_B=3, taus=[0.3])
+    finally:
+        del os.environ["ADAPMOE_GATEUP_BLOCKS"]
+        del os.environ["ADAPMOE_DYN_PCT"]
+    try:
+        X = synth.ar1_tokens(9, shape.H, 0.5, seed=52, dtype="bf16")
+        g = run_gate(ls, 0, X)
+        for rep in range(3):      # repeated launches: the counters are cleared in between by the down kernel
+            y = run_ffn(ls, 0, g)
+            Yref = OE.moe_block_rows(X, ls.experts_f32[0], g["ids"], g["w"].astype(np.float64), g["k"])
+            err = rel_err_per_token(y, Yref)
+            assert err.max() <= TOL["bf16"], (rep, err.max())
+    finally:
+        ls.close()

@@ -179,16 +179,21 @@ __device__ __forceinline__ void grouped_gemm_tile_loop(const char* wbase, size_t
       ++sa;
     };
     int sc = 0;
-    uint4 stage[kVecsPerThread];
-    auto fetch_operand = [&](int slab) {
+    // the workgroup's next operand slab on its way from L2 to LDS, a value (not an array written
+    // in place under a condition, which the compiler keeps in scratch memory)
+    struct Stage { uint4 v[kVecsPerThread]; };
+    auto fetch_operand = [&](int slab) -> Stage {
+      Stage st;
 #pragma unroll
       for (int v = 0; v < kVecsPerThread; ++v) {
         const int idx = v * kThreads + tid;                // vector index inside the slab: [term][step][lane]
         const int term = idx / (KS * 64), r = idx - term * (KS * 64);
         const uint4* src = term == 0 ? bop0 : bop1;
-        stage[v] = src[(size_t)slab * KS * 64 + r];
+        st.v[v] = src[(size_t)slab * KS * 64 + r];
       }
+      return st;
     };
+    Stage stage;
     auto consume = [&](const Slab& buf) {
       // single buffer: wait until everyone is done with the previous slab; double buffer: the
       // other half was last read two slabs ago and every wavefront has passed a barrier since
@@ -196,9 +201,9 @@ __device__ __forceinline__ void grouped_gemm_tile_loop(const char* wbase, size_t
       if constexpr (!DIRECT) {
         if (DB == 1) __syncthreads();
 #pragma unroll
-        for (int v = 0; v < kVecsPerThread; ++v) bslab[v * kThreads + tid] = stage[v];
+        for (int v = 0; v < kVecsPerThread; ++v) bslab[v * kThreads + tid] = stage.v[v];
         __syncthreads();
-        if (sc + 1 < nslabs) fetch_operand(sc + 1);
+        if (sc + 1 < nslabs) stage = fetch_operand(sc + 1);
       }
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt) {
@@ -223,7 +228,7 @@ __device__ __forceinline__ void grouped_gemm_tile_loop(const char* wbase, size_t
       }
       ++sc;
     };
-    if constexpr (!DIRECT) fetch_operand(0);
+    if constexpr (!DIRECT) stage = fetch_operand(0);
     stream_bufs<Slab>(nslabs, load_next, consume, [] {});
 #pragma unroll
     for (int rt = 0; rt < RT; ++rt) epilogue(row0 + 16 * rt, acc[rt]);

@@ -76,9 +76,8 @@ __global__ __launch_bounds__(kGateUpThreads) void ffn_gateup_kernel(FfnArgs p) {
     __syncthreads();
   };
 
-  bool all_resident = true;
-  for (int j = 0; j < kk; ++j) all_resident &= base[j] != nullptr || (windowed && j != p.j_only);
-
+  const bool need0 = !windowed || p.j_only == 0, need1 = kk > 1 && (!windowed || p.j_only == 1);
+  const bool all_resident = (!need0 || base[0] != nullptr) && (!need1 || base[1] != nullptr);
 
   if (NCH > 0 && all_resident && p.dyn_ctr != nullptr && !windowed) {
     // Static passes first, then rows drawn from the shared counters (see FfnArgs::dyn_ctr).
@@ -111,7 +110,7 @@ __global__ __launch_bounds__(kGateUpThreads) void ffn_gateup_kernel(FfnArgs p) {
     };
     auto load_half = [&](uint4(&buf)[NV], int r, int half) {
       const int j = r >= F ? 1 : 0;
-      load_vecs<NV>(base[j] + ((size_t)(r - j * F) * 2 + half) * row_bytes + lane * 16, buf);
+      load_vecs<NV>(pick2(base, j) + ((size_t)(r - j * F) * 2 + half) * row_bytes + lane * 16, buf);
     };
     uint4 A[NV], B[NV];
     int cur = next_row();
@@ -125,7 +124,7 @@ __global__ __launch_bounds__(kGateUpThreads) void ffn_gateup_kernel(FfnArgs p) {
       const float g = wave_sum(dot_x<BF16, NV>(A, xs, 0, lane, 0.f));
       if (nxt >= 0) load_half(A, nxt, 0);
       const float u = wave_sum(dot_x<BF16, NV>(B, xs, 0, lane, 0.f));
-      if (lane == 0) a_out[(cur >= F ? p.a_stride - F : 0) + cur] = wj[cur >= F ? 1 : 0] * silu_f32(g) * u;
+      if (lane == 0) a_out[(cur >= F ? p.a_stride - F : 0) + cur] = pick2(wj, cur >= F) * silu_f32(g) * u;
       if (nxt >= 0) load_half(B, nxt, 1);
       cur = nxt;
     }
@@ -134,7 +133,7 @@ __global__ __launch_bounds__(kGateUpThreads) void ffn_gateup_kernel(FfnArgs p) {
     int ra = first, half_a = 0;  // load cursor
     auto next_addr = [&]() -> const char* {
       const int j = ra >= F ? 1 : 0;
-      const char* q = base[j] + ((size_t)(ra - j * F) * 2 + half_a) * row_bytes + lane * 16;
+      const char* q = pick2(base, j) + ((size_t)(ra - j * F) * 2 + half_a) * row_bytes + lane * 16;
       if (half_a) ra += stride;
       half_a ^= 1;
       return q;
@@ -147,7 +146,7 @@ __global__ __launch_bounds__(kGateUpThreads) void ffn_gateup_kernel(FfnArgs p) {
         g = d;
       } else {
         const float gs = wave_sum(g), us = wave_sum(d);
-        if (lane == 0) a_out[(rc >= F ? p.a_stride - F : 0) + rc] = wj[rc >= F ? 1 : 0] * silu_f32(gs) * us;
+        if (lane == 0) a_out[(rc >= F ? p.a_stride - F : 0) + rc] = pick2(wj, rc >= F) * silu_f32(gs) * us;
         rc += stride;
       }
       half_c ^= 1;
@@ -158,11 +157,12 @@ __global__ __launch_bounds__(kGateUpThreads) void ffn_gateup_kernel(FfnArgs p) {
     for (int r = first; r < total; r += stride) {
       const int j = r >= F ? 1 : 0;
       float val = 0.f;
-      if (base[j]) {
-        const char* row = base[j] + (size_t)(r - j * F) * 2 * row_bytes;
+      const char* bj = pick2(base, j);
+      if (bj) {
+        const char* row = bj + (size_t)(r - j * F) * 2 * row_bytes;
         const float g = wave_sum(dot_row_generic<BF16>(row, xs, lane, nch));
         const float u = wave_sum(dot_row_generic<BF16>(row + row_bytes, xs, lane, nch));
-        val = wj[j] * silu_f32(g) * u;
+        val = pick2(wj, j) * silu_f32(g) * u;
       }
       if (lane == 0) a_out[(size_t)j * p.a_stride + (r - j * F)] = val;
     }
@@ -216,8 +216,9 @@ __global__ __launch_bounds__(kDownThreads) void ffn_down_kernel(FfnArgs p) {
   const int j0 = windowed ? p.j_only : 0;   // experts j0 .. j0 + nj - 1 take part
   const int nj = windowed ? 1 : kk;
   const int hlo = windowed ? p.r0 : 0, hhi = windowed ? p.r1 : H;
-  bool all_resident = true;
-  for (int j = j0; j < j0 + nj; ++j) all_resident &= base[j] != nullptr;
+  // the experts taking part, in order: one of the window, or all kk
+  const char* part[2] = {pick2(base, j0), nj > 1 ? base[1] : nullptr};
+  const bool all_resident = part[0] != nullptr && (nj < 2 || part[1] != nullptr);
 
   const float4* ag = reinterpret_cast<const float4*>(p.a + (size_t)b * 2 * p.a_stride);
   const int S4 = (int)(p.a_stride >> 2);
@@ -241,11 +242,11 @@ __global__ __launch_bounds__(kDownThreads) void ffn_down_kernel(FfnArgs p) {
     const int nbp = nch / NV;        // parts per row of one expert
     const int nb = nj * nbp;         // parts per output element
     const int nrows = first < hhi ? (hhi - first + hstride - 1) / hstride : 0;
-    const char* w2[2] = {base[j0] + p.w2_offset, nj > 1 ? base[1] + p.w2_offset : nullptr};
+    const char* w2[2] = {part[0] + p.w2_offset, nj > 1 ? part[1] + p.w2_offset : nullptr};
     int ha = first, ba = 0;  // load cursor
     auto next_addr = [&]() -> const char* {
       const int j = ba >= nbp ? 1 : 0;
-      const char* q = w2[j] + (size_t)ha * row_bytes + (size_t)(ba - j * nbp) * NV * kChunkBytes + lane * 16;
+      const char* q = pick2(w2, j) + (size_t)ha * row_bytes + (size_t)(ba - j * nbp) * NV * kChunkBytes + lane * 16;
       if (++ba == nb) { ba = 0; ha += hstride; }
       return q;
     };
@@ -268,9 +269,9 @@ __global__ __launch_bounds__(kDownThreads) void ffn_down_kernel(FfnArgs p) {
     for (int h = first; h < hhi; h += hstride) {
       float acc = 0.f;
       for (int jr = 0; jr < nj; ++jr) {
-        const int j = j0 + jr;
-        if (!base[j]) continue;
-        const char* row = base[j] + p.w2_offset + (size_t)h * row_bytes + lane * 16;
+        const char* bj = pick2(part, jr);
+        if (!bj) continue;
+        const char* row = bj + p.w2_offset + (size_t)h * row_bytes + lane * 16;
         for (int c = 0; c < nch; ++c) {
           uint4 buf[1];
           buf[0] = load_stream16(row + (size_t)c * kChunkBytes);
@@ -333,13 +334,12 @@ __global__ __launch_bounds__(kFusedThreads) void ffn_fused_kernel(FfnArgs p, Fus
   const char* base[2];
   float wj[2];
   const int kk = resolve_experts(p, 0, base, wj);
-  for (int j = 0; j < kk; ++j)
-    if (base[j] == nullptr) {
+  if (base[0] == nullptr || (kk > 1 && base[1] == nullptr)) {
       // flagged by resolve_experts; the same for every workgroup, so nobody waits at the barrier,
       // but the arrival is still counted to keep the counter in step with the launch number
       if (tid == 0) __hip_atomic_fetch_add(sy.counter, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       return;
-    }
+  }
 
   const int first = blockIdx.x * kWaves + wave;
   const int stride = gridDim.x * kWaves;
@@ -358,7 +358,7 @@ __global__ __launch_bounds__(kFusedThreads) void ffn_fused_kernel(FfnArgs p, Fus
     int ra = first, half_a = 0;
     auto next_addr = [&]() -> const char* {
       const int j = ra >= F ? 1 : 0;
-      const char* q = base[j] + ((size_t)(ra - j * F) * 2 + half_a) * row_bytes + lane * 16;
+      const char* q = pick2(base, j) + ((size_t)(ra - j * F) * 2 + half_a) * row_bytes + lane * 16;
       if (half_a) ra += stride;
       half_a ^= 1;
       return q;
@@ -373,7 +373,7 @@ __global__ __launch_bounds__(kFusedThreads) void ffn_fused_kernel(FfnArgs p, Fus
         const float gs = wave_sum(g), us = wave_sum(d);
         if (lane == 0) {
           float* dst = p.a + (rc >= F ? p.a_stride - F : 0) + rc;
-          const float val = wj[rc >= F ? 1 : 0] * silu_f32(gs) * us;
+          const float val = pick2(wj, rc >= F) * silu_f32(gs) * us;
           __hip_atomic_store(dst, val, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         rc += stride;
@@ -410,7 +410,7 @@ __global__ __launch_bounds__(kFusedThreads) void ffn_fused_kernel(FfnArgs p, Fus
     int ha = first, ba = 0;
     auto next_addr = [&]() -> const char* {
       const int j = ba >= nbp ? 1 : 0;
-      const char* q = w2[j] + (size_t)ha * row_bytes + (size_t)(ba - j * nbp) * UN * kChunkBytes + lane * 16;
+      const char* q = pick2(w2, j) + (size_t)ha * row_bytes + (size_t)(ba - j * nbp) * UN * kChunkBytes + lane * 16;
       if (++ba == nb) { ba = 0; ha += stride; }
       return q;
     };

@@ -160,13 +160,15 @@ __global__ __launch_bounds__(kI4GateUpThreads) void ffn_gateup_quant_kernel(FfnA
   const char* base[2];
   float wj[2];
   const int kk = resolve_experts(p, b, base, wj);
-  const char* rbase[2];
-  float rw[2];
-  int rj[2];
+  // resident activated experts taking part, rank order (written with selects: arrays indexed
+  // with run-time values would live in scratch memory)
   const bool windowed = p.j_only >= 0;
-  int nv = 0;  // resident activated experts taking part, rank order
-  for (int j = 0; j < kk; ++j)
-    if (base[j] && (!windowed || j == p.j_only)) { rbase[nv] = base[j]; rw[nv] = wj[j]; rj[nv] = j; ++nv; }
+  const bool t0 = base[0] != nullptr && (!windowed || p.j_only == 0);
+  const bool t1 = kk > 1 && base[1] != nullptr && (!windowed || p.j_only == 1);
+  const int nv = (int)t0 + (int)t1;
+  const char* rbase[2] = {t0 ? base[0] : base[1], base[1]};
+  const float rw[2] = {t0 ? wj[0] : wj[1], wj[1]};
+  const int rj[2] = {t0 ? 0 : 1, 1};
 
   // The lane's groups of x (bfloat16) and their sums.  x is read from global
   // memory in order (one 16-byte piece per thread) and turned through LDS:
@@ -202,7 +204,7 @@ __global__ __launch_bounds__(kI4GateUpThreads) void ffn_gateup_quant_kernel(FfnA
   int ra = first;
   auto load_next = [&](I4RowPair<BITS, NBLK>& buf) {
     const int j = ra >= F ? 1 : 0;
-    const char* row = rbase[j] + (size_t)(ra - j * F) * 2 * rb;
+    const char* row = pick2(rbase, j) + (size_t)(ra - j * F) * 2 * rb;
 #pragma unroll
     for (int i = 0; i < NBLK; ++i) {
       i4_load_group(row, H, i, lane, buf.g1[i]);
@@ -222,7 +224,7 @@ __global__ __launch_bounds__(kI4GateUpThreads) void ffn_gateup_quant_kernel(FfnA
     u = wave_sum(u);
     const int j = rc >= F ? 1 : 0;
     const int f = rc - j * F;
-    if (lane == 0) a_out[(size_t)rj[j] * 2 * p.a_stride + i4_a_pos(f)] = f32_to_bf16_bits(rw[j] * silu_f32(g) * u);
+    if (lane == 0) a_out[(size_t)pick2(rj, j) * 2 * p.a_stride + i4_a_pos(f)] = f32_to_bf16_bits(pick2(rw, j) * silu_f32(g) * u);
     rc += stride;
   };
   stream_bufs<I4RowPair<BITS, NBLK>>(nrows, load_next, consume, stage_x);

@@ -43,6 +43,12 @@ __device__ __forceinline__ int resolve_experts(const FfnArgs& p, int b, const ch
   return kk;
 }
 
+// a[j] for a run-time j in {0, 1}.  A local array indexed with a run-time value is placed in
+// scratch memory, which costs the kernel a private segment at dispatch and memory round trips;
+// a select keeps both elements in registers.
+template <class T>
+__device__ __forceinline__ T pick2(const T (&a)[2], int j) { return j ? a[1] : a[0]; }
+
 // ----------------------------------------------------------- part streaming --
 
 // Both GEMVs read, per wavefront, a known sequence of "parts": NV consecutive

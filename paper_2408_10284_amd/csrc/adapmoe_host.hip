@@ -674,7 +674,7 @@ int adapmoe_create(const adapmoe_config* cfg, adapmoe_ctx** out) {
   c->lc.batch_min = env_int("ADAPMOE_BATCH_MIN", 4);
   c->lc.batch_two_terms = env_int("ADAPMOE_BATCH_TWO_TERMS", 0);
   c->lc.fused_blocks = 0;
-  c->lc.dyn_pct = quant_bits(cfg->dtype) ? 0 : env_int("ADAPMOE_DYN_PCT", 15);
+  c->lc.dyn_pct = quant_bits(cfg->dtype) ? 0 : env_int("ADAPMOE_DYN_PCT", 20);
   const int B = cfg->max_B;
   bool ok = hipSetDevice(cfg->device) == hipSuccess;
   ok = ok && hipMalloc(&c->d_table, LN * sizeof(void*)) == hipSuccess;

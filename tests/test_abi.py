@@ -258,3 +258,24 @@ def test_bench_refuses_more_than_one_gpu():
     import sys
     r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True, timeout=120)
     assert r.returncode != 0 and "one GPU" in r.stderr
+
+
+def test_build_rejects_kernels_with_scratch_memory():
+    """The build parses the compiler's per-kernel resource remarks; scratch use must be seen (it costs every
+    dispatch a private-segment set-up) and the built library's kernels must all be at zero."""
+    from paper_2408_10284_amd import build as BLD
+    sample = (
+        "a.hip:5:1: remark: Function Name: k_good [-Rpass-analysis=kernel-resource-usage]\n"
+        "a.hip:5:1: remark:     VGPRs: 12 [-Rpass-analysis=kernel-resource-usage]\n"
+        "a.hip:5:1: remark:     ScratchSize [bytes/lane]: 0 [-Rpass-analysis=kernel-resource-usage]\n"
+        "a.hip:9:1: remark: Function Name: k_bad [-Rpass-analysis=kernel-resource-usage]\n"
+        "a.hip:9:1: remark:     ScratchSize [bytes/lane]: 32 [-Rpass-analysis=kernel-resource-usage]\n"
+        "a.hip:9:1: remark:     Occupancy [waves/SIMD]: 4 [-Rpass-analysis=kernel-resource-usage]\n")
+    res = BLD.kernel_resources(sample)
+    assert res == {"k_good": {"VGPRs": 12, "ScratchSize": 0}, "k_bad": {"ScratchSize": 32, "Occupancy": 4}}
+    if not os.path.exists(BLD.RESOURCES):
+        BLD.build(verbose=False)
+    rows = [l.split(" | ") for l in open(BLD.RESOURCES).read().splitlines()[1:]]
+    assert len(rows) >= 30                      # every kernel instantiation of the library
+    assert any("ffn_gateup_kernel" in r[0] for r in rows) and any("grouped_down_mfma_kernel" in r[0] for r in rows)
+    assert all(int(r[4]) == 0 for r in rows), [r[0] for r in rows if int(r[4]) != 0]

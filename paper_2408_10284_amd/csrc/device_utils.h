@@ -27,6 +27,14 @@ __device__ __forceinline__ float readlane_f32(float v, int lane) {
   return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
 }
 
+// The pointer held by lane `lane` (the same for the whole wavefront), for every lane.
+__device__ __forceinline__ const void* readlane_ptr(const void* v, int lane) {
+  const uint64_t u = reinterpret_cast<uint64_t>(v);
+  const uint32_t lo = __builtin_amdgcn_readlane((int)(uint32_t)u, lane);
+  const uint32_t hi = __builtin_amdgcn_readlane((int)(uint32_t)(u >> 32), lane);
+  return reinterpret_cast<const void*>(((uint64_t)hi << 32) | lo);
+}
+
 // Sum over the 64 lanes of a fully active wavefront; every lane gets the result.
 // Four DPP steps give each row of 16 lanes its row sum, the four row sums are
 // then read as scalars.  The order of additions is fixed, so results are

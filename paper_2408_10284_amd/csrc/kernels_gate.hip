@@ -28,6 +28,13 @@ __device__ __forceinline__ void gate_body(const GateArgs& a, int b, int r, float
     return;
   }
 
+  // Requested now, used after the decision (a dependent load there would add a memory round trip
+  // to a kernel that is all latency): the threshold and, for router 0, the residency-table entry of
+  // expert e in lane e of the deciding wavefront.
+  const float tau = a.tau[r];
+  const bool want_table = r == 0 && a.res != nullptr;
+  const void* tab = (want_table && wave == 0 && lane < N) ? a.table[lane] : nullptr;
+
   constexpr int VEC = BF16 ? 8 : 4;      // elements per 16-byte vector
   const size_t esz = BF16 ? 2 : 4;
   const char* xrow = static_cast<const char*>(a.x) + (size_t)b * H * esz;
@@ -83,8 +90,10 @@ __device__ __forceinline__ void gate_body(const GateArgs& a, int b, int r, float
   const float p2 = expf(m2 - m1) / S;
   const float alpha = p1 / (p1 + p2);
   const float v = p2 / (p1 + p2);          // weight of the second expert, the test value
-  const int k = (v <= a.tau[r]) ? 1 : 2;   // Eq.8 with tau = sqrt(T / sum diag(F))
+  const int k = (v <= tau) ? 1 : 2;       // Eq.8 with tau = sqrt(T / sum diag(F))
 
+  const void* tab1 = readlane_ptr(tab, e1);
+  const void* tab2 = readlane_ptr(tab, e2);
   if (lane == 0) {
     ids_out[0] = e1;
     ids_out[1] = e2;
@@ -94,10 +103,10 @@ __device__ __forceinline__ void gate_body(const GateArgs& a, int b, int r, float
       a.w[2 * b + 0] = w0;
       a.w[2 * b + 1] = w1;
     }
-    if (r == 0 && a.res != nullptr) {
+    if (want_table) {
       ResolvedExperts out;
-      out.base[0] = a.table[e1];
-      out.base[1] = (k == 2) ? a.table[e2] : nullptr;
+      out.base[0] = tab1;
+      out.base[1] = (k == 2) ? tab2 : nullptr;
       out.w[0] = w0;
       out.w[1] = w1;
       out.k = k;

@@ -544,6 +544,72 @@ def test_stack_token_equals_manual_loop():
     assert outs[0][1] == outs[1][1]
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+def test_free_running_stack_against_free_running_checker(dtype):
+    """Both sides run the same tokens through a 4-layer offloaded stack (8 slots) on their own, nobody fed the
+    other's intermediate values.  In fp32 every decision (ids, k, prediction), the whole cache trace and the
+    residual stream must agree: the checker reports its smallest logit gaps and distances to the thresholds,
+    and the test requires them to be far above fp32 rounding, so the agreement is not luck.  In bf16 the two
+    sides round x in different arithmetic, so a near-tie may flip a decision and the runs part from there on;
+    the test reports the first divergence and the share of identical decisions, and requires the first token
+    to agree in every layer and at least half of all decisions to be identical."""
+    shape = synth.MoEShape(H=512, F=1024, N=8, L=4, dtype=dtype)
+    taus = [0.2, 0.3, 0.25, 0.35]
+    slots = [2, 2, 2, 2]
+    n_tok, gamma = 16, 0.5
+    ls = GpuLayerSet(shape, seed=4, max_B=1, trace_capacity=1 << 14, resident=False, taus=taus)
+    try:
+        B.cache_alloc(ls.ctx, slots)
+        H0 = synth.ar1_tokens(n_tok, shape.H, 0.8, seed=9, dtype="f32") * 2.0
+        store = (lambda a: a.astype(np.float32)) if dtype == "f32" else synth.bf16_round
+        sim = OC.ExpertCache(slots)
+        ref = OS.run_stack(H0.astype(np.float64), ls.routers_f32, [np.float32(t) for t in taus],
+                           lambda l, e, x: OE.expert_ffn(x, *ls.experts_f32[l][e]), gamma, store=store, cache=sim)
+        got_ids = np.zeros((n_tok, shape.L, 2), np.int32)
+        got_k = np.zeros((n_tok, shape.L), np.int32)
+        got_pred = [[None] * shape.L for _ in range(n_tok)]
+        got_h = np.zeros((n_tok, shape.H), np.float64)
+        for t in range(n_tok):
+            B.adapmoe_set_token(ls.ctx, t)
+            h = torch.from_numpy(H0[t:t + 1].copy()).cuda()
+            x = torch.empty((1, shape.H), dtype=torch.float32 if dtype == "f32" else torch.bfloat16, device="cuda")
+            y = torch.empty((1, shape.H), dtype=torch.float32, device="cuda")
+            for l in range(shape.L):
+                B.moe_residual_rmsnorm(ls.ctx, h, y if l > 0 else None, gamma, x, 1)
+                B.moe_layer_step(ls.ctx, l, x, 1, y)
+                ids, k, pids, pk = B.adapmoe_last_decision(ls.ctx, 1)
+                got_ids[t, l], got_k[t, l] = ids, k[0]
+                got_pred[t][l] = [int(e) for e in pids[:pk[0]]]
+            B.moe_residual_rmsnorm(ls.ctx, h, y, gamma, x, 1)
+            B.adapmoe_check(ls.ctx)
+            got_h[t] = h.cpu().numpy()[0]
+        got_trace = [(t, l, kind, e, v) for (t, l, kind, e, v, _slot) in B.adapmoe_trace_read(ls.ctx)]
+
+        def agrees(t, l):
+            ok = tuple(got_ids[t, l, :got_k[t, l]]) == tuple(ref["ids"][t, l, :ref["k"][t, l]]) and got_k[t, l] == ref["k"][t, l]
+            if l + 1 < shape.L:
+                ok = ok and got_pred[t][l] == [int(e) for e in ref["pred"][t][l + 1]]
+            return bool(ok)
+
+        order = [(t, l) for t in range(n_tok) for l in range(shape.L)]
+        first_bad = next((tl for tl in order if not agrees(*tl)), None)
+        margin_tau = np.abs(ref["v"] - np.asarray(taus)[None, :])
+        if dtype == "f32":
+            # the seed is not a near-tie one: gaps and threshold margins are orders of magnitude above fp32 rounding
+            assert ref["gap23"].min() > 1e-4 and margin_tau.min() > 1e-5, (ref["gap23"].min(), margin_tau.min())
+            assert first_bad is None, first_bad
+            assert got_trace == [tuple(ev) for ev in sim.events]
+            err = np.max(np.abs(got_h - ref["h"][:, shape.L]), axis=1) / np.max(np.abs(ref["h"][:, shape.L]), axis=1)
+            assert err.max() <= 1e-5, err.max()
+        else:
+            same = sum(agrees(*tl) for tl in order) / len(order)
+            print(f"bf16 free run: first divergence {first_bad}, identical decisions {same:.3f}")
+            assert first_bad is None or first_bad[0] > 0, first_bad   # the first token agrees in every layer
+            assert same >= 0.5
+    finally:
+        ls.close()
+
+
 # ------------------------------------------------ fused single-token kernel ----
 
 @pytest.mark.parametrize("dtype,H,F", [("bf16", 4096, 3584), ("bf16", 4096, 4096), ("f32", 2048, 1792)])

@@ -10,16 +10,25 @@ typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
 
 constexpr int kWave = 64;
 
+// Index of the wavefront inside its workgroup, as a scalar: told that it is the same for all
+// lanes, the compiler keeps row numbers and row addresses derived from it in scalar registers and
+// computes them on the scalar unit instead of once per lane.
+__device__ __forceinline__ int wave_index() { return __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)); }
+
 // DPP controls (GCN3+ encoding)
 constexpr int kDppQuadSwap1 = 0xB1;      // quad_perm:[1,0,3,2]
 constexpr int kDppQuadSwap2 = 0x4E;      // quad_perm:[2,3,0,1]
 constexpr int kDppRowHalfMirror = 0x141;
 constexpr int kDppRowMirror = 0x140;
 
+// Value of `v` in the lane the control selects.  All patterns used here read inside a row of 16
+// lanes of a fully active wavefront, so no lane is without a source; "old" = 0 with bound_ctrl
+// lets the compiler fold the move into the add or max that follows (one v_add_f32_dpp per step
+// instead of a move, a DPP move and the add).
 template <int CTRL>
 __device__ __forceinline__ float dpp_f32(float v) {
   int i = __builtin_bit_cast(int, v);
-  i = __builtin_amdgcn_update_dpp(i, i, CTRL, 0xf, 0xf, false);
+  i = __builtin_amdgcn_update_dpp(0, i, CTRL, 0xf, 0xf, true);
   return __builtin_bit_cast(float, i);
 }
 

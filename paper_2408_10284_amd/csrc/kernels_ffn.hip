@@ -53,7 +53,7 @@ template <bool BF16, int NCH>
 __global__ __launch_bounds__(kGateUpThreads) void ffn_gateup_kernel(FfnArgs p) {
   extern __shared__ uint4 xs[];  // x[b,:] in its storage type
   const int b = blockIdx.y;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = wave_index();
   const size_t esz = BF16 ? 2 : 4;
   const size_t row_bytes = (size_t)p.H * esz;
   const int nch = (int)(row_bytes / kChunkBytes);
@@ -199,7 +199,7 @@ template <bool BF16, int UN>
 __global__ __launch_bounds__(kDownThreads) void ffn_down_kernel(FfnArgs p) {
   extern __shared__ float4 as4[];  // a[j][F] of the activated experts
   const int b = blockIdx.y;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = wave_index();
   const size_t esz = BF16 ? 2 : 4;
   const size_t row_bytes = (size_t)p.F * esz;
   const int nch = (int)(row_bytes / kChunkBytes);
@@ -327,7 +327,7 @@ __global__ __launch_bounds__(kFusedThreads) void ffn_fused_kernel(FfnArgs p, Fus
   __shared__ int s_ok;
   constexpr int NCH = 8;
   constexpr int kWaves = kFusedThreads / kWave;
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63, wave = wave_index();
   const size_t esz = BF16 ? 2 : 4;
   const int H = p.H, F = p.F;
 

@@ -152,7 +152,7 @@ struct I4RowPair {
 template <int BITS, int NBLK>
 __global__ __launch_bounds__(kI4GateUpThreads) void ffn_gateup_quant_kernel(FfnArgs p) {
   const int b = blockIdx.y;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, wave = wave_index();
   const int H = p.H, F = p.F;
   const size_t rb = q_row_bytes<BITS>(H);
   const I4Consts kc = q_consts<BITS>();
@@ -212,7 +212,21 @@ __global__ __launch_bounds__(kI4GateUpThreads) void ffn_gateup_quant_kernel(FfnA
     }
     ra += stride;
   };
-  int rc = first;
+  // The two sums of a row pair are parked in lane `ns` of gv / uv; SiLU, the product, the rounding
+  // and the store are then done for up to 64 row pairs at once, one per lane, instead of by the
+  // whole wavefront for every pair (the kernel is close to the vector-ALU limit).
+  float gv = 0.f, uv = 0.f;
+  int ns = 0, r_first = first;   // the parked sums belong to row pairs r_first + t * stride, t < ns
+  auto flush = [&]() {
+    if (lane < ns) {
+      const int r = r_first + lane * stride;
+      const int j = r >= F ? 1 : 0;
+      const int f = r - j * F;
+      a_out[(size_t)pick2(rj, j) * 2 * p.a_stride + i4_a_pos(f)] = f32_to_bf16_bits(pick2(rw, j) * silu_f32(gv) * uv);
+    }
+    r_first += ns * stride;
+    ns = 0;
+  };
   auto consume = [&](const I4RowPair<BITS, NBLK>& buf) {
     float g = 0.f, u = 0.f;
 #pragma unroll
@@ -222,12 +236,12 @@ __global__ __launch_bounds__(kI4GateUpThreads) void ffn_gateup_quant_kernel(FfnA
     }
     g = wave_sum(g);
     u = wave_sum(u);
-    const int j = rc >= F ? 1 : 0;
-    const int f = rc - j * F;
-    if (lane == 0) a_out[(size_t)pick2(rj, j) * 2 * p.a_stride + i4_a_pos(f)] = f32_to_bf16_bits(pick2(rw, j) * silu_f32(g) * u);
-    rc += stride;
+    gv = lane == ns ? g : gv;
+    uv = lane == ns ? u : uv;
+    if (++ns == kWave) flush();
   };
   stream_bufs<I4RowPair<BITS, NBLK>>(nrows, load_next, consume, stage_x);
+  flush();
 }
 
 // --------------------------------------------------------------------- down --
@@ -243,7 +257,7 @@ template <int BITS>
 __global__ __launch_bounds__(kI4DownThreads) void ffn_down_quant_kernel(FfnArgs p) {
   __shared__ float part[kI4DownThreads / kWave][kI4DownRows];
   const int b = blockIdx.y;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, wave = wave_index();
   const int H = p.H, F = p.F;
   const size_t rb = q_row_bytes<BITS>(F);
   const int G = F >> 6;

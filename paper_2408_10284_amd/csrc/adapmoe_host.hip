@@ -8,6 +8,7 @@
 #include <cstring>
 #include <deque>
 #include <mutex>
+#include <new>
 #include <string>
 #include <vector>
 
@@ -143,6 +144,18 @@ int fail(adapmoe_ctx* c, int code, const std::string& msg) {
     if (e_ != hipSuccess)                                                                 \
       return fail((ctx), ADAPMOE_EHIP, std::string(#call) + ": " + hipGetErrorString(e_)); \
   } while (0)
+
+// No exception crosses the C boundary: the containers of the context allocate, so every entry
+// point that can reach an allocation runs inside this pair.
+#define ABI_TRY try {
+#define ABI_CATCH(ctx)                                                                     \
+  }                                                                                        \
+  catch (const std::bad_alloc&) {                                                          \
+    return fail((ctx), ADAPMOE_ENOMEM, "host memory allocation failed");                   \
+  }                                                                                        \
+  catch (...) {                                                                            \
+    return fail((ctx), ADAPMOE_ESTATE, "unexpected exception inside the library");         \
+  }
 
 bool cfg_ok(const adapmoe_config* c) {
   if (!c) return false;
@@ -657,6 +670,7 @@ int adapmoe_create(const adapmoe_config* cfg, adapmoe_ctx** out) {
   if (hipGetDeviceCount(&ndev) != hipSuccess || cfg->device < 0 || cfg->device >= ndev) return ADAPMOE_EHIP;
   adapmoe_ctx* c = new (std::nothrow) adapmoe_ctx();
   if (!c) return ADAPMOE_ENOMEM;
+  try {
   c->cfg = *cfg;
   c->bf16_act = cfg->dtype != ADAPMOE_F32;
   adapmoe_expert_bytes(cfg, &c->image_bytes);
@@ -719,6 +733,10 @@ int adapmoe_create(const adapmoe_config* cfg, adapmoe_ctx** out) {
   if (!ok) {
     adapmoe_destroy(c);
     return ADAPMOE_EHIP;
+  }
+  } catch (...) {   // a container of the context could not allocate
+    adapmoe_destroy(c);
+    return ADAPMOE_ENOMEM;
   }
   *out = c;
   return ADAPMOE_OK;
@@ -812,6 +830,7 @@ double cache_cost(int N, int t, double a, double beta) {
 }
 
 int cache_plan(int L, int N, int C, const double* a, const double* beta, int32_t* t_out, double* cost_out) {
+  ABI_TRY
   if (L < 1 || N < 2 || C < 0 || !a || !beta || !t_out) return ADAPMOE_EINVAL;
   const double tie = 1e-12;
   std::vector<double> f((size_t)L * (N + 1));
@@ -839,9 +858,11 @@ int cache_plan(int L, int N, int C, const double* a, const double* beta, int32_t
   }
   if (cost_out) *cost_out = best[(size_t)L * W + C];
   return ADAPMOE_OK;
+  ABI_CATCH(nullptr)
 }
 
 int cache_alloc(adapmoe_ctx* c, const int32_t* slots_per_layer) {
+  ABI_TRY
   if (!c || !slots_per_layer) return fail(c, ADAPMOE_EINVAL, "cache_alloc: bad argument");
   if (c->cache_ready) return fail(c, ADAPMOE_ESTATE, "cache_alloc: already allocated");
   size_t total = 0;
@@ -875,9 +896,11 @@ int cache_alloc(adapmoe_ctx* c, const int32_t* slots_per_layer) {
   }
   c->cache_ready = true;
   return ADAPMOE_OK;
+  ABI_CATCH(c)
 }
 
 int cache_lookup(adapmoe_ctx* c, int layer, const int32_t* ids, int n, int32_t* slot_out, int touch) {
+  ABI_TRY
   if (!c || layer < 0 || layer >= c->cfg.L || !ids || !slot_out || n < 0) return fail(c, ADAPMOE_EINVAL, "cache_lookup: bad argument");
   LayerCache& lc = c->layers[layer];
   for (int i = 0; i < n; ++i) {
@@ -890,22 +913,26 @@ int cache_lookup(adapmoe_ctx* c, int layer, const int32_t* ids, int n, int32_t* 
     if (touch) lc.touch(pos);
   }
   return ADAPMOE_OK;
+  ABI_CATCH(c)
 }
 
 // ---- steps ------------------------------------------------------------------
 
 int moe_gate(adapmoe_ctx* c, int layer, const void* x, int B, int32_t* ids, float* w, int32_t* k, int32_t* pred_ids,
              int32_t* pred_k, void* stream) {
+  ABI_TRY
   if (!c || layer < 0 || layer >= c->cfg.L || !x || !ids || !w || !k || B < 1 || B > c->cfg.max_B)
     return fail(c, ADAPMOE_EINVAL, "moe_gate: bad argument");
   if ((pred_ids == nullptr) != (pred_k == nullptr)) return fail(c, ADAPMOE_EINVAL, "moe_gate: give both prediction outputs or neither");
   int32_t* pi[1] = {pred_ids};
   int32_t* pk[1] = {pred_k};
   return launch_gate_both(c, layer, x, B, ids, w, k, pred_ids ? 1 : 0, pi, pk, static_cast<hipStream_t>(stream));
+  ABI_CATCH(c)
 }
 
 int moe_expert_ffn(adapmoe_ctx* c, int layer, const void* x, int B, const int32_t* ids, const float* w, const int32_t* k,
                    float* y, void* stream) {
+  ABI_TRY
   if (!c || layer < 0 || layer >= c->cfg.L || !x || !ids || !w || !k || !y || B < 1 || B > c->cfg.max_B)
     return fail(c, ADAPMOE_EINVAL, "moe_expert_ffn: bad argument");
   hipStream_t s = static_cast<hipStream_t>(stream);
@@ -927,12 +954,15 @@ int moe_expert_ffn(adapmoe_ctx* c, int layer, const void* x, int B, const int32_
     sl.was_read = true;
   }
   return ADAPMOE_OK;
+  ABI_CATCH(c)
 }
 
 int moe_prefetch(adapmoe_ctx* c, int layer, const int32_t* ids_host, int n) {
+  ABI_TRY
   if (!c || layer < 0 || layer >= c->cfg.L || !ids_host || n < 0) return fail(c, ADAPMOE_EINVAL, "moe_prefetch: bad argument");
   if (!c->cache_ready) return fail(c, ADAPMOE_ESTATE, "moe_prefetch: cache not allocated");
   return prefetch_layer(c, layer, ids_host, n);
+  ABI_CATCH(c)
 }
 
 }  // extern "C"
@@ -1122,7 +1152,9 @@ int layer_step_impl(adapmoe_ctx* c, int layer, const void* x, int B, float* y, v
 extern "C" {
 
 int moe_layer_step(adapmoe_ctx* c, int layer, const void* x, int B, float* y, void* stream) {
+  ABI_TRY
   return layer_step_impl(c, layer, x, B, y, stream, nullptr);
+  ABI_CATCH(c)
 }
 
 int moe_residual_rmsnorm(adapmoe_ctx* c, float* h, const float* y, float gamma, void* x, int B, void* stream) {
@@ -1132,6 +1164,7 @@ int moe_residual_rmsnorm(adapmoe_ctx* c, float* h, const float* y, float gamma, 
 }
 
 int moe_stack_token(adapmoe_ctx* c, int token, float* h, void* x, float* y, int B, float gamma, void* stream) {
+  ABI_TRY
   if (!c || !h || !x || !y || B < 1 || B > c->cfg.max_B) return fail(c, ADAPMOE_EINVAL, "moe_stack_token: bad argument");
   c->token = token;
   hipStream_t s = static_cast<hipStream_t>(stream);
@@ -1143,6 +1176,7 @@ int moe_stack_token(adapmoe_ctx* c, int token, float* h, void* x, float* y, int 
   // last residual update (x is rewritten with the normalised final state, unused)
   HIPCHK(c, launch_residual_rmsnorm(h, y, gamma, x, c->bf16_act, B, c->cfg.H, s));
   return ADAPMOE_OK;
+  ABI_CATCH(c)
 }
 
 // ---- bookkeeping ---------------------------------------------------------------
@@ -1227,24 +1261,32 @@ int adapmoe_profile(adapmoe_ctx* c, int on) {
 }
 
 int adapmoe_profile_read(adapmoe_ctx* c, int cls, uint64_t* launches, double* total_ms) {
+  ABI_TRY
   if (!c || !launches || !total_ms) return fail(c, ADAPMOE_EINVAL, "profile_read: bad argument");
   uint64_t n = 0;
   double ms = 0.0;
   std::vector<TimedLaunch> keep;
+  hipError_t bad = hipSuccess;
   for (TimedLaunch& t : c->timed) {
     if (t.cls != cls) { keep.push_back(t); continue; }
-    HIPCHK(c, hipEventSynchronize(t.t1));
     float d = 0.f;
-    HIPCHK(c, hipEventElapsedTime(&d, t.t0, t.t1));
-    ms += d;
-    ++n;
-    c->event_pool.push_back(t.t0);
+    hipError_t e = hipEventSynchronize(t.t1);
+    if (e == hipSuccess) e = hipEventElapsedTime(&d, t.t0, t.t1);
+    if (e == hipSuccess) {
+      ms += d;
+      ++n;
+    } else {
+      bad = e;
+    }
+    c->event_pool.push_back(t.t0);   // every event stays owned by exactly one list
     c->event_pool.push_back(t.t1);
   }
   c->timed.swap(keep);
   *launches = n;
   *total_ms = ms;
+  if (bad != hipSuccess) return fail(c, ADAPMOE_EHIP, std::string("profile_read: ") + hipGetErrorString(bad));
   return ADAPMOE_OK;
+  ABI_CATCH(c)
 }
 
 }  // extern "C"

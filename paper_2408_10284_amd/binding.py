@@ -127,24 +127,77 @@ def _chk(ctx, rc):
         raise AdapMoEError(rc, text)
 
 
+# The C boundary takes raw addresses and cannot see how large a buffer is; a tensor that is too
+# small would make a kernel read or write out of bounds.  The wrappers therefore check, for every
+# tensor or array they are given (plain integer addresses are passed through unchecked), that it is
+# contiguous, lives where the call expects it (device or host) and holds at least the bytes the
+# header states for that argument.
+_CFG = {}   # context address -> Config of adapmoe_create
+
+
+def _cfg_of(ctx):
+    cfg = _CFG.get(ctx.value if hasattr(ctx, "value") else ctx)
+    if cfg is None:
+        raise ValueError("unknown context (not created through this module, or already destroyed)")
+    return cfg
+
+
+def _esz(cfg):
+    return 4 if cfg.dtype == F32 else 2
+
+
+def _need(name, t, nbytes, where=None):
+    if t is None or isinstance(t, int):
+        return
+    if hasattr(t, "element_size"):
+        have, contiguous, on_dev = t.numel() * t.element_size(), t.is_contiguous(), t.is_cuda
+    else:
+        have, contiguous, on_dev = t.nbytes, t.flags["C_CONTIGUOUS"], False
+    if not contiguous:
+        raise ValueError(f"{name}: must be contiguous")
+    if have < nbytes:
+        raise ValueError(f"{name}: {have} bytes given, {nbytes} needed")
+    if where == "dev" and not on_dev:
+        raise ValueError(f"{name}: must be a device tensor")
+    if where == "host" and on_dev:
+        raise ValueError(f"{name}: must be in host memory")
+
+
+def _need_step(cfg, B, x=None, y=None, h=None, ids=None, w=None, k=None):
+    if not 1 <= B <= cfg.max_B:
+        return   # the library rejects the call before touching any buffer
+    _need("x", x, B * cfg.H * _esz(cfg), "dev")
+    _need("y", y, B * cfg.H * 4, "dev")
+    _need("h", h, B * cfg.H * 4, "dev")
+    _need("ids", ids, 2 * B * 4, "dev")
+    _need("w", w, 2 * B * 4, "dev")
+    _need("k", k, B * 4, "dev")
+
+
 # ---- same names as the C entry points ---------------------------------------
 
 def adapmoe_create(H, F, N, L, dtype, max_B=1, device=0, trace_capacity=0):
     cfg = Config(H, F, N, L, dtype, max_B, device, trace_capacity)
     ctx = _P()
     _chk(None, load().adapmoe_create(C.byref(cfg), C.byref(ctx)))
+    _CFG[ctx.value] = cfg
     return ctx, cfg
 
 
 def adapmoe_destroy(ctx):
     _chk(None, load().adapmoe_destroy(ctx))
+    _CFG.pop(ctx.value if hasattr(ctx, "value") else ctx, None)
 
 
 def adapmoe_set_router(ctx, layer, Wg_dev):
+    cfg = _cfg_of(ctx)
+    _need("Wg", Wg_dev, cfg.N * cfg.H * _esz(cfg), "dev")
     _chk(ctx, load().adapmoe_set_router(ctx, layer, _ptr(Wg_dev)))
 
 
 def adapmoe_set_tau(ctx, tau):
+    if len(tau) != _cfg_of(ctx).L:
+        raise ValueError("tau: one threshold per layer")
     arr = (C.c_float * len(tau))(*[float(t) for t in tau])
     _chk(ctx, load().adapmoe_set_tau(ctx, arr))
 
@@ -156,22 +209,38 @@ def adapmoe_expert_bytes(cfg):
 
 
 def adapmoe_pack_expert(cfg, W1, W3, W2, out):
+    for name, m in (("W1", W1), ("W3", W3), ("W2", W2)):
+        _need(name, m, cfg.H * cfg.F * _esz(cfg), "host")
+    _need("out", out, 3 * cfg.H * cfg.F * _esz(cfg), "host")
     _chk(None, load().adapmoe_pack_expert(C.byref(cfg), _ptr(W1), _ptr(W3), _ptr(W2), _ptr(out)))
 
 
+def _need_quant(cfg, q1, s1, z1, q3, s3, z3, q2, s2, z2, out):
+    n = cfg.H * cfg.F
+    for name, m in (("q1", q1), ("q3", q3), ("q2", q2)):
+        _need(name, m, n, "host")                 # one code per byte
+    for name, m in (("s1", s1), ("z1", z1), ("s3", s3), ("z3", z3), ("s2", s2), ("z2", z2)):
+        _need(name, m, n // 64 * 2, "host")       # fp16 per group of 64
+    _need("out", out, adapmoe_expert_bytes(cfg), "host")
+
+
 def adapmoe_pack_expert_int4(cfg, q1, s1, z1, q3, s3, z3, q2, s2, z2, out):
+    _need_quant(cfg, q1, s1, z1, q3, s3, z3, q2, s2, z2, out)
     _chk(None, load().adapmoe_pack_expert_int4(C.byref(cfg), *[_ptr(a) for a in (q1, s1, z1, q3, s3, z3, q2, s2, z2, out)]))
 
 
 def adapmoe_pack_expert_int2(cfg, q1, s1, z1, q3, s3, z3, q2, s2, z2, out):
+    _need_quant(cfg, q1, s1, z1, q3, s3, z3, q2, s2, z2, out)
     _chk(None, load().adapmoe_pack_expert_int2(C.byref(cfg), *[_ptr(a) for a in (q1, s1, z1, q3, s3, z3, q2, s2, z2, out)]))
 
 
 def adapmoe_register_expert(ctx, layer, expert, image_host, nbytes):
+    _need("image_host", image_host, nbytes, "host")
     _chk(ctx, load().adapmoe_register_expert(ctx, layer, expert, _ptr(image_host), nbytes))
 
 
 def adapmoe_bind_expert_dev(ctx, layer, expert, image_dev):
+    _need("image_dev", image_dev, adapmoe_expert_bytes(_cfg_of(ctx)), "dev")
     _chk(ctx, load().adapmoe_bind_expert_dev(ctx, layer, expert, _ptr(image_dev)))
 
 
@@ -189,6 +258,8 @@ def cache_cost(N, t, a, beta):
 
 
 def cache_alloc(ctx, slots_per_layer):
+    if len(slots_per_layer) != _cfg_of(ctx).L:
+        raise ValueError("slots_per_layer: one count per layer")
     arr = (C.c_int32 * len(slots_per_layer))(*[int(v) for v in slots_per_layer])
     _chk(ctx, load().cache_alloc(ctx, arr))
 
@@ -202,10 +273,14 @@ def cache_lookup(ctx, layer, ids, touch=False):
 
 
 def moe_gate(ctx, layer, x, B, ids, w, k, pred_ids=None, pred_k=None, stream=None):
+    _need_step(_cfg_of(ctx), B, x=x, ids=ids, w=w, k=k)
+    _need("pred_ids", pred_ids, 2 * B * 4, "dev")
+    _need("pred_k", pred_k, B * 4, "dev")
     _chk(ctx, load().moe_gate(ctx, layer, _ptr(x), B, _ptr(ids), _ptr(w), _ptr(k), _ptr(pred_ids), _ptr(pred_k), _stream(stream)))
 
 
 def moe_expert_ffn(ctx, layer, x, B, ids, w, k, y, stream=None):
+    _need_step(_cfg_of(ctx), B, x=x, y=y, ids=ids, w=w, k=k)
     _chk(ctx, load().moe_expert_ffn(ctx, layer, _ptr(x), B, _ptr(ids), _ptr(w), _ptr(k), _ptr(y), _stream(stream)))
 
 
@@ -215,18 +290,23 @@ def moe_prefetch(ctx, layer, ids):
 
 
 def moe_layer_step(ctx, layer, x, B, y, stream=None):
+    _need_step(_cfg_of(ctx), B, x=x, y=y)
     _chk(ctx, load().moe_layer_step(ctx, layer, _ptr(x), B, _ptr(y), _stream(stream)))
 
 
 def moe_residual_rmsnorm(ctx, h, y, gamma, x, B, stream=None):
+    _need_step(_cfg_of(ctx), B, x=x, y=y, h=h)
     _chk(ctx, load().moe_residual_rmsnorm(ctx, _ptr(h), _ptr(y), float(gamma), _ptr(x), B, _stream(stream)))
 
 
 def moe_stack_token(ctx, token, h, x, y, B, gamma, stream=None):
+    _need_step(_cfg_of(ctx), B, x=x, y=y, h=h)
     _chk(ctx, load().moe_stack_token(ctx, token, _ptr(h), _ptr(x), _ptr(y), B, float(gamma), _stream(stream)))
 
 
 def adapmoe_set_first_layer_predictor(ctx, Gpre):
+    cfg = _cfg_of(ctx)
+    _need("Gpre", Gpre, cfg.N * cfg.H * _esz(cfg), "dev")
     _chk(ctx, load().adapmoe_set_first_layer_predictor(ctx, _ptr(Gpre) if Gpre is not None else None))
 
 

@@ -279,3 +279,30 @@ def test_build_rejects_kernels_with_scratch_memory():
     assert len(rows) >= 30                      # every kernel instantiation of the library
     assert any("ffn_gateup_kernel" in r[0] for r in rows) and any("grouped_down_mfma_kernel" in r[0] for r in rows)
     assert all(int(r[4]) == 0 for r in rows), [r[0] for r in rows if int(r[4]) != 0]
+
+
+def test_binding_refuses_buffers_that_are_too_small_or_misplaced():
+    """The wrappers check size, contiguity and placement of every array they marshal (the C side
+    sees raw addresses only); a short buffer must never reach a kernel."""
+    cfg = B.Config(512, 512, 4, 2, B.BF16, 1, 0, 0)
+    w = np.zeros((512, 512), dtype=np.uint16)
+    out = np.zeros(3 * 512 * 512 * 2, dtype=np.uint8)
+    B.adapmoe_pack_expert(cfg, w, w, w, out)                              # exact sizes pass
+    with pytest.raises(ValueError, match="bytes given"):
+        B.adapmoe_pack_expert(cfg, w, w, w, out[:-1])
+    with pytest.raises(ValueError, match="bytes given"):
+        B.adapmoe_pack_expert(cfg, w[:-1], w, w, out)
+    with pytest.raises(ValueError, match="contiguous"):
+        B.adapmoe_pack_expert(cfg, np.zeros((512, 1024), dtype=np.uint16)[:, ::2], w, w, out)
+    # a context address the module does not know
+    with pytest.raises(ValueError, match="unknown context"):
+        B.moe_layer_step(ctypes.c_void_p(1234), 0, None, 1, None)
+    # the checks themselves, on stand-ins for the step arguments
+    with pytest.raises(ValueError, match="device tensor"):
+        B._need_step(cfg, 1, x=np.zeros(512, np.uint16), y=None)          # a host array where HBM is expected
+    B._need_step(cfg, 7, x=np.zeros(1, np.uint16))                        # B out of range: left to the library to report
+    with pytest.raises(ValueError, match="x: 1022 bytes given, 1024 needed"):
+        B._need("x", np.zeros(511, np.uint16), 1024)
+    import torch
+    with pytest.raises(ValueError, match="device tensor"):
+        B._need("x", torch.zeros(512, dtype=torch.bfloat16), 1024, "dev")

@@ -5,6 +5,7 @@
 // same input to predict its experts (Sec. 4.3).
 #include "device_utils.h"
 #include "launch.h"
+#include "norm_core.h"
 
 namespace adapmoe {
 
@@ -123,43 +124,18 @@ __global__ __launch_bounds__(kGateThreads) void gate_kernel(GateArgs a) {
 }
 
 // Residual update and RMS normalisation of the block input (the wiring between blocks of the
-// multi-layer workloads) followed by the gate of one router, in one launch: the first 256
-// threads run exactly the arithmetic of the separate normalisation kernel, then the whole
-// workgroup runs the gate on the x it has just written.  Same results as the two launches.
+// multi-layer workloads) followed by the gate of one router, in one launch: the workgroup runs
+// exactly the arithmetic of the separate normalisation kernel, then the gate on the x it has just
+// written.  Same results as the two launches.
+static_assert(kNormThreads == kGateThreads, "the normalisation and the gate share one workgroup shape");
 template <bool BF16>
 __global__ __launch_bounds__(kGateThreads) void norm_gate_kernel(GateArgs a, NormArgs n) {
   __shared__ float part[kGateWaves][64];
-  __shared__ float npart[4];
-  const int b = blockIdx.x, tid = threadIdx.x;
+  __shared__ float npart[kNormThreads / kWave];
+  const int b = blockIdx.x;
   const int H = a.H;
-  constexpr int kNormThreads = 256;
-  float* hr = n.h + (size_t)b * H;
-  const float* yr = n.y ? n.y + (size_t)b * H : nullptr;
-  if (tid < kNormThreads) {
-    float ss = 0.f;
-    for (int i = tid; i < H; i += kNormThreads) {
-      float v = hr[i];
-      if (yr) {
-        v = fmaf(n.gamma, yr[i], v);
-        hr[i] = v;
-      }
-      ss = fmaf(v, v, ss);
-    }
-    ss = wave_sum(ss);
-    if ((tid & 63) == 0) npart[tid >> 6] = ss;
-  }
-  __syncthreads();
-  if (tid < kNormThreads) {
-    float tot = 0.f;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) tot += npart[i];
-    const float inv = 1.0f / sqrtf(tot / (float)H + 1e-6f);
-    for (int i = tid; i < H; i += kNormThreads) {
-      const float v = hr[i] * inv;
-      if (BF16) static_cast<uint16_t*>(n.x)[(size_t)b * H + i] = f32_to_bf16_bits(v);
-      else static_cast<float*>(n.x)[(size_t)b * H + i] = v;
-    }
-  }
+  void* xrow = static_cast<char*>(n.x) + (size_t)b * H * (BF16 ? 2 : 4);
+  residual_rmsnorm_row<BF16>(n.h + (size_t)b * H, n.y ? n.y + (size_t)b * H : nullptr, n.gamma, xrow, H, npart);
   __syncthreads();   // x of this token is written and visible to the workgroup
   gate_body<BF16>(a, b, 0, part);
 }

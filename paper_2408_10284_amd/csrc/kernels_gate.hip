@@ -17,8 +17,10 @@ constexpr int kGateThreads = kGateWaves * kWave;
 // at once (the kernel is latency-bound: 2*N*H bytes per token).  Each wavefront
 // reduces its partial logits with DPP, wavefront 0 adds the partials in a fixed
 // order and takes the decision.
+// xk != nullptr (bfloat16 only): the caller already holds this thread's 16-byte pieces of x, piece i
+// being the one at element (threadIdx.x + i * kGateThreads) * 8, and x is not read from memory.
 template <bool BF16>
-__device__ __forceinline__ void gate_body(const GateArgs& a, int b, int r, float (*part)[64]) {
+__device__ __forceinline__ void gate_body(const GateArgs& a, int b, int r, float (*part)[64], const uint4* xk = nullptr) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int N = a.N, H = a.H;
 
@@ -46,8 +48,7 @@ __device__ __forceinline__ void gate_body(const GateArgs& a, int b, int r, float
     float acc[8];
 #pragma unroll
     for (int e = 0; e < 8; ++e) acc[e] = 0.f;
-    for (int c = (wave * kWave + lane) * VEC; c < H; c += kGateThreads * VEC) {
-      const uint4 xv = *reinterpret_cast<const uint4*>(xrow + (size_t)c * esz);
+    auto piece = [&](int c, const uint4& xv) {   // the 16-byte piece of x at element c against 8 router rows
       uint4 wv[8];
 #pragma unroll
       for (int e = 0; e < 8; ++e)
@@ -58,6 +59,16 @@ __device__ __forceinline__ void gate_body(const GateArgs& a, int b, int r, float
           if (BF16) acc[e] = dot16_bf16(wv[e], xv, acc[e]);
           else acc[e] = dot16_f32(wv[e], __builtin_bit_cast(float4, xv), acc[e]);
         }
+    };
+    if (BF16 && xk != nullptr) {
+#pragma unroll
+      for (int i = 0; i < kNormKeep; ++i) {
+        const int c = (threadIdx.x + i * kGateThreads) * VEC;
+        if (c < H) piece(c, xk[i]);
+      }
+    } else {
+      for (int c = (wave * kWave + lane) * VEC; c < H; c += kGateThreads * VEC)
+        piece(c, *reinterpret_cast<const uint4*>(xrow + (size_t)c * esz));
     }
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
@@ -135,9 +146,14 @@ __global__ __launch_bounds__(kGateThreads) void norm_gate_kernel(GateArgs a, Nor
   const int b = blockIdx.x;
   const int H = a.H;
   void* xrow = static_cast<char*>(n.x) + (size_t)b * H * (BF16 ? 2 : 4);
-  residual_rmsnorm_row<BF16>(n.h + (size_t)b * H, n.y ? n.y + (size_t)b * H : nullptr, n.gamma, xrow, H, npart);
-  __syncthreads();   // x of this token is written and visible to the workgroup
-  gate_body<BF16>(a, b, 0, part);
+  uint4 xk[kNormKeep];
+  const bool kept = residual_rmsnorm_row<BF16>(n.h + (size_t)b * H, n.y ? n.y + (size_t)b * H : nullptr, n.gamma, xrow, H, npart, xk);
+  if (BF16 && kept) {
+    gate_body<BF16>(a, b, 0, part, xk);   // every thread holds its pieces of x already
+  } else {
+    __syncthreads();   // x of this token is written and visible to the workgroup
+    gate_body<BF16>(a, b, 0, part);
+  }
 }
 
 hipError_t launch_norm_gate(const GateArgs& a, const NormArgs& n, bool bf16, hipStream_t s) {

@@ -13,7 +13,8 @@ __global__ __launch_bounds__(kNormThreads) void residual_rmsnorm_kernel(float* h
   __shared__ float part[kNormThreads / kWave];
   const int b = blockIdx.x;
   void* xrow = static_cast<char*>(x) + (size_t)b * H * (BF16 ? 2 : 4);
-  residual_rmsnorm_row<BF16>(h + (size_t)b * H, y ? y + (size_t)b * H : nullptr, gamma, xrow, H, part);
+  uint4 xk[kNormKeep];
+  (void)residual_rmsnorm_row<BF16>(h + (size_t)b * H, y ? y + (size_t)b * H : nullptr, gamma, xrow, H, part, xk);
 }
 
 hipError_t launch_residual_rmsnorm(float* h, const float* y, float gamma, void* x, bool bf16, int B, int H, hipStream_t s) {

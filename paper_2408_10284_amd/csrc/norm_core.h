@@ -34,8 +34,9 @@ __device__ __forceinline__ float4 axpy4(float g, const float4& y, const float4& 
   return make_float4(fmaf(g, y.x, h.x), fmaf(g, y.y, h.y), fmaf(g, y.z, h.z), fmaf(g, y.w, h.w));
 }
 
+// Returns the chunk as stored when the storage type is bfloat16 (eight packed values).
 template <bool BF16>
-__device__ __forceinline__ void store_x8(void* xrow, int ci, const NormChunk& c, float inv) {
+__device__ __forceinline__ uint4 store_x8(void* xrow, int ci, const NormChunk& c, float inv) {
   const float v[8] = {c.lo.x * inv, c.lo.y * inv, c.lo.z * inv, c.lo.w * inv, c.hi.x * inv, c.hi.y * inv, c.hi.z * inv, c.hi.w * inv};
   if (BF16) {
     uint4 o;
@@ -44,17 +45,22 @@ __device__ __forceinline__ void store_x8(void* xrow, int ci, const NormChunk& c,
     o.z = f32_to_bf16_bits(v[4]) | ((uint32_t)f32_to_bf16_bits(v[5]) << 16);
     o.w = f32_to_bf16_bits(v[6]) | ((uint32_t)f32_to_bf16_bits(v[7]) << 16);
     static_cast<uint4*>(xrow)[ci] = o;
+    return o;
   } else {
     float4* x4 = static_cast<float4*>(xrow) + 2 * (size_t)ci;
     x4[0] = make_float4(v[0], v[1], v[2], v[3]);
     x4[1] = make_float4(v[4], v[5], v[6], v[7]);
+    return make_uint4(0, 0, 0, 0);
   }
 }
 
 // Called by all kNormThreads threads of the workgroup; `part` is LDS for kNormThreads / 64 floats.
-// H is a multiple of 8.  Ends with every store issued but without a barrier.
+// H is a multiple of 8.  Ends with every store issued but without a barrier.  Returns true when
+// the row was short enough to stay in registers; xk[i] then holds, for bfloat16 storage, the
+// stored chunk tid + i * kNormThreads (what a 16-byte load of x at that place would return).
 template <bool BF16>
-__device__ __forceinline__ void residual_rmsnorm_row(float* hr, const float* yr, float gamma, void* xrow, int H, float* part) {
+__device__ __forceinline__ bool residual_rmsnorm_row(float* hr, const float* yr, float gamma, void* xrow, int H, float* part,
+                                                     uint4 (&xk)[kNormKeep]) {
   const int tid = threadIdx.x;
   const int nchunks = H >> 3;
   float4* h4 = reinterpret_cast<float4*>(hr);
@@ -95,7 +101,7 @@ __device__ __forceinline__ void residual_rmsnorm_row(float* hr, const float* yr,
 #pragma unroll
     for (int i = 0; i < kNormKeep; ++i) {
       const int ci = tid + i * kNormThreads;
-      if (ci < nchunks) store_x8<BF16>(xrow, ci, kept[i], inv);
+      if (ci < nchunks) xk[i] = store_x8<BF16>(xrow, ci, kept[i], inv);
     }
   } else {
     for (int ci = tid; ci < nchunks; ci += kNormThreads) {
@@ -103,6 +109,7 @@ __device__ __forceinline__ void residual_rmsnorm_row(float* hr, const float* yr,
       store_x8<BF16>(xrow, ci, c, inv);
     }
   }
+  return keep;
 }
 
 }  // namespace adapmoe

@@ -370,7 +370,7 @@ def test_mixtral_layer_full_size():
     """One Mixtral-8x7B-shaped layer, bf16, 256 AR(1) tokens, threshold 0.2, launched
     the way the benchmark launches it (moe_layer_step, batch 1)."""
     shape = synth.MIXTRAL_LAYER
-    ls = GpuLayerSet(shape, seed=0, max_B=1, taus=[0.2])
+    ls = GpuLayerSet(shape, seed=0, max_B=16, taus=[0.2])
     try:
         X = synth.ar1_tokens(256, shape.H, 0.8, seed=1, dtype="bf16")
         g = run_gate(ls, 0, X)
@@ -391,8 +391,85 @@ def test_mixtral_layer_full_size():
         print(f"max rel err {err.max():.3e}")
         assert err.max() <= TOL["bf16"]
         assert np.all(np.isfinite(yh)) and np.all(np.abs(yh).max(axis=1) > 0)
+        # the same shape through the batched path (16 tokens per call, grouped GEMM on the matrix cores), the
+        # launch configuration of the batched benchmark: sampled tokens against the checker, all 16 against
+        # the single-token path (the batched down GEMM multiplies the intermediate vector rounded to bfloat16)
+        c0 = B.adapmoe_counters(ls.ctx)
+        y16 = torch.empty((16, shape.H), dtype=torch.float32, device="cuda")
+        B.moe_layer_step(ls.ctx, 0, g["x_dev"][0:16], 16, y16)
+        B.adapmoe_check(ls.ctx)
+        y16h = y16.cpu().numpy()
+        pick = np.array([0, 7, 15])
+        err16 = rel_err_per_token(y16h[pick], OE.moe_block_rows(X[pick], ls.experts_f32[0], g["ids"][pick],
+                                                               g["w"][pick].astype(np.float64), g["k"][pick]))
+        drift = rel_err_per_token(y16h, yh[:16])
+        print(f"batched: max rel err {err16.max():.3e}, against the single-token path {drift.max():.3e}")
+        assert err16.max() <= TOL["bf16"] and drift.max() <= 1e-2
+        assert B.adapmoe_counters(ls.ctx)["ffn_launches"] == c0["ffn_launches"] + 1
     finally:
         ls.close()
+
+
+@pytest.mark.parametrize("dtype", ["int4g64", "int2g64"])
+def test_mixtral_layer_full_size_quantised(dtype):
+    """One Mixtral-8x7B-shaped layer with group-quantised experts (Sec. 6.3), 256 AR(1) tokens, threshold 0.2,
+    launched the way the benchmark launches it.  The images are drawn and packed on the device (the generator
+    the benchmark uses); the checker decodes the documented image format on its own and evaluates sampled
+    tokens, chosen so that few experts have to be decoded."""
+    shape = synth.MoEShape(H=4096, F=14336, N=8, L=1, dtype=dtype)
+    four = dtype == "int4g64"
+    ctx, cfg = B.adapmoe_create(shape.H, shape.F, shape.N, shape.L, B.INT4G64 if four else B.INT2G64, max_B=1)
+    images = []
+    try:
+        wg = synth.router_weights(shape, 0, 0)
+        wg_dev = to_dev_act(dtype, wg)
+        B.adapmoe_set_router(ctx, 0, wg_dev)
+        B.adapmoe_set_tau(ctx, [0.2])
+        for e in range(shape.N):
+            img = (synth.expert_image_int4_torch if four else synth.expert_image_int2_torch)(shape, 0, e, seed=11)
+            assert img.numel() == B.adapmoe_expert_bytes(cfg)
+            images.append(img)
+            B.adapmoe_bind_expert_dev(ctx, 0, e, img)
+        X = synth.ar1_tokens(256, shape.H, 0.8, seed=1, dtype="bf16")
+        xd = to_dev_act(dtype, X)
+        ids = torch.empty((256, 2), dtype=torch.int32, device="cuda")
+        w = torch.empty((256, 2), dtype=torch.float32, device="cuda")
+        k = torch.empty(256, dtype=torch.int32, device="cuda")
+        y = torch.empty((256, shape.H), dtype=torch.float32, device="cuda")
+        for t in range(256):
+            B.moe_gate(ctx, 0, xd[t:t + 1], 1, ids[t:t + 1], w[t:t + 1], k[t:t + 1])
+            B.moe_layer_step(ctx, 0, xd[t:t + 1], 1, y[t:t + 1])
+        B.adapmoe_check(ctx)
+        ids_h, w_h, k_h, yh = ids.cpu().numpy(), w.cpu().numpy(), k.cpu().numpy(), y.cpu().numpy()
+        ref = OG.gate_batch(X, wg, np.float32(0.2))
+        check_gate(ids_h, k_h, w_h, ref, 0.2, 1e-5)
+        assert np.all(np.isfinite(yh)) and np.all(np.abs(yh).max(axis=1) > 0)
+        # sample: three k = 2 tokens of the most frequent expert pair and one k = 1 token, preferably of that pair
+        pairs = {}
+        for t in np.nonzero(k_h == 2)[0]:
+            pairs.setdefault(tuple(sorted(ids_h[t])), []).append(t)
+        pair, toks = max(pairs.items(), key=lambda kv: len(kv[1]))
+        single = [t for t in np.nonzero(k_h == 1)[0] if ids_h[t, 0] in pair] or list(np.nonzero(k_h == 1)[0])
+        sample = list(toks[:3]) + single[:1]
+        need = sorted({int(ids_h[t, j]) for t in sample for j in range(k_h[t])})
+        assert len(need) <= 3
+        outs = {}
+        for e in need:     # decode one expert at a time (1.4 GB of float64 each)
+            mats = (synth.decode_int4_image if four else synth.decode_int2_image)(images[e].cpu().numpy(), shape.H, shape.F)
+            W1, W3, W2 = (OE.decode_int4(q, sc, zr) for (q, sc, zr) in mats)
+            for t in sample:
+                if e in ids_h[t, :k_h[t]]:
+                    outs[(t, e)] = OE.expert_ffn(X[t].astype(np.float64), W1, W3, W2)
+            del W1, W3, W2, mats
+        worst = 0.0
+        for t in sample:
+            yref = sum(np.float64(w_h[t, j]) * outs[(t, int(ids_h[t, j]))] for j in range(k_h[t]))
+            worst = max(worst, float(rel_err_per_token(yh[t], yref)))
+        print(f"{dtype}: sampled tokens {sample}, experts decoded {need}, max rel err {worst:.3e}")
+        assert worst <= TOL[dtype]
+    finally:
+        torch.cuda.synchronize()
+        B.adapmoe_destroy(ctx)
 
 
 # ------------------------------------------------ batched path (MFMA grouped GEMM) ----

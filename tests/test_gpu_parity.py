@@ -521,18 +521,23 @@ def test_batched_path(H, F, N, Bt, tau, two_terms):
 
 # ---------------------------------------- offloaded stack at the real expert size ----
 
-def test_mixtral_offloaded_stack_full_size():
-    """Mixtral-8x7B-shaped experts (352 MB each) in pinned host memory, 3 layers with
-    2, 1 and 0 cache slots: every layer step is checked against the checker on the
+@pytest.mark.parametrize("dtype", ["bf16", "int4g64"])
+def test_mixtral_offloaded_stack_full_size(dtype):
+    """Mixtral-8x7B-shaped experts (352 MB each in bf16, 99 MB in int4) in pinned host memory, 3 layers
+    with 2, 1 and 0 cache slots: every layer step is checked against the checker on the
     GPU's own layer input (teacher forcing), the cache trace by replay."""
-    shape = synth.MoEShape(4096, 14336, 8, 3, "bf16")
+    shape = synth.MoEShape(4096, 14336, 8, 3, dtype)
+    four = dtype == "int4g64"
     slots, taus, gamma, n_tok = [2, 1, 0], [0.2, 0.25, 0.3], 0.3, 6
-    ctx, cfg = B.adapmoe_create(shape.H, shape.F, shape.N, shape.L, B.BF16, max_B=1, trace_capacity=4096)
+    ctx, cfg = B.adapmoe_create(shape.H, shape.F, shape.N, shape.L, B.INT4G64 if four else B.BF16, max_B=1, trace_capacity=4096)
     nbytes = B.adapmoe_expert_bytes(cfg)
     host, routers, routers_f32 = {}, [], []
     unpacked = {}
 
-    def expert_mats(l, e):     # canonical float32 matrices of an image, for the checker
+    def expert_mats(l, e):     # canonical matrices of an image, for the checker
+        if four:               # decoded anew at each use: three float64 matrices are 1.4 GB
+            mats = synth.decode_int4_image(host[(l, e)].numpy(), shape.H, shape.F)
+            return tuple(OE.decode_int4(q, sc, zr) for (q, sc, zr) in mats)
         if (l, e) not in unpacked:
             bits = host[(l, e)].view(torch.int16).numpy().view(np.uint16)
             unpacked[(l, e)] = synth.unpack_image_bf16(bits, shape.H, shape.F)
@@ -545,8 +550,8 @@ def test_mixtral_offloaded_stack_full_size():
             routers_f32.append(r.float().cpu().numpy())
             B.adapmoe_set_router(ctx, l, r)
             for e in range(shape.N):
-                img = synth.expert_image_bf16_torch(shape, l, e, seed=5)
-                h = torch.empty(img.numel(), dtype=torch.bfloat16, pin_memory=True)
+                img = (synth.expert_image_int4_torch if four else synth.expert_image_bf16_torch)(shape, l, e, seed=5)
+                h = torch.empty(img.numel(), dtype=img.dtype, pin_memory=True)
                 h.copy_(img)
                 host[(l, e)] = h
                 B.adapmoe_register_expert(ctx, l, e, h, nbytes)
@@ -577,8 +582,8 @@ def test_mixtral_offloaded_stack_full_size():
                 yref = OE.combine(ids, w, k[0], lambda e: OE.expert_ffn(xin, *expert_mats(l, e)))
                 max_err = max(max_err, float(rel_err_per_token(y.cpu().numpy()[0], yref)))
         B.adapmoe_check(ctx)
-        print(f"max rel err over {n_tok * shape.L} layer steps: {max_err:.3e}")
-        assert max_err <= TOL["bf16"]
+        print(f"{dtype}: max rel err over {n_tok * shape.L} layer steps: {max_err:.3e}")
+        assert max_err <= TOL[dtype]
         sim = _replay_trace(slots, decisions)
         got = [(t, l, kind, e, v) for (t, l, kind, e, v, _s) in B.adapmoe_trace_read(ctx)]
         assert got == [tuple(ev) for ev in sim.events]

@@ -71,10 +71,26 @@ __global__ __launch_bounds__(kGateUpThreads) void ffn_gateup_kernel(FfnArgs p) {
   float* a_out = p.a + (size_t)b * 2 * p.a_stride;
 
   const uint4* xg = reinterpret_cast<const uint4*>(static_cast<const char*>(p.x) + (size_t)b * row_bytes);
-  auto stage_x = [&]() {
-    for (int i = tid; i < nch * kWave; i += kGateUpThreads) xs[i] = xg[i];
+  // x is staged in two steps, its loads issued before the first weight loads and its LDS writes
+  // after them (see the down kernel).
+  constexpr int kStageX = 4;
+  const int nsx = nch * kWave;
+  struct StageX {   // passed by value (an array written through a captured reference ends up in scratch memory)
+    uint4 v[kStageX];
+  };
+  auto stage_x_issue = [&]() -> StageX {
+    StageX sx;
+#pragma unroll
+    for (int u = 0; u < kStageX; ++u) sx.v[u] = xg[min(tid + u * kGateUpThreads, nsx - 1)];
+    return sx;
+  };
+  auto stage_x_finish = [&](const StageX& sx) {
+#pragma unroll
+    for (int u = 0; u < kStageX; ++u) xs[min(tid + u * kGateUpThreads, nsx - 1)] = sx.v[u];   // unconditional, see the down kernel
+    for (int i = tid + kStageX * kGateUpThreads; i < nsx; i += kGateUpThreads) xs[i] = xg[i];
     __syncthreads();
   };
+  auto stage_x = [&]() { stage_x_finish(stage_x_issue()); };
 
   const bool need0 = !windowed || p.j_only == 0, need1 = kk > 1 && (!windowed || p.j_only == 1);
   const bool all_resident = (!need0 || base[0] != nullptr) && (!need1 || base[1] != nullptr);
@@ -114,11 +130,12 @@ __global__ __launch_bounds__(kGateUpThreads) void ffn_gateup_kernel(FfnArgs p) {
     };
     uint4 A[NV], B[NV];
     int cur = next_row();
+    const StageX sxv = stage_x_issue();
     if (cur >= 0) {
       load_half(A, cur, 0);
       load_half(B, cur, 1);
     }
-    stage_x();
+    stage_x_finish(sxv);
     while (cur >= 0) {
       const int nxt = next_row();
       const float g = wave_sum(dot_x<BF16, NV>(A, xs, 0, lane, 0.f));
@@ -151,7 +168,8 @@ __global__ __launch_bounds__(kGateUpThreads) void ffn_gateup_kernel(FfnArgs p) {
       }
       half_c ^= 1;
     };
-    stream_parts<(NCH > 0 ? NCH : 1)>(2 * nrows, next_addr, consume, stage_x);
+    const StageX sxv = stage_x_issue();
+    stream_parts<(NCH > 0 ? NCH : 1)>(2 * nrows, next_addr, consume, [&, sxv]() { stage_x_finish(sxv); });
   } else {
     stage_x();
     for (int r = first; r < total; r += stride) {
@@ -222,14 +240,39 @@ __global__ __launch_bounds__(kDownThreads) void ffn_down_kernel(FfnArgs p) {
 
   const float4* ag = reinterpret_cast<const float4*>(p.a + (size_t)b * 2 * p.a_stride);
   const int S4 = (int)(p.a_stride >> 2);
-  auto stage_a = [&]() {
-    for (int i = tid; i < nj * F4; i += kDownThreads) {
-      const int jr = i >= F4 ? 1 : 0;
-      const int f4 = i - jr * F4;
-      as4[jr * F4 + (BF16 ? lds_pos_bf16(f4) : f4)] = ag[(j0 + jr) * S4 + f4];
-    }
+  // Staging of a_j in two steps: the loads of the first kStageA vectors per thread are issued
+  // before the first weight loads, the LDS writes come after them, so that the small, fast loads
+  // of a_j are not queued behind 14 KB of weights per wavefront and do not wait one by one
+  // (a loop of load, wait, write cost the kernel seven memory round trips at its start).
+  constexpr int kStageA = 8;
+  const int nst = nj * F4;
+  struct StageA {   // passed by value: an array written through a captured reference ends up in scratch memory
+    float4 v[kStageA];
+  };
+  auto a_src = [&](int i) -> const float4* {
+    const int jr = i >= F4 ? 1 : 0;
+    return ag + (j0 + jr) * S4 + (i - jr * F4);
+  };
+  auto a_dst = [&](int i) -> float4* {
+    const int jr = i >= F4 ? 1 : 0;
+    const int f4 = i - jr * F4;
+    return as4 + jr * F4 + (BF16 ? lds_pos_bf16(f4) : f4);
+  };
+  auto stage_a_issue = [&]() -> StageA {
+    StageA st;
+#pragma unroll
+    for (int u = 0; u < kStageA; ++u) st.v[u] = *a_src(min(tid + u * kDownThreads, nst - 1));   // unconditional: a clamped repeat is dropped below
+    return st;
+  };
+  auto stage_a_finish = [&](const StageA& st) {
+    // unconditional as well (threads beyond the end rewrite the last vector with its own value):
+    // under a condition the compiler would move each load down to its write again
+#pragma unroll
+    for (int u = 0; u < kStageA; ++u) *a_dst(min(tid + u * kDownThreads, nst - 1)) = st.v[u];
+    for (int i = tid + kStageA * kDownThreads; i < nst; i += kDownThreads) *a_dst(i) = *a_src(i);   // very long rows only
     __syncthreads();
   };
+  auto stage_a = [&]() { stage_a_finish(stage_a_issue()); };
 
   const int first = hlo + blockIdx.x * kWaves + wave;
   const int hstride = gridDim.x * kWaves;
@@ -263,7 +306,8 @@ __global__ __launch_bounds__(kDownThreads) void ffn_down_kernel(FfnArgs p) {
         hc += hstride;
       }
     };
-    stream_parts<NV>(nrows * nb, next_addr, consume, stage_a);
+    const StageA sta = stage_a_issue();
+    stream_parts<NV>(nrows * nb, next_addr, consume, [&, sta]() { stage_a_finish(sta); });
   } else {
     stage_a();
     for (int h = first; h < hhi; h += hstride) {

@@ -179,11 +179,34 @@ __global__ __launch_bounds__(kI4GateUpThreads) void ffn_gateup_quant_kernel(FfnA
   uint4 x[NBLK][8];
   float xsum[NBLK];
   const uint4* xg = reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(p.x) + (size_t)b * H);
-  auto stage_x = [&]() {
-    const int pieces = H >> 3;
-    for (int c = threadIdx.x; c < NBLK * 512; c += kI4GateUpThreads) {
-      const int g = c >> 3, j = c & 7;
-      xs[((g >> 6) * 8 + j) * 64 + (g & 63)] = c < pieces ? xg[c] : make_uint4(0, 0, 0, 0);
+  // 2-bit codes: the pieces of x are requested before the first weight loads (stage_x_issue) and
+  // turned through LDS after them (stage_x), all without conditions, so that these small loads
+  // neither queue behind the weights nor wait one by one.  4-bit codes: a plain loop after the
+  // first weight loads (measured faster there by 0.4 us, while the other form gains 1.2 us with 2 bits).
+  constexpr int kXRounds = NBLK * 512 / kI4GateUpThreads;
+  struct StageX {
+    uint4 v[kXRounds];
+  };
+  const int pieces = H >> 3;
+  auto stage_x_issue = [&]() -> StageX {
+    StageX sx;
+#pragma unroll
+    for (int u = 0; u < kXRounds; ++u) sx.v[u] = xg[min((int)threadIdx.x + u * kI4GateUpThreads, pieces - 1)];
+    return sx;
+  };
+  auto stage_x = [&](const StageX& sx) {
+    if constexpr (BITS == 2) {
+#pragma unroll
+      for (int u = 0; u < kXRounds; ++u) {
+        const int c = threadIdx.x + u * kI4GateUpThreads;
+        const int g = c >> 3, j = c & 7;
+        xs[((g >> 6) * 8 + j) * 64 + (g & 63)] = c < pieces ? sx.v[u] : make_uint4(0, 0, 0, 0);
+      }
+    } else {
+      for (int c = threadIdx.x; c < NBLK * 512; c += kI4GateUpThreads) {
+        const int g = c >> 3, j = c & 7;
+        xs[((g >> 6) * 8 + j) * 64 + (g & 63)] = c < pieces ? xg[c] : make_uint4(0, 0, 0, 0);
+      }
     }
     __syncthreads();
 #pragma unroll
@@ -240,7 +263,12 @@ __global__ __launch_bounds__(kI4GateUpThreads) void ffn_gateup_quant_kernel(FfnA
     uv = lane == ns ? u : uv;
     if (++ns == kWave) flush();
   };
-  stream_bufs<I4RowPair<BITS, NBLK>>(nrows, load_next, consume, stage_x);
+  if constexpr (BITS == 2) {
+    const StageX sxv = stage_x_issue();
+    stream_bufs<I4RowPair<BITS, NBLK>>(nrows, load_next, consume, [&, sxv]() { stage_x(sxv); });
+  } else {
+    stream_bufs<I4RowPair<BITS, NBLK>>(nrows, load_next, consume, [&]() { stage_x(StageX{}); });
+  }
   flush();
 }
 

@@ -49,20 +49,26 @@ __global__ __launch_bounds__(kBThreads) void bucket_gather_kernel(BatchArgs p) {
     float w = 0.f;
     if (b < p.B) {
       int kk = p.k[b];
+      const int e_in = p.ids[2 * b + j];   // read together with k, not after it
+      const float w_in = p.w[2 * b + j];
       kk = kk < 1 ? 1 : (kk > 2 ? 2 : kk);
       if (j < kk) {
-        e = p.ids[2 * b + j];
-        w = p.w[2 * b + j];
+        e = e_in;
+        w = w_in;
         if (e < 0 || e >= p.N) {
           e = -1;
           if (blockIdx.x == 0 && blockIdx.y == 0) atomicOr(p.err, 2);
         }
       }
     }
+    // residency of all experts in one load per lane (a load per loop pass below would be N memory
+    // round trips one after the other)
+    const void* mine = lane < p.N ? p.table[lane] : nullptr;
+    const uint64_t resmask = __builtin_amdgcn_ballot_w64(mine != nullptr);
     for (int ex = 0; ex < p.N; ++ex) {
       const uint64_t m = __builtin_amdgcn_ballot_w64(e == ex);
       const int rank = __builtin_popcountll(m & ((1ull << lane) - 1));
-      const bool resident = p.table[ex] != nullptr;
+      const bool resident = (resmask >> ex) & 1;
       if (m && !resident && lane == 0 && blockIdx.x == 0 && blockIdx.y == 0) atomicOr(p.err, 1);
       if (lane == 0) s_count[ex] = resident ? __builtin_popcountll(m) : 0;
       if (e == ex && resident) {
@@ -75,7 +81,7 @@ __global__ __launch_bounds__(kBThreads) void bucket_gather_kernel(BatchArgs p) {
     }
     if (blockIdx.x == 0 && blockIdx.y == 0 && lane < p.N) {
       p.bkt_count[lane] = s_count[lane];
-      p.bkt_base[lane] = p.table[lane];
+      p.bkt_base[lane] = mine;
     }
   }
   __syncthreads();

@@ -24,18 +24,23 @@ __device__ __forceinline__ int resolve_experts(const FfnArgs& p, int b, const ch
     }
     return kk;
   }
+  // k, both ids and both weights are requested together (ids[B,2] and w[B,2] always exist); only
+  // the table entries depend on a previous load
   int kk = p.k[b];
+  const int e_in[2] = {p.ids[2 * b], p.ids[2 * b + 1]};
+  const float w_in[2] = {p.w[2 * b], p.w[2 * b + 1]};
   kk = kk < 1 ? 1 : (kk > 2 ? 2 : kk);
+#pragma unroll
   for (int j = 0; j < 2; ++j) {
     base[j] = nullptr;
     w[j] = 0.f;
     if (j < kk) {
-      const int e = p.ids[2 * b + j];
+      const int e = e_in[j];
       if (e < 0 || e >= p.N) {
         if (threadIdx.x == 0) atomicOr(p.err, 2);
       } else {
         base[j] = static_cast<const char*>(p.table[e]);
-        w[j] = p.w[2 * b + j];
+        w[j] = w_in[j];
         if (base[j] == nullptr && threadIdx.x == 0) atomicOr(p.err, 1);
       }
     }

@@ -685,7 +685,7 @@ int adapmoe_create(const adapmoe_config* cfg, adapmoe_ctx** out) {
   c->layers.resize(cfg->L);
   c->lc.gateup_blocks = env_int("ADAPMOE_GATEUP_BLOCKS", quant_bits(cfg->dtype) ? 1024 : 512);  // measured best on MI355X
   c->lc.down_blocks = env_int("ADAPMOE_DOWN_BLOCKS", 256);
-  c->lc.batch_min = env_int("ADAPMOE_BATCH_MIN", 4);
+  c->lc.batch_min = env_int("ADAPMOE_BATCH_MIN", 3);
   c->lc.batch_two_terms = env_int("ADAPMOE_BATCH_TWO_TERMS", 0);
   c->lc.fused_blocks = 0;
   c->lc.dyn_pct = quant_bits(cfg->dtype) ? 0 : env_int("ADAPMOE_DYN_PCT", 20);

@@ -272,7 +272,12 @@ int adapmoe_last_decision(adapmoe_ctx* ctx, int32_t* ids, int32_t* k, int32_t* p
 int adapmoe_check(adapmoe_ctx* ctx, void* stream);
 
 /* Kernel timing with HIP events on the launch stream: when on, every launch of
- * the expert-FFN kernels is bracketed by event records.  adapmoe_profile_read
+ * the gate and expert-FFN kernels carries a pair of events tied to its own
+ * dispatch, so the durations are the kernels' execution times (what a profiler's
+ * kernel trace reports), without the dispatch gaps that events recorded around a
+ * launch would include; the fused kernel and tile-wise launches are bracketed by
+ * event records.  Not to be switched on while a stream is being captured into a
+ * graph.  adapmoe_profile_read
  * synchronises and returns, per kernel class (0 = gate/up GEMV, 1 = down GEMV,
  * 2 = gate), the number of launches and their summed duration in ms, then resets.
  * Further classes: 3 bucket/gather, 4 grouped gate/up GEMM, 5 grouped down GEMM

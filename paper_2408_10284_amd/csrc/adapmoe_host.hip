@@ -363,6 +363,24 @@ struct ScopedTimer {
   }
 };
 
+// Launch configuration for one GEMV launch: while the context is profiling it carries a pair of
+// events that the launch ties to the kernel's own dispatch (execution time as a profiler reports
+// it), registered under the kernel class `cls`.
+LaunchCfg timed_cfg(adapmoe_ctx* c, int cls) {
+  LaunchCfg lc = c->lc;
+  if (!c->profiling) return lc;
+  TimedLaunch t{cls, get_event(c), get_event(c)};
+  if (!t.t0 || !t.t1) {
+    if (t.t0) c->event_pool.push_back(t.t0);
+    if (t.t1) c->event_pool.push_back(t.t1);
+    return lc;
+  }
+  lc.timing.start = t.t0;
+  lc.timing.stop = t.t1;
+  c->timed.push_back(t);
+  return lc;
+}
+
 FfnArgs ffn_args(adapmoe_ctx* c, int layer, const void* x, int B, const int32_t* ids, const float* w, const int32_t* k,
                  float* y, const ResolvedExperts* res) {
   FfnArgs p{};
@@ -413,18 +431,9 @@ int launch_ffn(adapmoe_ctx* c, int layer, const void* x, int B, const int32_t* i
       q.a_hi = c->d_ahi;
       q.a_lo = c->d_alo;
       q.two_terms = c->lc.batch_two_terms;
-      {
-        ScopedTimer t(c, 3, s);
-        HIPCHK(c, launch_bucket_gather(q, s));
-      }
-      {
-        ScopedTimer t(c, 4, s);
-        HIPCHK(c, launch_grouped_gateup(q, s));
-      }
-      {
-        ScopedTimer t(c, 5, s);
-        HIPCHK(c, launch_grouped_down(q, c->lc.batch_two_terms != 0, s));
-      }
+      HIPCHK(c, launch_bucket_gather(q, s, timed_cfg(c, 3).timing));
+      HIPCHK(c, launch_grouped_gateup(q, s, timed_cfg(c, 4).timing));
+      HIPCHK(c, launch_grouped_down(q, c->lc.batch_two_terms != 0, s, timed_cfg(c, 5).timing));
     }
     c->ctr.ffn_launches++;
     return ADAPMOE_OK;
@@ -447,16 +456,16 @@ int launch_ffn(adapmoe_ctx* c, int layer, const void* x, int B, const int32_t* i
   // of the previous step cleared them (both kernels always run as a pair on one stream)
   const bool dyn = c->lc.dyn_pct > 0 && !qb;
   {
-    ScopedTimer t(c, 0, s);
+    const LaunchCfg lc = timed_cfg(c, 0);
     p.dyn_ctr = dyn ? c->d_dyn : nullptr;
     p.dyn_clear = nullptr;
-    HIPCHK(c, qb ? launch_ffn_gateup_quant(p, qb, c->lc, s) : launch_ffn_gateup(p, c->cfg.dtype, c->lc, s));
+    HIPCHK(c, qb ? launch_ffn_gateup_quant(p, qb, lc, s) : launch_ffn_gateup(p, c->cfg.dtype, lc, s));
   }
   {
-    ScopedTimer t(c, 1, s);
+    const LaunchCfg lc = timed_cfg(c, 1);
     p.dyn_ctr = nullptr;
     p.dyn_clear = dyn ? c->d_dyn : nullptr;
-    HIPCHK(c, qb ? launch_ffn_down_quant(p, qb, c->lc, s) : launch_ffn_down(p, c->cfg.dtype, c->lc, s));
+    HIPCHK(c, qb ? launch_ffn_down_quant(p, qb, lc, s) : launch_ffn_down(p, c->cfg.dtype, lc, s));
   }
   c->ctr.ffn_launches++;
   return ADAPMOE_OK;
@@ -552,9 +561,9 @@ int launch_gate_both(adapmoe_ctx* c, int layer, const void* x, int B, int32_t* i
   }
   if (norm && depth > 0)   // several routers read x: it has to be complete before any of their workgroups starts
     HIPCHK(c, launch_residual_rmsnorm(norm->h, norm->y, norm->gamma, norm->x, c->bf16_act, B, c->cfg.H, s));
-  ScopedTimer t(c, 2, s);
-  if (norm && depth == 0) HIPCHK(c, launch_norm_gate(g, *norm, c->bf16_act, s));   // one router: normalise and gate in one launch
-  else HIPCHK(c, launch_gate(g, c->bf16_act, 1 + depth, s));
+  const KernelTiming kt = timed_cfg(c, 2).timing;
+  if (norm && depth == 0) HIPCHK(c, launch_norm_gate(g, *norm, c->bf16_act, s, kt));   // one router: normalise and gate in one launch
+  else HIPCHK(c, launch_gate(g, c->bf16_act, 1 + depth, s, kt));
   return ADAPMOE_OK;
 }
 

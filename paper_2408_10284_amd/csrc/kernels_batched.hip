@@ -327,23 +327,23 @@ static int env_flag(const char* name, int dflt) {
   return (v && *v) ? atoi(v) : dflt;
 }
 
-hipError_t launch_bucket_gather(const BatchArgs& p, hipStream_t s) {
+hipError_t launch_bucket_gather(const BatchArgs& p, hipStream_t s, const KernelTiming& t) {
   dim3 grid((p.H / 32 + 3) / 4, p.N), block(kBThreads);
-  hipLaunchKernelGGL(bucket_gather_kernel, grid, block, 0, s, p);
+  launch_kernel(bucket_gather_kernel, grid, block, 0, s, t, p);
   return hipGetLastError();
 }
 
-hipError_t launch_grouped_gateup(const BatchArgs& p, hipStream_t s) {
+hipError_t launch_grouped_gateup(const BatchArgs& p, hipStream_t s, const KernelTiming& t) {
   // gate/up: every wavefront loads its own operand vectors (no workgroup barriers), measured 10 %
   // faster than staging them per workgroup; ADAPMOE_BDIRECT=0 selects the staged variant
   static const int direct = env_flag("ADAPMOE_BDIRECT", 1);
   dim3 grid(p.F / (16 * kBWaves), p.N), block(kBThreads);
   if (direct) {
     constexpr size_t lds = grouped_lds_bytes<kGateUpKS, 2, 1, kBWaves, 0>();
-    hipLaunchKernelGGL((grouped_gateup_mfma_kernel<kGateUpKS, 0>), grid, block, lds, s, p);
+    launch_kernel(grouped_gateup_mfma_kernel<kGateUpKS, 0>, grid, block, lds, s, t, p);
   } else {
     constexpr size_t lds = grouped_lds_bytes<kGateUpKS, 2, 1, kBWaves, 1>();
-    hipLaunchKernelGGL((grouped_gateup_mfma_kernel<kGateUpKS, 1>), grid, block, lds, s, p);
+    launch_kernel(grouped_gateup_mfma_kernel<kGateUpKS, 1>, grid, block, lds, s, t, p);
   }
   return hipGetLastError();
 }
@@ -351,14 +351,14 @@ hipError_t launch_grouped_gateup(const BatchArgs& p, hipStream_t s) {
 // down: 8 wavefronts x 16 rows per workgroup, operand slab staged in LDS (the barrier-free variant
 // and 4 x 32 rows measured slower here).  `two_terms` multiplies by A = hi + lo (fp32 accuracy);
 // otherwise by A rounded to bfloat16 only.
-hipError_t launch_grouped_down(const BatchArgs& p, bool two_terms, hipStream_t s) {
+hipError_t launch_grouped_down(const BatchArgs& p, bool two_terms, hipStream_t s, const KernelTiming& t) {
   dim3 grid(p.H / 128, p.N), block(512);
   if (two_terms) {
     constexpr size_t lds = grouped_lds_bytes<kDownKS, 1, 2, 8, 1>();
-    hipLaunchKernelGGL((grouped_down_mfma_kernel<kDownKS, 1, 8, 2>), grid, block, lds, s, p);
+    launch_kernel(grouped_down_mfma_kernel<kDownKS, 1, 8, 2>, grid, block, lds, s, t, p);
   } else {
     constexpr size_t lds = grouped_lds_bytes<kDownKS, 1, 1, 8, 1>();
-    hipLaunchKernelGGL((grouped_down_mfma_kernel<kDownKS, 1, 8, 1>), grid, block, lds, s, p);
+    launch_kernel(grouped_down_mfma_kernel<kDownKS, 1, 8, 1>, grid, block, lds, s, t, p);
   }
   return hipGetLastError();
 }

@@ -497,12 +497,12 @@ hipError_t ffn_kernels_init(int dtype) {
 }
 
 template <bool BF16>
-static void launch_gateup_t(const FfnArgs& p, int nch, dim3 grid, size_t lds, hipStream_t s) {
+static void launch_gateup_t(const FfnArgs& p, int nch, dim3 grid, size_t lds, hipStream_t s, const KernelTiming& t) {
   dim3 block(kGateUpThreads);
-  if (nch == 8) hipLaunchKernelGGL((ffn_gateup_kernel<BF16, 8>), grid, block, lds, s, p);         // H = 4096 bf16, 2048 fp32
-  else if (nch == 12) hipLaunchKernelGGL((ffn_gateup_kernel<BF16, 12>), grid, block, lds, s, p);  // H = 6144 bf16 (8x22B)
-  else if (nch == 4) hipLaunchKernelGGL((ffn_gateup_kernel<BF16, 4>), grid, block, lds, s, p);
-  else hipLaunchKernelGGL((ffn_gateup_kernel<BF16, 0>), grid, block, lds, s, p);
+  if (nch == 8) launch_kernel(ffn_gateup_kernel<BF16, 8>, grid, block, lds, s, t, p);         // H = 4096 bf16, 2048 fp32
+  else if (nch == 12) launch_kernel(ffn_gateup_kernel<BF16, 12>, grid, block, lds, s, t, p);  // H = 6144 bf16 (8x22B)
+  else if (nch == 4) launch_kernel(ffn_gateup_kernel<BF16, 4>, grid, block, lds, s, t, p);
+  else launch_kernel(ffn_gateup_kernel<BF16, 0>, grid, block, lds, s, t, p);
 }
 
 hipError_t launch_ffn_gateup(const FfnArgs& p, int dtype, const LaunchCfg& lc, hipStream_t s) {
@@ -511,18 +511,18 @@ hipError_t launch_ffn_gateup(const FfnArgs& p, int dtype, const LaunchCfg& lc, h
   const int nch = (int)(row_bytes / kChunkBytes);
   dim3 grid(lc.gateup_blocks, p.B);
   if (p.j_only >= 0) grid.x = std::max(1, std::min(lc.gateup_blocks, (p.r1 - p.r0 + 3) / (kGateUpThreads / kWave)));
-  if (bf16) launch_gateup_t<true>(p, nch, grid, row_bytes, s);
-  else launch_gateup_t<false>(p, nch, grid, row_bytes, s);
+  if (bf16) launch_gateup_t<true>(p, nch, grid, row_bytes, s, lc.timing);
+  else launch_gateup_t<false>(p, nch, grid, row_bytes, s, lc.timing);
   return hipGetLastError();
 }
 
 template <bool BF16>
-static void launch_down_t(const FfnArgs& p, int nch, dim3 grid, size_t lds, hipStream_t s) {
+static void launch_down_t(const FfnArgs& p, int nch, dim3 grid, size_t lds, hipStream_t s, const KernelTiming& t) {
   dim3 block(kDownThreads);
-  if (nch % 7 == 0) hipLaunchKernelGGL((ffn_down_kernel<BF16, 7>), grid, block, lds, s, p);
-  else if (nch % 8 == 0) hipLaunchKernelGGL((ffn_down_kernel<BF16, 8>), grid, block, lds, s, p);
-  else if (nch % 4 == 0) hipLaunchKernelGGL((ffn_down_kernel<BF16, 4>), grid, block, lds, s, p);
-  else hipLaunchKernelGGL((ffn_down_kernel<BF16, 0>), grid, block, lds, s, p);
+  if (nch % 7 == 0) launch_kernel(ffn_down_kernel<BF16, 7>, grid, block, lds, s, t, p);
+  else if (nch % 8 == 0) launch_kernel(ffn_down_kernel<BF16, 8>, grid, block, lds, s, t, p);
+  else if (nch % 4 == 0) launch_kernel(ffn_down_kernel<BF16, 4>, grid, block, lds, s, t, p);
+  else launch_kernel(ffn_down_kernel<BF16, 0>, grid, block, lds, s, t, p);
 }
 
 hipError_t launch_ffn_down(const FfnArgs& p, int dtype, const LaunchCfg& lc, hipStream_t s) {
@@ -531,8 +531,8 @@ hipError_t launch_ffn_down(const FfnArgs& p, int dtype, const LaunchCfg& lc, hip
   dim3 grid(lc.down_blocks, p.B);
   if (p.j_only >= 0) grid.x = std::max(1, std::min(lc.down_blocks, (p.r1 - p.r0 + 15) / (kDownThreads / kWave)));
   const size_t lds = (size_t)2 * p.F * sizeof(float);
-  if (bf16) launch_down_t<true>(p, nch, grid, lds, s);
-  else launch_down_t<false>(p, nch, grid, lds, s);
+  if (bf16) launch_down_t<true>(p, nch, grid, lds, s, lc.timing);
+  else launch_down_t<false>(p, nch, grid, lds, s, lc.timing);
   return hipGetLastError();
 }
 

@@ -156,17 +156,17 @@ __global__ __launch_bounds__(kGateThreads) void norm_gate_kernel(GateArgs a, Nor
   }
 }
 
-hipError_t launch_norm_gate(const GateArgs& a, const NormArgs& n, bool bf16, hipStream_t s) {
+hipError_t launch_norm_gate(const GateArgs& a, const NormArgs& n, bool bf16, hipStream_t s, const KernelTiming& t) {
   dim3 grid(a.B), block(kGateThreads);
-  if (bf16) hipLaunchKernelGGL(norm_gate_kernel<true>, grid, block, 0, s, a, n);
-  else hipLaunchKernelGGL(norm_gate_kernel<false>, grid, block, 0, s, a, n);
+  if (bf16) launch_kernel(norm_gate_kernel<true>, grid, block, 0, s, t, a, n);
+  else launch_kernel(norm_gate_kernel<false>, grid, block, 0, s, t, a, n);
   return hipGetLastError();
 }
 
-hipError_t launch_gate(const GateArgs& a, bool bf16, int routers, hipStream_t s) {
+hipError_t launch_gate(const GateArgs& a, bool bf16, int routers, hipStream_t s, const KernelTiming& t) {
   dim3 grid(a.B, routers), block(kGateThreads);
-  if (bf16) hipLaunchKernelGGL(gate_kernel<true>, grid, block, 0, s, a);
-  else hipLaunchKernelGGL(gate_kernel<false>, grid, block, 0, s, a);
+  if (bf16) launch_kernel(gate_kernel<true>, grid, block, 0, s, t, a);
+  else launch_kernel(gate_kernel<false>, grid, block, 0, s, t, a);
   return hipGetLastError();
 }
 

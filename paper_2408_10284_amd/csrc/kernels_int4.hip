@@ -362,20 +362,20 @@ hipError_t launch_ffn_gateup_quant(const FfnArgs& p, int bits, const LaunchCfg& 
   if (p.j_only >= 0) grid.x = std::max(1, std::min(lc.gateup_blocks, (p.r1 - p.r0 + 3) / (kI4GateUpThreads / kWave)));
   const int nblk = ((p.H >> 6) + 63) >> 6;
   if (bits == 4) {
-    if (nblk == 1) hipLaunchKernelGGL((ffn_gateup_quant_kernel<4, 1>), grid, block, 1 * 8192, s, p);
-    else hipLaunchKernelGGL((ffn_gateup_quant_kernel<4, 2>), grid, block, 2 * 8192, s, p);
+    if (nblk == 1) launch_kernel(ffn_gateup_quant_kernel<4, 1>, grid, block, 1 * 8192, s, lc.timing, p);
+    else launch_kernel(ffn_gateup_quant_kernel<4, 2>, grid, block, 2 * 8192, s, lc.timing, p);
   } else {
-    if (nblk == 1) hipLaunchKernelGGL((ffn_gateup_quant_kernel<2, 1>), grid, block, 1 * 8192, s, p);
-    else hipLaunchKernelGGL((ffn_gateup_quant_kernel<2, 2>), grid, block, 2 * 8192, s, p);
+    if (nblk == 1) launch_kernel(ffn_gateup_quant_kernel<2, 1>, grid, block, 1 * 8192, s, lc.timing, p);
+    else launch_kernel(ffn_gateup_quant_kernel<2, 2>, grid, block, 2 * 8192, s, lc.timing, p);
   }
   return hipGetLastError();
 }
 
-hipError_t launch_ffn_down_quant(const FfnArgs& p, int bits, const LaunchCfg&, hipStream_t s) {
+hipError_t launch_ffn_down_quant(const FfnArgs& p, int bits, const LaunchCfg& lc, hipStream_t s) {
   const int rows = p.j_only >= 0 ? p.r1 - p.r0 : p.H;
   dim3 grid(std::max(1, (rows + kI4DownRows - 1) / kI4DownRows), p.B), block(kI4DownThreads);
-  if (bits == 4) hipLaunchKernelGGL(ffn_down_quant_kernel<4>, grid, block, 0, s, p);
-  else hipLaunchKernelGGL(ffn_down_quant_kernel<2>, grid, block, 0, s, p);
+  if (bits == 4) launch_kernel(ffn_down_quant_kernel<4>, grid, block, 0, s, lc.timing, p);
+  else launch_kernel(ffn_down_quant_kernel<2>, grid, block, 0, s, lc.timing, p);
   return hipGetLastError();
 }
 

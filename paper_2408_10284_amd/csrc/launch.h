@@ -1,6 +1,7 @@
 // Internal interface between the host library and the kernel translation units.
 #pragma once
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stddef.h>
 #include <stdint.h>
 
@@ -105,6 +106,19 @@ struct FusedSync {
   unsigned spin_limit;
 };
 
+// Events tied to one kernel dispatch (start and end of its execution, the interval a profiler
+// reports); null = plain launch.  Events recorded on the stream around a launch also cover the
+// processing of the event packets themselves, 1-2 us per side.
+struct KernelTiming {
+  hipEvent_t start = nullptr, stop = nullptr;
+};
+
+template <class K, class... A>
+inline void launch_kernel(K kernel, dim3 grid, dim3 block, size_t lds, hipStream_t s, const KernelTiming& t, A... args) {
+  if (t.start) hipExtLaunchKernelGGL(kernel, grid, block, (uint32_t)lds, s, t.start, t.stop, 0, args...);
+  else hipLaunchKernelGGL(kernel, grid, block, lds, s, args...);
+}
+
 struct LaunchCfg {
   int gateup_blocks;  // workgroups of the gate/up GEMV (256 threads each)
   int down_blocks;    // workgroups of the down GEMV (1024 threads each)
@@ -112,10 +126,11 @@ struct LaunchCfg {
   int batch_two_terms;  // batched path: intermediate activation as hi + lo bfloat16 (1) or bfloat16 only (0)
   int fused_blocks;   // workgroups of the fused single-token FFN kernel (0 = fused path off)
   int dyn_pct;        // percent of the row passes of the GEMV kernels that are scheduled dynamically (0 = none)
+  KernelTiming timing;  // set for one launch when the context is profiling
 };
 
-hipError_t launch_gate(const GateArgs& a, bool bf16, int routers, hipStream_t s);
-hipError_t launch_norm_gate(const GateArgs& a, const NormArgs& n, bool bf16, hipStream_t s);
+hipError_t launch_gate(const GateArgs& a, bool bf16, int routers, hipStream_t s, const KernelTiming& t = KernelTiming{});
+hipError_t launch_norm_gate(const GateArgs& a, const NormArgs& n, bool bf16, hipStream_t s, const KernelTiming& t = KernelTiming{});
 hipError_t launch_ffn_gateup(const FfnArgs& p, int dtype, const LaunchCfg& lc, hipStream_t s);
 hipError_t launch_ffn_down(const FfnArgs& p, int dtype, const LaunchCfg& lc, hipStream_t s);
 hipError_t ffn_kernels_init(int dtype);
@@ -126,9 +141,9 @@ hipError_t launch_ffn_fused(const FfnArgs& p, int dtype, const FusedSync& sy, in
 hipError_t launch_ffn_gateup_quant(const FfnArgs& p, int bits, const LaunchCfg& lc, hipStream_t s);
 hipError_t launch_ffn_down_quant(const FfnArgs& p, int bits, const LaunchCfg& lc, hipStream_t s);
 hipError_t batched_kernels_init();
-hipError_t launch_bucket_gather(const BatchArgs& p, hipStream_t s);
-hipError_t launch_grouped_gateup(const BatchArgs& p, hipStream_t s);
-hipError_t launch_grouped_down(const BatchArgs& p, bool two_terms, hipStream_t s);
+hipError_t launch_bucket_gather(const BatchArgs& p, hipStream_t s, const KernelTiming& t = KernelTiming{});
+hipError_t launch_grouped_gateup(const BatchArgs& p, hipStream_t s, const KernelTiming& t = KernelTiming{});
+hipError_t launch_grouped_down(const BatchArgs& p, bool two_terms, hipStream_t s, const KernelTiming& t = KernelTiming{});
 hipError_t launch_residual_rmsnorm(float* h, const float* y, float gamma, void* x, bool bf16, int B, int H, hipStream_t s);
 
 struct PokeArgs {   // up to 8 pointer-sized stores, ordered on the stream

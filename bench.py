@@ -173,7 +173,7 @@ def bench_layer(args):
     B.adapmoe_check(ctx)
     elapsed = t1 - t0
 
-    # second pass with HIP events around each kernel launch, on the launch stream
+    # second pass with a pair of HIP events tied to each kernel dispatch, on the launch stream (the kernel's execution time)
     B.adapmoe_profile(ctx, True)
     run(steps, warmup)
     torch.cuda.synchronize()

@@ -325,29 +325,133 @@ def test_cache_lookahead_depth_one_is_plain_prefetch_and_deeper_never_loads_afte
             layers = [ev[1] for ev in evs]
             assert layers == sorted(layers) and all(l < x < L for x in layers)
             for ev in evs:
-                if ev[2] == OC.PF_LOAD:
+                if ev[2] in (OC.PF_LOAD, OC.PF_LAND):
                     assert ev[1] == max(layers)
+                if ev[2] == OC.PF_LAND:
+                    assert ev[1] == l + 1      # only the prediction for the next layer uses landing buffers
     assert a.events == b.events
+
+
+class _StampCacheWithLanding:
+    """Independent model of one layer: last-use timestamps for the layer's own slots plus a set of
+    landed experts that lives until the end of the next demand."""
+
+    def __init__(self, cap):
+        self.cap, self.stamp, self.clock, self.landed = cap, {}, 0, set()
+
+    def _use(self, e):
+        self.clock += 1
+        self.stamp[e] = self.clock
+
+    def _make_room(self):
+        if len(self.stamp) >= self.cap:
+            del self.stamp[min(self.stamp, key=self.stamp.get)]
+
+    def demand(self, ids):
+        loads = 0
+        for e in ids:
+            if e in self.stamp:
+                self._use(e)
+            elif e in self.landed:
+                self.landed.discard(e)
+                if self.cap:
+                    self._make_room()
+                    self._use(e)
+            else:
+                loads += 1
+                if self.cap:
+                    self._make_room()
+                    self._use(e)
+        self.landed = set()
+        return loads
+
+    def prefetch(self, pred):
+        copies = 0
+        for i, e in enumerate(pred):
+            if e in self.landed:
+                continue
+            if i < self.cap:                 # distinct ids: the first cap of them use the layer's own slots
+                if e not in self.stamp:
+                    copies += 1
+                    self._make_room()
+                self._use(e)
+            else:
+                assert e not in self.stamp   # the cap own slots hold the cap experts predicted before it
+                self.landed.add(e)
+                copies += 1
+        return copies
 
 
 def test_cache_prefetch_against_timestamp_simulator():
     rng = np.random.default_rng(12)
-    for trial in range(50):
+    for trial in range(60):
         cap = int(rng.integers(0, 5))
         c = OC.ExpertCache([cap])
-        ref = _StampLRU(cap)
+        ref = _StampCacheWithLanding(cap)
         for n in range(60):
             k = int(rng.integers(1, 3))
             ids = rng.choice(6, size=2, replace=False)
-            for j in range(k):
-                ref.access(int(ids[j]))
-            c.demand(n, 0, ids, k)
-            pred = list(rng.choice(6, size=int(rng.integers(0, 3)), replace=False))
-            for e in pred[: min(len(pred), cap)]:
-                ref.access(int(e))
-            c.prefetch(n, 0, pred)
+            want_loads = ref.demand([int(e) for e in ids[:k]])
+            evs = c.demand(n, 0, ids, k)
+            assert sum(ev[2] in (OC.MISS, OC.BYPASS) for ev in evs) == want_loads
+            assert c.landed(0) == []                       # nothing survives the demand
+            pred = list(rng.choice(6, size=int(rng.integers(0, 4)), replace=False))
+            want_copies = ref.prefetch([int(e) for e in pred])
+            evs = c.prefetch(n, 0, pred)
+            assert sum(ev[2] in (OC.PF_LOAD, OC.PF_LAND) for ev in evs) == want_copies
             assert sorted(c.resident(0)) == sorted(ref.stamp)
+            assert sorted(c.landed(0)) == sorted(ref.landed)
             assert len(c.resident(0)) <= cap
+            assert len(evs) == len(pred)                   # every predicted expert is on the GPU afterwards
+            assert all(e in c.resident(0) or e in c.landed(0) for e in pred)
+
+
+def test_cache_landing_hand_trace(golden_dir):
+    g = _load(golden_dir, "cache_landing_trace.json")
+    for sc in g["scenarios"]:
+        c = OC.ExpertCache(sc["slots"])
+        for s in sc["steps"]:
+            c.demand(s["token"], s["layer"], s["demand"], s["k"])
+            if s["layer"] + 1 < len(sc["slots"]):
+                c.prefetch(s["token"], s["layer"] + 1, s["pred_for_next"])
+        assert [list(e) for e in c.events] == sc["events"]
+        assert [c.resident(l) for l in range(len(sc["slots"]))] == sc["final_resident"]
+        s = OC.summarise(c.events)
+        assert s["on_demand_loads"] == sc["on_demand_loads"] and s["prefetch_loads"] == sc["prefetch_loads"]
+        assert s["prefetch_landed"] == sc["prefetch_landed"] and s["prefetch_useful"] == sc["prefetch_useful"]
+
+
+def test_cache_without_slots_loads_on_demand_only_when_the_prefetch_was_wrong():
+    """The on-demand-load model counts, for a token that needs one expert, a load when the cache
+    misses and the prefetch was wrong: (1 - t/N)(1 - beta), which is 1 - beta for a layer without
+    slots (Sec. 4.4.2, Eq.11).  A layer with zero slots must therefore load on demand exactly for
+    the tokens whose prediction was wrong, and for two required experts exactly the wrongly
+    predicted ones."""
+    n_tok, N = 200, 8
+    rng = np.random.default_rng(3)
+    need = rng.integers(0, N, size=n_tok)
+    right = rng.random(n_tok) < 0.7
+    c = OC.ExpertCache([4, 0])
+    for n in range(n_tok):
+        c.demand(n, 0, [0, 1], 1)
+        c.prefetch(n, 1, [int(need[n]) if right[n] else int((need[n] + 1) % N)])
+        c.demand(n, 1, [int(need[n]), 0], 1)
+    l1 = [ev for ev in c.events if ev[1] == 1]
+    assert sum(ev[2] == OC.BYPASS for ev in l1) == int((~right).sum())
+    assert sum(ev[2] == OC.HIT_PF for ev in l1) == int(right.sum())
+    assert sum(ev[2] == OC.PF_LAND for ev in l1) == n_tok and c.resident(1) == [] and c.landed(1) == []
+    # two required, one of them predicted: one on-demand load (the case of Eq.13)
+    c = OC.ExpertCache([0])
+    c.prefetch(0, 0, [5])
+    evs = c.demand(0, 0, [5, 2], 2)
+    assert [ev[2] for ev in evs] == [OC.HIT_PF, OC.BYPASS]
+    # several tokens in one step share the landing buffers until the step ends
+    c = OC.ExpertCache([0])
+    c.prefetch(0, 0, [5, 6, 7])
+    a = c.demand(0, 0, [6, 1], 1, release=False)
+    b = c.demand(0, 0, [5, 6], 2, release=False)
+    c.release_landing(0)
+    assert [ev[2] for ev in a + b] == [OC.HIT_PF, OC.HIT_PF, OC.BYPASS] and c.landed(0) == []
 
 
 # --------------------------------------------------------------- planner ----

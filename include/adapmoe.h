@@ -74,11 +74,14 @@ typedef struct {
 /* Cache event kinds (Sec. 4.4 / Alg.1; one record per demanded or predicted expert). */
 enum {
   ADAPMOE_EV_HIT = 0,      /* demanded expert resident */
-  ADAPMOE_EV_HIT_PF = 1,   /* demanded expert resident thanks to a prefetch, first use since */
+  ADAPMOE_EV_HIT_PF = 1,   /* demanded expert resident (or in a landing buffer) thanks to a prefetch, first use since;
+                              a landed expert joins the layer's set if the layer owns slots (victim = evicted expert) */
   ADAPMOE_EV_MISS = 2,     /* demanded expert absent: loaded on demand (victim evicted if the layer was full) */
   ADAPMOE_EV_BYPASS = 3,   /* demanded expert absent and the layer owns no slot: loaded into a spare slot */
   ADAPMOE_EV_PF_TOUCH = 4, /* predicted expert already resident: recency refreshed */
-  ADAPMOE_EV_PF_LOAD = 5   /* predicted expert absent: copy started ahead of time */
+  ADAPMOE_EV_PF_LOAD = 5,  /* predicted expert absent: copy started ahead of time into one of the layer's slots */
+  ADAPMOE_EV_PF_LAND = 6   /* predicted expert absent and no slot of the layer free for it: copy started ahead of time
+                              into a landing buffer outside the cache budget, kept until the layer's next demand */
 };
 
 typedef struct {
@@ -94,10 +97,11 @@ typedef struct {
   uint64_t tokens_gated;     /* token-layers passed through moe_layer_step */
   uint64_t single_expert;    /* of which k == 1 */
   uint64_t hits, hits_after_prefetch, misses, bypasses;
-  uint64_t prefetch_touches, prefetch_loads;
+  uint64_t prefetch_touches, prefetch_loads;   /* prefetch_loads counts PF_LOAD and PF_LAND */
   uint64_t h2d_bytes;        /* bytes copied host -> HBM (demand + prefetch) */
   uint64_t ffn_launches;
   uint64_t tiled_ffn;       /* experts evaluated tile by tile while their copy was still running */
+  uint64_t prefetch_landed; /* of prefetch_loads: copies into landing buffers (PF_LAND) */
 } adapmoe_counters_t;
 
 const char* adapmoe_strerror(int code);
@@ -172,14 +176,20 @@ int cache_plan(int L, int N, int C, const double* a, const double* beta, int32_t
 /* Expected on-demand loads of one layer with t of N experts cached (Eq.15). */
 double cache_cost(int N, int t, double a, double beta);
 
-/* Allocates sum(slots_per_layer) + 2*max_B expert-sized slots in HBM (the spare
- * slots serve layers that own fewer slots than the experts one step runs) and
- * empties every layer's LRU set.  slots_per_layer[l] in 0..N.  May be called once. */
+/* Allocates sum(slots_per_layer) + 4*max_B expert-sized slots in HBM and empties every
+ * layer's LRU set.  slots_per_layer[l] in 0..N is the layer's cache size t_l of Sec. 4.4.
+ * The 4*max_B spare slots are outside that budget: 2*max_B hold what a running step reads
+ * beyond its layer's own slots (a layer that owns fewer slots than the step requires
+ * experts), 2*max_B are landing buffers for prefetched experts of the next layer that
+ * cannot take one of its slots (the on-demand-load model of Eq.11-14 credits a correct
+ * prefetch at every cache size, t = 0 included, so a prefetched expert must be able to
+ * land).  May be called once. */
 int cache_alloc(adapmoe_ctx* ctx, const int32_t* slots_per_layer);
 
-/* Residency query: slot_out[i] = physical slot of ids[i] in `layer`, -1 if
- * absent, -2 if bound to caller memory.  touch != 0 also makes found entries
- * most recently used (in the order given).  Host-only, no GPU work. */
+/* Residency query: slot_out[i] = physical slot of ids[i] in `layer` (in the layer's LRU
+ * set or in one of its landing buffers), -1 if absent, -2 if bound to caller memory.
+ * touch != 0 also makes entries found in the LRU set most recently used (in the order
+ * given).  Host-only, no GPU work. */
 int cache_lookup(adapmoe_ctx* ctx, int layer, const int32_t* ids_host, int n, int32_t* slot_out, int touch);
 
 /* ---- the block's steps ------------------------------------------------------ */
@@ -198,16 +208,33 @@ int moe_gate(adapmoe_ctx* ctx, int layer, const void* x_dev, int B,
 /* y[b] = sum_{j<k[b]} w[b][j] * E_{ids[b][j]}(x[b])  (Eq.2 over the activated
  * experts), E(x) = W2 (silu(W1 x) * (W3 x)).  Reads expert images through the
  * context's device-side residency table; every needed expert must be resident
- * (bound, or in a cache slot whose copy was ordered before this call on
- * `stream`).  A non-resident expert contributes nothing and raises a device
- * flag reported as ADAPMOE_ENORES by adapmoe_check(). */
+ * (bound, or brought into a cache slot by moe_demand / moe_prefetch before this
+ * call; the call makes `stream` wait for those copies).  A non-resident expert
+ * contributes nothing and raises a device flag reported as ADAPMOE_ENORES by
+ * adapmoe_check().  For a token with k == 2 the two ids must differ. */
 int moe_expert_ffn(adapmoe_ctx* ctx, int layer, const void* x_dev, int B,
                    const int32_t* ids_dev, const float* w_dev, const int32_t* k_dev,
                    float* y_dev, void* stream);
 
-/* Prefetch for `layer` (Sec. 4.3): for the first min(n, slots of layer) ids, in
- * order: resident -> most recently used; absent -> evict LRU if full, start an
- * asynchronous copy on the library's side stream.  Returns at once. */
+/* Demand phase of Alg.1 for `layer` (to_transfer <- E.in_CPU): the experts
+ * ids_host[b][0 .. k_host[b]-1] of the B tokens, in token then rank order, are looked up
+ * in the layer's LRU set and landing buffers.  Found -> most recently used (HIT, HIT_PF);
+ * absent -> least recently used entry evicted if the layer is full and an asynchronous copy
+ * started on the library's side stream (MISS), or into a spare slot if the layer owns no
+ * slot (BYPASS).  Prefetched experts in landing buffers that are not required are dropped.
+ * Host-side only; *loads_out (may be NULL) = number of on-demand loads started.
+ * The call must be followed by moe_expert_ffn() on the same layer, which waits for these
+ * copies on its stream, evaluates the experts and ends the step; a second moe_demand()
+ * before that returns ADAPMOE_ESTATE.  moe_layer_step() is this call, moe_prefetch() for
+ * the predicted experts and moe_expert_ffn() in one. */
+int moe_demand(adapmoe_ctx* ctx, int layer, const int32_t* ids_host, const int32_t* k_host, int B, int32_t* loads_out);
+
+/* Prefetch for `layer` (Sec. 4.3), ids in rank order.  At most as many of them as the layer
+ * owns slots go to its LRU set: resident -> most recently used; absent -> evict LRU if
+ * full, start an asynchronous copy on the library's side stream.  The others are copied
+ * into landing buffers outside the budget (at most 2*max_B per layer; further ones are
+ * left out) and kept until the layer's next demand (moe_demand / moe_layer_step, or a
+ * moe_expert_ffn that no moe_demand preceded).  Returns at once. */
 int moe_prefetch(adapmoe_ctx* ctx, int layer, const int32_t* ids_host, int n);
 
 /* One layer of Alg.1 for B tokens: gate + predict; (if the layer is not fully
@@ -236,7 +263,9 @@ int moe_stack_token(adapmoe_ctx* ctx, int token, float* h_dev, void* x_dev, floa
  * (default: layer 0 is served by its LRU set only).  When set, moe_layer_step on the last layer also
  * applies Gpre to that layer's block input, takes the adaptive decision with layer 0's threshold
  * and prefetches the predicted experts into layer 0's cache for the following token; the decision
- * is reported as the depth-1 prediction of that step.  Training the matrix is the caller's business. */
+ * is reported as the depth-1 prediction of that step.  Training the matrix is the caller's business.
+ * A one-layer context has no "last layer of the previous token" distinct from the layer that is
+ * running, so the call returns ADAPMOE_ESTATE when L == 1. */
 int adapmoe_set_first_layer_predictor(adapmoe_ctx* ctx, const void* Gpre_dev);
 
 /* Tile-wise loading (Sec. 5, Fig.6(b) and Alg.1: tile-wise scheduling).  tiles = 0 or 1: an expert image
@@ -258,6 +287,27 @@ int adapmoe_set_lookahead(adapmoe_ctx* ctx, int depth);
 /* Prediction of depth d (1..3) of the last moe_layer_step on a non-bound layer. */
 int adapmoe_last_lookahead(adapmoe_ctx* ctx, int depth, int32_t* pred_ids, int32_t* pred_k, int B);
 
+/* ---- tuning options -------------------------------------------------------------- */
+
+/* Options that select a code path or a launch shape.  None changes what is computed beyond
+ * the order of floating-point additions, except BATCH_TWO_TERMS (precision of the batched
+ * path's intermediate activation).  Set between calls, not while work of the context is
+ * being captured into a graph. */
+enum {
+  ADAPMOE_OPT_BATCH_MIN = 0,       /* tokens per call from which bf16 calls take the batched (matrix-core) path; default 3, >= 1 */
+  ADAPMOE_OPT_BATCH_TWO_TERMS = 1, /* batched down GEMM multiplies the intermediate activation as hi + lo bfloat16 (1) or rounded
+                                      to bfloat16 (0, default) */
+  ADAPMOE_OPT_FUSED = 2,           /* 1: single-token steps on fp32/bf16 experts run both GEMVs in one launch joined by a bounded
+                                      grid-wide barrier (slower on MI355X, default 0); ADAPMOE_ESTATE if the shape does not fit */
+  ADAPMOE_OPT_DYN_PCT = 3,         /* percent of the gate/up GEMV's row passes handed out dynamically, 0..100 (default 20) */
+  ADAPMOE_OPT_GATEUP_BLOCKS = 4,   /* workgroups of the gate/up GEMV, 1..65535 */
+  ADAPMOE_OPT_DOWN_BLOCKS = 5,     /* workgroups of the fp32/bf16 down GEMV, 1..65535 */
+  ADAPMOE_OPT_BATCH_DIRECT = 6     /* batched gate/up GEMM: wavefronts load their token operand themselves (1, default) or the
+                                      workgroup stages it through LDS (0) */
+};
+int adapmoe_set_option(adapmoe_ctx* ctx, int option, int value);
+int adapmoe_get_option(adapmoe_ctx* ctx, int option, int* value_out);
+
 /* ---- bookkeeping ------------------------------------------------------------- */
 
 int adapmoe_set_token(adapmoe_ctx* ctx, int token);
@@ -267,6 +317,18 @@ int adapmoe_counters(adapmoe_ctx* ctx, adapmoe_counters_t* out);
 /* Last gate decision brought to the host by moe_layer_step on a non-bound layer
  * (ids [B,2], k [B], pred_ids [B,2], pred_k [B]); any pointer may be NULL. */
 int adapmoe_last_decision(adapmoe_ctx* ctx, int32_t* ids, int32_t* k, int32_t* pred_ids, int32_t* pred_k, int B);
+/* Decision log (tracing aid; the gate results of steps that make no host round trip are
+ * otherwise not visible): while log_dev is non-NULL every moe_layer_step (also inside
+ * moe_stack_token) appends one record of 6*max_B int32 to the caller's device buffer
+ * log_dev, which holds `capacity` records: ids [B,2], k [B], then the prediction for the
+ * next layer pred_ids [B,2], pred_k [B] (Sec. 4.3) when the step computed one (steps on
+ * layers whose experts and whose successor's experts are all bound compute none and leave
+ * that part unspecified); the first 6*B entries are used.  The copy is enqueued on the
+ * step's stream after the gate.  Appending stops when the buffer is full.  Setting the log
+ * (or NULL) restarts at record 0.  Not to be used while a stream is being captured into a
+ * graph (the record position is decided on the host). */
+int adapmoe_set_decision_log(adapmoe_ctx* ctx, int32_t* log_dev, int capacity);
+
 /* Waits for all work of the context (both streams given so far) and reports
  * device-side flags: ADAPMOE_ENORES if an FFN met a non-resident expert. */
 int adapmoe_check(adapmoe_ctx* ctx, void* stream);

@@ -13,7 +13,8 @@ LIB_PATH = os.path.join(_HERE, "libadapmoe.so")
 
 OK, EINVAL, ENOMEM, ENOTREG, ENORES, EHIP, ESTATE = 0, -1, -2, -3, -4, -5, -6
 F32, BF16, INT4G64, INT2G64 = 0, 1, 2, 3
-EVENT_KINDS = ("HIT", "HIT_PF", "MISS", "BYPASS", "PF_TOUCH", "PF_LOAD")
+EVENT_KINDS = ("HIT", "HIT_PF", "MISS", "BYPASS", "PF_TOUCH", "PF_LOAD", "PF_LAND")
+OPT_BATCH_MIN, OPT_BATCH_TWO_TERMS, OPT_FUSED, OPT_DYN_PCT, OPT_GATEUP_BLOCKS, OPT_DOWN_BLOCKS, OPT_BATCH_DIRECT = range(7)
 
 
 class Config(C.Structure):
@@ -30,7 +31,7 @@ class Event(C.Structure):
 class Counters(C.Structure):
     _fields_ = [(n, C.c_uint64) for n in
                 ("tokens_gated", "single_expert", "hits", "hits_after_prefetch", "misses", "bypasses",
-                 "prefetch_touches", "prefetch_loads", "h2d_bytes", "ffn_launches", "tiled_ffn")]
+                 "prefetch_touches", "prefetch_loads", "h2d_bytes", "ffn_launches", "tiled_ffn", "prefetch_landed")]
 
 
 class AdapMoEError(RuntimeError):
@@ -62,7 +63,10 @@ _SIGS = {
     "cache_lookup": (C.c_int, [_P, C.c_int, C.POINTER(C.c_int32), C.c_int, C.POINTER(C.c_int32), C.c_int]),
     "moe_gate": (C.c_int, [_P, C.c_int, _P, C.c_int, _P, _P, _P, _P, _P, _P]),
     "moe_expert_ffn": (C.c_int, [_P, C.c_int, _P, C.c_int, _P, _P, _P, _P, _P]),
+    "moe_demand": (C.c_int, [_P, C.c_int, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_int, C.POINTER(C.c_int32)]),
     "moe_prefetch": (C.c_int, [_P, C.c_int, C.POINTER(C.c_int32), C.c_int]),
+    "adapmoe_set_option": (C.c_int, [_P, C.c_int, C.c_int]),
+    "adapmoe_get_option": (C.c_int, [_P, C.c_int, C.POINTER(C.c_int)]),
     "moe_layer_step": (C.c_int, [_P, C.c_int, _P, C.c_int, _P, _P]),
     "moe_residual_rmsnorm": (C.c_int, [_P, _P, _P, C.c_float, _P, C.c_int, _P]),
     "moe_stack_token": (C.c_int, [_P, C.c_int, _P, _P, _P, C.c_int, C.c_float, _P]),
@@ -75,6 +79,7 @@ _SIGS = {
     "adapmoe_counters": (C.c_int, [_P, C.POINTER(Counters)]),
     "adapmoe_last_decision": (C.c_int, [_P, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.POINTER(C.c_int32),
                                         C.POINTER(C.c_int32), C.c_int]),
+    "adapmoe_set_decision_log": (C.c_int, [_P, _P, C.c_int]),
     "adapmoe_check": (C.c_int, [_P, _P]),
     "adapmoe_profile": (C.c_int, [_P, C.c_int]),
     "adapmoe_profile_read": (C.c_int, [_P, C.c_int, C.POINTER(C.c_uint64), C.POINTER(C.c_double)]),
@@ -284,6 +289,19 @@ def moe_expert_ffn(ctx, layer, x, B, ids, w, k, y, stream=None):
     _chk(ctx, load().moe_expert_ffn(ctx, layer, _ptr(x), B, _ptr(ids), _ptr(w), _ptr(k), _ptr(y), _stream(stream)))
 
 
+def moe_demand(ctx, layer, ids, k):
+    """ids: 2 per token (flat or nested), k: one per token; returns the number of on-demand loads started."""
+    k = [int(v) for v in k]
+    flat = [int(v) for row in ids for v in (row if hasattr(row, "__len__") else [row])]
+    if len(flat) != 2 * len(k):
+        raise ValueError("ids: two per token")
+    a = (C.c_int32 * len(flat))(*flat)
+    kk = (C.c_int32 * len(k))(*k)
+    loads = C.c_int32()
+    _chk(ctx, load().moe_demand(ctx, layer, a, kk, len(k), C.byref(loads)))
+    return loads.value
+
+
 def moe_prefetch(ctx, layer, ids):
     arr = (C.c_int32 * len(ids))(*[int(v) for v in ids])
     _chk(ctx, load().moe_prefetch(ctx, layer, arr, len(ids)))
@@ -308,6 +326,16 @@ def adapmoe_set_first_layer_predictor(ctx, Gpre):
     cfg = _cfg_of(ctx)
     _need("Gpre", Gpre, cfg.N * cfg.H * _esz(cfg), "dev")
     _chk(ctx, load().adapmoe_set_first_layer_predictor(ctx, _ptr(Gpre) if Gpre is not None else None))
+
+
+def adapmoe_set_option(ctx, option, value):
+    _chk(ctx, load().adapmoe_set_option(ctx, int(option), int(value)))
+
+
+def adapmoe_get_option(ctx, option):
+    v = C.c_int()
+    _chk(ctx, load().adapmoe_get_option(ctx, int(option), C.byref(v)))
+    return v.value
 
 
 def adapmoe_set_tiles(ctx, tiles):
@@ -349,6 +377,12 @@ def adapmoe_last_decision(ctx, B):
     pk = (C.c_int32 * B)()
     _chk(ctx, load().adapmoe_last_decision(ctx, ids, k, pids, pk, B))
     return list(ids), list(k), list(pids), list(pk)
+
+
+def adapmoe_set_decision_log(ctx, log_dev, capacity):
+    if log_dev is not None:
+        _need("log_dev", log_dev, capacity * 6 * _cfg_of(ctx).max_B * 4, "dev")
+    _chk(ctx, load().adapmoe_set_decision_log(ctx, _ptr(log_dev), int(capacity)))
 
 
 def adapmoe_check(ctx, stream=None):

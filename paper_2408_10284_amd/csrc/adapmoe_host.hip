@@ -39,9 +39,18 @@ struct Entry {
 struct LayerCache {
   int cap = 0;
   std::vector<Entry> order;  // front = least recently used
+  // Prefetched experts that could not take one of the layer's own slots: held in spare slots
+  // outside the budget until the layer's next demand (the on-demand-load model of Sec. 4.4.2
+  // credits a correct prefetch whatever the layer's cache size, Eq.11-14).
+  std::vector<Entry> landing;
   int find(int e) const {
     for (size_t i = 0; i < order.size(); ++i)
       if (order[i].expert == e) return (int)i;
+    return -1;
+  }
+  int find_landing(int e) const {
+    for (size_t i = 0; i < landing.size(); ++i)
+      if (landing[i].expert == e) return (int)i;
     return -1;
   }
   void touch(int pos) {
@@ -54,6 +63,27 @@ struct LayerCache {
 struct TimedLaunch {
   int cls;
   hipEvent_t t0, t1;
+};
+
+// What the demand phase of one layer step leaves for the expert FFN that follows it and for the
+// end of the step (Alg.1: the compute queue of the required experts).
+struct StepState {
+  bool open = false;
+  int layer = -1;
+  std::vector<int> used_slots;                 // slots the FFN of this step reads
+  std::vector<std::pair<int, int>> transient;  // (expert, slot) to drop right after the FFN
+  std::vector<int> demanded;                   // experts needed by this step so far
+  int rank_slot[2] = {-1, -1};                 // slot of token 0's expert of rank j (-1: caller memory)
+  int k0 = 0;                                  // experts token 0 runs
+  void reset(int l) {
+    open = true;
+    layer = l;
+    used_slots.clear();
+    transient.clear();
+    demanded.clear();
+    rank_slot[0] = rank_slot[1] = -1;
+    k0 = 0;
+  }
 };
 
 }  // namespace
@@ -97,6 +127,9 @@ struct adapmoe_ctx {
   std::vector<int> free_slots;
   std::vector<LayerCache> layers;
   std::vector<std::pair<const void**, const void*>> pending_pokes;  // (device address, value), applied before the next FFN
+  StepState step;                       // demand phase of the running layer step
+  int32_t* dec_log = nullptr;           // caller's device buffer for gate decisions (tracing aid), records of 6*max_B ints
+  int dec_log_cap = 0, dec_log_pos = 0;
 
   std::deque<adapmoe_event> trace;
   adapmoe_counters_t ctr{};
@@ -188,14 +221,6 @@ size_t a_stride_for(const adapmoe_config& c) {
   return std::max((size_t)c.F, blocks * 2048);  // int4: blocks x 8 vectors x 64 lanes x 8 bf16
 }
 
-int env_int(const char* name, int dflt) {
-  const char* v = getenv(name);
-  if (!v || !*v) return dflt;
-  char* end = nullptr;
-  long x = strtol(v, &end, 10);
-  return (end != v && x >= 0) ? (int)x : dflt;
-}
-
 void record(adapmoe_ctx* c, int layer, int kind, int expert, int victim, int slot) {
   switch (kind) {
     case ADAPMOE_EV_HIT: c->ctr.hits++; break;
@@ -204,6 +229,7 @@ void record(adapmoe_ctx* c, int layer, int kind, int expert, int victim, int slo
     case ADAPMOE_EV_BYPASS: c->ctr.bypasses++; break;
     case ADAPMOE_EV_PF_TOUCH: c->ctr.prefetch_touches++; break;
     case ADAPMOE_EV_PF_LOAD: c->ctr.prefetch_loads++; break;
+    case ADAPMOE_EV_PF_LAND: c->ctr.prefetch_loads++; c->ctr.prefetch_landed++; break;
   }
   if (c->cfg.trace_capacity <= 0) return;
   if ((int)c->trace.size() >= c->cfg.trace_capacity) c->trace.pop_front();
@@ -282,52 +308,93 @@ void poke_resolved(adapmoe_ctx* c, int b, int j, const void* value) {
 }
 
 int flush_pokes(adapmoe_ctx* c, hipStream_t s) {
+  // One launch stores up to 8 values from 8 threads, in no defined order: when an address was given
+  // several values since the last flush (an expert evicted and loaded again within one step), only
+  // the last one is sent.
+  std::vector<std::pair<const void**, const void*>> last;
+  last.reserve(c->pending_pokes.size());
+  for (size_t i = 0; i < c->pending_pokes.size(); ++i) {
+    bool later = false;
+    for (size_t j = i + 1; j < c->pending_pokes.size() && !later; ++j) later = c->pending_pokes[j].first == c->pending_pokes[i].first;
+    if (!later) last.push_back(c->pending_pokes[i]);
+  }
+  c->pending_pokes.clear();
   size_t i = 0;
-  while (i < c->pending_pokes.size()) {
+  while (i < last.size()) {
     PokeArgs p{};
-    for (p.n = 0; p.n < 8 && i < c->pending_pokes.size(); ++p.n, ++i) {
-      p.addr[p.n] = c->pending_pokes[i].first;
-      p.value[p.n] = c->pending_pokes[i].second;
+    for (p.n = 0; p.n < 8 && i < last.size(); ++p.n, ++i) {
+      p.addr[p.n] = last[i].first;
+      p.value[p.n] = last[i].second;
     }
     HIPCHK(c, launch_poke(p, s));
   }
-  c->pending_pokes.clear();
   return ADAPMOE_OK;
 }
 
-// Prefetch policy for one layer (Sec. 4.3; Alg.1 transfer set): touch or load, rank order.
-int prefetch_layer(adapmoe_ctx* c, int layer, const int32_t* ids, int n) {
+// Prefetch policy for one layer (Sec. 4.3; Alg.1 transfer set), rank order.  At most as many of the
+// predicted experts as the layer owns slots are refreshed in or loaded into its LRU set (a prefetch
+// never evicts an expert predicted together with it); with `allow_landing` (the prediction for the
+// next layer) the others are copied into spare slots outside the budget and kept until the layer's
+// next demand, otherwise (deeper look-ahead) they are left out.
+int prefetch_layer(adapmoe_ctx* c, int layer, const int32_t* ids, int n, bool allow_landing) {
   LayerCache& lc = c->layers[layer];
   const int N = c->cfg.N;
-  int done = 0;
-  for (int i = 0; i < n && done < lc.cap; ++i) {
+  int own = 0;
+  for (int i = 0; i < n; ++i) {
     const int e = ids[i];
     if (e < 0 || e >= N) return fail(c, ADAPMOE_EINVAL, "prefetch: expert id out of range");
-    if (c->bound[(size_t)layer * N + e]) { ++done; continue; }  // lives in caller memory: nothing to do
-    ++done;
+    if (c->bound[(size_t)layer * N + e]) continue;  // lives in caller memory: nothing to do
+    const int lpos = lc.find_landing(e);
+    if (lpos >= 0) {
+      record(c, layer, ADAPMOE_EV_PF_TOUCH, e, -1, lc.landing[lpos].slot);
+      continue;
+    }
     const int pos = lc.find(e);
-    if (pos >= 0) {
+    if (own < lc.cap) {
+      ++own;
+      if (pos >= 0) {
+        const int slot = lc.order[pos].slot;
+        lc.touch(pos);
+        record(c, layer, ADAPMOE_EV_PF_TOUCH, e, -1, slot);
+        continue;
+      }
+      int victim = -1, slot;
+      if ((int)lc.order.size() >= lc.cap) {
+        victim = lc.order.front().expert;
+        slot = lc.order.front().slot;
+        lc.order.erase(lc.order.begin());
+        poke_later(c, layer, victim, nullptr);
+      } else {
+        if (c->free_slots.empty()) return fail(c, ADAPMOE_ENOMEM, "no free cache slot");
+        slot = c->free_slots.back();
+        c->free_slots.pop_back();
+      }
+      int rc = start_copy(c, layer, e, slot);
+      if (rc) return rc;
+      lc.order.push_back(Entry{e, slot, true});
+      poke_later(c, layer, e, c->slots[slot].dev);
+      record(c, layer, ADAPMOE_EV_PF_LOAD, e, victim, slot);
+      continue;
+    }
+    if (!allow_landing) continue;
+    if (pos >= 0) {   // listed twice by the caller: on the GPU already
       const int slot = lc.order[pos].slot;
       lc.touch(pos);
       record(c, layer, ADAPMOE_EV_PF_TOUCH, e, -1, slot);
       continue;
     }
-    int victim = -1, slot;
-    if ((int)lc.order.size() >= lc.cap) {
-      victim = lc.order.front().expert;
-      slot = lc.order.front().slot;
-      lc.order.erase(lc.order.begin());
-      poke_later(c, layer, victim, nullptr);
-    } else {
-      if (c->free_slots.empty()) return fail(c, ADAPMOE_ENOMEM, "no free cache slot");
-      slot = c->free_slots.back();
-      c->free_slots.pop_back();
-    }
+    if ((int)lc.landing.size() >= 2 * c->cfg.max_B) continue;   // one step cannot require more than 2 per token
+    if (c->free_slots.empty()) return fail(c, ADAPMOE_ENOMEM, "no spare slot for a prefetched expert");
+    const int slot = c->free_slots.back();
+    c->free_slots.pop_back();
     int rc = start_copy(c, layer, e, slot);
-    if (rc) return rc;
-    lc.order.push_back(Entry{e, slot, true});
+    if (rc) {
+      c->free_slots.push_back(slot);
+      return rc;
+    }
+    lc.landing.push_back(Entry{e, slot, true});
     poke_later(c, layer, e, c->slots[slot].dev);
-    record(c, layer, ADAPMOE_EV_PF_LOAD, e, victim, slot);
+    record(c, layer, ADAPMOE_EV_PF_LAND, e, -1, slot);
   }
   return ADAPMOE_OK;
 }
@@ -432,7 +499,7 @@ int launch_ffn(adapmoe_ctx* c, int layer, const void* x, int B, const int32_t* i
       q.a_lo = c->d_alo;
       q.two_terms = c->lc.batch_two_terms;
       HIPCHK(c, launch_bucket_gather(q, s, timed_cfg(c, 3).timing));
-      HIPCHK(c, launch_grouped_gateup(q, s, timed_cfg(c, 4).timing));
+      HIPCHK(c, launch_grouped_gateup(q, c->lc.batch_direct != 0, s, timed_cfg(c, 4).timing));
       HIPCHK(c, launch_grouped_down(q, c->lc.batch_two_terms != 0, s, timed_cfg(c, 5).timing));
     }
     c->ctr.ffn_launches++;
@@ -465,7 +532,13 @@ int launch_ffn(adapmoe_ctx* c, int layer, const void* x, int B, const int32_t* i
     const LaunchCfg lc = timed_cfg(c, 1);
     p.dyn_ctr = nullptr;
     p.dyn_clear = dyn ? c->d_dyn : nullptr;
-    HIPCHK(c, qb ? launch_ffn_down_quant(p, qb, lc, s) : launch_ffn_down(p, c->cfg.dtype, lc, s));
+    const hipError_t de = qb ? launch_ffn_down_quant(p, qb, lc, s) : launch_ffn_down(p, c->cfg.dtype, lc, s);
+    if (de != hipSuccess) {
+      // the gate/up kernel has drawn from its row counters and the kernel that clears them did not
+      // start: clear them here, or the next gate/up launch would skip its pool rows
+      if (dyn) (void)hipMemsetAsync(c->d_dyn, 0, (size_t)c->cfg.max_B * kDynQueues * kDynStride * sizeof(unsigned), s);
+      return fail(c, ADAPMOE_EHIP, std::string("down GEMV launch: ") + hipGetErrorString(de));
+    }
   }
   c->ctr.ffn_launches++;
   return ADAPMOE_OK;
@@ -564,6 +637,183 @@ int launch_gate_both(adapmoe_ctx* c, int layer, const void* x, int B, int32_t* i
   const KernelTiming kt = timed_cfg(c, 2).timing;
   if (norm && depth == 0) HIPCHK(c, launch_norm_gate(g, *norm, c->bf16_act, s, kt));   // one router: normalise and gate in one launch
   else HIPCHK(c, launch_gate(g, c->bf16_act, 1 + depth, s, kt));
+  return ADAPMOE_OK;
+}
+
+// Demand phase of one layer step (Alg.1: E.in_GPU are computed as they are, E.in_CPU go to the
+// transfer queue): for every token, in token order, its k[b] required experts in rank order are
+// looked up in the layer's LRU set and landing buffers; missing ones are copied on the side stream
+// (evicting the least recently used entry, or into a spare slot when the layer owns none).  Leaves
+// in c->step what the FFN has to wait for and what is released after it.  `resolved`: also write the
+// experts' addresses into the per-token records the gate left for the FFN kernels.
+int demand_tokens(adapmoe_ctx* c, int layer, const int32_t* ids, const int32_t* kk, int B, bool resolved) {
+  const int N = c->cfg.N;
+  LayerCache& lc = c->layers[layer];
+  StepState& st = c->step;
+  st.reset(layer);
+  st.k0 = kk[0];
+  auto& used_slots = st.used_slots;
+  auto& transient = st.transient;
+  auto& demanded = st.demanded;
+  int* rank_slot = st.rank_slot;
+  auto resolve = [&](int b, int j, const void* value) {
+    if (resolved) poke_resolved(c, b, j, value);
+  };
+  int rc;
+  for (int b = 0; b < B; ++b) {
+    for (int j = 0; j < kk[b] && j < 2; ++j) {
+      const int e = ids[2 * b + j];
+      if (e < 0 || e >= N) return fail(c, ADAPMOE_EINVAL, "demand: expert id out of range");
+      if (c->bound[(size_t)layer * N + e]) {
+        record(c, layer, ADAPMOE_EV_HIT, e, -1, -2);
+        resolve(b, j, c->bound[(size_t)layer * N + e]);
+        continue;
+      }
+      bool is_transient = false;
+      for (auto& t : transient) is_transient |= (t.first == e);
+      const int pos = lc.find(e);
+      if (pos >= 0) {
+        Entry& en = lc.order[pos];
+        record(c, layer, en.by_prefetch ? ADAPMOE_EV_HIT_PF : ADAPMOE_EV_HIT, e, -1, en.slot);
+        en.by_prefetch = false;
+        used_slots.push_back(en.slot);
+        resolve(b, j, c->slots[en.slot].dev);
+        if (b == 0) rank_slot[j] = en.slot;
+        lc.touch(pos);
+        demanded.push_back(e);
+        continue;
+      }
+      const int lpos = lc.find_landing(e);
+      if (lpos >= 0) {   // prefetched into a spare slot: no load; it joins the layer's set if the layer has one
+        const Entry en = lc.landing[lpos];
+        lc.landing.erase(lc.landing.begin() + lpos);
+        int victim = -1;
+        if (lc.cap > 0) {
+          if ((int)lc.order.size() >= lc.cap) {
+            const Entry v = lc.order.front();
+            lc.order.erase(lc.order.begin());
+            victim = v.expert;
+            if (std::find(demanded.begin(), demanded.end(), victim) != demanded.end()) {
+              transient.emplace_back(victim, v.slot);   // still read by this step's FFN
+            } else {
+              poke_later(c, layer, victim, nullptr);
+              c->free_slots.push_back(v.slot);
+            }
+          }
+          lc.order.push_back(Entry{e, en.slot, false});
+          demanded.push_back(e);
+        } else {
+          transient.emplace_back(e, en.slot);
+        }
+        record(c, layer, ADAPMOE_EV_HIT_PF, e, victim, en.slot);
+        used_slots.push_back(en.slot);
+        resolve(b, j, c->slots[en.slot].dev);
+        if (b == 0) rank_slot[j] = en.slot;
+        continue;
+      }
+      if (is_transient) {  // evicted or bypassed earlier in this same step, image still in its slot
+        if (lc.cap == 0) {
+          for (auto& t : transient)
+            if (t.first == e) {
+              resolve(b, j, c->slots[t.second].dev);
+              if (b == 0) rank_slot[j] = t.second;
+            }
+          record(c, layer, ADAPMOE_EV_BYPASS, e, -1, -1);
+          continue;
+        }
+        // falls through to a regular miss below: logically it is gone
+      }
+      int victim = -1, slot = -1;
+      if (lc.cap == 0) {
+        if (c->free_slots.empty()) return fail(c, ADAPMOE_ENOMEM, "no spare slot for a bypass load");
+        slot = c->free_slots.back();
+        c->free_slots.pop_back();
+        rc = start_copy(c, layer, e, slot);
+        if (rc) return rc;
+        poke_later(c, layer, e, c->slots[slot].dev);
+        transient.emplace_back(e, slot);
+        used_slots.push_back(slot);
+        resolve(b, j, c->slots[slot].dev);
+        if (b == 0) rank_slot[j] = slot;
+        record(c, layer, ADAPMOE_EV_BYPASS, e, -1, slot);
+        continue;
+      }
+      if ((int)lc.order.size() >= lc.cap) {
+        Entry v = lc.order.front();
+        lc.order.erase(lc.order.begin());
+        victim = v.expert;
+        const bool victim_needed = std::find(demanded.begin(), demanded.end(), victim) != demanded.end();
+        if (victim_needed) {  // still read by this step's FFN: keep its image, take another slot
+          transient.emplace_back(victim, v.slot);
+          if (c->free_slots.empty()) return fail(c, ADAPMOE_ENOMEM, "no spare slot");
+          slot = c->free_slots.back();
+          c->free_slots.pop_back();
+        } else {
+          slot = v.slot;
+          poke_later(c, layer, victim, nullptr);
+        }
+      } else {
+        if (c->free_slots.empty()) return fail(c, ADAPMOE_ENOMEM, "no free cache slot");
+        slot = c->free_slots.back();
+        c->free_slots.pop_back();
+      }
+      if (is_transient) {
+        // the expert was pushed out earlier in this step and is demanded again: reuse nothing, load again
+        for (auto& t : transient)
+          if (t.first == e) t.first = -1 - e;  // its old slot is still released, but the table entry now points to the new one
+      }
+      rc = start_copy(c, layer, e, slot);
+      if (rc) return rc;
+      lc.order.push_back(Entry{e, slot, false});
+      poke_later(c, layer, e, c->slots[slot].dev);
+      used_slots.push_back(slot);
+      resolve(b, j, c->slots[slot].dev);
+      if (b == 0) rank_slot[j] = slot;
+      demanded.push_back(e);
+      record(c, layer, ADAPMOE_EV_MISS, e, victim, slot);
+    }
+  }
+  // prefetched experts that this step does not require are dropped; nothing reads them
+  for (const Entry& en : lc.landing) {
+    poke_later(c, layer, en.expert, nullptr);
+    c->free_slots.push_back(en.slot);
+  }
+  lc.landing.clear();
+  return ADAPMOE_OK;
+}
+
+// Makes `s` wait for the copies of the experts the running step reads.
+int wait_for_step_copies(adapmoe_ctx* c, hipStream_t s) {
+  for (int slot : c->step.used_slots) {
+    Slot& sl = c->slots[slot];
+    if (sl.copy_pending) {
+      HIPCHK(c, hipStreamWaitEvent(s, sl.copy_done, 0));
+      sl.copy_pending = false;
+    }
+  }
+  return ADAPMOE_OK;
+}
+
+// End of a layer step, after its FFN has been enqueued on `s`: the slots it read are marked, and
+// what the step held beyond the layer's own slots goes back to the pool.
+int finish_step(adapmoe_ctx* c, hipStream_t s) {
+  StepState& st = c->step;
+  st.open = false;
+  for (int slot : st.used_slots) {
+    Slot& sl = c->slots[slot];
+    HIPCHK(c, hipEventRecord(sl.read_done, s));
+    sl.was_read = true;
+  }
+  for (auto& t : st.transient) {
+    if (t.first >= 0) poke_later(c, st.layer, t.first, nullptr);
+    c->free_slots.push_back(t.second);
+  }
+  if (!st.transient.empty()) {
+    int rc = flush_pokes(c, s);
+    if (rc) return rc;
+  }
+  st.used_slots.clear();
+  st.transient.clear();
   return ADAPMOE_OK;
 }
 
@@ -692,12 +942,14 @@ int adapmoe_create(const adapmoe_config* cfg, adapmoe_ctx** out) {
   c->bound.assign(LN, nullptr);
   c->bound_count.assign(cfg->L, 0);
   c->layers.resize(cfg->L);
-  c->lc.gateup_blocks = env_int("ADAPMOE_GATEUP_BLOCKS", quant_bits(cfg->dtype) ? 1024 : 512);  // measured best on MI355X
-  c->lc.down_blocks = env_int("ADAPMOE_DOWN_BLOCKS", 256);
-  c->lc.batch_min = env_int("ADAPMOE_BATCH_MIN", 3);
-  c->lc.batch_two_terms = env_int("ADAPMOE_BATCH_TWO_TERMS", 0);
+  // defaults measured best on MI355X; adapmoe_set_option changes them
+  c->lc.gateup_blocks = quant_bits(cfg->dtype) ? 1024 : 512;
+  c->lc.down_blocks = 256;
+  c->lc.batch_min = 3;
+  c->lc.batch_two_terms = 0;
+  c->lc.batch_direct = 1;
   c->lc.fused_blocks = 0;
-  c->lc.dyn_pct = quant_bits(cfg->dtype) ? 0 : env_int("ADAPMOE_DYN_PCT", 20);
+  c->lc.dyn_pct = quant_bits(cfg->dtype) ? 0 : 20;
   const int B = cfg->max_B;
   bool ok = hipSetDevice(cfg->device) == hipSuccess;
   ok = ok && hipMalloc(&c->d_table, LN * sizeof(void*)) == hipSuccess;
@@ -725,20 +977,6 @@ int adapmoe_create(const adapmoe_config* cfg, adapmoe_ctx** out) {
   }
   ok = ok && hipStreamCreateWithFlags(&c->copy_stream, hipStreamNonBlocking) == hipSuccess;
   ok = ok && ffn_kernels_init(cfg->dtype) == hipSuccess;
-  if (ok && !quant_bits(cfg->dtype) && env_int("ADAPMOE_FUSED", 0) == 1) {
-    // Opt-in (ADAPMOE_FUSED=1): single-token steps run both GEMVs in one launch with a grid-wide
-    // barrier in between.  Measured slower than two launches on MI355X (114 vs 108 us per
-    // Mixtral-shaped step) even though the barrier needs no cache maintenance: every workgroup
-    // re-reads a_j past its L2, and the slowest workgroup of the first phase holds up all others.
-    int cap = 0;
-    const hipError_t fe = ffn_fused_init(cfg->dtype);
-    if (fe == hipSuccess) cap = ffn_fused_capacity(cfg->dtype, cfg->H, cfg->F, cfg->device);
-    if (getenv("ADAPMOE_VERBOSE")) fprintf(stderr, "adapmoe: fused init %s, capacity %d\n", hipGetErrorString(fe), cap);
-    if (cap > 0 && hipMalloc(&c->d_fused_counter, sizeof(unsigned)) == hipSuccess &&
-        hipMemset(c->d_fused_counter, 0, sizeof(unsigned)) == hipSuccess)
-      c->lc.fused_blocks = cap;
-    (void)hipGetLastError();  // a shape the fused kernel does not take is not an error of the context
-  }
   if (!ok) {
     adapmoe_destroy(c);
     return ADAPMOE_EHIP;
@@ -879,7 +1117,7 @@ int cache_alloc(adapmoe_ctx* c, const int32_t* slots_per_layer) {
     if (slots_per_layer[l] < 0 || slots_per_layer[l] > c->cfg.N) return fail(c, ADAPMOE_EINVAL, "cache_alloc: slots per layer must be in 0..N");
     total += slots_per_layer[l];
   }
-  total += 2 * (size_t)c->cfg.max_B;  // spare slots: what one step may read beyond the layers' own slots
+  total += 4 * (size_t)c->cfg.max_B;  // spare slots: what one step may read beyond the layers' own slots + landing buffers of the next layer
   HIPCHK(c, hipSetDevice(c->cfg.device));
   c->slots.resize(total);
   for (size_t i = 0; i < total; ++i) {
@@ -917,7 +1155,11 @@ int cache_lookup(adapmoe_ctx* c, int layer, const int32_t* ids, int n, int32_t* 
     if (e < 0 || e >= c->cfg.N) return fail(c, ADAPMOE_EINVAL, "cache_lookup: expert id out of range");
     if (c->bound[(size_t)layer * c->cfg.N + e]) { slot_out[i] = -2; continue; }
     const int pos = lc.find(e);
-    if (pos < 0) { slot_out[i] = -1; continue; }
+    if (pos < 0) {
+      const int lpos = lc.find_landing(e);   // prefetched into a landing buffer: on the GPU, outside the LRU order
+      slot_out[i] = lpos >= 0 ? lc.landing[lpos].slot : -1;
+      continue;
+    }
     slot_out[i] = lc.order[pos].slot;
     if (touch) lc.touch(pos);
   }
@@ -947,21 +1189,65 @@ int moe_expert_ffn(adapmoe_ctx* c, int layer, const void* x, int B, const int32_
   hipStream_t s = static_cast<hipStream_t>(stream);
   int rc = flush_pokes(c, s);
   if (rc) return rc;
-  // the ids are on the device: wait for every copy into this layer's slots that is still unannounced
-  for (Entry& en : c->layers[layer].order) {
-    Slot& sl = c->slots[en.slot];
+  if (c->step.open && c->step.layer == layer) {
+    // moe_demand told which experts this step reads: wait for their copies, run, end the step
+    rc = wait_for_step_copies(c, s);
+    if (rc) return rc;
+    rc = launch_ffn(c, layer, x, B, ids, w, k, y, s);
+    if (rc) return rc;
+    return finish_step(c, s);
+  }
+  // the ids are on the device only: wait for every copy into this layer's slots that is still unannounced
+  LayerCache& lc = c->layers[layer];
+  auto each_entry = [&](auto fn) -> int {
+    for (Entry& en : lc.order) { int r = fn(c->slots[en.slot]); if (r) return r; }
+    for (Entry& en : lc.landing) { int r = fn(c->slots[en.slot]); if (r) return r; }
+    return ADAPMOE_OK;
+  };
+  rc = each_entry([&](Slot& sl) -> int {
     if (sl.copy_pending) {
       HIPCHK(c, hipStreamWaitEvent(s, sl.copy_done, 0));
       sl.copy_pending = false;
     }
-  }
+    return ADAPMOE_OK;
+  });
+  if (rc) return rc;
   rc = launch_ffn(c, layer, x, B, ids, w, k, y, s);
   if (rc) return rc;
-  for (Entry& en : c->layers[layer].order) {
-    Slot& sl = c->slots[en.slot];
+  rc = each_entry([&](Slot& sl) -> int {
     HIPCHK(c, hipEventRecord(sl.read_done, s));
     sl.was_read = true;
+    return ADAPMOE_OK;
+  });
+  if (rc) return rc;
+  // this was the layer's demand: prefetched experts held outside the layer's own slots are dropped
+  for (const Entry& en : lc.landing) {
+    poke_later(c, layer, en.expert, nullptr);
+    c->free_slots.push_back(en.slot);
   }
+  if (!lc.landing.empty()) {
+    lc.landing.clear();
+    return flush_pokes(c, s);
+  }
+  return ADAPMOE_OK;
+  ABI_CATCH(c)
+}
+
+int moe_demand(adapmoe_ctx* c, int layer, const int32_t* ids_host, const int32_t* k_host, int B, int32_t* loads_out) {
+  ABI_TRY
+  if (!c || layer < 0 || layer >= c->cfg.L || !ids_host || !k_host || B < 1 || B > c->cfg.max_B)
+    return fail(c, ADAPMOE_EINVAL, "moe_demand: bad argument");
+  if (!c->cache_ready && !layer_fully_bound(c, layer)) return fail(c, ADAPMOE_ESTATE, "moe_demand: cache not allocated");
+  for (int b = 0; b < B; ++b)
+    if (k_host[b] < 1 || k_host[b] > 2) return fail(c, ADAPMOE_EINVAL, "moe_demand: k must be 1 or 2");
+  if (c->step.open) return fail(c, ADAPMOE_ESTATE, "moe_demand: the previous demand has not been followed by moe_expert_ffn");
+  const uint64_t before = c->ctr.misses + c->ctr.bypasses;
+  const int rc = demand_tokens(c, layer, ids_host, k_host, B, false);
+  if (rc) {
+    c->step.open = false;
+    return rc;
+  }
+  if (loads_out) *loads_out = (int32_t)(c->ctr.misses + c->ctr.bypasses - before);
   return ADAPMOE_OK;
   ABI_CATCH(c)
 }
@@ -970,7 +1256,7 @@ int moe_prefetch(adapmoe_ctx* c, int layer, const int32_t* ids_host, int n) {
   ABI_TRY
   if (!c || layer < 0 || layer >= c->cfg.L || !ids_host || n < 0) return fail(c, ADAPMOE_EINVAL, "moe_prefetch: bad argument");
   if (!c->cache_ready) return fail(c, ADAPMOE_ESTATE, "moe_prefetch: cache not allocated");
-  return prefetch_layer(c, layer, ids_host, n);
+  return prefetch_layer(c, layer, ids_host, n, true);
   ABI_CATCH(c)
 }
 
@@ -984,7 +1270,6 @@ int layer_step_impl(adapmoe_ctx* c, int layer, const void* x, int B, float* y, v
   if (!c || layer < 0 || layer >= c->cfg.L || !x || !y || B < 1 || B > c->cfg.max_B)
     return fail(c, ADAPMOE_EINVAL, "moe_layer_step: bad argument");
   hipStream_t s = static_cast<hipStream_t>(stream);
-  const int N = c->cfg.N;
   int32_t* d_ids = c->d_dec;
   int32_t* d_k = c->d_dec + 2 * B;
   int32_t* d_pids[3] = {c->d_dec + 3 * B, c->d_dec + 6 * B, c->d_dec + 9 * B};
@@ -998,6 +1283,11 @@ int layer_step_impl(adapmoe_ctx* c, int layer, const void* x, int B, float* y, v
   int rc = launch_gate_both(c, layer, x, B, d_ids, c->d_w, d_k, depth, d_pids, d_pk, s, c->d_res, norm);
   if (rc) return rc;
   c->ctr.tokens_gated += B;
+  if (c->dec_log && c->dec_log_pos < c->dec_log_cap) {
+    HIPCHK(c, hipMemcpyAsync(c->dec_log + (size_t)c->dec_log_pos * 6 * c->cfg.max_B, c->d_dec, (size_t)6 * B * sizeof(int32_t),
+                             hipMemcpyDeviceToDevice, s));
+    c->dec_log_pos++;
+  }
 
   if (!host_path) {  // every expert of the layer lives in HBM: residency is a device-side table lookup
     rc = flush_pokes(c, s);
@@ -1012,97 +1302,10 @@ int layer_step_impl(adapmoe_ctx* c, int layer, const void* x, int B, float* y, v
   const int32_t* ids = c->h_dec;
   const int32_t* kk = c->h_dec + 2 * B;
 
-  LayerCache& lc = c->layers[layer];
-  std::vector<int> used_slots;                       // slots the FFN of this step reads
-  std::vector<std::pair<int, int>> transient;        // (expert, slot) to drop right after the FFN
-  std::vector<int> demanded;                         // experts needed by this step so far
-  int rank_slot[2] = {-1, -1};                       // slot of token 0's expert of rank j (-1: caller memory)
-  for (int b = 0; b < B; ++b) {
+  rc = demand_tokens(c, layer, ids, kk, B, true);
+  if (rc) return rc;
+  for (int b = 0; b < B; ++b)
     if (kk[b] == 1) c->ctr.single_expert++;
-    for (int j = 0; j < kk[b] && j < 2; ++j) {
-      const int e = ids[2 * b + j];
-      if (e < 0 || e >= N) return fail(c, ADAPMOE_EINVAL, "moe_layer_step: gate produced an id out of range");
-      if (c->bound[(size_t)layer * N + e]) {
-        record(c, layer, ADAPMOE_EV_HIT, e, -1, -2);
-        poke_resolved(c, b, j, c->bound[(size_t)layer * N + e]);
-        continue;
-      }
-      bool is_transient = false;
-      for (auto& t : transient) is_transient |= (t.first == e);
-      const int pos = lc.find(e);
-      if (pos >= 0) {
-        Entry& en = lc.order[pos];
-        record(c, layer, en.by_prefetch ? ADAPMOE_EV_HIT_PF : ADAPMOE_EV_HIT, e, -1, en.slot);
-        en.by_prefetch = false;
-        used_slots.push_back(en.slot);
-        poke_resolved(c, b, j, c->slots[en.slot].dev);
-        if (b == 0) rank_slot[j] = en.slot;
-        lc.touch(pos);
-        demanded.push_back(e);
-        continue;
-      }
-      if (is_transient) {  // evicted or bypassed earlier in this same step, image still in its slot
-        if (lc.cap == 0) {
-          for (auto& t : transient)
-            if (t.first == e) {
-              poke_resolved(c, b, j, c->slots[t.second].dev);
-              if (b == 0) rank_slot[j] = t.second;
-            }
-          record(c, layer, ADAPMOE_EV_BYPASS, e, -1, -1);
-          continue;
-        }
-        // falls through to a regular miss below: logically it is gone
-      }
-      int victim = -1, slot = -1;
-      if (lc.cap == 0) {
-        if (c->free_slots.empty()) return fail(c, ADAPMOE_ENOMEM, "no spare slot for a bypass load");
-        slot = c->free_slots.back();
-        c->free_slots.pop_back();
-        rc = start_copy(c, layer, e, slot);
-        if (rc) return rc;
-        poke_later(c, layer, e, c->slots[slot].dev);
-        transient.emplace_back(e, slot);
-        used_slots.push_back(slot);
-        poke_resolved(c, b, j, c->slots[slot].dev);
-        if (b == 0) rank_slot[j] = slot;
-        record(c, layer, ADAPMOE_EV_BYPASS, e, -1, slot);
-        continue;
-      }
-      if ((int)lc.order.size() >= lc.cap) {
-        Entry v = lc.order.front();
-        lc.order.erase(lc.order.begin());
-        victim = v.expert;
-        const bool victim_needed = std::find(demanded.begin(), demanded.end(), victim) != demanded.end();
-        if (victim_needed) {  // still read by this step's FFN: keep its image, take another slot
-          transient.emplace_back(victim, v.slot);
-          if (c->free_slots.empty()) return fail(c, ADAPMOE_ENOMEM, "no spare slot");
-          slot = c->free_slots.back();
-          c->free_slots.pop_back();
-        } else {
-          slot = v.slot;
-          poke_later(c, layer, victim, nullptr);
-        }
-      } else {
-        if (c->free_slots.empty()) return fail(c, ADAPMOE_ENOMEM, "no free cache slot");
-        slot = c->free_slots.back();
-        c->free_slots.pop_back();
-      }
-      if (is_transient) {
-        // the expert was pushed out earlier in this step and is demanded again: reuse nothing, load again
-        for (auto& t : transient)
-          if (t.first == e) t.first = -1 - e;  // its old slot is still released, but the table entry now points to the new one
-      }
-      rc = start_copy(c, layer, e, slot);
-      if (rc) return rc;
-      lc.order.push_back(Entry{e, slot, false});
-      poke_later(c, layer, e, c->slots[slot].dev);
-      used_slots.push_back(slot);
-      poke_resolved(c, b, j, c->slots[slot].dev);
-      if (b == 0) rank_slot[j] = slot;
-      demanded.push_back(e);
-      record(c, layer, ADAPMOE_EV_MISS, e, victim, slot);
-    }
-  }
 
   // Predicted experts go to the transfer queue after the demanded ones (Alg.1).  Look-ahead
   // (Sec. 4.3): the layer after next is served only if nothing had to be loaded for the nearer one.
@@ -1116,7 +1319,7 @@ int layer_step_impl(adapmoe_ctx* c, int layer, const void* x, int B, float* y, v
         for (int j = 0; j < pk[b] && j < 2; ++j)
           if (std::find(r.begin(), r.end(), pids[2 * b + j]) == r.end()) r.push_back(pids[2 * b + j]);
       const uint64_t loads_before = c->ctr.prefetch_loads;
-      rc = prefetch_layer(c, target, r.data(), (int)r.size());
+      rc = prefetch_layer(c, target, r.data(), (int)r.size(), d == 1);
       if (rc) return rc;
       if (c->ctr.prefetch_loads != loads_before) break;
     }
@@ -1124,36 +1327,19 @@ int layer_step_impl(adapmoe_ctx* c, int layer, const void* x, int B, float* y, v
 
   rc = flush_pokes(c, s);
   if (rc) return rc;
+  StepState& st = c->step;
   bool tile_path = false;
   if (c->tiles > 1 && B == 1 && c->lc.fused_blocks == 0)
-    for (int slot : used_slots) tile_path |= c->slots[slot].copy_pending && c->slots[slot].tiled;
+    for (int slot : st.used_slots) tile_path |= c->slots[slot].copy_pending && c->slots[slot].tiled;
   if (tile_path) {
-    rc = launch_ffn_tiled(c, layer, x, kk[0], rank_slot, y, s);
+    rc = launch_ffn_tiled(c, layer, x, kk[0], st.rank_slot, y, s);
   } else {
-    for (int slot : used_slots) {
-      Slot& sl = c->slots[slot];
-      if (sl.copy_pending) {
-        HIPCHK(c, hipStreamWaitEvent(s, sl.copy_done, 0));
-        sl.copy_pending = false;
-      }
-    }
+    rc = wait_for_step_copies(c, s);
+    if (rc) return rc;
     rc = launch_ffn(c, layer, x, B, d_ids, c->d_w, d_k, y, s, c->d_res);
   }
   if (rc) return rc;
-  for (int slot : used_slots) {
-    Slot& sl = c->slots[slot];
-    HIPCHK(c, hipEventRecord(sl.read_done, s));
-    sl.was_read = true;
-  }
-  for (auto& t : transient) {
-    if (t.first >= 0) poke_later(c, layer, t.first, nullptr);
-    c->free_slots.push_back(t.second);
-  }
-  if (!transient.empty()) {
-    rc = flush_pokes(c, s);
-    if (rc) return rc;
-  }
-  return ADAPMOE_OK;
+  return finish_step(c, s);
 }
 
 }  // namespace
@@ -1192,7 +1378,83 @@ int moe_stack_token(adapmoe_ctx* c, int token, float* h, void* x, float* y, int 
 
 int adapmoe_set_first_layer_predictor(adapmoe_ctx* c, const void* Gpre_dev) {
   if (!c) return ADAPMOE_EINVAL;
+  // with one layer the prefetch would target the layer that is running and could evict what its FFN reads
+  if (Gpre_dev && c->cfg.L == 1) return fail(c, ADAPMOE_ESTATE, "set_first_layer_predictor: needs at least two layers");
   c->first_pred = Gpre_dev;
+  return ADAPMOE_OK;
+}
+
+int adapmoe_set_option(adapmoe_ctx* c, int option, int value) {
+  if (!c) return ADAPMOE_EINVAL;
+  const bool quant = quant_bits(c->cfg.dtype) != 0;
+  switch (option) {
+    case ADAPMOE_OPT_BATCH_MIN:
+      if (value < 1) return fail(c, ADAPMOE_EINVAL, "set_option: BATCH_MIN must be >= 1");
+      c->lc.batch_min = value;
+      return ADAPMOE_OK;
+    case ADAPMOE_OPT_BATCH_TWO_TERMS:
+      if (value != 0 && value != 1) return fail(c, ADAPMOE_EINVAL, "set_option: BATCH_TWO_TERMS is 0 or 1");
+      c->lc.batch_two_terms = value;
+      return ADAPMOE_OK;
+    case ADAPMOE_OPT_BATCH_DIRECT:
+      if (value != 0 && value != 1) return fail(c, ADAPMOE_EINVAL, "set_option: BATCH_DIRECT is 0 or 1");
+      c->lc.batch_direct = value;
+      return ADAPMOE_OK;
+    case ADAPMOE_OPT_DYN_PCT:
+      if (value < 0 || value > 100) return fail(c, ADAPMOE_EINVAL, "set_option: DYN_PCT is 0..100");
+      c->lc.dyn_pct = quant ? 0 : value;   // the quantised GEMVs have no dynamic tail
+      return ADAPMOE_OK;
+    case ADAPMOE_OPT_GATEUP_BLOCKS:
+      if (value < 1 || value > 65535) return fail(c, ADAPMOE_EINVAL, "set_option: GATEUP_BLOCKS is 1..65535");
+      c->lc.gateup_blocks = value;
+      return ADAPMOE_OK;
+    case ADAPMOE_OPT_DOWN_BLOCKS:
+      if (value < 1 || value > 65535) return fail(c, ADAPMOE_EINVAL, "set_option: DOWN_BLOCKS is 1..65535");
+      c->lc.down_blocks = value;
+      return ADAPMOE_OK;
+    case ADAPMOE_OPT_FUSED: {
+      if (value == 0) {
+        c->lc.fused_blocks = 0;
+        return ADAPMOE_OK;
+      }
+      if (value != 1) return fail(c, ADAPMOE_EINVAL, "set_option: FUSED is 0 or 1");
+      if (quant) return fail(c, ADAPMOE_ESTATE, "set_option: the fused kernel takes fp32/bf16 experts only");
+      // Single-token steps run both GEMVs in one launch with a grid-wide barrier in between.
+      // Measured slower than two launches on MI355X (114 vs 108 us per Mixtral-shaped step) even
+      // though the barrier needs no cache maintenance: every workgroup re-reads a_j past its L2,
+      // and the slowest workgroup of the first phase holds up all others.
+      HIPCHK(c, hipSetDevice(c->cfg.device));
+      int cap = 0;
+      const hipError_t fe = ffn_fused_init(c->cfg.dtype);
+      if (fe == hipSuccess) cap = ffn_fused_capacity(c->cfg.dtype, c->cfg.H, c->cfg.F, c->cfg.device);
+      if (getenv("ADAPMOE_VERBOSE")) fprintf(stderr, "adapmoe: fused init %s, capacity %d\n", hipGetErrorString(fe), cap);
+      (void)hipGetLastError();  // a shape the fused kernel does not take is not an error of the runtime
+      if (cap <= 0) return fail(c, ADAPMOE_ESTATE, "set_option: shape does not fit the fused kernel");
+      if (!c->d_fused_counter) {
+        HIPCHK(c, hipMalloc(&c->d_fused_counter, sizeof(unsigned)));
+        HIPCHK(c, hipMemset(c->d_fused_counter, 0, sizeof(unsigned)));
+        c->fused_seq = 0;
+      }
+      c->lc.fused_blocks = cap;
+      return ADAPMOE_OK;
+    }
+    default:
+      return fail(c, ADAPMOE_EINVAL, "set_option: unknown option");
+  }
+}
+
+int adapmoe_get_option(adapmoe_ctx* c, int option, int* value_out) {
+  if (!c || !value_out) return ADAPMOE_EINVAL;
+  switch (option) {
+    case ADAPMOE_OPT_BATCH_MIN: *value_out = c->lc.batch_min; break;
+    case ADAPMOE_OPT_BATCH_TWO_TERMS: *value_out = c->lc.batch_two_terms; break;
+    case ADAPMOE_OPT_BATCH_DIRECT: *value_out = c->lc.batch_direct; break;
+    case ADAPMOE_OPT_DYN_PCT: *value_out = c->lc.dyn_pct; break;
+    case ADAPMOE_OPT_GATEUP_BLOCKS: *value_out = c->lc.gateup_blocks; break;
+    case ADAPMOE_OPT_DOWN_BLOCKS: *value_out = c->lc.down_blocks; break;
+    case ADAPMOE_OPT_FUSED: *value_out = c->lc.fused_blocks > 0 ? 1 : 0; break;
+    default: return fail(c, ADAPMOE_EINVAL, "get_option: unknown option");
+  }
   return ADAPMOE_OK;
 }
 
@@ -1248,6 +1510,14 @@ int adapmoe_last_decision(adapmoe_ctx* c, int32_t* ids, int32_t* k, int32_t* pre
   return ADAPMOE_OK;
 }
 
+int adapmoe_set_decision_log(adapmoe_ctx* c, int32_t* log_dev, int capacity) {
+  if (!c || capacity < 0 || (log_dev && capacity < 1)) return fail(c, ADAPMOE_EINVAL, "set_decision_log: bad argument");
+  c->dec_log = log_dev;
+  c->dec_log_cap = log_dev ? capacity : 0;
+  c->dec_log_pos = 0;
+  return ADAPMOE_OK;
+}
+
 int adapmoe_check(adapmoe_ctx* c, void* stream) {
   if (!c) return ADAPMOE_EINVAL;
   HIPCHK(c, hipStreamSynchronize(static_cast<hipStream_t>(stream)));
@@ -1257,7 +1527,7 @@ int adapmoe_check(adapmoe_ctx* c, void* stream) {
   if (flags) {
     HIPCHK(c, hipMemset(c->d_err, 0, sizeof(int32_t)));
     if (flags & 4) return fail(c, ADAPMOE_EHIP, "fused FFN kernel: grid barrier timed out (device shared with another long-running kernel?)");
-    if (flags & 2) return fail(c, ADAPMOE_EINVAL, "expert FFN met an expert id out of range");
+    if (flags & 2) return fail(c, ADAPMOE_EINVAL, "expert FFN met an expert id out of range (or the same expert twice for one token)");
     return fail(c, ADAPMOE_ENORES, "expert FFN met a non-resident expert");
   }
   return ADAPMOE_OK;

@@ -15,7 +15,6 @@
 //
 // Operand order: for reduction step s (32 elements) lane l = 16 q + n holds the
 // 8 elements k = 32 s + 8 q + i of token column n.
-#include <cstdlib>
 #include "../../include/adapmoe.h"
 #include "stream_parts.h"
 
@@ -50,12 +49,15 @@ __global__ __launch_bounds__(kBThreads) void bucket_gather_kernel(BatchArgs p) {
     if (b < p.B) {
       int kk = p.k[b];
       const int e_in = p.ids[2 * b + j];   // read together with k, not after it
+      const int e_other = p.ids[2 * b + (j ^ 1)];
       const float w_in = p.w[2 * b + j];
       kk = kk < 1 ? 1 : (kk > 2 ? 2 : kk);
       if (j < kk) {
         e = e_in;
         w = w_in;
-        if (e < 0 || e >= p.N) {
+        // a bucket has room for one pair per token: the same expert twice for one token is not a
+        // gate decision and would overflow it, so the second pair is dropped and flagged
+        if (e < 0 || e >= p.N || (j == 1 && e == e_other)) {
           e = -1;
           if (blockIdx.x == 0 && blockIdx.y == 0) atomicOr(p.err, 2);
         }
@@ -322,21 +324,15 @@ hipError_t batched_kernels_init() {
   return big_lds(grouped_down_mfma_kernel<kDownKS, 1, 8, 1>);
 }
 
-static int env_flag(const char* name, int dflt) {
-  const char* v = getenv(name);
-  return (v && *v) ? atoi(v) : dflt;
-}
-
 hipError_t launch_bucket_gather(const BatchArgs& p, hipStream_t s, const KernelTiming& t) {
   dim3 grid((p.H / 32 + 3) / 4, p.N), block(kBThreads);
   launch_kernel(bucket_gather_kernel, grid, block, 0, s, t, p);
   return hipGetLastError();
 }
 
-hipError_t launch_grouped_gateup(const BatchArgs& p, hipStream_t s, const KernelTiming& t) {
+hipError_t launch_grouped_gateup(const BatchArgs& p, bool direct, hipStream_t s, const KernelTiming& t) {
   // gate/up: every wavefront loads its own operand vectors (no workgroup barriers), measured 10 %
-  // faster than staging them per workgroup; ADAPMOE_BDIRECT=0 selects the staged variant
-  static const int direct = env_flag("ADAPMOE_BDIRECT", 1);
+  // faster than staging them per workgroup (direct = false selects the staged variant)
   dim3 grid(p.F / (16 * kBWaves), p.N), block(kBThreads);
   if (direct) {
     constexpr size_t lds = grouped_lds_bytes<kGateUpKS, 2, 1, kBWaves, 0>();

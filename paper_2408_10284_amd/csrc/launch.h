@@ -126,6 +126,7 @@ struct LaunchCfg {
   int batch_two_terms;  // batched path: intermediate activation as hi + lo bfloat16 (1) or bfloat16 only (0)
   int fused_blocks;   // workgroups of the fused single-token FFN kernel (0 = fused path off)
   int dyn_pct;        // percent of the row passes of the GEMV kernels that are scheduled dynamically (0 = none)
+  int batch_direct;   // batched gate/up GEMM: token operand loaded per wavefront (1) or staged per workgroup (0)
   KernelTiming timing;  // set for one launch when the context is profiling
 };
 
@@ -142,7 +143,7 @@ hipError_t launch_ffn_gateup_quant(const FfnArgs& p, int bits, const LaunchCfg& 
 hipError_t launch_ffn_down_quant(const FfnArgs& p, int bits, const LaunchCfg& lc, hipStream_t s);
 hipError_t batched_kernels_init();
 hipError_t launch_bucket_gather(const BatchArgs& p, hipStream_t s, const KernelTiming& t = KernelTiming{});
-hipError_t launch_grouped_gateup(const BatchArgs& p, hipStream_t s, const KernelTiming& t = KernelTiming{});
+hipError_t launch_grouped_gateup(const BatchArgs& p, bool direct, hipStream_t s, const KernelTiming& t = KernelTiming{});
 hipError_t launch_grouped_down(const BatchArgs& p, bool two_terms, hipStream_t s, const KernelTiming& t = KernelTiming{});
 hipError_t launch_residual_rmsnorm(float* h, const float* y, float gamma, void* x, bool bf16, int B, int H, hipStream_t s);
 

@@ -80,3 +80,32 @@ def rel_err_per_token(y, ref):
     y = np.asarray(y, dtype=np.float64)
     ref = np.asarray(ref, dtype=np.float64)
     return np.max(np.abs(y - ref), axis=-1) / np.max(np.abs(ref), axis=-1)
+
+
+def elementwise_violation(y, ref, tol):
+    """Largest |y_i - ref_i| / (tol*|ref_i| + tol*rms(ref)) over all elements: <= 1 means every element is
+    within tol of its reference value relative to its own size plus the same fraction of the row's rms
+    (a purely relative bound is meaningless for the elements of a row that happen to be near zero)."""
+    y = np.atleast_2d(np.asarray(y, dtype=np.float64))
+    ref = np.atleast_2d(np.asarray(ref, dtype=np.float64))
+    rms = np.sqrt(np.mean(ref * ref, axis=-1, keepdims=True))
+    return float(np.max(np.abs(y - ref) / (tol * np.abs(ref) + tol * rms + 1e-300)))
+
+
+def elementwise_err_with_floor(y, ref, floor=1e-3):
+    """max_i |y_i - ref_i| / max(|ref_i|, floor * rms(ref)) per row: the element-wise relative error with
+    small reference values floored at a fraction of the row's rms (reported next to the max-norm figure)."""
+    y = np.atleast_2d(np.asarray(y, dtype=np.float64))
+    ref = np.atleast_2d(np.asarray(ref, dtype=np.float64))
+    rms = np.sqrt(np.mean(ref * ref, axis=-1, keepdims=True))
+    return np.max(np.abs(y - ref) / np.maximum(np.abs(ref), floor * rms + 1e-300), axis=-1)
+
+
+def check_outputs(y, ref, tol, what=""):
+    """The floating-point bar in both forms: per token max-norm error <= tol, and every element within
+    tol*|ref_i| + tol*rms(ref).  Returns (largest max-norm error, largest floored element-wise error)."""
+    worst = float(np.max(rel_err_per_token(np.atleast_2d(y), np.atleast_2d(ref))))
+    assert worst <= tol, (what, worst)
+    v = elementwise_violation(y, ref, tol)
+    assert v <= 1.0, (what, "element-wise bound exceeded by a factor", v)
+    return worst, float(np.max(elementwise_err_with_floor(y, ref)))

@@ -196,16 +196,12 @@ def test_two_contexts_are_independent():
 def test_dynamic_tail_with_odd_grids(blocks, pct):
     """The gate/up kernel's dynamic tail must cover every row exactly once for any grid size and pool share
     (grids that are no multiple of 8 workgroups, fewer workgroups than queues, everything in the pool)."""
-    import os
     shape = synth.MoEShape(H=4096, F=1536, N=4, L=1, dtype="bf16")     # compile-time row length, 2 F no multiple of most grids
-    os.environ["ADAPMOE_GATEUP_BLOCKS"] = str(blocks)
-    os.environ["ADAPMOE_DYN_PCT"] = str(pct)
+    ls = GpuLayerSet(shape, seed=51, max_B=3, taus=[0.3])
     try:
-        ls = GpuLayerSet(shape, seed=51, max_B=3, taus=[0.3])
-    finally:
-        del os.environ["ADAPMOE_GATEUP_BLOCKS"]
-        del os.environ["ADAPMOE_DYN_PCT"]
-    try:
+        B.adapmoe_set_option(ls.ctx, B.OPT_GATEUP_BLOCKS, blocks)
+        B.adapmoe_set_option(ls.ctx, B.OPT_DYN_PCT, pct)
+        assert B.adapmoe_get_option(ls.ctx, B.OPT_GATEUP_BLOCKS) == blocks and B.adapmoe_get_option(ls.ctx, B.OPT_DYN_PCT) == pct
         X = synth.ar1_tokens(9, shape.H, 0.5, seed=52, dtype="bf16")
         g = run_gate(ls, 0, X)
         for rep in range(3):      # repeated launches: the counters are cleared in between by the down kernel

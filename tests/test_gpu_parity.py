@@ -10,7 +10,7 @@ from oracle import stack as OS
 from paper_2408_10284_amd import binding as B
 from paper_2408_10284_amd import synth
 
-from gpu_helpers import GpuLayerSet, rel_err_per_token, to_dev_act
+from gpu_helpers import GpuLayerSet, check_outputs, rel_err_per_token, to_dev_act
 
 pytestmark = pytest.mark.gpu
 
@@ -39,9 +39,10 @@ def run_gate(ls, layer, X, with_pred=False):
     return out
 
 
-def check_gate(got_ids, got_k, got_w, ref, tau, tol_w):
+def check_gate(got_ids, got_k, got_w, ref, tau, tol_w, max_tied=1):
     clear_ids = (ref["gap23"] > TIE_GAP) & (ref["gap12"] > TIE_GAP)
-    assert clear_ids.mean() > 0.9
+    assert (~clear_ids).sum() <= max_tied, f"{(~clear_ids).sum()} tokens with logits closer than {TIE_GAP}: pick another seed"
+
     np.testing.assert_array_equal(got_ids[clear_ids], ref["ids"][clear_ids])
     clear_k = clear_ids & (np.abs(ref["v"] - tau) > BAND)
     np.testing.assert_array_equal(got_k[clear_k], ref["k"][clear_k])
@@ -87,8 +88,7 @@ def test_tiny_fp32_gate_and_ffn(tiny, tau):
     # expert outputs are compared on the GPU's own decision so that a token in the
     # exclusion band still checks the FFN arithmetic
     Yref = OE.moe_block_rows(X, tiny.experts_f32[0], g["ids"], g["w"].astype(np.float64), g["k"])
-    err = rel_err_per_token(y, Yref)
-    assert err.max() <= TOL["f32"], err.max()
+    check_outputs(y, Yref, TOL["f32"], "tiny fp32")
     assert ok.sum() >= 60
 
 
@@ -157,8 +157,7 @@ def test_shapes_gate_and_ffn(dtype, H, F, N):
         check_gate(g["pids"], g["pk"], None, refp, 0.35, 1e-5)
         y = run_ffn(ls, 0, g)
         Yref = OE.moe_block_rows(X, ls.experts_f32[0], g["ids"], g["w"].astype(np.float64), g["k"])
-        err = rel_err_per_token(y, Yref)
-        assert err.max() <= TOL[dtype], err.max()
+        check_outputs(y, Yref, TOL[dtype], f"{dtype} {H}x{F}")
         # last layer has no successor: empty prediction
         g1 = run_gate(ls, 1, X, with_pred=True)
         assert np.all(g1["pk"] == 0)
@@ -210,7 +209,11 @@ def _replay_trace(slots, decisions, wrap=False):
 @pytest.mark.parametrize("dtype,slots", [("bf16", [2, 3, 1, 0]), ("bf16", [8, 8, 8, 8]), ("bf16", [1, 1, 1, 1]), ("bf16", [0, 2, 0, 4]),
                                          ("int4g64", [2, 3, 1, 0]), ("int4g64", [4, 4, 4, 4]), ("int2g64", [2, 3, 1, 0])])
 def test_offloaded_stack_trace_and_outputs(dtype, slots):
-    _offloaded_stack(dtype, slots, H=512, F=1024, tiles=0)
+    c = _offloaded_stack(dtype, slots, H=512, F=1024, tiles=0)
+    if 0 in slots or 1 in slots:
+        # a layer with no slot (or one slot and two predictions) still receives its prefetched experts
+        # (landing buffers, Sec. 4.4.2: the on-demand-load model credits a correct prefetch at every cache size)
+        assert c["prefetch_landed"] > 0 and c["hits_after_prefetch"] > 0
 
 
 @pytest.mark.parametrize("dtype,slots,tiles", [("bf16", [2, 3, 1, 0], 4), ("bf16", [1, 1, 1, 1], 3), ("f32", [2, 0, 3, 1], 8),
@@ -299,7 +302,8 @@ def _offloaded_stack(dtype, slots, H, F, tiles, first_pred=False):
         # residency reported by the library equals the checker's sets
         for l in range(shape.L):
             res = [e for e in range(shape.N) if B.cache_lookup(ls.ctx, l, [e])[0] >= 0]
-            assert sorted(res) == sorted(sim.resident(l))
+            assert sorted(res) == sorted(sim.resident(l) + sim.landed(l))
+        assert c["prefetch_landed"] == s["prefetch_landed"]
         return c
     finally:
         ls.close()
@@ -384,12 +388,10 @@ def test_mixtral_layer_full_size():
             B.moe_layer_step(ls.ctx, 0, g["x_dev"][t:t + 1], 1, y[t:t + 1])
         B.adapmoe_check(ls.ctx)
         yh = y.cpu().numpy()
-        sample = np.arange(0, 256, 8)
-        both = np.concatenate([sample, np.nonzero(ref["k"] == 1)[0][:4]])   # make sure k == 1 tokens are in
-        Yref = OE.moe_block_rows(X[both], ls.experts_f32[0], g["ids"][both], g["w"][both].astype(np.float64), g["k"][both])
-        err = rel_err_per_token(yh[both], Yref)
-        print(f"max rel err {err.max():.3e}")
-        assert err.max() <= TOL["bf16"]
+        # every one of the 256 tokens against the checker (evaluated expert by expert over the rows that use it)
+        Yref = OE.moe_block_rows(X, ls.experts_f32[0], g["ids"], g["w"].astype(np.float64), g["k"])
+        worst, worst_elem = check_outputs(yh, Yref, TOL["bf16"], "mixtral layer bf16")
+        print(f"max rel err over 256 tokens: {worst:.3e} (max-norm), {worst_elem:.3e} (element-wise, floor 1e-3 rms)")
         assert np.all(np.isfinite(yh)) and np.all(np.abs(yh).max(axis=1) > 0)
         # the same shape through the batched path (16 tokens per call, grouped GEMM on the matrix cores), the
         # launch configuration of the batched benchmark: sampled tokens against the checker, all 16 against
@@ -399,12 +401,11 @@ def test_mixtral_layer_full_size():
         B.moe_layer_step(ls.ctx, 0, g["x_dev"][0:16], 16, y16)
         B.adapmoe_check(ls.ctx)
         y16h = y16.cpu().numpy()
-        pick = np.array([0, 7, 15])
-        err16 = rel_err_per_token(y16h[pick], OE.moe_block_rows(X[pick], ls.experts_f32[0], g["ids"][pick],
-                                                               g["w"][pick].astype(np.float64), g["k"][pick]))
+        e16, e16_elem = check_outputs(y16h, Yref[:16], TOL["bf16"], "mixtral layer bf16, 16 tokens per call")
         drift = rel_err_per_token(y16h, yh[:16])
-        print(f"batched: max rel err {err16.max():.3e}, against the single-token path {drift.max():.3e}")
-        assert err16.max() <= TOL["bf16"] and drift.max() <= 1e-2
+        print(f"batched: max rel err {e16:.3e} (max-norm), {e16_elem:.3e} (element-wise, floor 1e-3 rms), "
+              f"against the single-token path {drift.max():.3e}")
+        assert drift.max() <= 1e-2
         assert B.adapmoe_counters(ls.ctx)["ffn_launches"] == c0["ffn_launches"] + 1
     finally:
         ls.close()
@@ -461,12 +462,13 @@ def test_mixtral_layer_full_size_quantised(dtype):
                 if e in ids_h[t, :k_h[t]]:
                     outs[(t, e)] = OE.expert_ffn(X[t].astype(np.float64), W1, W3, W2)
             del W1, W3, W2, mats
-        worst = 0.0
+        worst = worst_elem = 0.0
         for t in sample:
             yref = sum(np.float64(w_h[t, j]) * outs[(t, int(ids_h[t, j]))] for j in range(k_h[t]))
-            worst = max(worst, float(rel_err_per_token(yh[t], yref)))
-        print(f"{dtype}: sampled tokens {sample}, experts decoded {need}, max rel err {worst:.3e}")
-        assert worst <= TOL[dtype]
+            a, b = check_outputs(yh[t], yref, TOL[dtype], f"{dtype} token {t}")
+            worst, worst_elem = max(worst, a), max(worst_elem, b)
+        print(f"{dtype}: sampled tokens {sample}, experts decoded {need}, max rel err {worst:.3e} (max-norm), "
+              f"{worst_elem:.3e} (element-wise, floor 1e-3 rms)")
     finally:
         torch.cuda.synchronize()
         B.adapmoe_destroy(ctx)
@@ -485,16 +487,12 @@ def test_mixtral_layer_full_size_quantised(dtype):
 ])
 def test_batched_path(H, F, N, Bt, tau, two_terms):
     """Several tokens per call: grouped GEMM on the matrix cores.  By default the intermediate
-    activation is rounded to bfloat16 before the down GEMM (as a bf16 model does); with
-    ADAPMOE_BATCH_TWO_TERMS=1 it is carried as hi + lo and matches the per-token path to 1e-4."""
-    import os
+    activation is rounded to bfloat16 before the down GEMM (as a bf16 model does); with the option
+    BATCH_TWO_TERMS it is carried as hi + lo and matches the per-token path to 1e-4."""
     shape = synth.MoEShape(H=H, F=F, N=N, L=1, dtype="bf16")
-    os.environ["ADAPMOE_BATCH_TWO_TERMS"] = str(two_terms)
+    ls = GpuLayerSet(shape, seed=7, max_B=Bt, taus=[tau])
     try:
-        ls = GpuLayerSet(shape, seed=7, max_B=Bt, taus=[tau])
-    finally:
-        del os.environ["ADAPMOE_BATCH_TWO_TERMS"]
-    try:
+        B.adapmoe_set_option(ls.ctx, B.OPT_BATCH_TWO_TERMS, two_terms)
         X = synth.ar1_tokens(Bt, H, 0.5, seed=11, dtype="bf16")
         g = run_gate(ls, 0, X)
         ref = OG.gate_batch(X, ls.routers_f32[0], np.float32(tau))
@@ -502,7 +500,7 @@ def test_batched_path(H, F, N, Bt, tau, two_terms):
         y = run_ffn(ls, 0, g)                     # one call with Bt tokens -> batched kernels
         Yref = OE.moe_block_rows(X, ls.experts_f32[0], g["ids"], g["w"].astype(np.float64), g["k"])
         err = rel_err_per_token(y, Yref)
-        assert err.max() <= TOL["bf16"], err.max()
+        check_outputs(y, Yref, TOL["bf16"], "batched path")
         y1 = torch.empty((Bt, H), dtype=torch.float32, device="cuda")
         for t in range(Bt):
             B.moe_expert_ffn(ls.ctx, 0, g["x_dev"][t:t + 1], 1, g["ids_dev"][t:t + 1], g["w_dev"][t:t + 1], g["k_dev"][t:t + 1], y1[t:t + 1])
@@ -696,22 +694,18 @@ def test_free_running_stack_against_free_running_checker(dtype):
 
 @pytest.mark.parametrize("dtype,H,F", [("bf16", 4096, 3584), ("bf16", 4096, 4096), ("f32", 2048, 1792)])
 def test_fused_single_token_kernel_equals_two_kernel_path(dtype, H, F):
-    """With ADAPMOE_FUSED=1, moe_layer_step with one token runs gate/up and down in
+    """With the option FUSED, moe_layer_step with one token runs gate/up and down in
     one launch (grid-wide barrier in between, the intermediate vector crossing it through
     device-coherent accesses); the sums are taken in the same order as in the two-kernel
     path, so the outputs are bit-identical."""
-    import os
     shape = synth.MoEShape(H=H, F=F, N=8, L=1, dtype=dtype)
-    os.environ["ADAPMOE_FUSED"] = "1"      # the fused kernel is opt-in (read when the context is created)
-    try:
-        ls = GpuLayerSet(shape, seed=2, max_B=1, taus=[0.3])
-    finally:
-        del os.environ["ADAPMOE_FUSED"]
+    ls = GpuLayerSet(shape, seed=2, max_B=1, taus=[0.3])
     try:
         X = synth.ar1_tokens(12, H, 0.8, seed=6, dtype=dtype)
         g = run_gate(ls, 0, X)
         assert 2 in g["k"]
         y_two = run_ffn(ls, 0, g)
+        B.adapmoe_set_option(ls.ctx, B.OPT_FUSED, 1)      # the fused kernel is opt-in
         y = torch.empty((12, H), dtype=torch.float32, device="cuda")
         c0 = B.adapmoe_counters(ls.ctx)
         for rep in range(3):        # repeated launches: the barrier counter keeps growing
@@ -760,7 +754,8 @@ def test_offloaded_steps_with_several_tokens(Bt, slots, depth):
                 torch.cuda.synchronize()
                 ids = np.array(ids).reshape(Bt, 2)
                 for b in range(Bt):
-                    sim.demand(t, l, ids[b], k[b])
+                    sim.demand(t, l, ids[b], k[b], release=False)
+                sim.release_landing(l)
                 ahead = []
                 for d in range(1, depth + 1):
                     if l + d >= shape.L:

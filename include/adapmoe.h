@@ -229,6 +229,23 @@ int moe_expert_ffn(adapmoe_ctx* ctx, int layer, const void* x_dev, int B,
  * the predicted experts and moe_expert_ffn() in one. */
 int moe_demand(adapmoe_ctx* ctx, int layer, const int32_t* ids_host, const int32_t* k_host, int B, int32_t* loads_out);
 
+/* moe_expert_ffn for callers that cannot allocate: code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc.  No context: the shape (H, F, N, dtype as in
+ * adapmoe_config) and the residency table - table_dev, a device array of N image base pointers,
+ * NULL = expert absent - are arguments; x, ids, w, k, y as for moe_expert_ffn, on the current
+ * device.  The intermediate vectors live in a fixed device array inside the library (640 KiB per
+ * GPU, held until the process ends), so the call is limited to B <= 4 tokens and F <= 16384 and
+ * returns ADAPMOE_EINVAL beyond that; it always takes the weight-streaming (GEMV) kernels, also
+ * where moe_expert_ffn would take the batched path.  It calls no hipMalloc, hipFree or other
+ * allocating routine.  The first call on a GPU looks the array up and prepares the kernels
+ * (synchronous; make it outside a capture).  err_dev: optional device word that receives the
+ * flags (bit 0: an activated expert was absent and contributed nothing, bit 1: id out of range);
+ * NULL = flags dropped.  All calls on one GPU share the array, whatever their stream: calls that
+ * overlap on a GPU race; order them on one stream or with events. */
+int moe_expert_ffn_static(int32_t H, int32_t F, int32_t N, int32_t dtype, const void* const* table_dev,
+                          const void* x_dev, int B, const int32_t* ids_dev, const float* w_dev, const int32_t* k_dev,
+                          float* y_dev, int32_t* err_dev, void* stream);
+
 /* Prefetch for `layer` (Sec. 4.3), ids in rank order.  At most as many of them as the layer
  * owns slots go to its LRU set: resident -> most recently used; absent -> evict LRU if
  * full, start an asynchronous copy on the library's side stream.  The others are copied

@@ -65,6 +65,7 @@ _SIGS = {
     "moe_expert_ffn": (C.c_int, [_P, C.c_int, _P, C.c_int, _P, _P, _P, _P, _P]),
     "moe_demand": (C.c_int, [_P, C.c_int, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_int, C.POINTER(C.c_int32)]),
     "moe_prefetch": (C.c_int, [_P, C.c_int, C.POINTER(C.c_int32), C.c_int]),
+    "moe_expert_ffn_static": (C.c_int, [C.c_int32, C.c_int32, C.c_int32, C.c_int32, _P, _P, C.c_int, _P, _P, _P, _P, _P, _P]),
     "adapmoe_set_option": (C.c_int, [_P, C.c_int, C.c_int]),
     "adapmoe_get_option": (C.c_int, [_P, C.c_int, C.POINTER(C.c_int)]),
     "moe_layer_step": (C.c_int, [_P, C.c_int, _P, C.c_int, _P, _P]),
@@ -300,6 +301,20 @@ def moe_demand(ctx, layer, ids, k):
     loads = C.c_int32()
     _chk(ctx, load().moe_demand(ctx, layer, a, kk, len(k), C.byref(loads)))
     return loads.value
+
+
+def moe_expert_ffn_static(H, F, N, dtype, table, x, B, ids, w, k, y, err=None, stream=None):
+    esz = 4 if dtype == F32 else 2
+    _need("table", table, N * 8, "dev")
+    if 1 <= B <= 4:
+        _need("x", x, B * H * esz, "dev")
+        _need("y", y, B * H * 4, "dev")
+        _need("ids", ids, 2 * B * 4, "dev")
+        _need("w", w, 2 * B * 4, "dev")
+        _need("k", k, B * 4, "dev")
+    _need("err", err, 4, "dev")
+    _chk(None, load().moe_expert_ffn_static(H, F, N, dtype, _ptr(table), _ptr(x), B, _ptr(ids), _ptr(w), _ptr(k), _ptr(y),
+                                           _ptr(err), _stream(stream)))
 
 
 def moe_prefetch(ctx, layer, ids):

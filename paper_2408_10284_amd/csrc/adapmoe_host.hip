@@ -821,6 +821,56 @@ bool layer_fully_bound(const adapmoe_ctx* c, int layer) { return c->bound_count[
 
 }  // namespace
 
+// ---- expert FFN without any allocation ------------------------------------------------------
+
+// Scratch memory of moe_expert_ffn_static: the intermediate vectors a_j of up to kStaticMaxB tokens,
+// the row counters of the gate/up GEMV's dynamic tail and a flag word, in a fixed array that every
+// GPU the library runs on holds until the process ends.
+constexpr int kStaticMaxB = 4;
+constexpr size_t kStaticMaxStride = 16384;   // floats per (token, expert) of the a_j scratch: F <= 16384
+constexpr size_t kStaticABytes = (size_t)kStaticMaxB * 2 * kStaticMaxStride * sizeof(float);
+constexpr size_t kStaticDynBytes = (size_t)kStaticMaxB * adapmoe::kDynQueues * adapmoe::kDynStride * sizeof(unsigned);
+constexpr size_t kStaticScratchBytes = kStaticABytes + kStaticDynBytes + 256;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+
+constexpr int kMaxDevices = 64;
+std::mutex g_static_mu;
+void* g_static_ptr[kMaxDevices] = {};        // device address of `scratch` on each GPU (each holds its own copy)
+unsigned g_static_dtypes[kMaxDevices] = {};  // storage types whose kernels have been prepared on the GPU
+
+// Address of this GPU's copy of `scratch`, looked up once per device with that device current.
+// The array's name is only a handle on the host: kernels, memsets and copies get this address.
+int static_scratch(int dev, int dtype, char** out) {
+  std::lock_guard<std::mutex> lk(g_static_mu);
+  if (!g_static_ptr[dev]) {
+    void* ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+      (void)hipGetLastError();
+      return ADAPMOE_EHIP;
+    }
+    // the row counters must be zero when a gate/up launch starts (a fresh array is, and every down
+    // launch leaves them so; this covers a process that reloads the library's code object)
+    if (hipMemset(static_cast<char*>(ptr) + kStaticABytes, 0, kStaticDynBytes + 256) != hipSuccess) {
+      (void)hipGetLastError();
+      return ADAPMOE_EHIP;
+    }
+    g_static_ptr[dev] = ptr;
+  }
+  if (!(g_static_dtypes[dev] & (1u << dtype))) {
+    if (ffn_kernels_init(dtype) != hipSuccess) {
+      (void)hipGetLastError();
+      return ADAPMOE_EHIP;
+    }
+    g_static_dtypes[dev] |= 1u << dtype;
+  }
+  *out = static_cast<char*>(g_static_ptr[dev]);
+  return ADAPMOE_OK;
+}
+
+}  // namespace
+
 // ---------------------------------------------------------------------------
 
 extern "C" {
@@ -1258,6 +1308,63 @@ int moe_prefetch(adapmoe_ctx* c, int layer, const int32_t* ids_host, int n) {
   if (!c->cache_ready) return fail(c, ADAPMOE_ESTATE, "moe_prefetch: cache not allocated");
   return prefetch_layer(c, layer, ids_host, n, true);
   ABI_CATCH(c)
+}
+
+int moe_expert_ffn_static(int32_t H, int32_t F, int32_t N, int32_t dtype, const void* const* table_dev, const void* x, int B,
+                          const int32_t* ids, const float* w, const int32_t* k, float* y, int32_t* err_dev, void* stream) {
+  adapmoe_config cfg{};
+  cfg.H = H;
+  cfg.F = F;
+  cfg.N = N;
+  cfg.L = 1;
+  cfg.dtype = dtype;
+  cfg.max_B = B;
+  if (!cfg_ok(&cfg) || !table_dev || !x || !ids || !w || !k || !y) return ADAPMOE_EINVAL;
+  if (B < 1 || B > kStaticMaxB) return ADAPMOE_EINVAL;          // beyond the fixed scratch array
+  if (a_stride_for(cfg) > kStaticMaxStride) return ADAPMOE_EINVAL;
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return ADAPMOE_EHIP;
+  char* base = nullptr;
+  int rc = static_scratch(dev, dtype, &base);
+  if (rc) return rc;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  const int qb = quant_bits(dtype);
+  LaunchCfg lc{};
+  lc.gateup_blocks = qb ? 1024 : 512;
+  lc.down_blocks = 256;
+  lc.dyn_pct = qb ? 0 : 20;
+  unsigned* dyn = reinterpret_cast<unsigned*>(base + kStaticABytes);
+  FfnArgs p{};
+  p.table = table_dev;
+  p.res = nullptr;
+  p.x = x;
+  p.ids = ids;
+  p.w = w;
+  p.k = k;
+  p.a = reinterpret_cast<float*>(base);
+  p.a_stride = a_stride_for(cfg);
+  p.y = y;
+  p.err = err_dev ? err_dev : reinterpret_cast<int32_t*>(base + kStaticABytes + kStaticDynBytes);
+  p.B = B;
+  p.H = H;
+  p.F = F;
+  p.N = N;
+  p.w2_offset = qb ? (size_t)2 * F * q_row_bytes(qb, H) : (size_t)2 * F * H * elem_size(dtype);
+  p.j_only = -1;
+  p.dyn_pct = lc.dyn_pct;
+  p.dyn_ctr = lc.dyn_pct > 0 ? dyn : nullptr;
+  p.dyn_clear = nullptr;
+  if ((qb ? launch_ffn_gateup_quant(p, qb, lc, s) : launch_ffn_gateup(p, dtype, lc, s)) != hipSuccess) {
+    (void)hipGetLastError();
+    return ADAPMOE_EHIP;
+  }
+  p.dyn_ctr = nullptr;
+  p.dyn_clear = lc.dyn_pct > 0 ? dyn : nullptr;
+  if ((qb ? launch_ffn_down_quant(p, qb, lc, s) : launch_ffn_down(p, dtype, lc, s)) != hipSuccess) {
+    (void)hipGetLastError();
+    return ADAPMOE_EHIP;
+  }
+  return ADAPMOE_OK;
 }
 
 }  // extern "C"

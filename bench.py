@@ -53,6 +53,8 @@ def parse():
     ap.add_argument("--tiles", type=int, default=0, help="offload workload: tile-wise loading with this many gate/up tiles (0 = whole images)")
     ap.add_argument("--lookahead", type=int, default=1, help="offload workload: layers predicted and prefetched ahead (1..3)")
     ap.add_argument("--graph", action="store_true", help="mixtral_stack_resident: replay one captured HIP graph per token")
+    ap.add_argument("--opt", action="append", default=[], metavar="NAME=VALUE",
+                    help="library option for the benchmarked context, e.g. GATEUP_BLOCKS=768 (names of adapmoe_set_option)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 1 GiB device copy (reference kernel for the HBM byte counters)")
     return ap.parse_args()
@@ -89,6 +91,13 @@ def main():
     print(json.dumps(out))
 
 
+def apply_options(ctx, args):
+    from paper_2408_10284_amd import binding as B
+    for item in args.opt:
+        name, value = item.split("=")
+        B.adapmoe_set_option(ctx, getattr(B, "OPT_" + name.upper()), int(value))
+
+
 # --------------------------------------------------------------------------- one layer, batch 1 ----
 
 def bench_layer(args):
@@ -114,6 +123,7 @@ def bench_layer(args):
 
     t_setup = time.time()
     ctx, cfg = B.adapmoe_create(shape.H, shape.F, shape.N, shape.L, dt, max_B=1)
+    apply_options(ctx, args)
     nbytes = B.adapmoe_expert_bytes(cfg)
     keep = []
 

@@ -15,6 +15,16 @@ constexpr int kWave = 64;
 // computes them on the scalar unit instead of once per lane.
 __device__ __forceinline__ int wave_index() { return __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)); }
 
+// Workgroup barrier for data exchanged through LDS only.  __syncthreads() also orders global memory,
+// which makes every wavefront wait for all of its outstanding global loads - in the streaming
+// kernels that is the first burst of weight loads, microseconds at the start of a launch.  This
+// one waits for the wavefront's LDS operations only.
+__device__ __forceinline__ void lds_barrier() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  __builtin_amdgcn_s_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 // DPP controls (GCN3+ encoding)
 constexpr int kDppQuadSwap1 = 0xB1;      // quad_perm:[1,0,3,2]
 constexpr int kDppQuadSwap2 = 0x4E;      // quad_perm:[2,3,0,1]

@@ -170,7 +170,7 @@ __device__ __forceinline__ void grouped_gemm_tile_loop(const char* wbase, size_t
     constexpr bool DIRECT = DB == 0;
     using Slab = WSlab<NMAT, RT, DIRECT ? NTERM * KS : 0>;
     int sa = 0;
-    auto load_next = [&](Slab& buf) {
+    auto load_next = [&](Slab& buf, bool advance) {
 #pragma unroll
       for (int rt = 0; rt < RT; ++rt)
 #pragma unroll
@@ -184,7 +184,7 @@ __device__ __forceinline__ void grouped_gemm_tile_loop(const char* wbase, size_t
 #pragma unroll
           for (int s = 0; s < KS; ++s) buf.b[term * KS + s] = (term == 0 ? bop0 : bop1)[((size_t)sa * KS + s) * 64 + lane];
       }
-      ++sa;
+      if (advance) ++sa;
     };
     int sc = 0;
     // the workgroup's next operand slab on its way from L2 to LDS, a value (not an array written

@@ -58,21 +58,12 @@ __global__ __launch_bounds__(kGateUpThreads) void ffn_gateup_kernel(FfnArgs p) {
   const size_t row_bytes = (size_t)p.H * esz;
   const int nch = (int)(row_bytes / kChunkBytes);
 
-  const char* base[2];
-  float wj[2];
-  const int kk = resolve_experts(p, b, base, wj);
-  const int F = p.F;
-  const bool windowed = p.j_only >= 0;
-  if (windowed && p.j_only >= kk) return;
-  const int lo = windowed ? p.j_only * F + p.r0 : 0;        // rows are numbered expert-major: r = j*F + f
-  const int total = windowed ? p.j_only * F + p.r1 : kk * F;
-  const int stride = gridDim.x * (kGateUpThreads / kWave);
-  const int first = lo + blockIdx.x * (kGateUpThreads / kWave) + wave;
-  float* a_out = p.a + (size_t)b * 2 * p.a_stride;
-
   const uint4* xg = reinterpret_cast<const uint4*>(static_cast<const char*>(p.x) + (size_t)b * row_bytes);
-  // x is staged in two steps, its loads issued before the first weight loads and its LDS writes
-  // after them (see the down kernel).
+  // x is staged in two steps: its loads are issued first of all - before the expert pointers are
+  // fetched, so that they are ahead of every weight request of the launch (a small load issued
+  // among the weight requests of the whole chip comes back microseconds later) - and its LDS
+  // writes come after the first weight loads.  The barrier that follows orders LDS only: a full
+  // __syncthreads() would also wait for those weight loads.
   constexpr int kStageX = 4;
   const int nsx = nch * kWave;
   struct StageX {   // passed by value (an array written through a captured reference ends up in scratch memory)
@@ -88,9 +79,21 @@ __global__ __launch_bounds__(kGateUpThreads) void ffn_gateup_kernel(FfnArgs p) {
 #pragma unroll
     for (int u = 0; u < kStageX; ++u) xs[min(tid + u * kGateUpThreads, nsx - 1)] = sx.v[u];   // unconditional, see the down kernel
     for (int i = tid + kStageX * kGateUpThreads; i < nsx; i += kGateUpThreads) xs[i] = xg[i];
-    __syncthreads();
+    lds_barrier();
   };
-  auto stage_x = [&]() { stage_x_finish(stage_x_issue()); };
+  const StageX sxv = stage_x_issue();
+
+  const char* base[2];
+  float wj[2];
+  const int kk = resolve_experts(p, b, base, wj);
+  const int F = p.F;
+  const bool windowed = p.j_only >= 0;
+  if (windowed && p.j_only >= kk) return;
+  const int lo = windowed ? p.j_only * F + p.r0 : 0;        // rows are numbered expert-major: r = j*F + f
+  const int total = windowed ? p.j_only * F + p.r1 : kk * F;
+  const int stride = gridDim.x * (kGateUpThreads / kWave);
+  const int first = lo + blockIdx.x * (kGateUpThreads / kWave) + wave;
+  float* a_out = p.a + (size_t)b * 2 * p.a_stride;
 
   const bool need0 = !windowed || p.j_only == 0, need1 = kk > 1 && (!windowed || p.j_only == 1);
   const bool all_resident = (!need0 || base[0] != nullptr) && (!need1 || base[1] != nullptr);
@@ -130,7 +133,6 @@ __global__ __launch_bounds__(kGateUpThreads) void ffn_gateup_kernel(FfnArgs p) {
     };
     uint4 A[NV], B[NV];
     int cur = next_row();
-    const StageX sxv = stage_x_issue();
     if (cur >= 0) {
       load_half(A, cur, 0);
       load_half(B, cur, 1);
@@ -168,10 +170,9 @@ __global__ __launch_bounds__(kGateUpThreads) void ffn_gateup_kernel(FfnArgs p) {
       }
       half_c ^= 1;
     };
-    const StageX sxv = stage_x_issue();
     stream_parts<(NCH > 0 ? NCH : 1)>(2 * nrows, next_addr, consume, [&, sxv]() { stage_x_finish(sxv); });
   } else {
-    stage_x();
+    [&, sxv]() { stage_x_finish(sxv); }();
     for (int r = first; r < total; r += stride) {
       const int j = r >= F ? 1 : 0;
       float val = 0.f;
@@ -226,26 +227,19 @@ __global__ __launch_bounds__(kDownThreads) void ffn_down_kernel(FfnArgs p) {
   constexpr int kWaves = kDownThreads / kWave;
   constexpr int NV = UN > 0 ? UN : 1;
 
-  const char* base[2];
-  float wj[2];
-  const int kk = resolve_experts(p, b, base, wj);
   const bool windowed = p.j_only >= 0;
-  if (windowed && p.j_only >= kk) return;
   const int j0 = windowed ? p.j_only : 0;   // experts j0 .. j0 + nj - 1 take part
-  const int nj = windowed ? 1 : kk;
-  const int hlo = windowed ? p.r0 : 0, hhi = windowed ? p.r1 : H;
-  // the experts taking part, in order: one of the window, or all kk
-  const char* part[2] = {pick2(base, j0), nj > 1 ? base[1] : nullptr};
-  const bool all_resident = part[0] != nullptr && (nj < 2 || part[1] != nullptr);
-
   const float4* ag = reinterpret_cast<const float4*>(p.a + (size_t)b * 2 * p.a_stride);
   const int S4 = (int)(p.a_stride >> 2);
-  // Staging of a_j in two steps: the loads of the first kStageA vectors per thread are issued
-  // before the first weight loads, the LDS writes come after them, so that the small, fast loads
-  // of a_j are not queued behind 14 KB of weights per wavefront and do not wait one by one
-  // (a loop of load, wait, write cost the kernel seven memory round trips at its start).
+  // Staging of a_j in two steps.  The loads of the first kStageA vectors per thread are issued first
+  // of all - before the expert pointers are fetched, hence for both slots of the token whatever its
+  // k (an unused slot holds old values that nothing reads) - so that they are ahead of every weight
+  // request of the launch: a small load issued among the weight requests of the whole chip comes
+  // back microseconds later, and a loop of load, wait, write would cost seven such round trips.
+  // The LDS writes come after the first weight loads, and the barrier behind them orders LDS only
+  // (a full __syncthreads() would also wait for those weight loads).
   constexpr int kStageA = 8;
-  const int nst = nj * F4;
+  const int nst = (windowed ? 1 : 2) * F4;
   struct StageA {   // passed by value: an array written through a captured reference ends up in scratch memory
     float4 v[kStageA];
   };
@@ -270,9 +264,19 @@ __global__ __launch_bounds__(kDownThreads) void ffn_down_kernel(FfnArgs p) {
 #pragma unroll
     for (int u = 0; u < kStageA; ++u) *a_dst(min(tid + u * kDownThreads, nst - 1)) = st.v[u];
     for (int i = tid + kStageA * kDownThreads; i < nst; i += kDownThreads) *a_dst(i) = *a_src(i);   // very long rows only
-    __syncthreads();
+    lds_barrier();
   };
-  auto stage_a = [&]() { stage_a_finish(stage_a_issue()); };
+  const StageA sta = stage_a_issue();
+
+  const char* base[2];
+  float wj[2];
+  const int kk = resolve_experts(p, b, base, wj);
+  if (windowed && p.j_only >= kk) return;
+  const int nj = windowed ? 1 : kk;
+  const int hlo = windowed ? p.r0 : 0, hhi = windowed ? p.r1 : H;
+  // the experts taking part, in order: one of the window, or all kk
+  const char* part[2] = {pick2(base, j0), nj > 1 ? base[1] : nullptr};
+  const bool all_resident = part[0] != nullptr && (nj < 2 || part[1] != nullptr);
 
   const int first = hlo + blockIdx.x * kWaves + wave;
   const int hstride = gridDim.x * kWaves;
@@ -306,10 +310,9 @@ __global__ __launch_bounds__(kDownThreads) void ffn_down_kernel(FfnArgs p) {
         hc += hstride;
       }
     };
-    const StageA sta = stage_a_issue();
     stream_parts<NV>(nrows * nb, next_addr, consume, [&, sta]() { stage_a_finish(sta); });
   } else {
-    stage_a();
+    [&, sta]() { stage_a_finish(sta); }();   // through a by-value capture like the other branch, or the array lands in scratch memory
     for (int h = first; h < hhi; h += hstride) {
       float acc = 0.f;
       for (int jr = 0; jr < nj; ++jr) {
@@ -492,7 +495,7 @@ static hipError_t init_down() {
 }
 
 hipError_t ffn_kernels_init(int dtype) {
-  if (dtype == ADAPMOE_INT4G64 || dtype == ADAPMOE_INT2G64) return hipSuccess;  // quantised kernels use static LDS only
+  if (dtype == ADAPMOE_INT4G64 || dtype == ADAPMOE_INT2G64) return quant_kernels_init(dtype == ADAPMOE_INT4G64 ? 4 : 2);
   return dtype == ADAPMOE_F32 ? init_down<false>() : init_down<true>();
 }
 

@@ -19,83 +19,133 @@
 // is nb x 16 bytes, and inside a dword field s (s < 8, bits 2s) is element 2s and field s+8 is
 // element 2s+1 of the dword's 16 elements; 5/16 byte per weight.
 //
-// Arithmetic: a nibble pair masked into two bfloat16 mantissas with exponent
-// 2^7 reads as (128+q0, 128+q1); v_dot2_f32_bf16 multiplies it with a packed
-// bfloat16 activation pair and accumulates in fp32.  Per group
-//   sum (q s + z) x = s * sum (128+q) x + (z - 128 s) * sum x.
-// The gate/up kernel writes a_j = w_j silu(g) u rounded to bfloat16 (the down
-// kernel multiplies it on the same instruction); see the error budget in the
-// design notes.
+// Arithmetic: codes are turned into half-precision numbers without being moved.  A code field
+// that lies inside the 10 mantissa bits of a half whose exponent is 2^10 reads as 1024 + code
+// if it starts at bit 0 and as 1024 + 2^p * code if it starts at bit p, so one mask-and-or per
+// field position yields a packed pair of halves; the fields of the upper byte of each half are
+// brought down by one shift of the dword.  v_dot2_f32_f16 multiplies the pair with a packed pair
+// of activations (held as halves) and accumulates in fp32, one accumulator per field position p
+// ("class": 2 for 4-bit, 4 for 2-bit codes).  Per group, with xs_p the sum of the activations
+// that meet class p,
+//   sum (q s + z) x = s * sum_p 2^-p (acc_p - 1024 xs_p) + z * sum_p xs_p.
+// That is 9 vector operations per 8 weights (4-bit) instead of 11 with one shift per field.
+// Activations: x arrives as bfloat16 and is converted to half (exact for 6.1e-5 <= |x| <= 65504,
+// clamped above, rounded to the half subnormal grid of 6e-8 below); the gate/up kernel writes
+// a_j = w_j silu(g) u as halves for the down kernel.
+#include <algorithm>
 #include "../../include/adapmoe.h"
 #include "stream_parts.h"
 
 namespace adapmoe {
 
-constexpr int kI4GateUpThreads = 256;
-constexpr int kI4DownThreads = 256;   // 4 wavefronts = 4 blocks of 64 groups of a W2 row
-constexpr int kI4DownRows = 4;        // output rows per workgroup
+typedef __attribute__((ext_vector_type(2))) _Float16 f16x2_t;
+
+// gate/up workgroup: 4 wavefronts (16 per workgroup measured 1 us slower per launch at Mixtral size)
+template <int NBLK>
+constexpr int gateup_threads() { return 256; }
+constexpr int kQDownThreads = 1024;   // 16 wavefronts, one output row at a time each
 
 template <int BITS>
 __device__ __forceinline__ size_t q_row_bytes(int n) { return (size_t)n * BITS / 8 + (size_t)n / 16; }
 
-// The mask and the exponent pattern live in registers (fetched through opaque
+// field positions inside a byte that are used without a shift ("classes"): 4-bit codes at bits 0 and 4,
+// 2-bit codes at bits 0, 2, 4, 6
+template <int BITS>
+struct QTraits {
+  static constexpr int NC = 8 / BITS;
+};
+
+// The masks and the exponent pattern live in registers (fetched through opaque
 // moves) so that (v & mask) | pattern is a single v_and_or_b32; as literals the
 // compiler has to split it into two instructions (VOP3 takes no literals here).
-struct I4Consts {
-  uint32_t mask, magic;
+template <int BITS>
+struct QConsts {
+  uint32_t mask[QTraits<BITS>::NC];
+  uint32_t magic;
 };
 template <int BITS>
-__device__ __forceinline__ I4Consts q_consts() {
-  I4Consts k;
-  if constexpr (BITS == 4) asm("s_mov_b32 %0, 0x000F000F" : "=s"(k.mask));
-  else asm("s_mov_b32 %0, 0x00030003" : "=s"(k.mask));
-  asm("v_mov_b32 %0, 0x43004300" : "=v"(k.magic));
+__device__ __forceinline__ QConsts<BITS> q_consts() {
+  QConsts<BITS> k;
+  if constexpr (BITS == 4) {
+    asm("s_mov_b32 %0, 0x000F000F" : "=s"(k.mask[0]));
+    asm("s_mov_b32 %0, 0x00F000F0" : "=s"(k.mask[1]));
+  } else {
+    asm("s_mov_b32 %0, 0x00030003" : "=s"(k.mask[0]));
+    asm("s_mov_b32 %0, 0x000C000C" : "=s"(k.mask[1]));
+    asm("s_mov_b32 %0, 0x00300030" : "=s"(k.mask[2]));
+    asm("s_mov_b32 %0, 0x00C000C0" : "=s"(k.mask[3]));
+  }
+  asm("v_mov_b32 %0, 0x64006400" : "=v"(k.magic));   // two halves of value 1024
   return k;
 }
 
-// sum over the 32 codes of one 16-byte vector of (128+q) * x, x given as 4 vectors of packed bf16 pairs.
-// Four independent accumulators (one per nibble position) keep the dot2 pipeline busy.
-__device__ __forceinline__ void dot_codes16(const uint4& c, const uint4* x, float (&acc)[4], const I4Consts& k) {
+// acc += a.lo*b.lo + a.hi*b.hi for two packed half pairs, fp32 accumulate
+__device__ __forceinline__ float dot2_f16(uint32_t a, uint32_t b, float acc) {
+  return __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2_t, a), __builtin_bit_cast(f16x2_t, b), acc, false);
+}
+
+__device__ __forceinline__ uint32_t pick(const uint4& v, int c) { return c == 0 ? v.x : c == 1 ? v.y : c == 2 ? v.z : v.w; }
+
+// Accumulators of one group: [class][which copy of the dword: as loaded / shifted down by 8]
+template <int BITS>
+struct QAcc {
+  float v[QTraits<BITS>::NC][2];
+};
+template <int BITS>
+__device__ __forceinline__ void q_acc_clear(QAcc<BITS>& a) {
+#pragma unroll
+  for (int c = 0; c < QTraits<BITS>::NC; ++c) a.v[c][0] = a.v[c][1] = 0.f;
+}
+
+// One 16-byte vector of codes against the matching activations (packed half pairs):
+// 4-bit: 32 codes, x[0..3] (dword d meets x[d]: pairs .x .y .z .w are its nibble positions 0..3);
+// 2-bit: 64 codes, x[0..7] (dword d meets x[2d] with its fields 0..3 and x[2d+1] with its fields 4..7).
+template <int BITS>
+__device__ __forceinline__ void dot_codes16(const uint4& c, const uint4* x, QAcc<BITS>& acc, const QConsts<BITS>& k) {
   const uint32_t w[4] = {c.x, c.y, c.z, c.w};
 #pragma unroll
   for (int d = 0; d < 4; ++d) {
-    const uint4 xv = x[d];
-    acc[0] = dot2_bf16((w[d] & k.mask) | k.magic, xv.x, acc[0]);
-    acc[1] = dot2_bf16(((w[d] >> 4) & k.mask) | k.magic, xv.y, acc[1]);
-    acc[2] = dot2_bf16(((w[d] >> 8) & k.mask) | k.magic, xv.z, acc[2]);
-    acc[3] = dot2_bf16(((w[d] >> 12) & k.mask) | k.magic, xv.w, acc[3]);
-  }
-}
-
-// the same for a 16-byte vector of 64 two-bit codes, x given as 8 vectors
-__device__ __forceinline__ void dot_codes16_2bit(const uint4& c, const uint4* x, float (&acc)[4], const I4Consts& k) {
-  const uint32_t w[4] = {c.x, c.y, c.z, c.w};
+    const uint32_t t = w[d] >> 8;
+    if constexpr (BITS == 4) {
+      const uint4 xv = x[d];
+      acc.v[0][0] = dot2_f16((w[d] & k.mask[0]) | k.magic, xv.x, acc.v[0][0]);
+      acc.v[1][0] = dot2_f16((w[d] & k.mask[1]) | k.magic, xv.y, acc.v[1][0]);
+      acc.v[0][1] = dot2_f16((t & k.mask[0]) | k.magic, xv.z, acc.v[0][1]);
+      acc.v[1][1] = dot2_f16((t & k.mask[1]) | k.magic, xv.w, acc.v[1][1]);
+    } else {
+      const uint4 xa = x[2 * d], xb = x[2 * d + 1];
 #pragma unroll
-  for (int d = 0; d < 4; ++d) {
-    const uint4 xa = x[2 * d], xb = x[2 * d + 1];
-    acc[0] = dot2_bf16((w[d] & k.mask) | k.magic, xa.x, acc[0]);
-    acc[1] = dot2_bf16(((w[d] >> 2) & k.mask) | k.magic, xa.y, acc[1]);
-    acc[2] = dot2_bf16(((w[d] >> 4) & k.mask) | k.magic, xa.z, acc[2]);
-    acc[3] = dot2_bf16(((w[d] >> 6) & k.mask) | k.magic, xa.w, acc[3]);
-    acc[0] = dot2_bf16(((w[d] >> 8) & k.mask) | k.magic, xb.x, acc[0]);
-    acc[1] = dot2_bf16(((w[d] >> 10) & k.mask) | k.magic, xb.y, acc[1]);
-    acc[2] = dot2_bf16(((w[d] >> 12) & k.mask) | k.magic, xb.z, acc[2]);
-    acc[3] = dot2_bf16(((w[d] >> 14) & k.mask) | k.magic, xb.w, acc[3]);
+      for (int cl = 0; cl < 4; ++cl) {
+        acc.v[cl][0] = dot2_f16((w[d] & k.mask[cl]) | k.magic, pick(xa, cl), acc.v[cl][0]);
+        acc.v[cl][1] = dot2_f16((t & k.mask[cl]) | k.magic, pick(xb, cl), acc.v[cl][1]);
+      }
+    }
   }
 }
 
-// sum of the 64 bfloat16 values of a group held as 8 vectors of packed pairs
-__device__ __forceinline__ float sum_group(const uint4* x) {
-  const uint32_t ones = 0x3F803F80u;
+// What a group's activations contribute besides the code products: xsum = sum of its 64 values,
+// xq = 1024 * sum_p 2^-p xs_p (the offsets that the mantissa trick adds, see the file comment).
+struct GroupSums {
+  float xsum, xq;
+};
+// x: the group's 64 halves as 8 vectors of packed pairs.  In both formats component c of every vector
+// meets class c mod NC.
+template <int BITS>
+__device__ __forceinline__ GroupSums group_sums(const uint4* x) {
+  const uint32_t ones = 0x3C003C00u;
   float s[4] = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
-    s[0] = dot2_bf16(x[j].x, ones, s[0]);
-    s[1] = dot2_bf16(x[j].y, ones, s[1]);
-    s[2] = dot2_bf16(x[j].z, ones, s[2]);
-    s[3] = dot2_bf16(x[j].w, ones, s[3]);
+    s[0] = dot2_f16(x[j].x, ones, s[0]);
+    s[1] = dot2_f16(x[j].y, ones, s[1]);
+    s[2] = dot2_f16(x[j].z, ones, s[2]);
+    s[3] = dot2_f16(x[j].w, ones, s[3]);
   }
-  return (s[0] + s[1]) + (s[2] + s[3]);
+  GroupSums g;
+  g.xsum = (s[0] + s[1]) + (s[2] + s[3]);
+  if constexpr (BITS == 4) g.xq = 1024.f * ((s[0] + s[2]) + 0.0625f * (s[1] + s[3]));
+  else g.xq = 1024.f * ((s[0] + 0.25f * s[1]) + (0.0625f * s[2] + 0.015625f * s[3]));
+  return g;
 }
 
 template <int BITS>
@@ -106,9 +156,9 @@ struct QGroup {  // what one lane holds of one row block: its group's codes (BIT
 
 // lane's share of block `blk` (nb groups) of the row starting at `row`.  Lanes
 // beyond nb re-read the block's last group (no branch around the loads, so the
-// compiler can count outstanding loads exactly); i4_group_dot ignores them.
+// compiler can count outstanding loads exactly); q_group_dot ignores them.
 template <int BITS>
-__device__ __forceinline__ void i4_load_group(const char* row, int n, int blk, int lane, QGroup<BITS>& g) {
+__device__ __forceinline__ void q_load_group(const char* row, int n, int blk, int lane, QGroup<BITS>& g) {
   const int G = n >> 6;
   const int nb = min(64, G - blk * 64);
   const int l = min(lane, nb - 1);
@@ -118,22 +168,39 @@ __device__ __forceinline__ void i4_load_group(const char* row, int n, int blk, i
   g.sz = load_stream4(row + (size_t)n * BITS / 8 + (size_t)(blk * 64 + l) * 4);
 }
 
-// value of the lane's group: sum (q s + z) x, with xs = sum of the group's x
+// value of the lane's group: sum (q s + z) x
 template <int BITS>
-__device__ __forceinline__ float i4_group_dot(const QGroup<BITS>& g, const uint4* x, float xsum, const I4Consts& k, bool live) {
-  float a0[4] = {0.f, 0.f, 0.f, 0.f}, a1[4] = {0.f, 0.f, 0.f, 0.f};
+__device__ __forceinline__ float q_group_dot(const QGroup<BITS>& g, const uint4* x, const GroupSums& gs, const QConsts<BITS>& k, bool live) {
+  QAcc<BITS> acc;
+  q_acc_clear(acc);
   if constexpr (BITS == 4) {
-    dot_codes16(g.c[0], x, a0, k);
-    dot_codes16(g.c[1], x + 4, a1, k);
+    dot_codes16<4>(g.c[0], x, acc, k);
+    dot_codes16<4>(g.c[1], x + 4, acc, k);
   } else {
-    dot_codes16_2bit(g.c[0], x, a0, k);
+    dot_codes16<2>(g.c[0], x, acc, k);
   }
-  const float d = ((a0[0] + a0[1]) + (a0[2] + a0[3])) + ((a1[0] + a1[1]) + (a1[2] + a1[3]));
+  float d;
+  if constexpr (BITS == 4) d = (acc.v[0][0] + acc.v[0][1]) + 0.0625f * (acc.v[1][0] + acc.v[1][1]);
+  else d = ((acc.v[0][0] + acc.v[0][1]) + 0.25f * (acc.v[1][0] + acc.v[1][1])) +
+           (0.0625f * (acc.v[2][0] + acc.v[2][1]) + 0.015625f * (acc.v[3][0] + acc.v[3][1]));
   const float s = half_bits_to_float(g.sz & 0xffffu), z = half_bits_to_float(g.sz >> 16);
-  return live ? fmaf(s, d, (z - 128.f * s) * xsum) : 0.f;
+  return live ? fmaf(s, d - gs.xq, z * gs.xsum) : 0.f;
 }
 
-// position (in bfloat16 elements) of a_j[f] in the scratch vector the down kernel reads:
+// float -> half bits, round to nearest even, clamped to the finite range
+__device__ __forceinline__ uint32_t f32_to_f16_bits(float f) {
+  f = __builtin_fminf(__builtin_fmaxf(f, -65504.f), 65504.f);
+  return (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)f);
+}
+// a packed pair of bfloat16 -> a packed pair of halves
+__device__ __forceinline__ uint32_t bf16x2_to_f16x2(uint32_t u) {
+  return f32_to_f16_bits(bf16_lo(u)) | (f32_to_f16_bits(bf16_hi(u)) << 16);
+}
+__device__ __forceinline__ uint4 bf16x8_to_f16x8(const uint4& v) {
+  return make_uint4(bf16x2_to_f16x2(v.x), bf16x2_to_f16x2(v.y), bf16x2_to_f16x2(v.z), bf16x2_to_f16x2(v.w));
+}
+
+// position (in 16-bit elements) of a_j[f] in the scratch vector the down kernel reads:
 // [block of 64 groups][vector c of 8][lane = group in block][8 elements]
 __device__ __forceinline__ int i4_a_pos(int f) {
   const int g = f >> 6, i = f & 63;
@@ -150,12 +217,56 @@ struct I4RowPair {
 // One wavefront per row pair; lane l owns group l (+64 per further block) of
 // both rows, its share of x stays in registers for the whole kernel.
 template <int BITS, int NBLK>
-__global__ __launch_bounds__(kI4GateUpThreads) void ffn_gateup_quant_kernel(FfnArgs p) {
+__global__ __launch_bounds__(gateup_threads<NBLK>()) void ffn_gateup_quant_kernel(FfnArgs p) {
+  constexpr int kI4GateUpThreads = gateup_threads<NBLK>();
   const int b = blockIdx.y;
   const int lane = threadIdx.x & 63, wave = wave_index();
   const int H = p.H, F = p.F;
   const size_t rb = q_row_bytes<BITS>(H);
-  const I4Consts kc = q_consts<BITS>();
+  const QConsts<BITS> kc = q_consts<BITS>();
+
+  // The lane's groups of x (as halves) and their sums.  x is read from global
+  // memory in order (one 16-byte piece per thread), converted and turned through LDS:
+  // piece j of group g goes to slot (block, j, lane = g % 64), which each lane
+  // then reads back without bank conflicts.  This runs after the first weight
+  // loads have been issued.
+  extern __shared__ uint4 xs[];
+  uint4 x[NBLK][8];
+  GroupSums xsum[NBLK];
+  const uint4* xg = reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(p.x) + (size_t)b * H);
+  // The pieces of x are requested first of all, before the expert pointers are fetched, and turned
+  // through LDS after the first weight requests, all without conditions.  The weight requests of the
+  // whole chip start a microsecond into the launch and keep the queues of the memory system full
+  // from then on: a small load issued among them comes back microseconds later, and no wavefront
+  // can compute before x is in its registers.  Issued ahead of all of them, x is there within 2 us.
+  constexpr int kXRounds = (NBLK * 512 + kI4GateUpThreads - 1) / kI4GateUpThreads;
+  struct StageX {
+    uint4 v[kXRounds];
+  };
+  const int pieces = H >> 3;
+  auto stage_x_issue = [&]() -> StageX {
+    StageX sx;
+#pragma unroll
+    for (int u = 0; u < kXRounds; ++u) sx.v[u] = xg[min((int)threadIdx.x + u * kI4GateUpThreads, pieces - 1)];
+    return sx;
+  };
+  auto stage_x = [&](const StageX& sx) {
+#pragma unroll
+    for (int u = 0; u < kXRounds; ++u) {
+      const int c = threadIdx.x + u * kI4GateUpThreads;
+      const int g = c >> 3, j = c & 7;
+      if (c < NBLK * 512) xs[((g >> 6) * 8 + j) * 64 + (g & 63)] = c < pieces ? bf16x8_to_f16x8(sx.v[u]) : make_uint4(0, 0, 0, 0);
+    }
+    lds_barrier();
+#pragma unroll
+    for (int i = 0; i < NBLK; ++i) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) x[i][j] = xs[(i * 8 + j) * 64 + lane];
+      xsum[i] = group_sums<BITS>(x[i]);
+    }
+  };
+
+  const StageX sxv = stage_x_issue();   // before anything else of this launch asks for memory
 
   const char* base[2];
   float wj[2];
@@ -170,52 +281,6 @@ __global__ __launch_bounds__(kI4GateUpThreads) void ffn_gateup_quant_kernel(FfnA
   const float rw[2] = {t0 ? wj[0] : wj[1], wj[1]};
   const int rj[2] = {t0 ? 0 : 1, 1};
 
-  // The lane's groups of x (bfloat16) and their sums.  x is read from global
-  // memory in order (one 16-byte piece per thread) and turned through LDS:
-  // piece j of group g goes to slot (block, j, lane = g % 64), which each lane
-  // then reads back without bank conflicts.  This runs after the first weight
-  // loads have been issued.
-  extern __shared__ uint4 xs[];
-  uint4 x[NBLK][8];
-  float xsum[NBLK];
-  const uint4* xg = reinterpret_cast<const uint4*>(static_cast<const uint16_t*>(p.x) + (size_t)b * H);
-  // 2-bit codes: the pieces of x are requested before the first weight loads (stage_x_issue) and
-  // turned through LDS after them (stage_x), all without conditions, so that these small loads
-  // neither queue behind the weights nor wait one by one.  4-bit codes: a plain loop after the
-  // first weight loads (measured faster there by 0.4 us, while the other form gains 1.2 us with 2 bits).
-  constexpr int kXRounds = NBLK * 512 / kI4GateUpThreads;
-  struct StageX {
-    uint4 v[kXRounds];
-  };
-  const int pieces = H >> 3;
-  auto stage_x_issue = [&]() -> StageX {
-    StageX sx;
-#pragma unroll
-    for (int u = 0; u < kXRounds; ++u) sx.v[u] = xg[min((int)threadIdx.x + u * kI4GateUpThreads, pieces - 1)];
-    return sx;
-  };
-  auto stage_x = [&](const StageX& sx) {
-    if constexpr (BITS == 2) {
-#pragma unroll
-      for (int u = 0; u < kXRounds; ++u) {
-        const int c = threadIdx.x + u * kI4GateUpThreads;
-        const int g = c >> 3, j = c & 7;
-        xs[((g >> 6) * 8 + j) * 64 + (g & 63)] = c < pieces ? sx.v[u] : make_uint4(0, 0, 0, 0);
-      }
-    } else {
-      for (int c = threadIdx.x; c < NBLK * 512; c += kI4GateUpThreads) {
-        const int g = c >> 3, j = c & 7;
-        xs[((g >> 6) * 8 + j) * 64 + (g & 63)] = c < pieces ? xg[c] : make_uint4(0, 0, 0, 0);
-      }
-    }
-    __syncthreads();
-#pragma unroll
-    for (int i = 0; i < NBLK; ++i) {
-#pragma unroll
-      for (int j = 0; j < 8; ++j) x[i][j] = xs[(i * 8 + j) * 64 + lane];
-      xsum[i] = sum_group(x[i]);
-    }
-  };
 
   // rows are numbered r = (index among the taking-part experts) * F + f
   const int total = windowed ? (nv ? p.r1 : 0) : nv * F;
@@ -224,143 +289,271 @@ __global__ __launch_bounds__(kI4GateUpThreads) void ffn_gateup_quant_kernel(FfnA
   const int nrows = first < total ? (total - first + stride - 1) / stride : 0;
   uint16_t* a_out = reinterpret_cast<uint16_t*>(p.a + (size_t)b * 2 * p.a_stride);
 
-  int ra = first;
-  auto load_next = [&](I4RowPair<BITS, NBLK>& buf) {
-    const int j = ra >= F ? 1 : 0;
-    const char* row = pick2(rbase, j) + (size_t)(ra - j * F) * 2 * rb;
+  auto load_row = [&](I4RowPair<BITS, NBLK>& buf, int r) {
+    const int j = r >= F ? 1 : 0;
+    const char* row = pick2(rbase, j) + (size_t)(r - j * F) * 2 * rb;
 #pragma unroll
     for (int i = 0; i < NBLK; ++i) {
-      i4_load_group(row, H, i, lane, buf.g1[i]);
-      i4_load_group(row + rb, H, i, lane, buf.g3[i]);
+      q_load_group(row, H, i, lane, buf.g1[i]);
+      q_load_group(row + rb, H, i, lane, buf.g3[i]);
     }
-    ra += stride;
   };
-  // The two sums of a row pair are parked in lane `ns` of gv / uv; SiLU, the product, the rounding
-  // and the store are then done for up to 64 row pairs at once, one per lane, instead of by the
-  // whole wavefront for every pair (the kernel is close to the vector-ALU limit).
+  // The two sums of a row pair are parked in lane `ns` of gv / uv (its row number in rv); SiLU, the
+  // product, the rounding and the store are then done for up to 64 row pairs at once, one per lane,
+  // instead of by the whole wavefront for every pair (the kernel is close to the vector-ALU limit).
   float gv = 0.f, uv = 0.f;
-  int ns = 0, r_first = first;   // the parked sums belong to row pairs r_first + t * stride, t < ns
+  int rv = 0, ns = 0;
   auto flush = [&]() {
     if (lane < ns) {
-      const int r = r_first + lane * stride;
-      const int j = r >= F ? 1 : 0;
-      const int f = r - j * F;
-      a_out[(size_t)pick2(rj, j) * 2 * p.a_stride + i4_a_pos(f)] = f32_to_bf16_bits(pick2(rw, j) * silu_f32(gv) * uv);
+      const int j = rv >= F ? 1 : 0;
+      const int f = rv - j * F;
+      a_out[(size_t)pick2(rj, j) * 2 * p.a_stride + i4_a_pos(f)] = (uint16_t)f32_to_f16_bits(pick2(rw, j) * silu_f32(gv) * uv);
     }
-    r_first += ns * stride;
     ns = 0;
   };
-  auto consume = [&](const I4RowPair<BITS, NBLK>& buf) {
+  auto consume_row = [&](const I4RowPair<BITS, NBLK>& buf, int r) {
     float g = 0.f, u = 0.f;
 #pragma unroll
     for (int i = 0; i < NBLK; ++i) {
-      g += i4_group_dot(buf.g1[i], x[i], xsum[i], kc, i * 64 + lane < (H >> 6));
-      u += i4_group_dot(buf.g3[i], x[i], xsum[i], kc, i * 64 + lane < (H >> 6));
+      g += q_group_dot(buf.g1[i], x[i], xsum[i], kc, i * 64 + lane < (H >> 6));
+      u += q_group_dot(buf.g3[i], x[i], xsum[i], kc, i * 64 + lane < (H >> 6));
     }
     g = wave_sum(g);
     u = wave_sum(u);
     gv = lane == ns ? g : gv;
     uv = lane == ns ? u : uv;
+    rv = lane == ns ? r : rv;
     if (++ns == kWave) flush();
   };
-  if constexpr (BITS == 2) {
-    const StageX sxv = stage_x_issue();
-    stream_bufs<I4RowPair<BITS, NBLK>>(nrows, load_next, consume, [&, sxv]() { stage_x(sxv); });
+
+  // Dynamic tail (see FfnArgs::dyn_ctr), an option that is off by default here: the wavefronts of a
+  // launch all have the same number of row pairs, yet they finish up to a factor of two apart (the
+  // memory system does not serve the compute units evenly), so the last passes over the grid can be
+  // drawn row by row from shared counters.  With only seven row pairs per wavefront at Mixtral size
+  // the round trip of each draw costs more than the balancing returns (22.2-23.4 against 21.5 us per
+  // launch).  The first two rows of a wavefront are always static: their loads are issued without
+  // conditions, which keeps the wait for x exact (see stream_bufs).
+  const int nfull = total / stride;
+  const int npool = nfull >= 2 ? max(1, (nfull * p.dyn_pct + 50) / 100) : nfull;
+  const int nstatic = nfull - npool;
+  if (p.dyn_ctr != nullptr && !windowed && nstatic >= 2) {
+    unsigned* ctr = p.dyn_ctr + (size_t)b * kDynQueues * kDynStride;
+    const int pool_start = nstatic * stride, pool_len = total - pool_start;
+    // queue q of nq holds pool rows pool_start + q + nq * t; workgroups 8m .. 8m+7 (one per
+    // compute-unit group under round-robin dispatch) share queue m % nq
+    const int nq = min(kDynQueues, (int)(gridDim.x + 7) >> 3);
+    const int q = (blockIdx.x >> 3) % nq;
+    const int qlen = (pool_len - q + nq - 1) / nq;
+    int it = 2;
+    bool pool_open = true;
+    auto next_row = [&]() -> int {
+      if (it < nstatic) return first + (it++) * stride;
+      if (!pool_open) return -1;
+      unsigned old = 0;
+      if (lane == 0) old = __hip_atomic_fetch_add(ctr + q * kDynStride, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      old = __builtin_amdgcn_readfirstlane(old);
+      if ((int)old < qlen) return pool_start + q + nq * (int)old;
+      pool_open = false;
+      return -1;
+    };
+    I4RowPair<BITS, NBLK> A, B;
+    int r0 = first, r1 = first + stride;
+    load_row(A, r0);
+    stage_x(sxv);
+    load_row(B, r1);
+    for (;;) {
+      consume_row(A, r0);
+      r0 = next_row();
+      if (r0 >= 0) load_row(A, r0);
+      if (r1 < 0) break;
+      consume_row(B, r1);
+      r1 = next_row();
+      if (r1 >= 0) load_row(B, r1);
+      if (r0 < 0) break;
+    }
   } else {
-    stream_bufs<I4RowPair<BITS, NBLK>>(nrows, load_next, consume, [&]() { stage_x(StageX{}); });
+    int ra = first, rc = first;
+    auto load_next = [&](I4RowPair<BITS, NBLK>& buf, bool advance) {
+      load_row(buf, ra);
+      if (advance) ra += stride;
+    };
+    auto consume = [&](const I4RowPair<BITS, NBLK>& buf) {
+      consume_row(buf, rc);
+      rc += stride;
+    };
+    stream_bufs<I4RowPair<BITS, NBLK>, 1>(nrows, load_next, consume, [&, sxv]() { stage_x(sxv); });
   }
   flush();
 }
 
 // --------------------------------------------------------------------- down --
 
-template <int BITS>
-struct I4DownRows {
-  QGroup<BITS> g[kI4DownRows];
+// A piece of one W2 row of one expert as a wavefront holds it: lane l owns group l of each of the
+// piece's PB blocks of 64 groups.
+template <int BITS, int PB>
+struct QRow {
+  QGroup<BITS> g[PB];
 };
 
-// One workgroup per kI4DownRows consecutive output rows; wavefront w owns block
-// w (64 groups) of every W2 row and keeps its share of a_j in registers.
-template <int BITS>
-__global__ __launch_bounds__(kI4DownThreads) void ffn_down_quant_kernel(FfnArgs p) {
-  __shared__ float part[kI4DownThreads / kWave][kI4DownRows];
+// One wavefront per output element y[h], the rows of a workgroup's 16 wavefronts walked with two
+// four register buffers (the unit in flight is one block of 64 groups of a row: 36 bytes per lane).  The intermediate vectors a_j of the activated experts (halves, written by the
+// gate/up kernel in the order [block][vector][lane]) are staged in LDS once per workgroup together
+// with the two sums per group that the dequantisation needs, so that the weight stream is the only
+// traffic that grows with the number of rows; a lane reads its group's 64 values back with eight
+// conflict-free 16-byte reads per block.
+template <int BITS, int NBLK>
+__global__ __launch_bounds__(kQDownThreads) void ffn_down_quant_kernel(FfnArgs p) {
+  extern __shared__ uint4 smem[];   // a[jj][NBLK*8*64] vectors of 8 halves, then sums[jj][NBLK*64]
   const int b = blockIdx.y;
-  const int lane = threadIdx.x & 63, wave = wave_index();
+  const int tid = threadIdx.x, lane = tid & 63, wave = wave_index();
   const int H = p.H, F = p.F;
   const size_t rb = q_row_bytes<BITS>(F);
   const int G = F >> 6;
-  const int nblk = (G + 63) >> 6;
-  const I4Consts kc = q_consts<BITS>();
+  const QConsts<BITS> kc = q_consts<BITS>();
+  constexpr int kWaves = kQDownThreads / kWave;
+  constexpr int kAVecs = NBLK * 8 * 64;          // 16-byte vectors of one expert's a_j
+  constexpr int PB = 1;                          // blocks per piece
+  constexpr int NP = NBLK / PB;                  // pieces per row
+
+  uint4* as = smem;
+  GroupSums* sums = reinterpret_cast<GroupSums*>(smem + 2 * kAVecs);
+
+  // Staging of a_j, both slots of the token whatever its k (an unused slot holds old values that
+  // nothing reads).  The loads are issued first of all, before the expert pointers are fetched: the
+  // weight loads of the whole chip follow a microsecond later and fill the queues of the memory
+  // system for the first 5 us of the launch; a small load issued among them comes back only then,
+  // and no wavefront can start computing before a_j is in LDS.  Issued ahead of all of them, a_j
+  // arrives within 2 us.  The LDS writes come after the first weight requests.
+  const uint4* ag = reinterpret_cast<const uint4*>(p.a + (size_t)b * 2 * p.a_stride);
+  const int S4 = (int)(p.a_stride >> 2);      // 16-byte vectors per (token, expert) of the scratch
+  constexpr int kStage = (2 * kAVecs + kQDownThreads - 1) / kQDownThreads;
+  struct StageA {
+    uint4 v[kStage];
+  };
+  auto stage_issue = [&]() -> StageA {
+    StageA st;
+#pragma unroll
+    for (int u = 0; u < kStage; ++u) {
+      const int i = min(tid + u * kQDownThreads, 2 * kAVecs - 1);
+      const int jj = i >= kAVecs ? 1 : 0;
+      st.v[u] = ag[(size_t)jj * S4 + (i - jj * kAVecs)];
+    }
+    return st;
+  };
+  const StageA sta = stage_issue();
 
   const char* base[2];
   float wj[2];
   const int kk = resolve_experts(p, b, base, wj);
-  const char* w2[2];
-  int rj[2];
-  int nv = 0;
   const size_t w2_off = (size_t)2 * F * q_row_bytes<BITS>(H);
   const bool windowed = p.j_only >= 0;
-  for (int j = 0; j < kk; ++j)
-    if (base[j] && (!windowed || j == p.j_only)) { w2[nv] = base[j] + w2_off; rj[nv] = j; ++nv; }
+  // resident activated experts taking part, rank order (selects, not run-time-indexed arrays)
+  const bool t0 = base[0] != nullptr && (!windowed || p.j_only == 0);
+  const bool t1 = kk > 1 && base[1] != nullptr && (!windowed || p.j_only == 1);
+  const int nv = (int)t0 + (int)t1;
+  const char* w2[2] = {(t0 ? base[0] : base[1]) + w2_off, base[1] + w2_off};   // w2[1] is used only when nv == 2
+  const int rj[2] = {t0 ? 0 : 1, 1};
 
-  const int h0 = (windowed ? p.r0 : 0) + blockIdx.x * kI4DownRows;
-  const int hhi = windowed ? p.r1 : H;
-  float acc[kI4DownRows];
-#pragma unroll
-  for (int r = 0; r < kI4DownRows; ++r) acc[r] = 0.f;
+  const int hlo = windowed ? p.r0 : 0, hhi = windowed ? p.r1 : H;
+  const int first = hlo + blockIdx.x * kWaves + wave;
+  const int hstride = gridDim.x * kWaves;
+  const int nrows = (nv > 0 && first < hhi) ? (hhi - first + hstride - 1) / hstride : 0;
+  float* y = p.y + (size_t)b * H;
+  const bool accumulate = p.accumulate != 0;
+  // the gate/up kernel's row counters are cleared here, ready for its next launch
+  if (blockIdx.x == 0 && tid < kDynQueues && p.dyn_clear && !windowed) p.dyn_clear[((size_t)b * kDynQueues + tid) * kDynStride] = 0u;
 
-  if (wave < nblk) {
-    const bool has_group = wave * 64 + lane < G;
-    I4DownRows<BITS> buf[2];
-    uint4 a[2][8];
-    // all weight loads of the workgroup's rows go out first, then the lane's 64 values of
-    // each a_j (written by the gate/up kernel as packed bfloat16 pairs, L2-resident)
+  auto stage_finish = [&](const StageA& st) {
 #pragma unroll
-    for (int jj = 0; jj < 2; ++jj)
-      if (jj < nv) {
+    for (int u = 0; u < kStage; ++u) as[min(tid + u * kQDownThreads, 2 * kAVecs - 1)] = st.v[u];
+    lds_barrier();
+    // two sums per group: thread t takes group t % (NBLK*64) of slot t / (NBLK*64)
+    if (tid < 2 * NBLK * 64) {
+      const int jj = tid / (NBLK * 64), g = tid - jj * (NBLK * 64);
+      const uint4* src = as + jj * kAVecs + (g >> 6) * 512 + (g & 63);
+      uint4 v[8];
 #pragma unroll
-        for (int r = 0; r < kI4DownRows; ++r) {
-          const int h = min(h0 + r, H - 1);
-          i4_load_group(w2[jj] + (size_t)h * rb, F, wave, lane, buf[jj].g[r]);
-        }
+      for (int c = 0; c < 8; ++c) v[c] = src[c * 64];
+      sums[jj * (NBLK * 64) + g] = group_sums<BITS>(v);
+    }
+    lds_barrier();
+  };
+
+  // The number of pieces per row is hidden from the optimiser: when it equals the four buffers of the
+  // streamer the compiler specialises the loop body per piece and runs out of registers (spills).
+  int np_rt = NP;
+  asm volatile("" : "+s"(np_rt));
+  int ha = first, ja = 0, pa = 0;   // load cursor
+  auto load_next = [&](QRow<BITS, PB>& buf, bool advance) {
+    const char* row = pick2(w2, ja) + (size_t)ha * rb;
+#pragma unroll
+    for (int i = 0; i < PB; ++i) q_load_group(row, F, pa * PB + i, lane, buf.g[i]);
+    if (advance && ++pa == np_rt) {
+      pa = 0;
+      if (++ja == nv) { ja = 0; ha += hstride; }
+    }
+  };
+  int hc = first, jc = 0, pc = 0;   // consume cursor
+  float acc = 0.f;
+  auto consume = [&](const QRow<BITS, PB>& buf) {
+    const int slot = pick2(rj, jc);
+    const uint4* aj = as + slot * kAVecs + pc * (PB * 512) + lane;
+    const GroupSums* sj = sums + slot * (NBLK * 64) + pc * (PB * 64) + lane;
+#pragma unroll
+    for (int i = 0; i < PB; ++i) {
+      uint4 a[8];
+#pragma unroll
+      for (int c = 0; c < 8; ++c) a[c] = aj[(i * 8 + c) * 64];
+      acc += q_group_dot(buf.g[i], a, sj[i * 64], kc, (pc * PB + i) * 64 + lane < G);
+      __builtin_amdgcn_sched_barrier(0);   // one block at a time: hoisting the next block's LDS reads costs 32 registers
+    }
+    if (++pc == np_rt) {
+      pc = 0;
+      if (++jc == nv) {
+        const float s = wave_sum(acc);
+        if (lane == 0) y[hc] = accumulate ? y[hc] + s : s;
+        acc = 0.f;
+        jc = 0;
+        hc += hstride;
       }
-#pragma unroll
-    for (int jj = 0; jj < 2; ++jj)
-      if (jj < nv) {
-        const uint4* ag = reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(p.a + (size_t)b * 2 * p.a_stride) +
-                                                          (size_t)rj[jj] * 2 * p.a_stride);
-#pragma unroll
-        for (int c = 0; c < 8; ++c) a[jj][c] = has_group ? ag[(wave * 8 + c) * 64 + lane] : make_uint4(0, 0, 0, 0);
-      }
-#pragma unroll
-    for (int jj = 0; jj < 2; ++jj)
-      if (jj < nv) {
-        const float asum = sum_group(a[jj]);
-#pragma unroll
-        for (int r = 0; r < kI4DownRows; ++r) acc[r] += i4_group_dot(buf[jj].g[r], a[jj], asum, kc, has_group);
-      }
-  }
-#pragma unroll
-  for (int r = 0; r < kI4DownRows; ++r) {
-    const float s = wave_sum(acc[r]);
-    if (lane == 0) part[wave][r] = s;
-  }
-  __syncthreads();
-  if (threadIdx.x < kI4DownRows && h0 + threadIdx.x < hhi) {
-    float y = 0.f;
-#pragma unroll
-    for (int w = 0; w < kI4DownThreads / kWave; ++w) y += part[w][threadIdx.x];
-    float* out = p.y + (size_t)b * H + h0 + threadIdx.x;
-    *out = p.accumulate ? *out + y : y;
-  }
+    }
+  };
+  stream_bufs4<QRow<BITS, PB>, 1>(nrows * nv * NP, load_next, consume, [&, sta]() { stage_finish(sta); });
+  // no activated expert of this token is resident (flagged by resolve_experts): the output is zero
+  if (nv == 0 && !accumulate)
+    for (int h = first; h < hhi; h += hstride)
+      if (lane == 0) y[h] = 0.f;
 }
 
 // ------------------------------------------------------------------ launch ---
 
+template <int BITS, int NBLK>
+static constexpr size_t q_down_lds() { return (size_t)2 * NBLK * 8 * 64 * 16 + (size_t)2 * NBLK * 64 * sizeof(GroupSums); }
+
+template <typename K>
+static hipError_t allow_lds(K kernel, size_t bytes) {
+  return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
+}
+
+template <int BITS>
+static hipError_t quant_init_bits() {
+  hipError_t e;
+  if ((e = allow_lds(ffn_down_quant_kernel<BITS, 1>, q_down_lds<BITS, 1>())) != hipSuccess) return e;
+  if ((e = allow_lds(ffn_down_quant_kernel<BITS, 2>, q_down_lds<BITS, 2>())) != hipSuccess) return e;
+  if ((e = allow_lds(ffn_down_quant_kernel<BITS, 3>, q_down_lds<BITS, 3>())) != hipSuccess) return e;
+  return allow_lds(ffn_down_quant_kernel<BITS, 4>, q_down_lds<BITS, 4>());
+}
+
+hipError_t quant_kernels_init(int bits) { return bits == 4 ? quant_init_bits<4>() : quant_init_bits<2>(); }
+
 hipError_t launch_ffn_gateup_quant(const FfnArgs& p, int bits, const LaunchCfg& lc, hipStream_t s) {
-  dim3 grid(lc.gateup_blocks, p.B), block(kI4GateUpThreads);
-  if (p.j_only >= 0) grid.x = std::max(1, std::min(lc.gateup_blocks, (p.r1 - p.r0 + 3) / (kI4GateUpThreads / kWave)));
   const int nblk = ((p.H >> 6) + 63) >> 6;
+  const int threads = nblk == 1 ? gateup_threads<1>() : gateup_threads<2>();
+  const int waves = threads / kWave;
+  // lc.gateup_blocks counts workgroups of 16 wavefronts; smaller workgroups are launched in proportion
+  int blocks = lc.gateup_blocks * (1024 / threads);
+  if (p.j_only >= 0) blocks = std::max(1, std::min(blocks, (p.r1 - p.r0 + waves - 1) / waves));
+  dim3 grid(blocks, p.B), block(threads);
   if (bits == 4) {
     if (nblk == 1) launch_kernel(ffn_gateup_quant_kernel<4, 1>, grid, block, 1 * 8192, s, lc.timing, p);
     else launch_kernel(ffn_gateup_quant_kernel<4, 2>, grid, block, 2 * 8192, s, lc.timing, p);
@@ -371,11 +564,22 @@ hipError_t launch_ffn_gateup_quant(const FfnArgs& p, int bits, const LaunchCfg& 
   return hipGetLastError();
 }
 
+template <int BITS>
+static void launch_down_quant_t(const FfnArgs& p, int nblk, dim3 grid, hipStream_t s, const KernelTiming& t) {
+  dim3 block(kQDownThreads);
+  if (nblk == 1) launch_kernel(ffn_down_quant_kernel<BITS, 1>, grid, block, q_down_lds<BITS, 1>(), s, t, p);
+  else if (nblk == 2) launch_kernel(ffn_down_quant_kernel<BITS, 2>, grid, block, q_down_lds<BITS, 2>(), s, t, p);
+  else if (nblk == 3) launch_kernel(ffn_down_quant_kernel<BITS, 3>, grid, block, q_down_lds<BITS, 3>(), s, t, p);
+  else launch_kernel(ffn_down_quant_kernel<BITS, 4>, grid, block, q_down_lds<BITS, 4>(), s, t, p);
+}
+
 hipError_t launch_ffn_down_quant(const FfnArgs& p, int bits, const LaunchCfg& lc, hipStream_t s) {
   const int rows = p.j_only >= 0 ? p.r1 - p.r0 : p.H;
-  dim3 grid(std::max(1, (rows + kI4DownRows - 1) / kI4DownRows), p.B), block(kI4DownThreads);
-  if (bits == 4) launch_kernel(ffn_down_quant_kernel<4>, grid, block, 0, s, lc.timing, p);
-  else launch_kernel(ffn_down_quant_kernel<2>, grid, block, 0, s, lc.timing, p);
+  const int waves = kQDownThreads / kWave;
+  dim3 grid(std::max(1, std::min(lc.down_blocks, (rows + waves - 1) / waves)), p.B);
+  const int nblk = ((p.F >> 6) + 63) >> 6;     // F <= 16384: at most 4 blocks of 64 groups
+  if (bits == 4) launch_down_quant_t<4>(p, nblk, grid, s, lc.timing);
+  else launch_down_quant_t<2>(p, nblk, grid, s, lc.timing);
   return hipGetLastError();
 }
 

@@ -141,6 +141,7 @@ hipError_t launch_ffn_fused(const FfnArgs& p, int dtype, const FusedSync& sy, in
 // group-quantised experts, bits = 4 or 2
 hipError_t launch_ffn_gateup_quant(const FfnArgs& p, int bits, const LaunchCfg& lc, hipStream_t s);
 hipError_t launch_ffn_down_quant(const FfnArgs& p, int bits, const LaunchCfg& lc, hipStream_t s);
+hipError_t quant_kernels_init(int bits);
 hipError_t batched_kernels_init();
 hipError_t launch_bucket_gather(const BatchArgs& p, hipStream_t s, const KernelTiming& t = KernelTiming{});
 hipError_t launch_grouped_gateup(const BatchArgs& p, bool direct, hipStream_t s, const KernelTiming& t = KernelTiming{});

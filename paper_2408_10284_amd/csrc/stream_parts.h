@@ -101,28 +101,84 @@ __device__ __forceinline__ void stream_parts(int Q, AddrFn next_addr, ConsumeFn 
   if (q + 2 < Q) consume(A);
 }
 
-// Same pipeline for parts that are not a plain run of vectors: load_next(buf)
-// fills a buffer with the next part in sequence.
-// (Here the first loads stay conditional: measured, the kernels that use this form are 1-2 %
-// faster with the more cautious waits that result, see stream_parts.)
-template <class Buf, class LoadFn, class ConsumeFn, class MidFn>
+// Same pipeline for parts that are not a plain run of vectors: load_next(buf, advance) fills a
+// buffer with the part under its cursor and then moves the cursor on if `advance` is set.
+// The first loads are issued without conditions (a wavefront with fewer parts than buffers reads
+// its last part again): the compiler counts outstanding loads per control-flow path and takes the
+// most cautious count where paths join, so with conditional first loads every wait that follows -
+// in particular the wait for small loads that after_first_loads() depends on, issued BEFORE these
+// - would wait for the whole first burst of weights (measured: 5 us at the start of the quantised
+// kernels).  A wavefront without any part only runs after_first_loads().
+// EARLY = number of buffers requested before after_first_loads(), the others right after it.  A
+// load instruction is held back while the memory pipeline of the compute unit is full, so a
+// wavefront that requests all of its buffers first reaches after_first_loads() only when the
+// opening burst of the whole workgroup has been accepted - microseconds, when every wavefront of
+// the chip starts the same way.  EARLY = 1 keeps the memory system busy while the staging runs and
+// lets the rest of the burst follow it.
+template <class Buf, int EARLY = 2, class LoadFn, class ConsumeFn, class MidFn>
 __device__ __forceinline__ void stream_bufs(int Q, LoadFn load_next, ConsumeFn consume, MidFn after_first_loads) {
+  if (Q <= 0) {
+    after_first_loads();
+    return;
+  }
   Buf A, B;
-  if (Q > 0) load_next(A);
-  if (Q > 1) load_next(B);
+  load_next(A, Q > 1);
+  if (EARLY > 1) load_next(B, true);
   after_first_loads();
-  if (Q <= 0) return;
+  if (EARLY <= 1) load_next(B, true);
   int q = 0;
   for (; q + 3 < Q; q += 2) {
     consume(A);
-    load_next(A);
+    load_next(A, true);
     consume(B);
-    load_next(B);
+    load_next(B, true);
   }
   consume(A);
-  if (q + 2 < Q) load_next(A);
+  if (q + 2 < Q) load_next(A, true);
   if (q + 1 < Q) consume(B);
   if (q + 2 < Q) consume(A);
+}
+
+// The same with four buffers in flight, for parts that are small (a few registers each): a
+// wavefront keeps up to four parts outstanding.
+template <class Buf, int EARLY = 4, class LoadFn, class ConsumeFn, class MidFn>
+__device__ __forceinline__ void stream_bufs4(int Q, LoadFn load_next, ConsumeFn consume, MidFn after_first_loads) {
+  if (Q <= 0) {
+    after_first_loads();
+    return;
+  }
+  Buf A, B, C, D;
+  load_next(A, Q > 1);
+  if (EARLY > 1) load_next(B, Q > 2);
+  if (EARLY > 2) load_next(C, Q > 3);
+  if (EARLY > 3) load_next(D, true);
+  after_first_loads();
+  if (EARLY <= 1) load_next(B, Q > 2);
+  if (EARLY <= 2) load_next(C, Q > 3);
+  if (EARLY <= 3) load_next(D, true);
+  int q = 0;
+  for (; q + 7 < Q; q += 4) {   // at least four more parts to request beyond the four in flight
+    consume(A);
+    load_next(A, true);
+    consume(B);
+    load_next(B, true);
+    consume(C);
+    load_next(C, true);
+    consume(D);
+    load_next(D, true);
+  }
+  // 1 to 7 parts left, the first min(left, 4) of them in A, B, C, D
+  const int left = Q - q;
+  consume(A);
+  if (left > 4) load_next(A, true);
+  if (left > 1) consume(B);
+  if (left > 5) load_next(B, true);
+  if (left > 2) consume(C);
+  if (left > 6) load_next(C, true);
+  if (left > 3) consume(D);
+  if (left > 4) consume(A);
+  if (left > 5) consume(B);
+  if (left > 6) consume(C);
 }
 
 }  // namespace adapmoe

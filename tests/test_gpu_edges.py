@@ -192,11 +192,12 @@ def test_two_contexts_are_independent():
         b.close()
 
 
-@pytest.mark.parametrize("blocks,pct", [(40, 50), (7, 100), (1000, 15), (512, 0)])
-def test_dynamic_tail_with_odd_grids(blocks, pct):
-    """The gate/up kernel's dynamic tail must cover every row exactly once for any grid size and pool share
+@pytest.mark.parametrize("dtype,blocks,pct", [("bf16", 40, 50), ("bf16", 7, 100), ("bf16", 1000, 15), ("bf16", 512, 0),
+                                              ("int4g64", 10, 50), ("int4g64", 3, 100), ("int4g64", 37, 30), ("int2g64", 16, 40)])
+def test_dynamic_tail_with_odd_grids(dtype, blocks, pct):
+    """The gate/up kernels' dynamic tail must cover every row exactly once for any grid size and pool share
     (grids that are no multiple of 8 workgroups, fewer workgroups than queues, everything in the pool)."""
-    shape = synth.MoEShape(H=4096, F=1536, N=4, L=1, dtype="bf16")     # compile-time row length, 2 F no multiple of most grids
+    shape = synth.MoEShape(H=4096, F=1536, N=4, L=1, dtype=dtype)     # compile-time row length, 2 F no multiple of most grids
     ls = GpuLayerSet(shape, seed=51, max_B=3, taus=[0.3])
     try:
         B.adapmoe_set_option(ls.ctx, B.OPT_GATEUP_BLOCKS, blocks)
@@ -208,6 +209,6 @@ def test_dynamic_tail_with_odd_grids(blocks, pct):
             y = run_ffn(ls, 0, g)
             Yref = OE.moe_block_rows(X, ls.experts_f32[0], g["ids"], g["w"].astype(np.float64), g["k"])
             err = rel_err_per_token(y, Yref)
-            assert err.max() <= TOL["bf16"], (rep, err.max())
+            assert err.max() <= TOL[dtype], (rep, err.max())
     finally:
         ls.close()

@@ -46,11 +46,17 @@ def parse():
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget for the CPU-checker baseline (0 = skip)")
     ap.add_argument("--workload", default="mixtral_layer_bf16",
                     choices=["mixtral_layer_bf16", "mixtral_layer_int4", "mixtral_layer_int2", "tiny_f32", "mixtral_stack_offload",
-                             "mixtral_batched", "mixtral_stack_resident"])
+                             "mixtral_batched", "mixtral_stack_resident", "mixtral22_layer_bf16", "mixtral22_layer_int4",
+                             "mixtral22_layer_int2"])
+    ap.add_argument("--stacks", type=int, default=None,
+                    help="1: add short runs of the multi-layer and int4 workloads to the record (default for the default workload), 0: do not")
     ap.add_argument("--layers", type=int, default=None, help="layers of the stack workloads (default: offload 14, batched 32)")
     ap.add_argument("--cache", type=int, default=None, help="total cache slots of the offload workload (default 2 per layer)")
     ap.add_argument("--dtype", default="bf16", choices=["bf16", "int4", "int2"], help="expert storage of the offload workload")
     ap.add_argument("--tiles", type=int, default=0, help="offload workload: tile-wise loading with this many gate/up tiles (0 = whole images)")
+    ap.add_argument("--staging", type=int, default=0,
+                    help="offload workload: expert images in pageable host memory, loads staged through this many pinned buffers "
+                         "(for stacks larger than the box lets a process pin, e.g. --layers 32 in bf16)")
     ap.add_argument("--lookahead", type=int, default=1, help="offload workload: layers predicted and prefetched ahead (1..3)")
     ap.add_argument("--graph", action="store_true", help="mixtral_stack_resident: replay one captured HIP graph per token")
     ap.add_argument("--opt", action="append", default=[], metavar="NAME=VALUE",
@@ -88,6 +94,9 @@ def main():
         out = bench_stack_resident(args)
     else:
         out = bench_layer(args)
+        want_stacks = args.stacks if args.stacks is not None else int(args.workload == "mixtral_layer_bf16" and args.steps is None)
+        if want_stacks:
+            out["stacks"] = bench_stacks(args)
     print(json.dumps(out))
 
 
@@ -96,6 +105,95 @@ def apply_options(ctx, args):
     for item in args.opt:
         name, value = item.split("=")
         B.adapmoe_set_option(ctx, getattr(B, "OPT_" + name.upper()), int(value))
+
+
+class _LazyList:
+    """list-like whose items are produced on first use (expert matrices read back from device images)."""
+
+    def __init__(self, n, make):
+        self.n, self.make, self.cache = n, make, {}
+
+    def __len__(self):
+        return self.n
+
+    def __getitem__(self, i):
+        if i not in self.cache:
+            self.cache[i] = self.make(i)
+        return self.cache[i]
+
+
+def cpu_baseline_stack(shape, routers, images_dev, taus, h0, gamma, budget_s, n_layers, what):
+    """The CPU checker's multi-layer loop (oracle/stack.py), as it stands, on the first tokens of the same stream
+    through the first `n_layers` layers (reading the experts back from the device images costs more time than
+    evaluating them, so the sample is bounded by layers as well as by tokens).  The rate is scaled to the full depth."""
+    import numpy as np
+    import torch
+    from oracle import expert as OE
+    from oracle import stack as OS
+    from paper_2408_10284_amd import synth
+    try:
+        from threadpoolctl import threadpool_info
+        threads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+    except Exception:
+        threads = 1
+    L = min(n_layers, shape.L)
+    cache = {}
+
+    def mats(l, e):
+        if (l, e) not in cache:
+            img = images_dev[l][e]
+            if shape.dtype == "bf16":
+                cache[(l, e)] = synth.unpack_image_bf16(img.view(torch.int16).cpu().numpy().view(np.uint16), shape.H, shape.F)
+            else:
+                dec = synth.decode_int4_image if shape.dtype == "int4g64" else synth.decode_int2_image
+                cache[(l, e)] = tuple(OE.decode_int4(q, s, z) for (q, s, z) in dec(img.cpu().numpy(), shape.H, shape.F))
+        return cache[(l, e)]
+
+    routers_f32 = [routers[l].float().cpu().numpy() for l in range(L)]
+    n = 0
+    t0 = time.perf_counter()
+    while n < h0.shape[0] and time.perf_counter() - t0 < budget_s:
+        OS.run_stack(h0[n:n + 1].astype(np.float64), routers_f32, [np.float32(t) for t in taus[:L]],
+                     lambda l, e, x: OE.expert_ffn(x, *mats(l, e)), gamma, store=synth.bf16_round)
+        n += 1
+    dt = time.perf_counter() - t0
+    return {"value": round(n * L / dt / shape.L, 4), "unit": f"tokens/s ({shape.L}-layer stack)", "cores": int(threads), "kind": "oracle",
+            "sample": f"{what}: first {n} token(s) through the first {L} of {shape.L} layers with the float64 NumPy checker "
+                      f"(oracle/stack.py), {dt:.1f} s wall incl. reading the experts back from HBM; rate scaled to {shape.L} layers; "
+                      f"host has {os.cpu_count()} logical CPUs"}
+
+
+def read_decisions(ctx, logbuf, n_records, max_B, Bt):
+    """(ids [n,Bt,2], k [n,Bt]) from a decision-log buffer."""
+    rec = logbuf[:n_records].cpu().numpy().reshape(n_records, 6 * max_B)
+    return rec[:, :2 * Bt].reshape(n_records, Bt, 2), rec[:, 2 * Bt:3 * Bt]
+
+
+def bench_stacks(args):
+    """Short runs of the other workloads of the path, for the default record: the 32-layer stack with all experts
+    resident at batch 1 and with 16 streams (the same 90 GB of images), and the int4 layer."""
+    import copy
+    out = {}
+    shared = {}
+    a = copy.copy(args)
+    a.steps, a.warmup, a.layers, a.graph = 64, 8, None, False
+    a.cpu_seconds = min(args.cpu_seconds, 12.0)
+    try:
+        out["mixtral_stack_resident"] = bench_stack_resident(a, shared)
+        a.steps, a.warmup = 24, 4
+        out["mixtral_batched"] = bench_batched(a, shared)
+    finally:
+        shared.clear()
+        import torch
+        torch.cuda.empty_cache()
+    a = copy.copy(args)
+    a.workload, a.steps, a.warmup, a.gpu_images = "mixtral_layer_int4", 1024, 128, True
+    a.cpu_seconds = min(args.cpu_seconds, 10.0)
+    out["mixtral_layer_int4"] = bench_layer(a)
+    for rec in out.values():      # the sub-records repeat only what differs from the headline record
+        for key in ("metric", "n_gpus", "higher_is_better", "scaling", "vs_baseline", "data"):
+            rec.pop(key, None)
+    return out
 
 
 # --------------------------------------------------------------------------- one layer, batch 1 ----
@@ -109,16 +207,20 @@ def bench_layer(args):
 
     steps = args.steps if args.steps is not None else 2048
     warmup = args.warmup if args.warmup is not None else 256
-    if args.workload == "tiny_f32":
+    wl = args.workload
+    big = wl.startswith("mixtral22")                 # Mixtral-8x22B expert shape (Sec. 6.1): H 6144, F 16384
+    Hh, Ff = (6144, 16384) if big else (4096, 14336)
+    gpu_images = big or getattr(args, "gpu_images", False)    # images drawn and packed on the GPU (seconds instead of minutes)
+    if wl == "tiny_f32":
         shape, tau, act, dt = synth.TINY, 0.3, "f32", B.F32
         X = synth.iid_tokens(args.tokens, shape.H, seed=1, dtype="f32")
-    elif args.workload in ("mixtral_layer_int4", "mixtral_layer_int2"):
-        four = args.workload == "mixtral_layer_int4"
-        shape = synth.MoEShape(4096, 14336, 8, 1, "int4g64" if four else "int2g64")
+    elif wl.endswith("int4") or wl.endswith("int2"):
+        four = wl.endswith("int4")
+        shape = synth.MoEShape(Hh, Ff, 8, 1, "int4g64" if four else "int2g64")
         tau, act, dt = 0.2, "bf16", (B.INT4G64 if four else B.INT2G64)
         X = synth.ar1_tokens(args.tokens, shape.H, 0.8, seed=1, dtype="bf16")
     else:
-        shape, tau, act, dt = synth.MIXTRAL_LAYER, 0.2, "bf16", B.BF16
+        shape, tau, act, dt = synth.MoEShape(Hh, Ff, 8, 1, "bf16"), 0.2, "bf16", B.BF16
         X = synth.ar1_tokens(args.tokens, shape.H, 0.8, seed=1, dtype="bf16")
 
     t_setup = time.time()
@@ -132,12 +234,25 @@ def bench_layer(args):
             return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
         return torch.from_numpy(synth.bf16_bits(a).view(np.int16)).cuda()
 
-    wg = synth.router_weights(shape, 0)
-    wg_d = dev(wg)
+    if gpu_images:
+        wg_t = synth.router_bf16_torch(shape, 0, 0)
+        wg = wg_t.float().cpu().numpy()
+        wg_d = wg_t
+    else:
+        wg = synth.router_weights(shape, 0)
+        wg_d = dev(wg)
     B.adapmoe_set_router(ctx, 0, wg_d)
     B.adapmoe_set_tau(ctx, [tau])
-    experts = []        # what the CPU baseline evaluates: float32 matrices (decoded codes for int4)
+    experts = []        # what the CPU baseline evaluates: float32 matrices (codes, scales, zeros for int4), or None = decode the image
     for e in range(shape.N):
+        if gpu_images:
+            gen = {B.INT4G64: synth.expert_image_int4_torch, B.INT2G64: synth.expert_image_int2_torch}.get(dt, synth.expert_image_bf16_torch)
+            t = gen(shape, 0, e, 0)
+            assert t.numel() * t.element_size() == nbytes
+            keep.append(t)
+            experts.append(None)
+            B.adapmoe_bind_expert_dev(ctx, 0, e, t)
+            continue
         w1, w3, w2 = synth.expert_weights(shape, 0, e)
         img = np.empty(nbytes, dtype=np.uint8)
         if dt in (B.INT4G64, B.INT2G64):
@@ -155,6 +270,15 @@ def bench_layer(args):
         t = torch.from_numpy(img).cuda()
         keep.append(t)
         B.adapmoe_bind_expert_dev(ctx, 0, e, t)
+    if gpu_images:
+        torch.cuda.synchronize()
+
+        def image_mats(e):      # canonical matrices of expert e for the CPU baseline, read back from the image
+            if dt == B.BF16:
+                return synth.unpack_image_bf16(keep[e].view(torch.int16).cpu().numpy().view(np.uint16), shape.H, shape.F)
+            dec = synth.decode_int4_image if dt == B.INT4G64 else synth.decode_int2_image
+            return dec(keep[e].cpu().numpy(), shape.H, shape.F)
+        experts = _LazyList(shape.N, image_mats)
     xd = dev(X).reshape(args.tokens, shape.H)
     y = torch.empty((1, shape.H), dtype=torch.float32, device="cuda")
     stream = torch.cuda.current_stream()
@@ -219,8 +343,12 @@ def bench_layer(args):
 
     cpu = cpu_baseline_layer(args, shape, X, wg, experts, tau, quantised) if args.cpu_seconds > 0 else None
     gu_name = "ffn_fused_kernel" if fused else ("ffn_gateup_quant_kernel" if quantised else "ffn_gateup_kernel")
-    traffic = {"mixtral_layer_bf16": measured_traffic(gu_name),
-               "mixtral_layer_int4": measured_traffic("ffn_gateup_quant_kernel<4", "pmc_traffic_int4.json")}.get(args.workload)
+    # HBM bytes per launch from the committed counter runs of this workload.  Those runs launch every one of the
+    # 256 tokens once, so their per-launch average belongs to the mean k of the token set; it is scaled to the
+    # mean k of the launches timed here (one launch reads k experts).
+    per_launch_ref = {"mixtral_layer_bf16": measured_traffic(gu_name),
+                      "mixtral_layer_int4": measured_traffic("ffn_gateup_quant_kernel<4", "pmc_traffic_int4.json")}.get(args.workload)
+    traffic = round(per_launch_ref / float(k_host.mean()) * float(ks.mean())) if per_launch_ref and args.tokens == 256 else None
     out = {
         "metric": METRIC, "value": round(steps / elapsed, 2), "unit": "tokens/s (one MoE layer, batch 1)",
         "n_gpus": 1, "steps": steps, "warmup": warmup,
@@ -233,6 +361,8 @@ def bench_layer(args):
                    "expert_bytes": nbytes, "setup_s": round(t_setup, 1)},
         "roofline": {"bound": "hbm", "kernel": gu_name, "achieved": round(gu_gbs, 1), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(gu_gbs / HBM_PEAK_GBS, 4), "traffic": traffic,
+                     "traffic_note": "HBM bytes per launch (read + written) from profiles/pmc_traffic*.json, scaled from the mean k of "
+                                     "the counter runs to the mean k of the launches timed here",
                      "avg_us": round(ms_gu / max(n_gu, 1) * 1e3, 2), "launches": n_gu,
                      "bytes_per_launch": round(bytes_gu / max(n_gu, 1)),
                      "measured_device_copy_GBs": round(copy_gbs, 1), "frac_of_device_copy": round(gu_gbs / copy_gbs, 4)},
@@ -297,7 +427,7 @@ def cpu_baseline_layer(args, shape, X, wg, experts, tau, int4):
 
 # --------------------------------------------------------------------------- stack helpers ----
 
-def build_stack(shape, seed, keep_on_device, pin_host):
+def build_stack(shape, seed, keep_on_device, pin_host, pageable=False):
     """Routers and expert images of an L-layer stack drawn on the GPU.  Returns
     (routers_dev[L], images_dev[L][N] or None, images_host[L][N] or None)."""
     import torch
@@ -315,7 +445,7 @@ def build_stack(shape, seed, keep_on_device, pin_host):
             else:
                 img = synth.expert_image_bf16_torch(shape, l, e, seed)
             if pin_host:
-                h = torch.empty(img.numel(), dtype=img.dtype, pin_memory=True)
+                h = torch.empty(img.numel(), dtype=img.dtype, pin_memory=not pageable)
                 h.copy_(img)
                 hrow.append(h)
             if keep_on_device:
@@ -407,7 +537,7 @@ def bench_stack_offload(args):
     gamma = 0.3
     taus = synth.tau_profile(L)
     t_setup = time.time()
-    routers, images_dev, images_host = build_stack(shape, 0, keep_on_device=True, pin_host=True)
+    routers, images_dev, images_host = build_stack(shape, 0, keep_on_device=True, pin_host=True, pageable=args.staging > 0)
     H0 = torch.from_numpy(synth.ar1_tokens(64 + warmup + steps, shape.H, 0.8, seed=1, dtype="f32")).cuda()
     a, beta, cos = profile_gate_statistics(shape, routers, images_dev, taus, H0[:64], gamma)
     slots, plan_cost = B.cache_plan(L, shape.N, C, a, beta)
@@ -415,7 +545,8 @@ def bench_stack_offload(args):
     torch.cuda.empty_cache()
 
     ctx, cfg = B.adapmoe_create(shape.H, shape.F, shape.N, L, {"int4": B.INT4G64, "int2": B.INT2G64}.get(args.dtype, B.BF16),
-                                max_B=1, trace_capacity=0)
+                                max_B=1, trace_capacity=1 << 20)
+    apply_options(ctx, args)
     nbytes = B.adapmoe_expert_bytes(cfg)
     for l in range(L):
         B.adapmoe_set_router(ctx, l, routers[l])
@@ -425,6 +556,8 @@ def bench_stack_offload(args):
     B.cache_alloc(ctx, slots)
     if args.tiles:
         B.adapmoe_set_tiles(ctx, args.tiles)
+    if args.staging:
+        B.adapmoe_set_staging(ctx, args.staging, 8)
     B.adapmoe_set_lookahead(ctx, args.lookahead)
     t_setup = time.time() - t_setup
 
@@ -439,33 +572,64 @@ def bench_stack_offload(args):
 
     run(0, warmup)
     torch.cuda.synchronize()
+    B.adapmoe_trace_read(ctx, 1 << 20)          # drop the warm-up events
     c0 = B.adapmoe_counters(ctx)
+    B.adapmoe_profile(ctx, True)                # kernel durations of the timed steps (their sum = time the compute stream worked)
     t0 = time.perf_counter()
     run(warmup, steps)
     B.adapmoe_check(ctx, stream)
     t1 = time.perf_counter()
     c1 = B.adapmoe_counters(ctx)
+    compute_busy = sum(B.adapmoe_profile_read(ctx, c)[1] for c in (0, 1, 2)) * 1e-3
+    B.adapmoe_profile(ctx, False)
     elapsed = t1 - t0
     d = {k: c1[k] - c0[k] for k in c1}
     demand = d["hits"] + d["misses"] + d["bypasses"]
     h2d_gbs = d["h2d_bytes"] / elapsed / 1e9
+    # on-demand loads per token and layer, measured (cache events) against the planner's model f_{l,t_l} (Eq.15)
+    per_layer = np.zeros(L)
+    for (_t, l, kind, _e, _v, _s) in B.adapmoe_trace_read(ctx, 1 << 20):
+        if kind in ("MISS", "BYPASS"):
+            per_layer[l] += 1
+    per_layer /= steps
+    model = np.array([B.cache_cost(shape.N, slots[l], float(a[l]), float(beta[l])) for l in range(L)])
 
     # pinned-copy reference: the same 352 MB images copied back to back on one stream
     buf = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
     torch.cuda.synchronize()
     r0 = time.perf_counter()
+    ref_imgs = [images_host[i % L][i % shape.N] for i in range(8)]
+    if args.staging:      # the link's rate is a property of pinned memory: copy one image into a pinned buffer and send that
+        pinned = torch.empty(images_host[0][0].numel(), dtype=images_host[0][0].dtype, pin_memory=True)
+        pinned.copy_(images_host[0][0])
+        ref_imgs = [pinned] * 8
+        buf.view(pinned.dtype).copy_(pinned, non_blocking=True)
+        torch.cuda.synchronize()
+        r0 = time.perf_counter()
     for i in range(8):
-        buf.view(images_host[0][0].dtype).copy_(images_host[i % L][i % shape.N], non_blocking=True)
+        buf.view(images_host[0][0].dtype).copy_(ref_imgs[i], non_blocking=True)
     torch.cuda.synchronize()
     link_gbs = 8 * nbytes / (time.perf_counter() - r0) / 1e9
+    copy_busy = d["h2d_bytes"] / (link_gbs * 1e9)            # time the side stream needs for the copies at the link's rate
+    # time during which both streams worked: at least copy + compute - elapsed, at most the shorter of the two
+    overlap_lo = max(0.0, min(copy_busy, compute_busy, copy_busy + compute_busy - elapsed))
+    overlap_hi = min(copy_busy, compute_busy)
+    served = d["hits_after_prefetch"] + d["misses"] + d["bypasses"]
+    # CPU baseline: the checker's stack on the same tokens (expert images read back from pinned memory), compute only
+    class _HostImages:
+        def __getitem__(self, l):
+            return [images_host[l][e] for e in range(shape.N)]
+    cpu = (cpu_baseline_stack(shape, routers, _HostImages(), taus, H0[64 + warmup:].cpu().numpy(), gamma, min(args.cpu_seconds, 12.0),
+                              2 if int4 else 8, "the timed stream, no transfers on the CPU side") if args.cpu_seconds > 0 else None)
 
     out = {
         "metric": METRIC, "value": round(steps / elapsed, 3), "unit": f"tokens/s ({L}-layer stack, batch 1, offloaded experts)",
         "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(elapsed / steps * 1e3, 3),
         "us_per_layer": round(elapsed / steps / L * 1e6, 1),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
-        "config": {"workload": f"mixtral_stack_offload ({args.dtype}): H=4096 F=14336 N=8 L={L}, {L * 8} experts ({L * 8 * nbytes / 1e9:.1f} GB) in pinned "
-                               f"host memory, cache of {C} slots sized by the planner, LRU + prefetch {args.lookahead} layer(s) ahead, "
+        "config": {"workload": f"mixtral_stack_offload ({args.dtype}): H=4096 F=14336 N=8 L={L}, {L * 8} experts ({L * 8 * nbytes / 1e9:.1f} GB) in "
+                               + (f"pageable host memory staged through {args.staging} pinned buffers" if args.staging else "pinned host memory")
+                               + f", cache of {C} slots sized by the planner, LRU + prefetch {args.lookahead} layer(s) ahead, "
                                f"{'tile-wise loading (' + str(args.tiles) + ' tiles)' if args.tiles else 'whole-image loading'}, gamma={gamma}",
                    "slots_per_layer": slots, "planner_cost": round(plan_cost, 4),
                    "a_l_mean": round(float(a.mean()), 4), "beta_l_mean": round(float(beta[1:].mean()), 4) if L > 1 else None,
@@ -479,8 +643,23 @@ def bench_stack_offload(args):
                   "single_expert_ratio": round(d["single_expert"] / max(d["tokens_gated"], 1), 4),
                   "h2d_GB": round(d["h2d_bytes"] / 1e9, 2),
                   "loads_per_token": round((d["misses"] + d["bypasses"] + d["prefetch_loads"]) / steps, 2),
+                  "prefetch_landed_outside_budget": d["prefetch_landed"],
                   "experts_evaluated_tile_wise": d["tiled_ffn"]},
-        "cpu_baseline": None,
+        "on_demand_loads_per_token": {"planner_model": round(float(model.sum()), 3), "measured": round(float(per_layer.sum()), 3),
+                                      "per_layer_planner": [round(float(v), 3) for v in model],
+                                      "per_layer_measured": [round(float(v), 3) for v in per_layer],
+                                      "note": "model = sum of f_{l,t_l} (Eq.15) with the profiled a_l, beta_l; it takes the cached set "
+                                              "for a random one, LRU with routing locality does better"},
+        "overlap": {"copy_busy_s": round(copy_busy, 4), "compute_busy_s": round(compute_busy, 4), "elapsed_s": round(elapsed, 4),
+                    "both_streams_busy_s": [round(overlap_lo, 4), round(overlap_hi, 4)],
+                    "frac_of_copy_time_hidden_behind_compute": [round(overlap_lo / max(copy_busy, 1e-9), 4), round(overlap_hi / max(copy_busy, 1e-9), 4)],
+                    "frac_of_loaded_demands_transferred_ahead_of_time": round(d["hits_after_prefetch"] / max(served, 1), 4),
+                    "note": "copy_busy = bytes / measured link rate; compute_busy = sum of kernel durations; the time both streams "
+                            "worked lies between copy + compute - elapsed and the shorter of the two (pairs are lower, upper bound). "
+                            "The link is the bottleneck here: compute is a few percent of the time, so what prefetch hides is the "
+                            "wait of a demand, counted as the share of experts that had to come over the link and were already "
+                            "there when demanded"},
+        "cpu_baseline": cpu,
     }
     torch.cuda.synchronize()
     B.adapmoe_destroy(ctx)
@@ -489,7 +668,17 @@ def bench_stack_offload(args):
 
 # --------------------------------------------------------------------------- batched, resident ----
 
-def bench_batched(args):
+def shared_stack(shape, shared):
+    """Routers and device images of the 32-layer bf16 stack, built once for the workloads that share them."""
+    key = (shape.H, shape.F, shape.N, shape.L, shape.dtype)
+    if shared is None:
+        return build_stack(shape, 0, keep_on_device=True, pin_host=False)[:2]
+    if key not in shared:
+        shared[key] = build_stack(shape, 0, keep_on_device=True, pin_host=False)[:2]
+    return shared[key]
+
+
+def bench_batched(args, shared=None):
     import numpy as np
     import torch
 
@@ -504,8 +693,9 @@ def bench_batched(args):
     gamma = 0.3
     taus = synth.tau_profile(L)
     t_setup = time.time()
-    routers, images_dev, _ = build_stack(shape, 0, keep_on_device=True, pin_host=False)
+    routers, images_dev = shared_stack(shape, shared)
     ctx, cfg = B.adapmoe_create(shape.H, shape.F, shape.N, L, B.BF16, max_B=Bt)
+    apply_options(ctx, args)
     nbytes = B.adapmoe_expert_bytes(cfg)
     for l in range(L):
         B.adapmoe_set_router(ctx, l, routers[l])
@@ -533,18 +723,36 @@ def bench_batched(args):
     elapsed = time.perf_counter() - t0
     B.adapmoe_check(ctx)
 
+    # instrumented pass: kernel durations from events tied to the dispatches, and the gate decisions of every
+    # layer step (decision log), which give the experts each launch really streamed and the pairs it really computed
+    n_prof = min(steps, 16)
+    logbuf = torch.zeros((n_prof * L, 6 * Bt), dtype=torch.int32, device="cuda")
+    B.adapmoe_set_decision_log(ctx, logbuf, n_prof * L)
     B.adapmoe_profile(ctx, True)
-    run(warmup, min(steps, 16))
+    run(warmup, n_prof)
     torch.cuda.synchronize()
     prof = {c: B.adapmoe_profile_read(ctx, c) for c in (2, 3, 4, 5)}
     B.adapmoe_profile(ctx, False)
-    # bytes: the kernels of one launch stream every touched expert once; 7.9 of 8 are touched on average,
-    # counted here as all 8 only if the launch count says so -> use the measured average below
+    B.adapmoe_set_decision_log(ctx, None, 0)
+    ids, kk = read_decisions(ctx, logbuf, n_prof * L, Bt, Bt)
+    touched = pairs = 0
+    for r in range(n_prof * L):
+        act = set()
+        for b in range(Bt):
+            act.update(int(e) for e in ids[r, b, :kk[r, b]])
+        touched += len(act)
+        pairs += int(kk[r].sum())
+    touched /= n_prof * L          # experts streamed per layer step
+    pairs /= n_prof * L            # (token, expert) pairs per layer step
     n_l = prof[4][0]
     per_matrix = nbytes / 3.0
-    # touched experts are not known on the host on this path: bound the achieved figure from below with 7 experts
     gu_us = prof[4][1] / max(n_l, 1) * 1e3
     dn_us = prof[5][1] / max(prof[5][0], 1) * 1e3
+    gu_gbs = touched * 2 * per_matrix / (gu_us * 1e-6) / 1e9
+    own_flops = pairs * 2 * 3 * shape.H * shape.F          # multiply-adds of the method itself, both GEMMs
+    issued_flops = touched * 16 * 2 * 3 * shape.H * shape.F  # what the 16-column matrix instructions execute
+    cpu = (cpu_baseline_stack(shape, routers, images_dev, taus, Xs[warmup:, 0, :], gamma, args.cpu_seconds, 3, "stream 0 of the 16")
+           if args.cpu_seconds > 0 else None)
     out = {
         "metric": METRIC, "value": round(Bt * steps / elapsed, 2), "unit": f"tokens/s ({L}-layer stack, {Bt} decode streams per step)",
         "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(elapsed / steps * 1e3, 3),
@@ -552,18 +760,23 @@ def bench_batched(args):
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": f"mixtral_batched: H=4096 F=14336 N=8 L={L}, {Bt} AR(1) streams, experts resident in HBM "
                                f"({L * 8 * nbytes / 1e9:.1f} GB), MFMA grouped GEMM over tokens bucketed by expert, gamma={gamma}",
+                   "experts_streamed_per_layer_step": round(touched, 3), "token_expert_pairs_per_layer_step": round(pairs, 2),
                    "setup_s": round(t_setup, 1)},
-        "roofline": {"bound": "hbm", "kernel": "grouped_gateup_mfma_kernel", "achieved": round(8 * 2 * per_matrix / (gu_us * 1e-6) / 1e9, 1),
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(8 * 2 * per_matrix / (gu_us * 1e-6) / 1e9 / HBM_PEAK_GBS, 4),
+        "roofline": {"bound": "hbm", "kernel": "grouped_gateup_mfma_kernel", "achieved": round(gu_gbs, 1),
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gu_gbs / HBM_PEAK_GBS, 4),
                      "traffic": measured_traffic("grouped_gateup_mfma_kernel", "pmc_traffic_batched.json"),
                      "avg_us": round(gu_us, 1), "launches": n_l,
-                     "note": "bytes counted as all 8 experts of the layer per launch (7.9 are touched on average)"},
-        "kernels": {"grouped_down_mfma_kernel": {"avg_us": round(dn_us, 1), "achieved_GBs": round(8 * per_matrix / (dn_us * 1e-6) / 1e9, 1)},
+                     "bytes_per_launch": round(touched * 2 * per_matrix),
+                     "note": "bytes = W1 and W3 of the experts the launches really streamed (from the decision log)"},
+        "kernels": {"grouped_down_mfma_kernel": {"avg_us": round(dn_us, 1), "achieved_GBs": round(touched * per_matrix / (dn_us * 1e-6) / 1e9, 1)},
                     "bucket_gather_kernel": {"avg_us": round(prof[3][1] / max(prof[3][0], 1) * 1e3, 2)},
                     "gate_kernel": {"avg_us": round(prof[2][1] / max(prof[2][0], 1) * 1e3, 2)},
-                    "mfma_flops_per_layer_step": 2 * 3 * shape.H * shape.F * 16 * 8,
-                    "mfma_util_of_2.5PFLOPs": round(2 * 3 * shape.H * shape.F * 16 * 8 / ((gu_us + dn_us) * 1e-6) / 2.5e15, 4)},
-        "cpu_baseline": None,
+                    "mfma": {"own_flops_per_layer_step": round(own_flops), "issued_flops_per_layer_step": round(issued_flops),
+                             "util_own_of_2.5PFLOPs": round(own_flops / ((gu_us + dn_us) * 1e-6) / 2.5e15, 5),
+                             "util_issued_of_2.5PFLOPs": round(issued_flops / ((gu_us + dn_us) * 1e-6) / 2.5e15, 5),
+                             "note": "own = the (token, expert) pairs the gate activated; issued = 16 token columns per "
+                                     "streamed expert, the shape of the matrix instruction (most columns are padding)"}},
+        "cpu_baseline": cpu,
     }
     torch.cuda.synchronize()
     B.adapmoe_destroy(ctx)
@@ -572,7 +785,8 @@ def bench_batched(args):
 
 # --------------------------------------------------------------------------- batch 1, resident stack ----
 
-def bench_stack_resident(args):
+def bench_stack_resident(args, shared=None):
+    import numpy as np
     import torch
 
     from paper_2408_10284_amd import binding as B
@@ -585,15 +799,17 @@ def bench_stack_resident(args):
     gamma = 0.3
     taus = synth.tau_profile(L)
     t_setup = time.time()
-    routers, images_dev, _ = build_stack(shape, 0, keep_on_device=True, pin_host=False)
+    routers, images_dev = shared_stack(shape, shared)
     ctx, cfg = B.adapmoe_create(shape.H, shape.F, shape.N, L, B.BF16, max_B=1)
+    apply_options(ctx, args)
     nbytes = B.adapmoe_expert_bytes(cfg)
     for l in range(L):
         B.adapmoe_set_router(ctx, l, routers[l])
         for e in range(shape.N):
             B.adapmoe_bind_expert_dev(ctx, l, e, images_dev[l][e])
     B.adapmoe_set_tau(ctx, taus)
-    H0 = torch.from_numpy(synth.ar1_tokens(warmup + steps, shape.H, 0.8, seed=1, dtype="f32")).cuda()
+    H0_host = synth.ar1_tokens(warmup + steps, shape.H, 0.8, seed=1, dtype="f32")
+    H0 = torch.from_numpy(H0_host).cuda()
     t_setup = time.time() - t_setup
     x = torch.empty((1, shape.H), dtype=torch.bfloat16, device="cuda")
     y = torch.empty((1, shape.H), dtype=torch.float32, device="cuda")
@@ -631,21 +847,26 @@ def bench_stack_resident(args):
     elapsed = time.perf_counter() - t0
     B.adapmoe_check(ctx)
     graph_steps, graph = graph is not None, None      # the instrumented pass below runs eagerly
-    # the host does not see the decisions on this path (no round trip): the single-expert ratio comes from a
-    # separate pass over 16 of the tokens that reads the gate's outputs
-    a_l, _, _ = profile_gate_statistics(shape, routers, images_dev, taus, H0[warmup:warmup + 16], gamma)
-    single = float(a_l.mean())
 
+    # instrumented pass: kernel durations (events tied to the dispatches) and the k of every layer step (decision log)
+    n_prof = min(steps, 32)
+    logbuf = torch.zeros((n_prof * L, 6), dtype=torch.int32, device="cuda")
+    B.adapmoe_set_decision_log(ctx, logbuf, n_prof * L)
     B.adapmoe_profile(ctx, True)
-    run(warmup, min(steps, 32))
+    run(warmup, n_prof)
     torch.cuda.synchronize()
     n_gu, ms_gu = B.adapmoe_profile_read(ctx, 0)
     n_dn, ms_dn = B.adapmoe_profile_read(ctx, 1)
+    n_gt, ms_gt = B.adapmoe_profile_read(ctx, 2)
     B.adapmoe_profile(ctx, False)
-    mean_k = 2.0 - single
+    B.adapmoe_set_decision_log(ctx, None, 0)
+    _, kk = read_decisions(ctx, logbuf, n_prof * L, 1, 1)
+    mean_k = float(kk.mean())
     per_matrix = nbytes / 3.0
     gu_gbs = mean_k * 2 * per_matrix / (ms_gu / max(n_gu, 1) * 1e-3) / 1e9
     dn_gbs = mean_k * per_matrix / (ms_dn / max(n_dn, 1) * 1e-3) / 1e9
+    cpu = (cpu_baseline_stack(shape, routers, images_dev, taus, H0_host[warmup:], gamma, args.cpu_seconds, 8, "the timed stream")
+           if args.cpu_seconds > 0 else None)
     out = {
         "metric": METRIC, "value": round(steps / elapsed, 2), "unit": f"tokens/s ({L}-layer stack, batch 1, experts resident)",
         "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(elapsed / steps * 1e3, 3),
@@ -654,13 +875,16 @@ def bench_stack_resident(args):
         "config": {"workload": f"mixtral_stack_resident: H=4096 F=14336 N=8 L={L}, one AR(1) stream, experts resident in HBM "
                                f"({L * 8 * nbytes / 1e9:.1f} GB), residual + RMS norm between blocks, gamma={gamma}"
                                + (", one HIP graph replay per token" if graph_steps else ""),
-                   "single_expert_ratio": round(single, 4), "setup_s": round(t_setup, 1)},
+                   "mean_k": round(mean_k, 4), "single_expert_ratio": round(float((kk == 1).mean()), 4), "setup_s": round(t_setup, 1)},
         "roofline": {"bound": "hbm", "kernel": "ffn_gateup_kernel", "achieved": round(gu_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": round(gu_gbs / HBM_PEAK_GBS, 4), "traffic": None,
-                     "avg_us": round(ms_gu / max(n_gu, 1) * 1e3, 2), "launches": n_gu},
-        "kernels": {"down": {"achieved_GBs": round(dn_gbs, 1), "avg_us": round(ms_dn / max(n_dn, 1) * 1e3, 2)},
-                    "whole_step_GBs": round(mean_k * nbytes * L / (elapsed / steps) / 1e9, 1)},
-        "cpu_baseline": None,
+                     "avg_us": round(ms_gu / max(n_gu, 1) * 1e3, 2), "launches": n_gu,
+                     "bytes_per_launch": round(mean_k * 2 * per_matrix)},
+        "kernels": {"down": {"achieved_GBs": round(dn_gbs, 1), "frac": round(dn_gbs / HBM_PEAK_GBS, 4), "avg_us": round(ms_dn / max(n_dn, 1) * 1e3, 2)},
+                    "norm_gate": {"avg_us": round(ms_gt / max(n_gt, 1) * 1e3, 2)},
+                    "whole_step_GBs": round(mean_k * nbytes * L / (elapsed / steps) / 1e9, 1),
+                    "whole_step_frac": round(mean_k * nbytes * L / (elapsed / steps) / 1e9 / HBM_PEAK_GBS, 4)},
+        "cpu_baseline": cpu,
     }
     torch.cuda.synchronize()
     B.adapmoe_destroy(ctx)

@@ -294,6 +294,16 @@ int adapmoe_set_first_layer_predictor(adapmoe_ctx* ctx, const void* Gpre_dev);
  * agree up to the order of the final additions.  Calls with B > 1 wait for whole images. */
 int adapmoe_set_tiles(adapmoe_ctx* ctx, int tiles);
 
+/* Expert images in pageable host memory (Alg.1's transfer queue with the host copy as an extra
+ * stage; for stacks larger than the process may pin).  buffers >= 2 (at most 16): every load is
+ * served by a worker thread of the library, in request order: it copies the registered image into
+ * one of `buffers` pinned buffers of one image each (owned by the library; `host_threads` threads
+ * share the copy, 0 = 6) and sends it from there to its slot on the side stream, so the host copy of
+ * one image runs while the previous one crosses the link.  Cache decisions, events and results are
+ * unchanged; tile-wise loading is not used for staged copies.  buffers = 0 switches staging off
+ * (images are then read directly and should be pinned).  Call between layer steps. */
+int adapmoe_set_staging(adapmoe_ctx* ctx, int buffers, int host_threads);
+
 /* Look-ahead depth of moe_layer_step, 1..3 (default 1) (Sec. 4.3, prefetch beyond the next layer).
  * With depth D the gate launch also applies the routers of layers l+2 .. l+D to the
  * same input.  The prediction for layer l+d (d >= 2) is acted on only when every
@@ -319,8 +329,14 @@ enum {
   ADAPMOE_OPT_DYN_PCT = 3,         /* percent of the gate/up GEMV's row passes handed out dynamically, 0..100 (default 20) */
   ADAPMOE_OPT_GATEUP_BLOCKS = 4,   /* workgroups of the gate/up GEMV, 1..65535 */
   ADAPMOE_OPT_DOWN_BLOCKS = 5,     /* workgroups of the fp32/bf16 down GEMV, 1..65535 */
-  ADAPMOE_OPT_BATCH_DIRECT = 6     /* batched gate/up GEMM: wavefronts load their token operand themselves (1, default) or the
+  ADAPMOE_OPT_BATCH_DIRECT = 6,    /* batched gate/up GEMM: wavefronts load their token operand themselves (1, default) or the
                                       workgroup stages it through LDS (0) */
+  ADAPMOE_OPT_POISON_SLOTS = 7     /* debugging aid for the ordering of copies and kernels (default 0): 1 fills a cache slot
+                                      with all-ones bytes (not-a-number in every storage type, scales and zeros of the
+                                      quantised types included) on the side stream right before each copy into it, so that a
+                                      kernel reading the slot before its copy has landed, or a copy starting while a kernel
+                                      still reads the slot's previous expert, shows up as non-finite output instead of as
+                                      plausible numbers.  Costs one fill per load. */
 };
 int adapmoe_set_option(adapmoe_ctx* ctx, int option, int value);
 int adapmoe_get_option(adapmoe_ctx* ctx, int option, int* value_out);

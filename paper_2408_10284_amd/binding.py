@@ -14,7 +14,7 @@ LIB_PATH = os.path.join(_HERE, "libadapmoe.so")
 OK, EINVAL, ENOMEM, ENOTREG, ENORES, EHIP, ESTATE = 0, -1, -2, -3, -4, -5, -6
 F32, BF16, INT4G64, INT2G64 = 0, 1, 2, 3
 EVENT_KINDS = ("HIT", "HIT_PF", "MISS", "BYPASS", "PF_TOUCH", "PF_LOAD", "PF_LAND")
-OPT_BATCH_MIN, OPT_BATCH_TWO_TERMS, OPT_FUSED, OPT_DYN_PCT, OPT_GATEUP_BLOCKS, OPT_DOWN_BLOCKS, OPT_BATCH_DIRECT = range(7)
+OPT_BATCH_MIN, OPT_BATCH_TWO_TERMS, OPT_FUSED, OPT_DYN_PCT, OPT_GATEUP_BLOCKS, OPT_DOWN_BLOCKS, OPT_BATCH_DIRECT, OPT_POISON_SLOTS = range(8)
 
 
 class Config(C.Structure):
@@ -73,6 +73,7 @@ _SIGS = {
     "moe_stack_token": (C.c_int, [_P, C.c_int, _P, _P, _P, C.c_int, C.c_float, _P]),
     "adapmoe_set_first_layer_predictor": (C.c_int, [_P, _P]),
     "adapmoe_set_tiles": (C.c_int, [_P, C.c_int]),
+    "adapmoe_set_staging": (C.c_int, [_P, C.c_int, C.c_int]),
     "adapmoe_set_lookahead": (C.c_int, [_P, C.c_int]),
     "adapmoe_last_lookahead": (C.c_int, [_P, C.c_int, C.POINTER(C.c_int32), C.POINTER(C.c_int32), C.c_int]),
     "adapmoe_set_token": (C.c_int, [_P, C.c_int]),
@@ -351,6 +352,10 @@ def adapmoe_get_option(ctx, option):
     v = C.c_int()
     _chk(ctx, load().adapmoe_get_option(ctx, int(option), C.byref(v)))
     return v.value
+
+
+def adapmoe_set_staging(ctx, buffers, host_threads=0):
+    _chk(ctx, load().adapmoe_set_staging(ctx, int(buffers), int(host_threads)))
 
 
 def adapmoe_set_tiles(ctx, tiles):

@@ -2,7 +2,9 @@
 // demand loads and prefetch on a side stream, the cache-size planner, and the
 // C entry points declared in include/adapmoe.h.
 #include <algorithm>
+#include <atomic>
 #include <cmath>
+#include <condition_variable>
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
@@ -10,6 +12,7 @@
 #include <mutex>
 #include <new>
 #include <string>
+#include <thread>
 #include <vector>
 
 #include "../../include/adapmoe.h"
@@ -28,6 +31,7 @@ struct Slot {
   std::vector<hipEvent_t> tile_done;  // tile-wise copies: one event per tile, in transfer order (created on first use)
   bool tiled = false;              // the last copy into the slot was issued tile by tile
   uint64_t copy_seq = 0;           // position of the last copy in the side stream's order
+  uint64_t stage_seq = 0;          // staged copies: number of the request that fills the slot (0 = none)
 };
 
 struct Entry {
@@ -86,6 +90,34 @@ struct StepState {
   }
 };
 
+// Staging of expert images that live in pageable host memory (more experts than the machine lets a
+// process pin): a worker thread copies each requested image into one of a few pinned buffers and
+// from there to its slot on the side stream, so that the copy of image n+1 into a pinned buffer runs
+// while image n crosses the link (Alg.1's transfer queue and communication stream, with the host
+// copy as an extra stage).  Requests are served in order.
+struct StageBuf {
+  char* host = nullptr;
+  hipEvent_t done = nullptr;   // the transfer out of this buffer has finished
+  bool used = false;
+};
+struct CopyReq {
+  const void* src;
+  int slot;
+  bool wait_read;              // the slot was read by a kernel: the transfer waits for its read_done event
+};
+struct Stager {
+  std::thread worker;
+  std::mutex mu;
+  std::condition_variable cv_req, cv_done;
+  std::deque<CopyReq> queue;
+  bool stop = false;
+  uint64_t requested = 0, issued = 0;   // requests queued so far / requests whose transfer is on the side stream
+  hipError_t err = hipSuccess;
+  std::vector<StageBuf> bufs;
+  int next_buf = 0;
+  int threads = 6;                      // host threads that share one copy into a pinned buffer
+};
+
 }  // namespace
 
 struct adapmoe_ctx {
@@ -103,6 +135,8 @@ struct adapmoe_ctx {
   int lookahead = 1;                    // layers ahead that are predicted and prefetched (Sec. 4.3)
   const void* first_pred = nullptr;     // predictive gate for layer 0 of the following token (Sec. 4.3, Eq.9), device [N,H]
   int tiles = 0;                        // > 1: expert copies are cut into tiles and a waiting FFN runs tile by tile (Alg.1)
+  bool poison = false;                  // fill a slot with all-ones bytes before every copy into it (ordering check)
+  Stager* stager = nullptr;             // non-null: host images are pageable and go through pinned staging buffers
   uint64_t copy_seq = 0;
   float* d_w = nullptr;                 // [B,2]
   float* d_a = nullptr;                 // [B][2][a_stride]
@@ -272,7 +306,23 @@ int start_copy(adapmoe_ctx* c, int layer, int expert, int slot) {
   const void* src = c->host_image[(size_t)layer * c->cfg.N + expert];
   if (!src) return fail(c, ADAPMOE_ENOTREG, "expert has no registered host image");
   Slot& s = c->slots[slot];
+  if (c->stager) {   // the worker thread stages the image and puts the transfer on the side stream
+    Stager& st = *c->stager;
+    {
+      std::lock_guard<std::mutex> lk(st.mu);
+      if (st.err != hipSuccess) return fail(c, ADAPMOE_EHIP, std::string("staged copy: ") + hipGetErrorString(st.err));
+      st.queue.push_back(CopyReq{src, slot, s.was_read});
+      s.stage_seq = ++st.requested;
+    }
+    st.cv_req.notify_one();
+    s.tiled = false;
+    s.copy_pending = true;
+    s.copy_seq = ++c->copy_seq;
+    c->ctr.h2d_bytes += c->image_bytes;
+    return ADAPMOE_OK;
+  }
   if (s.was_read) HIPCHK(c, hipStreamWaitEvent(c->copy_stream, s.read_done, 0));
+  if (c->poison) HIPCHK(c, hipMemsetAsync(s.dev, 0xFF, c->image_bytes, c->copy_stream));
   s.tiled = c->tiles > 1;
   if (s.tiled) {
     // tiles in storage order: row-pair blocks of the interleaved W1/W3 part, then row blocks of W2
@@ -296,6 +346,89 @@ int start_copy(adapmoe_ctx* c, int layer, int expert, int slot) {
   s.copy_seq = ++c->copy_seq;
   c->ctr.h2d_bytes += c->image_bytes;
   return ADAPMOE_OK;
+}
+
+// Staged copies: blocks until the worker has put the transfer into `sl` on the side stream, so that
+// the slot's copy_done event stands for that transfer (an event that has not been recorded yet
+// would let a waiting stream through).
+int wait_issued(adapmoe_ctx* c, const Slot& sl) {
+  if (!c->stager || sl.stage_seq == 0) return ADAPMOE_OK;
+  Stager& st = *c->stager;
+  std::unique_lock<std::mutex> lk(st.mu);
+  st.cv_done.wait(lk, [&] { return st.issued >= sl.stage_seq || st.err != hipSuccess; });
+  if (st.err != hipSuccess) return fail(c, ADAPMOE_EHIP, std::string("staged copy: ") + hipGetErrorString(st.err));
+  return ADAPMOE_OK;
+}
+
+// Blocks until every requested staged copy is on the side stream.
+int drain_stager(adapmoe_ctx* c) {
+  if (!c->stager) return ADAPMOE_OK;
+  Stager& st = *c->stager;
+  std::unique_lock<std::mutex> lk(st.mu);
+  st.cv_done.wait(lk, [&] { return st.issued >= st.requested || st.err != hipSuccess; });
+  if (st.err != hipSuccess) return fail(c, ADAPMOE_EHIP, std::string("staged copy: ") + hipGetErrorString(st.err));
+  return ADAPMOE_OK;
+}
+
+void parallel_memcpy(char* dst, const char* src, size_t bytes, int threads) {
+  const size_t chunk = ((bytes + threads - 1) / threads + 4095) & ~(size_t)4095;
+  std::vector<std::thread> pool;
+  for (size_t off = chunk; off < bytes; off += chunk)
+    pool.emplace_back([=] { memcpy(dst + off, src + off, std::min(chunk, bytes - off)); });
+  memcpy(dst, src, std::min(chunk, bytes));
+  for (std::thread& t : pool) t.join();
+}
+
+void stager_main(adapmoe_ctx* c) {
+  Stager& st = *c->stager;
+  hipError_t e = hipSetDevice(c->cfg.device);
+  for (;;) {
+    CopyReq req;
+    {
+      std::unique_lock<std::mutex> lk(st.mu);
+      st.cv_req.wait(lk, [&] { return st.stop || !st.queue.empty(); });
+      if (st.queue.empty()) return;   // stop requested and nothing left
+      req = st.queue.front();
+      st.queue.pop_front();
+    }
+    StageBuf& b = st.bufs[st.next_buf];
+    st.next_buf = (st.next_buf + 1) % (int)st.bufs.size();
+    if (e == hipSuccess && b.used) e = hipEventSynchronize(b.done);   // the buffer's previous transfer has left it
+    if (e == hipSuccess) {
+      parallel_memcpy(b.host, static_cast<const char*>(req.src), c->image_bytes, st.threads);
+      Slot& s = c->slots[req.slot];
+      if (req.wait_read) e = hipStreamWaitEvent(c->copy_stream, s.read_done, 0);
+      if (e == hipSuccess && c->poison) e = hipMemsetAsync(s.dev, 0xFF, c->image_bytes, c->copy_stream);
+      if (e == hipSuccess) e = hipMemcpyAsync(s.dev, b.host, c->image_bytes, hipMemcpyHostToDevice, c->copy_stream);
+      if (e == hipSuccess) e = hipEventRecord(b.done, c->copy_stream);
+      if (e == hipSuccess) e = hipEventRecord(s.copy_done, c->copy_stream);
+      b.used = true;
+    }
+    {
+      std::lock_guard<std::mutex> lk(st.mu);
+      st.issued++;
+      if (e != hipSuccess && st.err == hipSuccess) st.err = e;
+    }
+    st.cv_done.notify_all();
+  }
+}
+
+void stop_stager(adapmoe_ctx* c) {
+  if (!c->stager) return;
+  Stager& st = *c->stager;
+  {
+    std::lock_guard<std::mutex> lk(st.mu);
+    st.stop = true;
+  }
+  st.cv_req.notify_all();
+  if (st.worker.joinable()) st.worker.join();
+  hipStreamSynchronize(c->copy_stream);
+  for (StageBuf& b : st.bufs) {
+    if (b.host) hipHostFree(b.host);
+    if (b.done) hipEventDestroy(b.done);
+  }
+  delete c->stager;
+  c->stager = nullptr;
 }
 
 void poke_later(adapmoe_ctx* c, int layer, int expert, const void* value) {
@@ -574,6 +707,10 @@ int launch_ffn_tiled(adapmoe_ctx* c, int layer, const void* x, int kk, const int
     p.accumulate = i > 0;
     Slot* sl = rank_slot[j] >= 0 ? &c->slots[rank_slot[j]] : nullptr;
     int rc;
+    if (sl && sl->copy_pending) {
+      rc = wait_issued(c, *sl);
+      if (rc) return rc;
+    }
     if (sl && sl->copy_pending && hipEventQuery(sl->copy_done) == hipSuccess) sl->copy_pending = false;  // already landed
     (void)hipGetLastError();  // hipErrorNotReady from the query is not an error
     if (sl && sl->copy_pending && sl->tiled) {
@@ -787,6 +924,8 @@ int wait_for_step_copies(adapmoe_ctx* c, hipStream_t s) {
   for (int slot : c->step.used_slots) {
     Slot& sl = c->slots[slot];
     if (sl.copy_pending) {
+      int rc = wait_issued(c, sl);
+      if (rc) return rc;
       HIPCHK(c, hipStreamWaitEvent(s, sl.copy_done, 0));
       sl.copy_pending = false;
     }
@@ -1042,6 +1181,7 @@ int adapmoe_create(const adapmoe_config* cfg, adapmoe_ctx** out) {
 int adapmoe_destroy(adapmoe_ctx* c) {
   if (!c) return ADAPMOE_EINVAL;
   hipSetDevice(c->cfg.device);
+  stop_stager(c);
   hipDeviceSynchronize();
   for (Slot& s : c->slots) {
     if (s.dev) hipFree(s.dev);
@@ -1256,6 +1396,8 @@ int moe_expert_ffn(adapmoe_ctx* c, int layer, const void* x, int B, const int32_
   };
   rc = each_entry([&](Slot& sl) -> int {
     if (sl.copy_pending) {
+      int r = wait_issued(c, sl);
+      if (r) return r;
       HIPCHK(c, hipStreamWaitEvent(s, sl.copy_done, 0));
       sl.copy_pending = false;
     }
@@ -1519,6 +1661,10 @@ int adapmoe_set_option(adapmoe_ctx* c, int option, int value) {
       if (value < 1 || value > 65535) return fail(c, ADAPMOE_EINVAL, "set_option: DOWN_BLOCKS is 1..65535");
       c->lc.down_blocks = value;
       return ADAPMOE_OK;
+    case ADAPMOE_OPT_POISON_SLOTS:
+      if (value != 0 && value != 1) return fail(c, ADAPMOE_EINVAL, "set_option: POISON_SLOTS is 0 or 1");
+      c->poison = value != 0;
+      return ADAPMOE_OK;
     case ADAPMOE_OPT_FUSED: {
       if (value == 0) {
         c->lc.fused_blocks = 0;
@@ -1560,9 +1706,39 @@ int adapmoe_get_option(adapmoe_ctx* c, int option, int* value_out) {
     case ADAPMOE_OPT_GATEUP_BLOCKS: *value_out = c->lc.gateup_blocks; break;
     case ADAPMOE_OPT_DOWN_BLOCKS: *value_out = c->lc.down_blocks; break;
     case ADAPMOE_OPT_FUSED: *value_out = c->lc.fused_blocks > 0 ? 1 : 0; break;
+    case ADAPMOE_OPT_POISON_SLOTS: *value_out = c->poison ? 1 : 0; break;
     default: return fail(c, ADAPMOE_EINVAL, "get_option: unknown option");
   }
   return ADAPMOE_OK;
+}
+
+int adapmoe_set_staging(adapmoe_ctx* c, int buffers, int host_threads) {
+  ABI_TRY
+  if (!c || buffers < 0 || buffers > 16 || host_threads < 0 || host_threads > 64) return fail(c, ADAPMOE_EINVAL, "set_staging: buffers 0..16, host threads 0..64");
+  if (c->step.open) return fail(c, ADAPMOE_ESTATE, "set_staging: a layer step is open");
+  HIPCHK(c, hipSetDevice(c->cfg.device));
+  if (c->stager) {
+    int rc = drain_stager(c);
+    if (rc) return rc;
+    stop_stager(c);
+  }
+  if (buffers == 0) return ADAPMOE_OK;
+  if (buffers < 2) return fail(c, ADAPMOE_EINVAL, "set_staging: at least two buffers (one fills while the other crosses the link)");
+  Stager* st = new Stager();
+  st->threads = host_threads > 0 ? host_threads : 6;
+  st->bufs.resize(buffers);
+  c->stager = st;
+  for (StageBuf& b : st->bufs) {
+    if (hipHostMalloc(reinterpret_cast<void**>(&b.host), c->image_bytes, hipHostMallocDefault) != hipSuccess ||
+        hipEventCreateWithFlags(&b.done, hipEventDisableTiming) != hipSuccess) {
+      (void)hipGetLastError();
+      stop_stager(c);
+      return fail(c, ADAPMOE_ENOMEM, "set_staging: pinned buffer allocation failed");
+    }
+  }
+  st->worker = std::thread(stager_main, c);
+  return ADAPMOE_OK;
+  ABI_CATCH(c)
 }
 
 int adapmoe_set_tiles(adapmoe_ctx* c, int tiles) {
@@ -1628,6 +1804,8 @@ int adapmoe_set_decision_log(adapmoe_ctx* c, int32_t* log_dev, int capacity) {
 int adapmoe_check(adapmoe_ctx* c, void* stream) {
   if (!c) return ADAPMOE_EINVAL;
   HIPCHK(c, hipStreamSynchronize(static_cast<hipStream_t>(stream)));
+  int drc = drain_stager(c);
+  if (drc) return drc;
   HIPCHK(c, hipStreamSynchronize(c->copy_stream));
   int32_t flags = 0;
   HIPCHK(c, hipMemcpy(&flags, c->d_err, sizeof(flags), hipMemcpyDeviceToHost));

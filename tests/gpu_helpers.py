@@ -24,7 +24,7 @@ class GpuLayerSet:
     """L layers of N experts: weights from synth, packed by the library, resident in HBM
     (bound) or registered as pinned host images."""
 
-    def __init__(self, shape, seed=0, max_B=1, trace_capacity=0, resident=True, taus=None):
+    def __init__(self, shape, seed=0, max_B=1, trace_capacity=0, resident=True, taus=None, expert_layers=None, pageable=False):
         self.shape = shape
         dt = {"f32": B.F32, "bf16": B.BF16, "int4g64": B.INT4G64, "int2g64": B.INT2G64}[shape.dtype]
         self.ctx, self.cfg = B.adapmoe_create(shape.H, shape.F, shape.N, shape.L, dt, max_B=max_B,
@@ -41,6 +41,9 @@ class GpuLayerSet:
             self.routers_dev.append(d)
             B.adapmoe_set_router(self.ctx, l, d)
             row = []
+            if expert_layers is not None and l not in expert_layers:     # router only (a layer that is just predicted for)
+                self.experts_f32.append(row)
+                continue
             for e in range(shape.N):
                 w1, w3, w2 = synth.expert_weights(shape, l, e, seed)
                 img = np.empty(self.nbytes, dtype=np.uint8)
@@ -61,7 +64,7 @@ class GpuLayerSet:
                     t = torch.from_numpy(img).cuda()
                     B.adapmoe_bind_expert_dev(self.ctx, l, e, t)
                 else:
-                    t = torch.from_numpy(img).pin_memory()
+                    t = torch.from_numpy(img) if pageable else torch.from_numpy(img).pin_memory()
                     B.adapmoe_register_expert(self.ctx, l, e, t, self.nbytes)
                 self.images.append(t)
             self.experts_f32.append(row)

@@ -249,7 +249,7 @@ def test_product_and_checker_do_not_touch_each_other():
     for node in tree.body:
         if isinstance(node, ast.FunctionDef):
             uses = [n for n in ast.walk(node) if isinstance(n, ast.ImportFrom) and n.module and n.module.startswith("oracle")]
-            assert not uses or node.name == "cpu_baseline_layer", node.name
+            assert not uses or node.name.startswith("cpu_baseline_"), node.name   # only the CPU-baseline legs touch the checker
     assert not [n for n in tree.body if isinstance(n, (ast.Import, ast.ImportFrom)) and "oracle" in ast.dump(n)]
 
 

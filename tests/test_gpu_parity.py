@@ -143,12 +143,14 @@ def test_nonresident_expert_is_reported_not_faulted():
     ("int2g64", 512, 4352, 8),    # W2 rows of 68 groups = one full block + 4 groups
     ("int2g64", 6144, 256, 3),    # x rows of 96 groups: two blocks
     ("int2g64", 256, 14336, 2),   # W2 rows of 224 groups
+    ("int4g64", 6144, 16384, 2),  # Mixtral-8x22B expert shape, 4-bit (the paper's 8x22B runs are quantised, Sec. 6.1, 6.3)
+    ("int2g64", 6144, 16384, 2),  # the same with 2-bit codes
 ])
 def test_shapes_gate_and_ffn(dtype, H, F, N):
     shape = synth.MoEShape(H=H, F=F, N=N, L=2, dtype=dtype)
-    ls = GpuLayerSet(shape, seed=3, max_B=4, taus=[0.25, 0.35])
+    ls = GpuLayerSet(shape, seed=3, max_B=4, taus=[0.25, 0.35], expert_layers=[0])   # layer 1 only lends its router
     try:
-        n = 22   # not a multiple of max_B
+        n = 22 if H * F < 5e7 else 6   # not a multiple of max_B
         X = synth.ar1_tokens(n, H, 0.8, seed=2, dtype=dtype)
         g = run_gate(ls, 0, X, with_pred=True)
         ref = OG.gate_batch(X, ls.routers_f32[0], np.float32(0.25))
@@ -225,6 +227,16 @@ def test_tile_wise_loading(dtype, slots, tiles):
     assert c["tiled_ffn"] > 0
 
 
+@pytest.mark.parametrize("dtype,slots,buffers", [("bf16", [2, 3, 1, 0], 2), ("int4g64", [1, 0, 2, 2], 3), ("f32", [0, 0, 0, 0], 2), ("bf16", [8, 8, 8, 8], 5)])
+def test_offloaded_stack_from_pageable_memory(dtype, slots, buffers):
+    """Expert images in pageable host memory, every load staged by the library's worker thread through a few pinned
+    buffers (Alg.1's transfer queue with the host copy as an extra stage): same cache trace as the checker's replay
+    and outputs within the bar, with every slot poisoned before each transfer so that a kernel running ahead of a
+    staged transfer would show."""
+    c = _offloaded_stack(dtype, slots, H=1024, F=2048, tiles=0, staging=buffers)
+    assert c["h2d_bytes"] > 0
+
+
 @pytest.mark.parametrize("dtype,slots", [("bf16", [2, 3, 1, 0]), ("bf16", [0, 2, 2, 2]), ("int4g64", [3, 3, 3, 3])])
 def test_first_layer_predictive_gate(dtype, slots):
     """Predictive gate for layer 0 (Sec. 4.3, Eq.9): applied to the last layer's input, decision equal to
@@ -233,12 +245,14 @@ def test_first_layer_predictive_gate(dtype, slots):
     assert c["prefetch_loads"] + c["prefetch_touches"] > 0
 
 
-def _offloaded_stack(dtype, slots, H, F, tiles, first_pred=False):
+def _offloaded_stack(dtype, slots, H, F, tiles, first_pred=False, staging=0):
     shape = synth.MoEShape(H=H, F=F, N=8, L=4, dtype=dtype)
     taus = [0.2, 0.3, 0.25, 0.35]
-    ls = GpuLayerSet(shape, seed=4, max_B=1, trace_capacity=1 << 16, resident=False, taus=taus)
+    ls = GpuLayerSet(shape, seed=4, max_B=1, trace_capacity=1 << 16, resident=False, taus=taus, pageable=staging > 0)
     try:
         B.cache_alloc(ls.ctx, slots)
+        if staging:
+            B.adapmoe_set_staging(ls.ctx, staging, 3)
         gpre_f32 = gpre_dev = None
         if first_pred:   # an untrained stand-in: the first router plus noise (training is outside this path)
             noise = synth.router_weights(shape, 0, seed=77)
@@ -252,6 +266,9 @@ def _offloaded_stack(dtype, slots, H, F, tiles, first_pred=False):
             B.adapmoe_set_first_layer_predictor(ls.ctx, gpre_dev)
         if tiles:
             B.adapmoe_set_tiles(ls.ctx, tiles)
+        # every copy is preceded by a fill of its slot with not-a-number patterns: a kernel that read a slot before
+        # its copy landed, or a copy that overtook the last reader of the slot's previous expert, would show in y
+        B.adapmoe_set_option(ls.ctx, B.OPT_POISON_SLOTS, 1)
         n_tok, gamma = 24, 0.5
         H0 = synth.ar1_tokens(n_tok, shape.H, 0.8, seed=9, dtype="f32") * 2.0
         decisions = []
@@ -289,7 +306,7 @@ def _offloaded_stack(dtype, slots, H, F, tiles, first_pred=False):
                 max_err = max(max_err, float(rel_err_per_token(y.cpu().numpy()[0], yref)))
                 B.moe_residual_rmsnorm(ls.ctx, h, y, gamma, x, 1)
         B.adapmoe_check(ls.ctx)
-        assert max_err <= TOL[dtype], max_err
+        assert np.isfinite(max_err) and max_err <= TOL[dtype], max_err
         sim = _replay_trace(slots, decisions, wrap=first_pred)
         got = [(t, l, kind, e, v) for (t, l, kind, e, v, _slot) in B.adapmoe_trace_read(ls.ctx)]
         assert got == [tuple(ev) for ev in sim.events]

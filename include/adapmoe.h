@@ -194,7 +194,7 @@ int cache_lookup(adapmoe_ctx* ctx, int layer, const int32_t* ids_host, int n, in
 
 /* ---- the block's steps ------------------------------------------------------ */
 
-/* Gate of `layer` on x (Eq.1, Eq.3-4, Eq.8): one wavefront per token computes
+/* Gate of `layer` on x (Eq.1, Eq.3-4, Eq.8): one workgroup per token computes
  * the N logits, the softmax, the two largest (ties: lower index), alpha and
  * the test (1-alpha) <= tau_layer.  Writes ids[b] = (e1,e2), k[b] in {1,2},
  * w[b] = (1,0) if k==1 else (alpha,1-alpha).  If pred_ids_dev/pred_k_dev are
@@ -326,7 +326,8 @@ enum {
                                       to bfloat16 (0, default) */
   ADAPMOE_OPT_FUSED = 2,           /* 1: single-token steps on fp32/bf16 experts run both GEMVs in one launch joined by a bounded
                                       grid-wide barrier (slower on MI355X, default 0); ADAPMOE_ESTATE if the shape does not fit */
-  ADAPMOE_OPT_DYN_PCT = 3,         /* percent of the gate/up GEMV's row passes handed out dynamically, 0..100 (default 20) */
+  ADAPMOE_OPT_DYN_PCT = 3,         /* percent of the gate/up GEMV's row passes handed out dynamically, 0..100 (default 20 for fp32/bf16
+                                      experts, 0 for quantised ones) */
   ADAPMOE_OPT_GATEUP_BLOCKS = 4,   /* workgroups of the gate/up GEMV, 1..65535 */
   ADAPMOE_OPT_DOWN_BLOCKS = 5,     /* workgroups of the fp32/bf16 down GEMV, 1..65535 */
   ADAPMOE_OPT_BATCH_DIRECT = 6,    /* batched gate/up GEMM: wavefronts load their token operand themselves (1, default) or the

@@ -67,6 +67,38 @@ __device__ __forceinline__ float wave_sum(float v) {
   return (r0 + r1) + (r2 + r3);
 }
 
+// A pointer that is the same in every lane, moved into scalar registers: addresses derived from it
+// with wavefront-uniform offsets are then computed on the scalar unit, and loads take the form
+// "scalar base + 32-bit lane offset" instead of a 64-bit address per lane.
+__device__ __forceinline__ const char* uniform_ptr(const void* p) {
+  const uint64_t u = reinterpret_cast<uint64_t>(p);
+  const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)u), hi = __builtin_amdgcn_readfirstlane((uint32_t)(u >> 32));
+  return reinterpret_cast<const char*>(((uint64_t)hi << 32) | lo);
+}
+
+// Sums of two values over the 64 lanes at once: returns sum(g) in lanes 0..31 and sum(u) in lanes
+// 32..63.  v_permlane32_swap exchanges the upper half of its first operand with the lower half of
+// its second, so one swap and one add leave 32 partial sums of g in the lower and of u in the upper
+// half; four DPP steps sum inside rows of 16 lanes and a row swap adds neighbouring rows.  11
+// instructions for both sums (the order of additions is fixed).
+typedef unsigned u32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ float pair_sum(float g, float u) {
+  const u32x2_t h = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(unsigned, g), __builtin_bit_cast(unsigned, u), false, false);
+  float v = __builtin_bit_cast(float, h.x) + __builtin_bit_cast(float, h.y);
+  v += dpp_f32<kDppQuadSwap1>(v);
+  v += dpp_f32<kDppQuadSwap2>(v);
+  v += dpp_f32<kDppRowHalfMirror>(v);
+  v += dpp_f32<kDppRowMirror>(v);
+  const u32x2_t r = __builtin_amdgcn_permlane16_swap(__builtin_bit_cast(unsigned, v), __builtin_bit_cast(unsigned, v), false, false);
+  return __builtin_bit_cast(float, r.x) + __builtin_bit_cast(float, r.y);
+}
+// lane l (< 32) gets the value of lane l + 32 and the other way round
+__device__ __forceinline__ float swap_halves(float v) {
+  const u32x2_t h = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(unsigned, v), __builtin_bit_cast(unsigned, v), false, false);
+  // h.x = (lower, lower), h.y = (upper, upper)
+  return (threadIdx.x & 32) ? __builtin_bit_cast(float, h.x) : __builtin_bit_cast(float, h.y);
+}
+
 __device__ __forceinline__ float wave_max(float v) {
   v = fmaxf(v, dpp_f32<kDppQuadSwap1>(v));
   v = fmaxf(v, dpp_f32<kDppQuadSwap2>(v));

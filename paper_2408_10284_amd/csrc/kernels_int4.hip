@@ -86,16 +86,11 @@ __device__ __forceinline__ float dot2_f16(uint32_t a, uint32_t b, float acc) {
 
 __device__ __forceinline__ uint32_t pick(const uint4& v, int c) { return c == 0 ? v.x : c == 1 ? v.y : c == 2 ? v.z : v.w; }
 
-// Accumulators of one group: [class][which copy of the dword: as loaded / shifted down by 8]
+// Accumulators of one group, one per class.
 template <int BITS>
 struct QAcc {
-  float v[QTraits<BITS>::NC][2];
+  float v[QTraits<BITS>::NC];
 };
-template <int BITS>
-__device__ __forceinline__ void q_acc_clear(QAcc<BITS>& a) {
-#pragma unroll
-  for (int c = 0; c < QTraits<BITS>::NC; ++c) a.v[c][0] = a.v[c][1] = 0.f;
-}
 
 // One 16-byte vector of codes against the matching activations (packed half pairs):
 // 4-bit: 32 codes, x[0..3] (dword d meets x[d]: pairs .x .y .z .w are its nibble positions 0..3);
@@ -108,25 +103,26 @@ __device__ __forceinline__ void dot_codes16(const uint4& c, const uint4* x, QAcc
     const uint32_t t = w[d] >> 8;
     if constexpr (BITS == 4) {
       const uint4 xv = x[d];
-      acc.v[0][0] = dot2_f16((w[d] & k.mask[0]) | k.magic, xv.x, acc.v[0][0]);
-      acc.v[1][0] = dot2_f16((w[d] & k.mask[1]) | k.magic, xv.y, acc.v[1][0]);
-      acc.v[0][1] = dot2_f16((t & k.mask[0]) | k.magic, xv.z, acc.v[0][1]);
-      acc.v[1][1] = dot2_f16((t & k.mask[1]) | k.magic, xv.w, acc.v[1][1]);
+      acc.v[0] = dot2_f16((w[d] & k.mask[0]) | k.magic, xv.x, acc.v[0]);
+      acc.v[1] = dot2_f16((w[d] & k.mask[1]) | k.magic, xv.y, acc.v[1]);
+      acc.v[0] = dot2_f16((t & k.mask[0]) | k.magic, xv.z, acc.v[0]);
+      acc.v[1] = dot2_f16((t & k.mask[1]) | k.magic, xv.w, acc.v[1]);
     } else {
       const uint4 xa = x[2 * d], xb = x[2 * d + 1];
 #pragma unroll
       for (int cl = 0; cl < 4; ++cl) {
-        acc.v[cl][0] = dot2_f16((w[d] & k.mask[cl]) | k.magic, pick(xa, cl), acc.v[cl][0]);
-        acc.v[cl][1] = dot2_f16((t & k.mask[cl]) | k.magic, pick(xb, cl), acc.v[cl][1]);
+        acc.v[cl] = dot2_f16((w[d] & k.mask[cl]) | k.magic, pick(xa, cl), acc.v[cl]);
+        acc.v[cl] = dot2_f16((t & k.mask[cl]) | k.magic, pick(xb, cl), acc.v[cl]);
       }
     }
   }
 }
 
 // What a group's activations contribute besides the code products: xsum = sum of its 64 values,
-// xq = 1024 * sum_p 2^-p xs_p (the offsets that the mantissa trick adds, see the file comment).
+// nxq = -1024 * sum_p 2^-p xs_p (minus the offsets that the mantissa trick adds, see the file
+// comment; the accumulator of class 0 starts from it).
 struct GroupSums {
-  float xsum, xq;
+  float xsum, nxq;
 };
 // x: the group's 64 halves as 8 vectors of packed pairs.  In both formats component c of every vector
 // meets class c mod NC.
@@ -143,8 +139,8 @@ __device__ __forceinline__ GroupSums group_sums(const uint4* x) {
   }
   GroupSums g;
   g.xsum = (s[0] + s[1]) + (s[2] + s[3]);
-  if constexpr (BITS == 4) g.xq = 1024.f * ((s[0] + s[2]) + 0.0625f * (s[1] + s[3]));
-  else g.xq = 1024.f * ((s[0] + 0.25f * s[1]) + (0.0625f * s[2] + 0.015625f * s[3]));
+  if constexpr (BITS == 4) g.nxq = -1024.f * ((s[0] + s[2]) + 0.0625f * (s[1] + s[3]));
+  else g.nxq = -1024.f * ((s[0] + 0.25f * s[1]) + (0.0625f * s[2] + 0.015625f * s[3]));
   return g;
 }
 
@@ -154,25 +150,34 @@ struct QGroup {  // what one lane holds of one row block: its group's codes (BIT
   uint32_t sz;
 };
 
-// lane's share of block `blk` (nb groups) of the row starting at `row`.  Lanes
-// beyond nb re-read the block's last group (no branch around the loads, so the
-// compiler can count outstanding loads exactly); q_group_dot ignores them.
-template <int BITS>
-__device__ __forceinline__ void q_load_group(const char* row, int n, int blk, int lane, QGroup<BITS>& g) {
-  const int G = n >> 6;
-  const int nb = min(64, G - blk * 64);
+// Byte offsets of a lane inside a row block of nb groups: its 16-byte code vectors and its
+// (scale, zero) pair.  Lanes beyond nb take the block's last group (no branch around the loads, so
+// the compiler can count outstanding loads exactly); their activations are zero, so they add nothing.
+struct LaneOff {
+  uint32_t c16, s4;
+};
+__device__ __forceinline__ LaneOff lane_off(int lane, int nb) {
   const int l = min(lane, nb - 1);
-  const char* cb = row + (size_t)blk * (64 * BITS * 8);
-#pragma unroll
-  for (int v = 0; v < BITS / 2; ++v) g.c[v] = load_stream16(cb + v * nb * 16 + l * 16);
-  g.sz = load_stream4(row + (size_t)n * BITS / 8 + (size_t)(blk * 64 + l) * 4);
+  return LaneOff{(uint32_t)l * 16u, (uint32_t)l * 4u};
 }
 
-// value of the lane's group: sum (q s + z) x
+// lane's share of block `blk` (nb groups) of the row starting at `row`.  `row`, n and blk are the
+// same for all lanes (the address is a scalar base plus the lane's 32-bit offset).
 template <int BITS>
-__device__ __forceinline__ float q_group_dot(const QGroup<BITS>& g, const uint4* x, const GroupSums& gs, const QConsts<BITS>& k, bool live) {
+__device__ __forceinline__ void q_load_group(const char* row, int n, int blk, int nb, const LaneOff& lo, QGroup<BITS>& g) {
+  const char* cb = row + (size_t)blk * (64 * BITS * 8);
+#pragma unroll
+  for (int v = 0; v < BITS / 2; ++v) g.c[v] = load_stream16(cb + (size_t)(v * nb * 16) + lo.c16);
+  g.sz = load_stream4(row + ((size_t)n * BITS / 8 + (size_t)blk * 256) + lo.s4);
+}
+
+// value of the lane's group: sum (q s + z) x.  Activations of lanes without a group must be zero.
+template <int BITS>
+__device__ __forceinline__ float q_group_dot(const QGroup<BITS>& g, const uint4* x, const GroupSums& gs, const QConsts<BITS>& k) {
   QAcc<BITS> acc;
-  q_acc_clear(acc);
+  acc.v[0] = gs.nxq;
+#pragma unroll
+  for (int c = 1; c < QTraits<BITS>::NC; ++c) acc.v[c] = 0.f;
   if constexpr (BITS == 4) {
     dot_codes16<4>(g.c[0], x, acc, k);
     dot_codes16<4>(g.c[1], x + 4, acc, k);
@@ -180,11 +185,10 @@ __device__ __forceinline__ float q_group_dot(const QGroup<BITS>& g, const uint4*
     dot_codes16<2>(g.c[0], x, acc, k);
   }
   float d;
-  if constexpr (BITS == 4) d = (acc.v[0][0] + acc.v[0][1]) + 0.0625f * (acc.v[1][0] + acc.v[1][1]);
-  else d = ((acc.v[0][0] + acc.v[0][1]) + 0.25f * (acc.v[1][0] + acc.v[1][1])) +
-           (0.0625f * (acc.v[2][0] + acc.v[2][1]) + 0.015625f * (acc.v[3][0] + acc.v[3][1]));
+  if constexpr (BITS == 4) d = fmaf(0.0625f, acc.v[1], acc.v[0]);
+  else d = fmaf(0.015625f, acc.v[3], fmaf(0.0625f, acc.v[2], fmaf(0.25f, acc.v[1], acc.v[0])));
   const float s = half_bits_to_float(g.sz & 0xffffu), z = half_bits_to_float(g.sz >> 16);
-  return live ? fmaf(s, d - gs.xq, z * gs.xsum) : 0.f;
+  return fmaf(s, d, z * gs.xsum);
 }
 
 // float -> half bits, round to nearest even, clamped to the finite range

@@ -81,22 +81,21 @@ __device__ __forceinline__ const char* uniform_ptr(const void* p) {
 // its second, so one swap and one add leave 32 partial sums of g in the lower and of u in the upper
 // half; four DPP steps sum inside rows of 16 lanes and a row swap adds neighbouring rows.  11
 // instructions for both sums (the order of additions is fixed).
-typedef unsigned u32x2_t __attribute__((ext_vector_type(2)));
 __device__ __forceinline__ float pair_sum(float g, float u) {
-  const u32x2_t h = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(unsigned, g), __builtin_bit_cast(unsigned, u), false, false);
-  float v = __builtin_bit_cast(float, h.x) + __builtin_bit_cast(float, h.y);
+  const auto h = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(unsigned, g), __builtin_bit_cast(unsigned, u), false, false);
+  float v = __builtin_bit_cast(float, (unsigned)h[0]) + __builtin_bit_cast(float, (unsigned)h[1]);
   v += dpp_f32<kDppQuadSwap1>(v);
   v += dpp_f32<kDppQuadSwap2>(v);
   v += dpp_f32<kDppRowHalfMirror>(v);
   v += dpp_f32<kDppRowMirror>(v);
-  const u32x2_t r = __builtin_amdgcn_permlane16_swap(__builtin_bit_cast(unsigned, v), __builtin_bit_cast(unsigned, v), false, false);
-  return __builtin_bit_cast(float, r.x) + __builtin_bit_cast(float, r.y);
+  const auto r = __builtin_amdgcn_permlane16_swap(__builtin_bit_cast(unsigned, v), __builtin_bit_cast(unsigned, v), false, false);
+  return __builtin_bit_cast(float, (unsigned)r[0]) + __builtin_bit_cast(float, (unsigned)r[1]);
 }
 // lane l (< 32) gets the value of lane l + 32 and the other way round
 __device__ __forceinline__ float swap_halves(float v) {
-  const u32x2_t h = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(unsigned, v), __builtin_bit_cast(unsigned, v), false, false);
-  // h.x = (lower, lower), h.y = (upper, upper)
-  return (threadIdx.x & 32) ? __builtin_bit_cast(float, h.x) : __builtin_bit_cast(float, h.y);
+  const auto h = __builtin_amdgcn_permlane32_swap(__builtin_bit_cast(unsigned, v), __builtin_bit_cast(unsigned, v), false, false);
+  // h[0] = (lower, lower), h[1] = (upper, upper)
+  return (threadIdx.x & 32) ? __builtin_bit_cast(float, (unsigned)h[0]) : __builtin_bit_cast(float, (unsigned)h[1]);
 }
 
 __device__ __forceinline__ float wave_max(float v) {

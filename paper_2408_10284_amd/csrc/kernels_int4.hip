@@ -165,10 +165,25 @@ __device__ __forceinline__ LaneOff lane_off(int lane, int nb) {
 // same for all lanes (the address is a scalar base plus the lane's 32-bit offset).
 template <int BITS>
 __device__ __forceinline__ void q_load_group(const char* row, int n, int blk, int nb, const LaneOff& lo, QGroup<BITS>& g) {
-  const char* cb = row + (size_t)blk * (64 * BITS * 8);
+  // every uniform part of an address is folded into a scalar base first (pinned to scalar registers
+  // by the empty asm statement), so that each load is "scalar base + the lane's 32-bit offset"
 #pragma unroll
-  for (int v = 0; v < BITS / 2; ++v) g.c[v] = load_stream16(cb + (size_t)(v * nb * 16) + lo.c16);
-  g.sz = load_stream4(row + ((size_t)n * BITS / 8 + (size_t)blk * 256) + lo.s4);
+  for (int v = 0; v < BITS / 2; ++v) {
+    const char* pv = row + ((size_t)blk * (64 * BITS * 8) + (size_t)(v * nb * 16));
+    asm volatile("" : "+s"(pv));
+    g.c[v] = load_stream16(pv + lo.c16);
+  }
+  const char* ps = row + ((size_t)n * BITS / 8 + (size_t)blk * 256);
+  asm volatile("" : "+s"(ps));
+  g.sz = load_stream4(ps + lo.s4);
+}
+
+// The lane offsets, opaque to the optimiser from here on: the instruction selector forms "scalar
+// base + 32-bit lane offset" addresses only if it sees the widening of the offset in the same block
+// as the load; a widening hoisted out of the streaming loop costs a 64-bit vector addition per load.
+__device__ __forceinline__ LaneOff fresh(LaneOff lo) {
+  asm volatile("" : "+v"(lo.c16), "+v"(lo.s4));
+  return lo;
 }
 
 // value of the lane's group: sum (q s + z) x.  Activations of lanes without a group must be zero.
@@ -219,7 +234,9 @@ struct I4RowPair {
 };
 
 // One wavefront per row pair; lane l owns group l (+64 per further block) of
-// both rows, its share of x stays in registers for the whole kernel.
+// both rows, its share of x stays in registers for the whole kernel.  Row numbers and row
+// addresses are wavefront-uniform and kept on the scalar unit: the kernel sits close to the
+// vector-ALU limit, so whatever is not arithmetic on the codes is kept off the vector unit.
 template <int BITS, int NBLK>
 __global__ __launch_bounds__(gateup_threads<NBLK>()) void ffn_gateup_quant_kernel(FfnArgs p) {
   constexpr int kI4GateUpThreads = gateup_threads<NBLK>();
@@ -232,8 +249,7 @@ __global__ __launch_bounds__(gateup_threads<NBLK>()) void ffn_gateup_quant_kerne
   // The lane's groups of x (as halves) and their sums.  x is read from global
   // memory in order (one 16-byte piece per thread), converted and turned through LDS:
   // piece j of group g goes to slot (block, j, lane = g % 64), which each lane
-  // then reads back without bank conflicts.  This runs after the first weight
-  // loads have been issued.
+  // then reads back without bank conflicts.  Lanes without a group get zeros.
   extern __shared__ uint4 xs[];
   uint4 x[NBLK][8];
   GroupSums xsum[NBLK];
@@ -274,7 +290,11 @@ __global__ __launch_bounds__(gateup_threads<NBLK>()) void ffn_gateup_quant_kerne
 
   const char* base[2];
   float wj[2];
-  const int kk = resolve_experts(p, b, base, wj);
+  // what resolve_experts returns was loaded per lane; told that it is the same in every lane, the
+  // compiler keeps everything derived from it (row counts, cursors, branches) on the scalar unit
+  const int kk = __builtin_amdgcn_readfirstlane(resolve_experts(p, b, base, wj));
+  base[0] = uniform_ptr(base[0]);
+  base[1] = uniform_ptr(base[1]);
   // resident activated experts taking part, rank order (written with selects: arrays indexed
   // with run-time values would live in scratch memory)
   const bool windowed = p.j_only >= 0;
@@ -285,7 +305,6 @@ __global__ __launch_bounds__(gateup_threads<NBLK>()) void ffn_gateup_quant_kerne
   const float rw[2] = {t0 ? wj[0] : wj[1], wj[1]};
   const int rj[2] = {t0 ? 0 : 1, 1};
 
-
   // rows are numbered r = (index among the taking-part experts) * F + f
   const int total = windowed ? (nv ? p.r1 : 0) : nv * F;
   const int stride = gridDim.x * (kI4GateUpThreads / kWave);
@@ -293,100 +312,66 @@ __global__ __launch_bounds__(gateup_threads<NBLK>()) void ffn_gateup_quant_kerne
   const int nrows = first < total ? (total - first + stride - 1) / stride : 0;
   uint16_t* a_out = reinterpret_cast<uint16_t*>(p.a + (size_t)b * 2 * p.a_stride);
 
-  auto load_row = [&](I4RowPair<BITS, NBLK>& buf, int r) {
+  // groups per block and the lane's offsets inside each block
+  int nbs[NBLK];
+  LaneOff lo[NBLK];
+#pragma unroll
+  for (int i = 0; i < NBLK; ++i) {
+    nbs[i] = min(64, (H >> 6) - i * 64);
+    lo[i] = lane_off(lane, nbs[i]);
+  }
+
+  auto load_row = [&](I4RowPair<BITS, NBLK>& buf, int r_any) {
+    const int r = __builtin_amdgcn_readfirstlane(r_any);   // the same in every lane: address arithmetic on the scalar unit
     const int j = r >= F ? 1 : 0;
     const char* row = pick2(rbase, j) + (size_t)(r - j * F) * 2 * rb;
 #pragma unroll
     for (int i = 0; i < NBLK; ++i) {
-      q_load_group(row, H, i, lane, buf.g1[i]);
-      q_load_group(row + rb, H, i, lane, buf.g3[i]);
+      const LaneOff l = fresh(lo[i]);
+      q_load_group(row, H, i, nbs[i], l, buf.g1[i]);
+      q_load_group(row + rb, H, i, nbs[i], l, buf.g3[i]);
     }
   };
-  // The two sums of a row pair are parked in lane `ns` of gv / uv (its row number in rv); SiLU, the
-  // product, the rounding and the store are then done for up to 64 row pairs at once, one per lane,
-  // instead of by the whole wavefront for every pair (the kernel is close to the vector-ALU limit).
-  float gv = 0.f, uv = 0.f;
-  int rv = 0, ns = 0;
+  // The two sums of a row pair come out of one joint reduction (gate sum in lanes 0..31, up sum in
+  // lanes 32..63) and are parked in lanes ns and ns + 32 of `parked`; SiLU, the product, the rounding
+  // and the store are then done for up to 32 row pairs at once, one per lane, instead of by the whole
+  // wavefront for every pair.  Parked pairs are consecutive rows of this wavefront: pair i of a batch
+  // is row rpark + i * stride.
+  float parked = 0.f;
+  int ns = 0, rpark = first;
+  const int lane31 = lane & 31;
   auto flush = [&]() {
+    const float other = swap_halves(parked);   // lanes < 32: the up sum of their pair
     if (lane < ns) {
+      const int rv = rpark + lane * stride;
       const int j = rv >= F ? 1 : 0;
       const int f = rv - j * F;
-      a_out[(size_t)pick2(rj, j) * 2 * p.a_stride + i4_a_pos(f)] = (uint16_t)f32_to_f16_bits(pick2(rw, j) * silu_f32(gv) * uv);
+      a_out[(size_t)pick2(rj, j) * 2 * p.a_stride + i4_a_pos(f)] = (uint16_t)f32_to_f16_bits(pick2(rw, j) * silu_f32(parked) * other);
     }
+    rpark += ns * stride;
     ns = 0;
   };
-  auto consume_row = [&](const I4RowPair<BITS, NBLK>& buf, int r) {
-    float g = 0.f, u = 0.f;
+  auto consume_row = [&](const I4RowPair<BITS, NBLK>& buf) {
+    float g = q_group_dot(buf.g1[0], x[0], xsum[0], kc), u = q_group_dot(buf.g3[0], x[0], xsum[0], kc);
 #pragma unroll
-    for (int i = 0; i < NBLK; ++i) {
-      g += q_group_dot(buf.g1[i], x[i], xsum[i], kc, i * 64 + lane < (H >> 6));
-      u += q_group_dot(buf.g3[i], x[i], xsum[i], kc, i * 64 + lane < (H >> 6));
+    for (int i = 1; i < NBLK; ++i) {
+      g += q_group_dot(buf.g1[i], x[i], xsum[i], kc);
+      u += q_group_dot(buf.g3[i], x[i], xsum[i], kc);
     }
-    g = wave_sum(g);
-    u = wave_sum(u);
-    gv = lane == ns ? g : gv;
-    uv = lane == ns ? u : uv;
-    rv = lane == ns ? r : rv;
-    if (++ns == kWave) flush();
+    const float s = pair_sum(g, u);
+    parked = lane31 == ns ? s : parked;
+    if (++ns == 32) flush();
   };
 
-  // Dynamic tail (see FfnArgs::dyn_ctr), an option that is off by default here: the wavefronts of a
-  // launch all have the same number of row pairs, yet they finish up to a factor of two apart (the
-  // memory system does not serve the compute units evenly), so the last passes over the grid can be
-  // drawn row by row from shared counters.  With only seven row pairs per wavefront at Mixtral size
-  // the round trip of each draw costs more than the balancing returns (22.2-23.4 against 21.5 us per
-  // launch).  The first two rows of a wavefront are always static: their loads are issued without
-  // conditions, which keeps the wait for x exact (see stream_bufs).
-  const int nfull = total / stride;
-  const int npool = nfull >= 2 ? max(1, (nfull * p.dyn_pct + 50) / 100) : nfull;
-  const int nstatic = nfull - npool;
-  if (p.dyn_ctr != nullptr && !windowed && nstatic >= 2) {
-    unsigned* ctr = p.dyn_ctr + (size_t)b * kDynQueues * kDynStride;
-    const int pool_start = nstatic * stride, pool_len = total - pool_start;
-    // queue q of nq holds pool rows pool_start + q + nq * t; workgroups 8m .. 8m+7 (one per
-    // compute-unit group under round-robin dispatch) share queue m % nq
-    const int nq = min(kDynQueues, (int)(gridDim.x + 7) >> 3);
-    const int q = (blockIdx.x >> 3) % nq;
-    const int qlen = (pool_len - q + nq - 1) / nq;
-    int it = 2;
-    bool pool_open = true;
-    auto next_row = [&]() -> int {
-      if (it < nstatic) return first + (it++) * stride;
-      if (!pool_open) return -1;
-      unsigned old = 0;
-      if (lane == 0) old = __hip_atomic_fetch_add(ctr + q * kDynStride, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      old = __builtin_amdgcn_readfirstlane(old);
-      if ((int)old < qlen) return pool_start + q + nq * (int)old;
-      pool_open = false;
-      return -1;
-    };
-    I4RowPair<BITS, NBLK> A, B;
-    int r0 = first, r1 = first + stride;
-    load_row(A, r0);
-    stage_x(sxv);
-    load_row(B, r1);
-    for (;;) {
-      consume_row(A, r0);
-      r0 = next_row();
-      if (r0 >= 0) load_row(A, r0);
-      if (r1 < 0) break;
-      consume_row(B, r1);
-      r1 = next_row();
-      if (r1 >= 0) load_row(B, r1);
-      if (r0 < 0) break;
-    }
-  } else {
-    int ra = first, rc = first;
-    auto load_next = [&](I4RowPair<BITS, NBLK>& buf, bool advance) {
-      load_row(buf, ra);
-      if (advance) ra += stride;
-    };
-    auto consume = [&](const I4RowPair<BITS, NBLK>& buf) {
-      consume_row(buf, rc);
-      rc += stride;
-    };
-    stream_bufs<I4RowPair<BITS, NBLK>, 1>(nrows, load_next, consume, [&, sxv]() { stage_x(sxv); });
-  }
+  // Rows are dealt out in advance, row first + i * stride to this wavefront.  (Drawing the last
+  // passes from shared counters, as the fp32/bf16 kernel does, was measured slower here in every
+  // form tried: a wavefront has only seven row pairs at Mixtral size and each draw costs a round trip.)
+  int ra = first;
+  auto load_next = [&](I4RowPair<BITS, NBLK>& buf, bool advance) {
+    load_row(buf, ra);
+    if (advance) ra += stride;
+  };
+  stream_bufs<I4RowPair<BITS, NBLK>, 1>(nrows, load_next, consume_row, [&, sxv]() { stage_x(sxv); });
   flush();
 }
 
@@ -448,7 +433,11 @@ __global__ __launch_bounds__(kQDownThreads) void ffn_down_quant_kernel(FfnArgs p
 
   const char* base[2];
   float wj[2];
-  const int kk = resolve_experts(p, b, base, wj);
+  // what resolve_experts returns was loaded per lane; told that it is the same in every lane, the
+  // compiler keeps everything derived from it (row counts, cursors, branches) on the scalar unit
+  const int kk = __builtin_amdgcn_readfirstlane(resolve_experts(p, b, base, wj));
+  base[0] = uniform_ptr(base[0]);
+  base[1] = uniform_ptr(base[1]);
   const size_t w2_off = (size_t)2 * F * q_row_bytes<BITS>(H);
   const bool windowed = p.j_only >= 0;
   // resident activated experts taking part, rank order (selects, not run-time-indexed arrays)
@@ -469,7 +458,14 @@ __global__ __launch_bounds__(kQDownThreads) void ffn_down_quant_kernel(FfnArgs p
 
   auto stage_finish = [&](const StageA& st) {
 #pragma unroll
-    for (int u = 0; u < kStage; ++u) as[min(tid + u * kQDownThreads, 2 * kAVecs - 1)] = st.v[u];
+    for (int u = 0; u < kStage; ++u) {
+      // vector i of a slot belongs to group (i / 512) * 64 + i % 64; groups beyond the row's G do not
+      // exist (the scratch vector holds old values there) and are staged as zeros
+      const int i = min(tid + u * kQDownThreads, 2 * kAVecs - 1);
+      const int iv = i >= kAVecs ? i - kAVecs : i;
+      const bool real = ((iv >> 9) << 6) + (iv & 63) < G;
+      as[i] = real ? st.v[u] : make_uint4(0, 0, 0, 0);
+    }
     lds_barrier();
     // two sums per group: thread t takes group t % (NBLK*64) of slot t / (NBLK*64)
     if (tid < 2 * NBLK * 64) {
@@ -483,15 +479,28 @@ __global__ __launch_bounds__(kQDownThreads) void ffn_down_quant_kernel(FfnArgs p
     lds_barrier();
   };
 
+  // The lane's offsets inside a full block and inside the row's last block (which may hold fewer
+  // than 64 groups).
+  const int nb_last = G - (NBLK - 1) * 64;
+  const LaneOff lo_full = lane_off(lane, 64), lo_last = lane_off(lane, nb_last);
+
   // The number of pieces per row is hidden from the optimiser: when it equals the four buffers of the
   // streamer the compiler specialises the loop body per piece and runs out of registers (spills).
   int np_rt = NP;
   asm volatile("" : "+s"(np_rt));
+  // Cursors are wavefront-uniform; the empty asm statements pin them to scalar registers so that row
+  // addresses are computed on the scalar unit and the loads take a scalar base plus the lane's offset.
   int ha = first, ja = 0, pa = 0;   // load cursor
   auto load_next = [&](QRow<BITS, PB>& buf, bool advance) {
+    asm volatile("" : "+s"(ha), "+s"(ja), "+s"(pa));
     const char* row = pick2(w2, ja) + (size_t)ha * rb;
 #pragma unroll
-    for (int i = 0; i < PB; ++i) q_load_group(row, F, pa * PB + i, lane, buf.g[i]);
+    for (int i = 0; i < PB; ++i) {
+      const int blk = pa * PB + i;
+      const bool last = blk == NBLK - 1;
+      const LaneOff lo = fresh(LaneOff{last ? lo_last.c16 : lo_full.c16, last ? lo_last.s4 : lo_full.s4});
+      q_load_group(row, F, blk, last ? nb_last : 64, lo, buf.g[i]);
+    }
     if (advance && ++pa == np_rt) {
       pa = 0;
       if (++ja == nv) { ja = 0; ha += hstride; }
@@ -500,15 +509,16 @@ __global__ __launch_bounds__(kQDownThreads) void ffn_down_quant_kernel(FfnArgs p
   int hc = first, jc = 0, pc = 0;   // consume cursor
   float acc = 0.f;
   auto consume = [&](const QRow<BITS, PB>& buf) {
+    asm volatile("" : "+s"(hc), "+s"(jc), "+s"(pc));
     const int slot = pick2(rj, jc);
-    const uint4* aj = as + slot * kAVecs + pc * (PB * 512) + lane;
-    const GroupSums* sj = sums + slot * (NBLK * 64) + pc * (PB * 64) + lane;
+    const uint4* aj = as + (slot * kAVecs + pc * (PB * 512)) + lane;
+    const GroupSums* sj = sums + (slot * (NBLK * 64) + pc * (PB * 64)) + lane;
 #pragma unroll
     for (int i = 0; i < PB; ++i) {
       uint4 a[8];
 #pragma unroll
       for (int c = 0; c < 8; ++c) a[c] = aj[(i * 8 + c) * 64];
-      acc += q_group_dot(buf.g[i], a, sj[i * 64], kc, (pc * PB + i) * 64 + lane < G);
+      acc += q_group_dot(buf.g[i], a, sj[i * 64], kc);
       __builtin_amdgcn_sched_barrier(0);   // one block at a time: hoisting the next block's LDS reads costs 32 registers
     }
     if (++pc == np_rt) {

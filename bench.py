@@ -762,9 +762,9 @@ def bench_batched(args, shared=None):
                                f"({L * 8 * nbytes / 1e9:.1f} GB), MFMA grouped GEMM over tokens bucketed by expert, gamma={gamma}",
                    "experts_streamed_per_layer_step": round(touched, 3), "token_expert_pairs_per_layer_step": round(pairs, 2),
                    "setup_s": round(t_setup, 1)},
-        "roofline": {"bound": "hbm", "kernel": "grouped_gateup_mfma_kernel", "achieved": round(gu_gbs, 1),
+        "roofline": {"bound": "hbm", "kernel": "grouped_gateup_stream_kernel", "achieved": round(gu_gbs, 1),
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gu_gbs / HBM_PEAK_GBS, 4),
-                     "traffic": measured_traffic("grouped_gateup_mfma_kernel", "pmc_traffic_batched.json"),
+                     "traffic": measured_traffic("grouped_gateup_stream_kernel", "pmc_traffic_batched.json"),
                      "avg_us": round(gu_us, 1), "launches": n_l,
                      "bytes_per_launch": round(touched * 2 * per_matrix),
                      "note": "bytes = W1 and W3 of the experts the launches really streamed (from the decision log)"},

@@ -326,12 +326,14 @@ enum {
                                       to bfloat16 (0, default) */
   ADAPMOE_OPT_FUSED = 2,           /* 1: single-token steps on fp32/bf16 experts run both GEMVs in one launch joined by a bounded
                                       grid-wide barrier (slower on MI355X, default 0); ADAPMOE_ESTATE if the shape does not fit */
-  ADAPMOE_OPT_DYN_PCT = 3,         /* percent of the gate/up GEMV's row passes handed out dynamically, 0..100 (default 20 for fp32/bf16
-                                      experts, 0 for quantised ones) */
+  ADAPMOE_OPT_DYN_PCT = 3,         /* percent of the gate/up GEMV's row passes handed out dynamically, 0..100 (default 20; fp32/bf16
+                                      experts only, the quantised kernels assign every row in advance) */
   ADAPMOE_OPT_GATEUP_BLOCKS = 4,   /* workgroups of the gate/up GEMV, 1..65535 */
   ADAPMOE_OPT_DOWN_BLOCKS = 5,     /* workgroups of the fp32/bf16 down GEMV, 1..65535 */
-  ADAPMOE_OPT_BATCH_DIRECT = 6,    /* batched gate/up GEMM: wavefronts load their token operand themselves (1, default) or the
-                                      workgroup stages it through LDS (0) */
+  ADAPMOE_OPT_BATCH_DIRECT = 6,    /* batched gate/up GEMM: 2 (default) one workgroup per compute unit, every wavefront streams
+                                      through its row tiles without a break; 1 one row tile per workgroup, wavefronts load their
+                                      token operand themselves; 0 one row tile per workgroup, operand staged through LDS.
+                                      Same results in all three. */
   ADAPMOE_OPT_POISON_SLOTS = 7     /* debugging aid for the ordering of copies and kernels (default 0): 1 fills a cache slot
                                       with all-ones bytes (not-a-number in every storage type, scales and zeros of the
                                       quantised types included) on the side stream right before each copy into it, so that a

@@ -149,6 +149,7 @@ struct adapmoe_ctx {
   int32_t* d_bkt_tok = nullptr;
   float* d_bkt_w = nullptr;
   const void** d_bkt_base = nullptr;
+  int32_t* d_bkt_active = nullptr;
   uint16_t* d_xop = nullptr;
   uint16_t* d_ahi = nullptr;
   uint16_t* d_alo = nullptr;
@@ -627,12 +628,13 @@ int launch_ffn(adapmoe_ctx* c, int layer, const void* x, int B, const int32_t* i
       q.bkt_tok = c->d_bkt_tok;
       q.bkt_w = c->d_bkt_w;
       q.bkt_base = c->d_bkt_base;
+      q.bkt_active = c->d_bkt_active;
       q.xop = c->d_xop;
       q.a_hi = c->d_ahi;
       q.a_lo = c->d_alo;
       q.two_terms = c->lc.batch_two_terms;
       HIPCHK(c, launch_bucket_gather(q, s, timed_cfg(c, 3).timing));
-      HIPCHK(c, launch_grouped_gateup(q, c->lc.batch_direct != 0, s, timed_cfg(c, 4).timing));
+      HIPCHK(c, launch_grouped_gateup(q, c->lc.batch_direct, s, timed_cfg(c, 4).timing));
       HIPCHK(c, launch_grouped_down(q, c->lc.batch_two_terms != 0, s, timed_cfg(c, 5).timing));
     }
     c->ctr.ffn_launches++;
@@ -1136,7 +1138,7 @@ int adapmoe_create(const adapmoe_config* cfg, adapmoe_ctx** out) {
   c->lc.down_blocks = 256;
   c->lc.batch_min = 3;
   c->lc.batch_two_terms = 0;
-  c->lc.batch_direct = 1;
+  c->lc.batch_direct = 2;
   c->lc.fused_blocks = 0;
   c->lc.dyn_pct = quant_bits(cfg->dtype) ? 0 : 20;   // quantised gate/up: measured 1 us slower per launch with a dynamic tail
   const int B = cfg->max_B;
@@ -1159,6 +1161,7 @@ int adapmoe_create(const adapmoe_config* cfg, adapmoe_ctx** out) {
     ok = ok && hipMalloc(&c->d_bkt_tok, N * 16 * sizeof(int32_t)) == hipSuccess;
     ok = ok && hipMalloc(&c->d_bkt_w, N * 16 * sizeof(float)) == hipSuccess;
     ok = ok && hipMalloc(&c->d_bkt_base, N * sizeof(void*)) == hipSuccess;
+    ok = ok && hipMalloc(&c->d_bkt_active, (N + 1) * sizeof(int32_t)) == hipSuccess;
     ok = ok && hipMalloc(&c->d_xop, N * (size_t)cfg->H * 16 * 2) == hipSuccess;
     ok = ok && hipMalloc(&c->d_ahi, N * (size_t)cfg->F * 16 * 2) == hipSuccess;
     ok = ok && hipMalloc(&c->d_alo, N * (size_t)cfg->F * 16 * 2) == hipSuccess;
@@ -1207,6 +1210,7 @@ int adapmoe_destroy(adapmoe_ctx* c) {
   if (c->d_bkt_tok) hipFree(c->d_bkt_tok);
   if (c->d_bkt_w) hipFree(c->d_bkt_w);
   if (c->d_bkt_base) hipFree(c->d_bkt_base);
+  if (c->d_bkt_active) hipFree(c->d_bkt_active);
   if (c->d_xop) hipFree(c->d_xop);
   if (c->d_ahi) hipFree(c->d_ahi);
   if (c->d_alo) hipFree(c->d_alo);
@@ -1646,7 +1650,7 @@ int adapmoe_set_option(adapmoe_ctx* c, int option, int value) {
       c->lc.batch_two_terms = value;
       return ADAPMOE_OK;
     case ADAPMOE_OPT_BATCH_DIRECT:
-      if (value != 0 && value != 1) return fail(c, ADAPMOE_EINVAL, "set_option: BATCH_DIRECT is 0 or 1");
+      if (value < 0 || value > 2) return fail(c, ADAPMOE_EINVAL, "set_option: BATCH_DIRECT is 0, 1 or 2");
       c->lc.batch_direct = value;
       return ADAPMOE_OK;
     case ADAPMOE_OPT_DYN_PCT:

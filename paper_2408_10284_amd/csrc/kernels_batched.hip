@@ -15,6 +15,7 @@
 //
 // Operand order: for reduction step s (32 elements) lane l = 16 q + n holds the
 // 8 elements k = 32 s + 8 q + i of token column n.
+#include <algorithm>
 #include "../../include/adapmoe.h"
 #include "stream_parts.h"
 
@@ -81,9 +82,16 @@ __global__ __launch_bounds__(kBThreads) void bucket_gather_kernel(BatchArgs p) {
         }
       }
     }
-    if (blockIdx.x == 0 && blockIdx.y == 0 && lane < p.N) {
-      p.bkt_count[lane] = s_count[lane];
-      p.bkt_base[lane] = mine;
+    if (blockIdx.x == 0 && blockIdx.y == 0) {
+      if (lane < p.N) {
+        p.bkt_count[lane] = s_count[lane];
+        p.bkt_base[lane] = mine;
+      }
+      // the experts that have tokens, in ascending order, and how many they are
+      const bool active = lane < p.N && s_count[lane] > 0;
+      const uint64_t am = __builtin_amdgcn_ballot_w64(active);
+      if (active) p.bkt_active[__builtin_popcountll(am & ((1ull << lane) - 1))] = lane;
+      if (lane == 0) p.bkt_active[p.N] = __builtin_popcountll(am);
     }
   }
   __syncthreads();
@@ -282,6 +290,120 @@ __global__ __launch_bounds__(kBThreads) void grouped_gateup_mfma_kernel(BatchArg
                                    xop, xop, lds, epilogue);
 }
 
+// gate/up without a break between tiles.  With one tile per workgroup a compute unit starts from an
+// empty pipeline seven times per launch at Mixtral size (1792 workgroups of one wavefront per SIMD each):
+// the last loads of a tile are issued two slabs before its end and the next workgroup's first loads
+// only after it has been dispatched.  Here a launch has one workgroup per compute unit and every
+// wavefront walks its own sequence of units (16 row pairs of one active expert, all slabs) as one
+// stream of slabs: the loads of the next unit are in flight while the current one is finished.
+// Units are dealt out round robin over the experts that have tokens (bucket_gather_kernel lists
+// them), so that experts without tokens cost nothing.  Same arithmetic, same order of additions
+// and same results as the tile-per-workgroup kernel.
+template <int KS>
+__global__ __launch_bounds__(kBThreads) void grouped_gateup_stream_kernel(BatchArgs p) {
+  extern __shared__ uint4 lds[];
+  __shared__ int s_act[64];
+  __shared__ const char* s_base[64];
+  __shared__ float s_w[64 * kBTok];
+  const int tid = threadIdx.x, lane = tid & 63, wave = wave_index();
+  const int nact = p.bkt_active[p.N];
+  if (tid < 64) {
+    const int e = tid < nact ? p.bkt_active[tid] : 0;
+    s_act[tid] = e;
+    s_base[tid] = tid < nact ? static_cast<const char*>(p.bkt_base[e]) : nullptr;
+  }
+  for (int i = tid; i < nact * kBTok; i += kBThreads) {
+    const int e = p.bkt_active[i / kBTok], n = i % kBTok;
+    s_w[i] = n < p.bkt_count[e] ? p.bkt_w[e * kBTok + n] : 0.f;
+  }
+  __syncthreads();
+
+  const int m = lane & 15, q = lane >> 4;
+  constexpr int kRowB = wtile_row_bytes<KS>();
+  char* wt = reinterpret_cast<char*>(lds) + (size_t)wave * 2 * 16 * kRowB;   // this wavefront's tiles (W1 rows, W3 rows)
+  char* wt_store = wt + (lane >> 5) * kRowB + (lane & 31) * 16;
+  const char* wt_read = wt + m * kRowB + q * 16;
+  const size_t row_bytes = (size_t)p.H * 2;
+  const int nslabs = p.H / 32 / KS, upe = p.F / 16;       // slabs per unit, units per expert
+  const int total = nact * upe, nwaves = gridDim.x * kBWaves, w0 = blockIdx.x * kBWaves + wave;
+  const int nunits = w0 < total ? (total - w0 + nwaves - 1) / nwaves : 0;
+  const uint4* xop_all = reinterpret_cast<const uint4*>(p.xop);
+  const size_t xop_stride = (size_t)(p.H / 32) * 64;      // 16-byte vectors per expert
+
+  using Slab = WSlab<2, 1, KS>;
+  // load cursor: unit ua (its expert's position among the active ones and its first row pair), slab sa
+  int ua = w0, sa = 0;
+  const char* wsrc = nullptr;
+  const uint4* bsrc = nullptr;
+  auto open_load_unit = [&](int u) {
+    const int a = u / upe, f0 = (u - a * upe) * 16;
+    wsrc = s_base[a] + (size_t)(f0 + (lane >> 5)) * 2 * row_bytes + (lane & 31) * 16;
+    bsrc = xop_all + (size_t)s_act[a] * xop_stride + lane;
+  };
+  if (nunits > 0) open_load_unit(ua);
+  auto load_next = [&](Slab& buf, bool advance) {
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+        buf.a[t][0][i] = load_stream16(wsrc + t * row_bytes + (size_t)(2 * i) * 2 * row_bytes + (size_t)sa * KS * 64);
+#pragma unroll
+    for (int s = 0; s < KS; ++s) buf.b[s] = bsrc[((size_t)sa * KS + s) * 64];
+    if (advance && ++sa == nslabs) {
+      sa = 0;
+      ua += nwaves;
+      if (ua < total) open_load_unit(ua);
+    }
+  };
+  // consume cursor
+  int uc = w0, sc = 0;
+  f32x4_t acc[2];
+  auto consume = [&](const Slab& buf) {
+    if (sc == 0) acc[0] = acc[1] = f32x4_t{0.f, 0.f, 0.f, 0.f};
+    // the wavefront's own LDS tile: written and read by this wavefront only, program order suffices
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int i = 0; i < 8; ++i)
+        *reinterpret_cast<uint4*>(wt_store + (size_t)t * 16 * kRowB + (size_t)(2 * i) * kRowB) = buf.a[t][0][i];
+#pragma unroll
+    for (int s = 0; s < KS; ++s) {
+#pragma unroll
+      for (int t = 0; t < 2; ++t) {
+        const uint4 a = *reinterpret_cast<const uint4*>(wt_read + (size_t)t * 16 * kRowB + s * 64);
+        acc[t] = mfma16(a, buf.b[s], acc[t]);
+      }
+    }
+    if (++sc == nslabs) {
+      // lane holds rows f0 + 4 q + r (r = 0..3) of token column m; A goes out in the operand order of
+      // the down GEMM (reduction index f), as hi + lo bfloat16 or rounded to bfloat16
+      const int a = uc / upe, f0 = (uc - a * upe) * 16;
+      const int e = s_act[a];
+      const float wn = s_w[a * kBTok + m];
+      uint16_t hi[4], lo[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const float v = wn * silu_f32(acc[0][r]) * acc[1][r];
+        if (p.two_terms) {
+          const uint32_t h = __builtin_bit_cast(uint32_t, v) & 0xffff0000u;   // truncated high part, v - hi is exact
+          hi[r] = (uint16_t)(h >> 16);
+          lo[r] = f32_to_bf16_bits(v - __builtin_bit_cast(float, h));
+        } else {
+          hi[r] = f32_to_bf16_bits(v);
+          lo[r] = 0;
+        }
+      }
+      const int f = f0 + 4 * q;
+      const size_t pos = (size_t)e * p.F * kBTok + ((size_t)(f >> 5) * 64 + ((f >> 3) & 3) * 16 + m) * 8 + (f & 7);
+      *reinterpret_cast<uint2*>(p.a_hi + pos) = make_uint2(hi[0] | ((uint32_t)hi[1] << 16), hi[2] | ((uint32_t)hi[3] << 16));
+      *reinterpret_cast<uint2*>(p.a_lo + pos) = make_uint2(lo[0] | ((uint32_t)lo[1] << 16), lo[2] | ((uint32_t)lo[3] << 16));
+      sc = 0;
+      uc += nwaves;
+    }
+  };
+  stream_bufs<Slab>(nunits * nslabs, load_next, consume, [] {});
+}
+
 // down: rows h of W2, reduction over F, result added into y of the bucket's tokens
 template <int KS, int RT, int NW, int NTERM>
 __global__ __launch_bounds__(NW * kWave) void grouped_down_mfma_kernel(BatchArgs p) {
@@ -320,6 +442,9 @@ hipError_t batched_kernels_init() {
   hipError_t e;
   if ((e = big_lds(grouped_gateup_mfma_kernel<kGateUpKS, 1>)) != hipSuccess) return e;
   if ((e = big_lds(grouped_gateup_mfma_kernel<kGateUpKS, 0>)) != hipSuccess) return e;
+  // this kernel also has static LDS arrays: ask for what its wavefront tiles need, not for all of the LDS
+  if ((e = hipFuncSetAttribute(reinterpret_cast<const void*>(grouped_gateup_stream_kernel<kGateUpKS>), hipFuncAttributeMaxDynamicSharedMemorySize,
+                               (int)grouped_lds_bytes<kGateUpKS, 2, 1, kBWaves, 0>())) != hipSuccess) return e;
   if ((e = big_lds(grouped_down_mfma_kernel<kDownKS, 1, 8, 2>)) != hipSuccess) return e;
   return big_lds(grouped_down_mfma_kernel<kDownKS, 1, 8, 1>);
 }
@@ -330,11 +455,25 @@ hipError_t launch_bucket_gather(const BatchArgs& p, hipStream_t s, const KernelT
   return hipGetLastError();
 }
 
-hipError_t launch_grouped_gateup(const BatchArgs& p, bool direct, hipStream_t s, const KernelTiming& t) {
-  // gate/up: every wavefront loads its own operand vectors (no workgroup barriers), measured 10 %
-  // faster than staging them per workgroup (direct = false selects the staged variant)
+hipError_t launch_grouped_gateup(const BatchArgs& p, int mode, hipStream_t s, const KernelTiming& t) {
+  // mode 1: every wavefront loads its own operand vectors (no workgroup barriers), measured 10 %
+  // faster than staging them per workgroup (mode 0); mode 2: the same with one workgroup per compute
+  // unit, every wavefront streaming through its units without a break (needs at least two slabs per unit)
+  if (mode == 2 && p.H / 32 / kGateUpKS >= 2) {
+    static int cus = 0;
+    if (cus == 0) {
+      int dev = 0, n = 0;
+      if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n < 1) n = 256;
+      cus = n;
+    }
+    const int units = p.N * (p.F / 16);
+    dim3 grid(std::max(1, std::min(cus, (units + kBWaves - 1) / kBWaves))), block(kBThreads);   // two workgroups per compute unit measured no faster
+    constexpr size_t lds = grouped_lds_bytes<kGateUpKS, 2, 1, kBWaves, 0>();
+    launch_kernel(grouped_gateup_stream_kernel<kGateUpKS>, grid, block, lds, s, t, p);
+    return hipGetLastError();
+  }
   dim3 grid(p.F / (16 * kBWaves), p.N), block(kBThreads);
-  if (direct) {
+  if (mode != 0) {
     constexpr size_t lds = grouped_lds_bytes<kGateUpKS, 2, 1, kBWaves, 0>();
     launch_kernel(grouped_gateup_mfma_kernel<kGateUpKS, 0>, grid, block, lds, s, t, p);
   } else {

@@ -211,9 +211,12 @@ __device__ __forceinline__ uint32_t f32_to_f16_bits(float f) {
   f = __builtin_fminf(__builtin_fmaxf(f, -65504.f), 65504.f);
   return (uint32_t)__builtin_bit_cast(uint16_t, (_Float16)f);
 }
-// a packed pair of bfloat16 -> a packed pair of halves
+// a packed pair of bfloat16 -> a packed pair of halves.  A bfloat16 has fewer mantissa bits than a
+// half, so inside the half's normal range the conversion is exact whatever the rounding; the
+// round-toward-zero pack instruction is used because it also clamps: magnitudes beyond the range
+// come out as 65504 instead of infinity (below 6.1e-5 it truncates to the subnormal grid of 6e-8).
 __device__ __forceinline__ uint32_t bf16x2_to_f16x2(uint32_t u) {
-  return f32_to_f16_bits(bf16_lo(u)) | (f32_to_f16_bits(bf16_hi(u)) << 16);
+  return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(bf16_lo(u), bf16_hi(u)));
 }
 __device__ __forceinline__ uint4 bf16x8_to_f16x8(const uint4& v) {
   return make_uint4(bf16x2_to_f16x2(v.x), bf16x2_to_f16x2(v.y), bf16x2_to_f16x2(v.z), bf16x2_to_f16x2(v.w));

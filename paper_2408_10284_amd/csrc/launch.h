@@ -90,6 +90,7 @@ struct BatchArgs {
   int32_t* bkt_tok;          // [N][16] token index
   float* bkt_w;              // [N][16] routing weight
   const void** bkt_base;     // [N] image base pointer
+  int32_t* bkt_active;       // [N+1] experts with at least one token, ascending; entry N = how many
   uint16_t* xop;             // [N][H/32][64][8] x of the bucket's tokens in MFMA operand order
   uint16_t* a_hi;            // [N][F/32][64][8] A in operand order, high bfloat16 part
   uint16_t* a_lo;            //                                      low part
@@ -126,7 +127,8 @@ struct LaunchCfg {
   int batch_two_terms;  // batched path: intermediate activation as hi + lo bfloat16 (1) or bfloat16 only (0)
   int fused_blocks;   // workgroups of the fused single-token FFN kernel (0 = fused path off)
   int dyn_pct;        // percent of the row passes of the GEMV kernels that are scheduled dynamically (0 = none)
-  int batch_direct;   // batched gate/up GEMM: token operand loaded per wavefront (1) or staged per workgroup (0)
+  int batch_direct;   // batched gate/up GEMM: 2 = wavefronts stream through their tiles without a break, 1 = one tile per
+                      // workgroup with the token operand loaded per wavefront, 0 = one tile per workgroup, operand staged in LDS
   KernelTiming timing;  // set for one launch when the context is profiling
 };
 
@@ -144,7 +146,7 @@ hipError_t launch_ffn_down_quant(const FfnArgs& p, int bits, const LaunchCfg& lc
 hipError_t quant_kernels_init(int bits);
 hipError_t batched_kernels_init();
 hipError_t launch_bucket_gather(const BatchArgs& p, hipStream_t s, const KernelTiming& t = KernelTiming{});
-hipError_t launch_grouped_gateup(const BatchArgs& p, bool direct, hipStream_t s, const KernelTiming& t = KernelTiming{});
+hipError_t launch_grouped_gateup(const BatchArgs& p, int mode, hipStream_t s, const KernelTiming& t = KernelTiming{});
 hipError_t launch_grouped_down(const BatchArgs& p, bool two_terms, hipStream_t s, const KernelTiming& t = KernelTiming{});
 hipError_t launch_residual_rmsnorm(float* h, const float* y, float gamma, void* x, bool bf16, int B, int H, hipStream_t s);
 

@@ -195,8 +195,10 @@ def test_two_contexts_are_independent():
 @pytest.mark.parametrize("dtype,blocks,pct", [("bf16", 40, 50), ("bf16", 7, 100), ("bf16", 1000, 15), ("bf16", 512, 0),
                                               ("int4g64", 10, 50), ("int4g64", 3, 100), ("int4g64", 37, 30), ("int2g64", 16, 40)])
 def test_dynamic_tail_with_odd_grids(dtype, blocks, pct):
-    """The gate/up kernels' dynamic tail must cover every row exactly once for any grid size and pool share
-    (grids that are no multiple of 8 workgroups, fewer workgroups than queues, everything in the pool)."""
+    """The gate/up kernel's dynamic tail must cover every row exactly once for any grid size and pool share
+    (grids that are no multiple of 8 workgroups, fewer workgroups than queues, everything in the pool).
+    The quantised kernels assign every row in advance whatever the option says: their cases check odd grid
+    sizes (rows that do not divide over the wavefronts, wavefronts with one row pair or none)."""
     shape = synth.MoEShape(H=4096, F=1536, N=4, L=1, dtype=dtype)     # compile-time row length, 2 F no multiple of most grids
     ls = GpuLayerSet(shape, seed=51, max_B=3, taus=[0.3])
     try:

@@ -341,6 +341,23 @@ def bench_layer(args):
     copy_gbs = 5 * 2 * float(1 << 30) / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
     del src, dst
 
+    # what the memory system delivers for the gate/up kernel's access pattern with no arithmetic at all: a load-only
+    # kernel of the library, same number of workgroups, same bytes as a launch with one and with two activated experts
+    probe = None
+    if not quantised and not fused and shape.H * (4 if act == "f32" else 2) in (1024, 2048, 4096, 8192, 16384):
+        row_bytes = shape.H * (4 if act == "f32" else 2)
+        wgs = B.adapmoe_get_option(ctx, B.OPT_GATEUP_BLOCKS)
+        pbuf = torch.empty(2 * 2 * shape.F * row_bytes, dtype=torch.uint8, device="cuda").fill_(1)
+        us = {kx: B.adapmoe_stream_probe(pbuf, kx * 2 * shape.F, row_bytes, 2, row_bytes, wgs, 20) for kx in (1, 2)}
+        del pbuf
+        n1, n2 = float((ks == 1).sum()), float((ks == 2).sum())
+        avg = (n1 * us[1] + n2 * us[2]) / max(n1 + n2, 1.0)
+        probe = {"pattern": "a wavefront reads whole row pairs one after the other, two 16 KiB buffers in flight, "
+                            f"{wgs} workgroups of 256 threads, loads only",
+                 "us_one_expert": round(us[1], 2), "us_two_experts": round(us[2], 2),
+                 "GBs_two_experts": round(2 * 2 * per_matrix / (us[2] * 1e-6) / 1e9, 1),
+                 "us_for_this_run's_k": round(avg, 2), "kernel_over_probe": round(ms_gu / max(n_gu, 1) * 1e3 / avg, 4)}
+
     cpu = cpu_baseline_layer(args, shape, X, wg, experts, tau, quantised) if args.cpu_seconds > 0 else None
     gu_name = "ffn_fused_kernel" if fused else ("ffn_gateup_quant_kernel" if quantised else "ffn_gateup_kernel")
     # HBM bytes per launch from the committed counter runs of this workload.  Those runs launch every one of the
@@ -365,7 +382,8 @@ def bench_layer(args):
                                      "the counter runs to the mean k of the launches timed here",
                      "avg_us": round(ms_gu / max(n_gu, 1) * 1e3, 2), "launches": n_gu,
                      "bytes_per_launch": round(bytes_gu / max(n_gu, 1)),
-                     "measured_device_copy_GBs": round(copy_gbs, 1), "frac_of_device_copy": round(gu_gbs / copy_gbs, 4)},
+                     "measured_device_copy_GBs": round(copy_gbs, 1), "frac_of_device_copy": round(gu_gbs / copy_gbs, 4),
+                     "stream_probe": probe},
         "kernels": {"down": {"achieved_GBs": round(dn_gbs, 1), "frac": round(dn_gbs / HBM_PEAK_GBS, 4),
                              "avg_us": round(ms_dn / max(n_dn, 1) * 1e3, 2)},
                     "gate": {"avg_us": round(ms_gt / max(n_gt, 1) * 1e3, 2)},
@@ -753,6 +771,15 @@ def bench_batched(args, shared=None):
     issued_flops = touched * 16 * 2 * 3 * shape.H * shape.F  # what the 16-column matrix instructions execute
     cpu = (cpu_baseline_stack(shape, routers, images_dev, taus, Xs[warmup:, 0, :], gamma, args.cpu_seconds, 3, "stream 0 of the 16")
            if args.cpu_seconds > 0 else None)
+    # the grouped GEMM's access pattern with loads only: 512 bytes of each of 32 rows per step, one workgroup per compute unit
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    pbuf = torch.empty(8 * 2 * shape.F * shape.H * 2, dtype=torch.uint8, device="cuda").fill_(1)
+    probe_us = B.adapmoe_stream_probe(pbuf, 8 * 2 * shape.F, shape.H * 2, 32, 512, cus, 10)
+    del pbuf
+    probe = {"pattern": f"a wavefront reads 512 bytes of each of 32 rows per step, two 16 KiB buffers in flight, {cus} workgroups of "
+                        "256 threads, loads only, W1 and W3 of 8 experts",
+             "us": round(probe_us, 1), "GBs": round(8 * 2 * per_matrix / (probe_us * 1e-6) / 1e9, 1),
+             "kernel_GBs_over_probe_GBs": round(gu_gbs / (8 * 2 * per_matrix / (probe_us * 1e-6) / 1e9), 4)}
     out = {
         "metric": METRIC, "value": round(Bt * steps / elapsed, 2), "unit": f"tokens/s ({L}-layer stack, {Bt} decode streams per step)",
         "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(elapsed / steps * 1e3, 3),
@@ -767,7 +794,8 @@ def bench_batched(args, shared=None):
                      "traffic": measured_traffic("grouped_gateup_stream_kernel", "pmc_traffic_batched.json"),
                      "avg_us": round(gu_us, 1), "launches": n_l,
                      "bytes_per_launch": round(touched * 2 * per_matrix),
-                     "note": "bytes = W1 and W3 of the experts the launches really streamed (from the decision log)"},
+                     "note": "bytes = W1 and W3 of the experts the launches really streamed (from the decision log)",
+                     "stream_probe": probe},
         "kernels": {"grouped_down_mfma_kernel": {"avg_us": round(dn_us, 1), "achieved_GBs": round(touched * per_matrix / (dn_us * 1e-6) / 1e9, 1)},
                     "bucket_gather_kernel": {"avg_us": round(prof[3][1] / max(prof[3][0], 1) * 1e3, 2)},
                     "gate_kernel": {"avg_us": round(prof[2][1] / max(prof[2][0], 1) * 1e3, 2)},

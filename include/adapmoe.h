@@ -383,6 +383,18 @@ int adapmoe_check(adapmoe_ctx* ctx, void* stream);
 int adapmoe_profile(adapmoe_ctx* ctx, int on);
 int adapmoe_profile_read(adapmoe_ctx* ctx, int kernel_class, uint64_t* launches, double* total_ms);
 
+/* Measurement aid: what the memory system delivers for the access pattern of a kernel, without the
+ * kernel's arithmetic.  Launches `reps` load-only kernels over the matrix buf_dev (device memory,
+ * nrows rows of row_bytes) on `stream`, timed with a pair of events, and returns the average duration
+ * of one pass in microseconds.  A wavefront reads units of rows_per_unit consecutive rows, chunk_bytes
+ * of each row per step, with two 16 KiB register buffers in flight as the expert kernels have:
+ * (rows_per_unit 2, chunk_bytes = row_bytes) is the single-token gate/up GEMV reading a row pair,
+ * (32, 512) the grouped GEMM of the batched path.  chunk_bytes is 512 or equal to row_bytes (a multiple of
+ * 1024 up to 16384); rows_per_unit * chunk_bytes must be a multiple of 16384 and nrows of
+ * rows_per_unit; workgroups (256 threads) in 1..65535.  Reads only; ADAPMOE_EINVAL otherwise. */
+int adapmoe_stream_probe(const void* buf_dev, int64_t nrows, int row_bytes, int rows_per_unit, int chunk_bytes,
+                         int workgroups, int reps, double* us_per_pass_out, void* stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -85,6 +85,7 @@ _SIGS = {
     "adapmoe_check": (C.c_int, [_P, _P]),
     "adapmoe_profile": (C.c_int, [_P, C.c_int]),
     "adapmoe_profile_read": (C.c_int, [_P, C.c_int, C.POINTER(C.c_uint64), C.POINTER(C.c_double)]),
+    "adapmoe_stream_probe": (C.c_int, [_P, C.c_int64, C.c_int, C.c_int, C.c_int, C.c_int, C.c_int, C.POINTER(C.c_double), _P]),
 }
 
 
@@ -411,6 +412,16 @@ def adapmoe_check(ctx, stream=None):
 
 def adapmoe_profile(ctx, on):
     _chk(ctx, load().adapmoe_profile(ctx, 1 if on else 0))
+
+
+def adapmoe_stream_probe(buf, nrows, row_bytes, rows_per_unit, chunk_bytes, workgroups, reps, stream=None):
+    """Average duration in microseconds of one load-only pass over `buf` ([nrows, row_bytes] bytes on the device)."""
+    if buf.numel() * buf.element_size() < nrows * row_bytes:
+        raise ValueError("stream_probe: buffer smaller than nrows * row_bytes")
+    us = C.c_double()
+    _chk(None, load().adapmoe_stream_probe(_ptr(buf), int(nrows), int(row_bytes), int(rows_per_unit), int(chunk_bytes), int(workgroups),
+                                           int(reps), C.byref(us), _stream(stream)))
+    return us.value
 
 
 def adapmoe_profile_read(ctx, kernel_class):

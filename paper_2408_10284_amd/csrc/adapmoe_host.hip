@@ -1857,4 +1857,36 @@ int adapmoe_profile_read(adapmoe_ctx* c, int cls, uint64_t* launches, double* to
   ABI_CATCH(c)
 }
 
+int adapmoe_stream_probe(const void* buf_dev, int64_t nrows, int row_bytes, int rows_per_unit, int chunk_bytes, int workgroups, int reps,
+                         double* us_out, void* stream) {
+  ABI_TRY
+  const bool whole = chunk_bytes == row_bytes;
+  if (!buf_dev || !us_out || nrows < 1 || row_bytes < 512 || rows_per_unit < 1 || reps < 1 || workgroups < 1 || workgroups > 65535)
+    return ADAPMOE_EINVAL;
+  if (whole ? (chunk_bytes % 1024 != 0 || chunk_bytes > 16384 || 16384 % chunk_bytes != 0) : (chunk_bytes != 512 || row_bytes % 512 != 0))
+    return ADAPMOE_EINVAL;
+  if (((int64_t)rows_per_unit * chunk_bytes) % 16384 != 0 || nrows % rows_per_unit != 0) return ADAPMOE_EINVAL;
+  // parts per wavefront must fit the streamer's 32-bit count
+  const int64_t units = nrows / rows_per_unit, parts = (int64_t)(rows_per_unit / (16384 / chunk_bytes)) * (row_bytes / chunk_bytes);
+  if ((units / ((int64_t)workgroups * 4) + 1) * parts > 0x7fffffff) return ADAPMOE_EINVAL;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  hipError_t e = hipEventCreate(&e0);
+  if (e == hipSuccess) e = hipEventCreate(&e1);
+  if (e == hipSuccess) e = launch_stream_probe(buf_dev, (long)nrows, row_bytes, rows_per_unit, chunk_bytes, workgroups, nullptr, s);   // warm-up
+  if (e == hipSuccess) e = hipEventRecord(e0, s);
+  for (int r = 0; r < reps && e == hipSuccess; ++r)
+    e = launch_stream_probe(buf_dev, (long)nrows, row_bytes, rows_per_unit, chunk_bytes, workgroups, nullptr, s);
+  if (e == hipSuccess) e = hipEventRecord(e1, s);
+  if (e == hipSuccess) e = hipEventSynchronize(e1);
+  float ms = 0.f;
+  if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+  if (e0) hipEventDestroy(e0);
+  if (e1) hipEventDestroy(e1);
+  if (e != hipSuccess) return ADAPMOE_EHIP;
+  *us_out = (double)ms * 1e3 / reps;
+  return ADAPMOE_OK;
+  ABI_CATCH(nullptr)
+}
+
 }  // extern "C"

@@ -145,6 +145,7 @@ hipError_t launch_ffn_gateup_quant(const FfnArgs& p, int bits, const LaunchCfg& 
 hipError_t launch_ffn_down_quant(const FfnArgs& p, int bits, const LaunchCfg& lc, hipStream_t s);
 hipError_t quant_kernels_init(int bits);
 hipError_t batched_kernels_init();
+hipError_t launch_stream_probe(const void* buf, long nrows, int row_bytes, int R, int C, int workgroups, unsigned* sink, hipStream_t s);
 hipError_t launch_bucket_gather(const BatchArgs& p, hipStream_t s, const KernelTiming& t = KernelTiming{});
 hipError_t launch_grouped_gateup(const BatchArgs& p, int mode, hipStream_t s, const KernelTiming& t = KernelTiming{});
 hipError_t launch_grouped_down(const BatchArgs& p, bool two_terms, hipStream_t s, const KernelTiming& t = KernelTiming{});

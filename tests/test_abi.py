@@ -306,3 +306,23 @@ def test_binding_refuses_buffers_that_are_too_small_or_misplaced():
     import torch
     with pytest.raises(ValueError, match="device tensor"):
         B._need("x", torch.zeros(512, dtype=torch.bfloat16), 1024, "dev")
+
+
+def test_stream_probe_rejects_bad_patterns_without_gpu(lib):
+    """The load-only probe checks its pattern before anything touches the GPU: rows that are no
+    power-of-two number of KiB, chunks other than 512 bytes or a whole row, units that do not fill
+    whole 16 KiB buffers, a row count that is no multiple of the unit, empty launches."""
+    us = ctypes.c_double()
+    buf = ctypes.c_void_p(4096)          # never dereferenced: every call below fails its argument check
+
+    def rc(nrows, row_bytes, unit, chunk, wgs=64, reps=1, b=buf):
+        return lib.adapmoe_stream_probe(b, nrows, row_bytes, unit, chunk, wgs, reps, ctypes.byref(us), None)
+
+    assert rc(64, 8192, 2, 8192, b=None) == B.EINVAL
+    assert rc(64, 12288, 2, 12288) == B.EINVAL        # 16384 is no multiple of the row
+    assert rc(64, 8192, 32, 1024) == B.EINVAL         # neither 512 nor the whole row
+    assert rc(64, 8192, 16, 512) == B.EINVAL          # 16 x 512 bytes do not fill a buffer
+    assert rc(66, 8192, 4, 8192) == B.EINVAL          # 66 rows are no whole number of units
+    assert rc(64, 8192, 2, 8192, wgs=0) == B.EINVAL
+    assert rc(64, 8192, 2, 8192, reps=0) == B.EINVAL
+    assert rc(0, 8192, 2, 8192) == B.EINVAL

@@ -214,3 +214,20 @@ def test_dynamic_tail_with_odd_grids(dtype, blocks, pct):
             assert err.max() <= TOL[dtype], (rep, err.max())
     finally:
         ls.close()
+
+
+def test_stream_probe_runs_and_reports_a_plausible_rate():
+    """The load-only probe of the kernels' access patterns: both patterns run over a small matrix (ragged
+    share of units per wavefront, more wavefronts than units) and report a duration that corresponds to
+    less than the chip's HBM peak."""
+    rows, row_bytes = 64 * 1024, 8192                # 512 MiB
+    buf = torch.ones(rows * row_bytes, dtype=torch.uint8, device="cuda")
+    for unit, chunk, wgs in ((2, 8192, 512), (32, 512, 256), (2, 8192, 3), (32, 512, 1000)):
+        us = B.adapmoe_stream_probe(buf, rows, row_bytes, unit, chunk, wgs, 3)
+        gbs = rows * row_bytes / (us * 1e-6) / 1e9
+        assert 50.0 < gbs < 8000.0, (unit, chunk, wgs, us, gbs)
+    # fewer units than wavefronts, and a single unit
+    assert B.adapmoe_stream_probe(buf, 64, row_bytes, 32, 512, 256, 2) > 0.0
+    assert B.adapmoe_stream_probe(buf, 2, row_bytes, 2, 8192, 1, 2) > 0.0
+    with pytest.raises(ValueError):
+        B.adapmoe_stream_probe(buf, rows + 2, row_bytes, 2, 8192, 64, 1)     # larger than the buffer

@@ -30,7 +30,7 @@
 //   sum (q s + z) x = s * sum_p 2^-p (acc_p - 1024 xs_p) + z * sum_p xs_p.
 // That is 9 vector operations per 8 weights (4-bit) instead of 11 with one shift per field.
 // Activations: x arrives as bfloat16 and is converted to half (exact for 6.1e-5 <= |x| <= 65504,
-// clamped above, rounded to the half subnormal grid of 6e-8 below); the gate/up kernel writes
+// clamped above, truncated to the half subnormal grid of 6e-8 below); the gate/up kernel writes
 // a_j = w_j silu(g) u as halves for the down kernel.
 #include <algorithm>
 #include "../../include/adapmoe.h"
@@ -387,8 +387,9 @@ struct QRow {
   QGroup<BITS> g[PB];
 };
 
-// One wavefront per output element y[h], the rows of a workgroup's 16 wavefronts walked with two
-// four register buffers (the unit in flight is one block of 64 groups of a row: 36 bytes per lane).  The intermediate vectors a_j of the activated experts (halves, written by the
+// One wavefront per output element y[h]; a wavefront streams its rows through four register
+// buffers (the unit in flight is one block of 64 groups of a row: 36 bytes per lane with 4-bit
+// codes).  The intermediate vectors a_j of the activated experts (halves, written by the
 // gate/up kernel in the order [block][vector][lane]) are staged in LDS once per workgroup together
 // with the two sums per group that the dequantisation needs, so that the weight stream is the only
 // traffic that grows with the number of rows; a lane reads its group's 64 values back with eight

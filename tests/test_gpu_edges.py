@@ -126,22 +126,24 @@ def test_degenerate_inputs(dtype):
         ls.close()
 
 
-def test_resident_stack_step_can_be_captured_in_a_graph():
+@pytest.mark.parametrize("Bt", [1, 6])
+def test_resident_stack_step_can_be_captured_in_a_graph(Bt):
     """With every expert resident, moe_stack_token makes no host round trip, allocates nothing and clears
     its own counters in kernels, so a HIP graph can hold it.  The graph is replayed several times, on new
-    inputs, with eager work in between, and every replay is compared with the eager result."""
+    inputs, with eager work in between, and every replay is compared with the eager result.  Bt = 6 takes
+    the batched kernels (bucketing, streaming grouped GEMM, atomic adds onto a y cleared by a kernel)."""
     shape = synth.MoEShape(H=1024, F=2048, N=8, L=3, dtype="bf16")
-    ls = GpuLayerSet(shape, seed=21, max_B=1, taus=[0.2, 0.3, 0.25])
+    ls = GpuLayerSet(shape, seed=21, max_B=Bt, taus=[0.2, 0.3, 0.25])
     try:
         n = 5
-        H0 = torch.from_numpy(synth.ar1_tokens(n, shape.H, 0.8, seed=3, dtype="f32") * 2.0).cuda()
-        x = torch.empty((1, shape.H), dtype=torch.bfloat16, device="cuda")
-        y = torch.empty((1, shape.H), dtype=torch.float32, device="cuda")
-        h = torch.empty((1, shape.H), dtype=torch.float32, device="cuda")
+        H0 = torch.from_numpy(synth.ar1_streams(n, Bt, shape.H, 0.8, seed=3, dtype="f32") * 2.0).cuda()
+        x = torch.empty((Bt, shape.H), dtype=torch.bfloat16, device="cuda")
+        y = torch.empty((Bt, shape.H), dtype=torch.float32, device="cuda")
+        h = torch.empty((Bt, shape.H), dtype=torch.float32, device="cuda")
 
         def eager(t):
-            h.copy_(H0[t:t + 1])
-            B.moe_stack_token(ls.ctx, t, h, x, y, 1, 0.5, torch.cuda.current_stream())
+            h.copy_(H0[t])
+            B.moe_stack_token(ls.ctx, t, h, x, y, Bt, 0.5, torch.cuda.current_stream())
             torch.cuda.synchronize()
             return h.clone(), y.clone()
 
@@ -150,15 +152,15 @@ def test_resident_stack_step_can_be_captured_in_a_graph():
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
         with torch.cuda.stream(side):
-            h.copy_(H0[0:1])
-            B.moe_stack_token(ls.ctx, 0, h, x, y, 1, 0.5, side)       # warm-up on the capture stream
+            h.copy_(H0[0])
+            B.moe_stack_token(ls.ctx, 0, h, x, y, Bt, 0.5, side)       # warm-up on the capture stream
             side.synchronize()
             with torch.cuda.graph(g, stream=side):
-                B.moe_stack_token(ls.ctx, 0, h, x, y, 1, 0.5, torch.cuda.current_stream())
+                B.moe_stack_token(ls.ctx, 0, h, x, y, Bt, 0.5, torch.cuda.current_stream())
         torch.cuda.current_stream().wait_stream(side)
         for rep in range(2):
             for t in range(n):
-                h.copy_(H0[t:t + 1])
+                h.copy_(H0[t])
                 g.replay()
                 torch.cuda.synchronize()
                 assert torch.equal(h, ref[t][0]) and torch.equal(y, ref[t][1]), (rep, t)

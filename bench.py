@@ -58,6 +58,9 @@ def parse():
                     help="offload workload: expert images in pageable host memory, loads staged through this many pinned buffers "
                          "(for stacks larger than the box lets a process pin, e.g. --layers 32 in bf16)")
     ap.add_argument("--lookahead", type=int, default=1, help="offload workload: layers predicted and prefetched ahead (1..3)")
+    ap.add_argument("--model", default="8x7b", choices=["8x7b", "8x22b"],
+                    help="offload workload: expert shapes and depth of Mixtral-8x7B (H 4096, F 14336, 32 layers) or of "
+                         "Mixtral-8x22B (H 6144, F 16384, 56 layers; quantised experts only, staged from pageable memory)")
     ap.add_argument("--graph", action="store_true", help="mixtral_stack_resident: replay one captured HIP graph per token")
     ap.add_argument("--opt", action="append", default=[], metavar="NAME=VALUE",
                     help="library option for the benchmarked context, e.g. GATEUP_BLOCKS=768 (names of adapmoe_set_option)")
@@ -547,8 +550,15 @@ def bench_stack_offload(args):
     # workload (2 slots per layer, 25 %); --layers 32 needs a box that can pin 90 GB.  The int4
     # workload (25.4 GB) runs all 32 layers with 128 slots.
     int4 = args.dtype in ("int4", "int2")      # quantised images: all 32 layers fit the pinning limit
-    L = args.layers or (32 if int4 else 14)
-    shape = synth.MoEShape(4096, 14336, 8, L, {"int4": "int4g64", "int2": "int2g64"}.get(args.dtype, "bf16"))
+    big = args.model == "8x22b"
+    if big and not int4:
+        print("bench.py: --model 8x22b takes --dtype int4 or int2 (its bf16 experts, 270 GB, do not fit the box's host memory)", file=sys.stderr)
+        sys.exit(2)
+    L = args.layers or (56 if big else (32 if int4 else 14))
+    Hm, Fm = (6144, 16384) if big else (4096, 14336)
+    shape = synth.MoEShape(Hm, Fm, 8, L, {"int4": "int4g64", "int2": "int2g64"}.get(args.dtype, "bf16"))
+    if big and not args.staging and L > 24:
+        args.staging = 4                       # 448 experts of 170 MB are more than a process may pin here
     C = args.cache if args.cache is not None else (4 * L if int4 else 2 * L)
     steps = args.steps if args.steps is not None else 48
     warmup = args.warmup if args.warmup is not None else 16
@@ -612,7 +622,7 @@ def bench_stack_offload(args):
     per_layer /= steps
     model = np.array([B.cache_cost(shape.N, slots[l], float(a[l]), float(beta[l])) for l in range(L)])
 
-    # pinned-copy reference: the same 352 MB images copied back to back on one stream
+    # pinned-copy reference: the same expert images copied back to back on one stream
     buf = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
     torch.cuda.synchronize()
     r0 = time.perf_counter()
@@ -645,7 +655,7 @@ def bench_stack_offload(args):
         "n_gpus": 1, "steps": steps, "warmup": warmup, "ms_per_step": round(elapsed / steps * 1e3, 3),
         "us_per_layer": round(elapsed / steps / L * 1e6, 1),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
-        "config": {"workload": f"mixtral_stack_offload ({args.dtype}): H=4096 F=14336 N=8 L={L}, {L * 8} experts ({L * 8 * nbytes / 1e9:.1f} GB) in "
+        "config": {"workload": f"mixtral_stack_offload ({args.model}, {args.dtype}): H={shape.H} F={shape.F} N=8 L={L}, {L * 8} experts ({L * 8 * nbytes / 1e9:.1f} GB) in "
                                + (f"pageable host memory staged through {args.staging} pinned buffers" if args.staging else "pinned host memory")
                                + f", cache of {C} slots sized by the planner, LRU + prefetch {args.lookahead} layer(s) ahead, "
                                f"{'tile-wise loading (' + str(args.tiles) + ' tiles)' if args.tiles else 'whole-image loading'}, gamma={gamma}",

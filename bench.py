@@ -57,6 +57,7 @@ def parse():
     ap.add_argument("--staging", type=int, default=0,
                     help="offload workload: expert images in pageable host memory, loads staged through this many pinned buffers "
                          "(for stacks larger than the box lets a process pin, e.g. --layers 32 in bf16)")
+    ap.add_argument("--staging-threads", type=int, default=8, help="offload workload: host threads that fill a staging buffer together")
     ap.add_argument("--lookahead", type=int, default=1, help="offload workload: layers predicted and prefetched ahead (1..3)")
     ap.add_argument("--model", default="8x7b", choices=["8x7b", "8x22b"],
                     help="offload workload: expert shapes and depth of Mixtral-8x7B (H 4096, F 14336, 32 layers) or of "
@@ -585,7 +586,7 @@ def bench_stack_offload(args):
     if args.tiles:
         B.adapmoe_set_tiles(ctx, args.tiles)
     if args.staging:
-        B.adapmoe_set_staging(ctx, args.staging, 8)
+        B.adapmoe_set_staging(ctx, args.staging, args.staging_threads)
     B.adapmoe_set_lookahead(ctx, args.lookahead)
     t_setup = time.time() - t_setup
 

@@ -299,8 +299,9 @@ int adapmoe_set_tiles(adapmoe_ctx* ctx, int tiles);
  * served by a worker thread of the library, in request order: it copies the registered image into
  * one of `buffers` pinned buffers of one image each (owned by the library; `host_threads` threads
  * share the copy, 0 = 6) and sends it from there to its slot on the side stream, so the host copy of
- * one image runs while the previous one crosses the link.  Cache decisions, events and results are
- * unchanged; tile-wise loading is not used for staged copies.  buffers = 0 switches staging off
+ * one image runs while the previous one crosses the link; an image that finds the link idle is
+ * staged and sent in pieces of 32 MiB instead, so that its transfer starts after the first piece.
+ * Cache decisions, events and results are unchanged; tile-wise loading is not used for staged copies.  buffers = 0 switches staging off
  * (images are then read directly and should be pinned).  Call between layer steps. */
 int adapmoe_set_staging(adapmoe_ctx* ctx, int buffers, int host_threads);
 

@@ -116,6 +116,17 @@ struct Stager {
   std::vector<StageBuf> bufs;
   int next_buf = 0;
   int threads = 6;                      // host threads that share one copy into a pinned buffer
+  hipEvent_t last_done = nullptr;       // done event of the latest transfer put on the side stream (the link is idle once it has fired)
+  // helper threads of the worker: each copies its share of the job posted last
+  std::vector<std::thread> helpers;
+  std::mutex pool_mu;
+  std::condition_variable pool_job, pool_done;
+  char* job_dst = nullptr;
+  const char* job_src = nullptr;
+  size_t job_bytes = 0, job_share = 0;
+  uint64_t job_gen = 0;
+  int job_pending = 0;
+  bool pool_stop = false;
 };
 
 }  // namespace
@@ -371,14 +382,53 @@ int drain_stager(adapmoe_ctx* c) {
   return ADAPMOE_OK;
 }
 
-void parallel_memcpy(char* dst, const char* src, size_t bytes, int threads) {
-  const size_t chunk = ((bytes + threads - 1) / threads + 4095) & ~(size_t)4095;
-  std::vector<std::thread> pool;
-  for (size_t off = chunk; off < bytes; off += chunk)
-    pool.emplace_back([=] { memcpy(dst + off, src + off, std::min(chunk, bytes - off)); });
-  memcpy(dst, src, std::min(chunk, bytes));
-  for (std::thread& t : pool) t.join();
+// Helper i copies share i + 1 of every job; the worker copies share 0 and waits for the others.
+void pool_helper(Stager* st, int index) {
+  uint64_t seen = 0;
+  for (;;) {
+    char* dst;
+    const char* src;
+    size_t bytes, share;
+    {
+      std::unique_lock<std::mutex> lk(st->pool_mu);
+      st->pool_job.wait(lk, [&] { return st->pool_stop || st->job_gen != seen; });
+      if (st->pool_stop) return;
+      seen = st->job_gen;
+      dst = st->job_dst; src = st->job_src; bytes = st->job_bytes; share = st->job_share;
+    }
+    const size_t off = share * (size_t)(index + 1);
+    if (off < bytes) memcpy(dst + off, src + off, std::min(share, bytes - off));
+    {
+      std::lock_guard<std::mutex> lk(st->pool_mu);
+      if (--st->job_pending == 0) st->pool_done.notify_one();
+    }
+  }
 }
+
+// dst[0, bytes) = src[0, bytes) by the worker and its helpers together (only the worker calls this)
+void pool_copy(Stager* st, char* dst, const char* src, size_t bytes) {
+  const size_t parts = st->helpers.size() + 1;
+  const size_t share = ((bytes + parts - 1) / parts + 4095) & ~(size_t)4095;
+  if (!st->helpers.empty()) {
+    std::lock_guard<std::mutex> lk(st->pool_mu);
+    st->job_dst = dst; st->job_src = src; st->job_bytes = bytes; st->job_share = share;
+    st->job_pending = (int)st->helpers.size();
+    ++st->job_gen;
+  }
+  st->pool_job.notify_all();
+  memcpy(dst, src, std::min(share, bytes));
+  if (!st->helpers.empty()) {
+    std::unique_lock<std::mutex> lk(st->pool_mu);
+    st->pool_done.wait(lk, [&] { return st->job_pending == 0; });
+  }
+}
+
+// An image that finds the link idle is staged and sent in pieces, so that its first bytes cross
+// the link while the rest is still being copied into the pinned buffer (a load that nothing
+// overlaps would otherwise take the staging time on top of the transfer time); an image that
+// queues behind another transfer is staged whole while that one is under way and sent with one
+// command (every further copy command leaves the link idle for some microseconds).
+constexpr size_t kStagePiece = (size_t)32 << 20;
 
 void stager_main(adapmoe_ctx* c) {
   Stager& st = *c->stager;
@@ -396,14 +446,28 @@ void stager_main(adapmoe_ctx* c) {
     st.next_buf = (st.next_buf + 1) % (int)st.bufs.size();
     if (e == hipSuccess && b.used) e = hipEventSynchronize(b.done);   // the buffer's previous transfer has left it
     if (e == hipSuccess) {
-      parallel_memcpy(b.host, static_cast<const char*>(req.src), c->image_bytes, st.threads);
+      bool idle = true;                                                // has the latest transfer finished?
+      if (st.last_done) {
+        const hipError_t q = hipEventQuery(st.last_done);
+        if (q == hipErrorNotReady) idle = false;
+        else if (q != hipSuccess) e = q;
+      }
+      const size_t piece = idle ? kStagePiece : c->image_bytes;
       Slot& s = c->slots[req.slot];
-      if (req.wait_read) e = hipStreamWaitEvent(c->copy_stream, s.read_done, 0);
-      if (e == hipSuccess && c->poison) e = hipMemsetAsync(s.dev, 0xFF, c->image_bytes, c->copy_stream);
-      if (e == hipSuccess) e = hipMemcpyAsync(s.dev, b.host, c->image_bytes, hipMemcpyHostToDevice, c->copy_stream);
+      const char* src = static_cast<const char*>(req.src);
+      for (size_t off = 0; off < c->image_bytes && e == hipSuccess; off += piece) {
+        const size_t n = std::min(piece, c->image_bytes - off);
+        pool_copy(&st, b.host + off, src + off, n);
+        if (off == 0) {
+          if (req.wait_read) e = hipStreamWaitEvent(c->copy_stream, s.read_done, 0);
+          if (e == hipSuccess && c->poison) e = hipMemsetAsync(s.dev, 0xFF, c->image_bytes, c->copy_stream);
+        }
+        if (e == hipSuccess) e = hipMemcpyAsync(s.dev + off, b.host + off, n, hipMemcpyHostToDevice, c->copy_stream);
+      }
       if (e == hipSuccess) e = hipEventRecord(b.done, c->copy_stream);
       if (e == hipSuccess) e = hipEventRecord(s.copy_done, c->copy_stream);
       b.used = true;
+      st.last_done = b.done;
     }
     {
       std::lock_guard<std::mutex> lk(st.mu);
@@ -423,6 +487,13 @@ void stop_stager(adapmoe_ctx* c) {
   }
   st.cv_req.notify_all();
   if (st.worker.joinable()) st.worker.join();
+  {
+    std::lock_guard<std::mutex> lk(st.pool_mu);
+    st.pool_stop = true;
+  }
+  st.pool_job.notify_all();
+  for (std::thread& t : st.helpers)
+    if (t.joinable()) t.join();
   hipStreamSynchronize(c->copy_stream);
   for (StageBuf& b : st.bufs) {
     if (b.host) hipHostFree(b.host);
@@ -1740,6 +1811,7 @@ int adapmoe_set_staging(adapmoe_ctx* c, int buffers, int host_threads) {
       return fail(c, ADAPMOE_ENOMEM, "set_staging: pinned buffer allocation failed");
     }
   }
+  for (int i = 0; i + 1 < st->threads; ++i) st->helpers.emplace_back(pool_helper, st, i);
   st->worker = std::thread(stager_main, c);
   return ADAPMOE_OK;
   ABI_CATCH(c)

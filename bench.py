@@ -9,17 +9,23 @@ expert GEMVs, combine.  Inputs are synthetic and already in HBM when the timed
 region starts.
 
 Prints one JSON line: decode tokens/s for the layer, the roofline figures of the
-dominant kernel from HIP-event timing on the launch stream, and the CPU checker
-timed on a bounded sample of the same tokens as a baseline.
+dominant kernel from HIP-event timing on the launch stream (with a load-only
+kernel of the same access pattern timed beside it), and the CPU checker timed on
+a bounded sample of the same tokens as a baseline.  With no flags the record also
+carries, under "stacks", short runs of the 32-layer resident stack, the 32-layer
+batched stack and the int4 layer.
 
 Other workloads (same JSON shape, selected with --workload):
   mixtral_layer_int4     same layer with group-64 int4 experts (dequantisation fused)
   mixtral_layer_int2     same layer with group-64 2-bit experts
+  mixtral22_layer_bf16 / _int4 / _int2   one layer with Mixtral-8x22B expert shapes (H 6144, F 16384)
   mixtral_stack_resident 32 layers, all experts resident in HBM (90 GB bf16), batch-1 decode through the whole stack
-  mixtral_stack_offload  L-layer stack, experts in pinned host memory, bounded HBM cache
-                         sized by the planner, LRU + next-layer prefetch (host-link bound)
+  mixtral_stack_offload  L-layer stack, experts in host memory (pinned, or pageable with --staging), bounded HBM
+                         cache sized by the planner, LRU + next-layer prefetch (host-link bound);
+                         --dtype int4|int2, --model 8x22b, --layers, --cache, --lookahead, --tiles
   mixtral_batched        16 decode streams per step, experts resident, MFMA grouped GEMM
   tiny_f32               the small fp32 layer
+--opt NAME=VALUE sets a library option (adapmoe_set_option) for the benchmarked context.
 """
 from __future__ import annotations
 

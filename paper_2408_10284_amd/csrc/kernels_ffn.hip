@@ -213,9 +213,11 @@ __device__ __forceinline__ float dot_a(const uint4 (&buf)[NV], const float4* aj,
 
 // One wavefront per output element y[h]; a part is UN vectors of a row
 // W2_j[h,:].  UN == 0 selects the plain loop (row length not a multiple of the
-// part size).  A missing expert also takes the plain loop.
-template <bool BF16, int UN>
-__global__ __launch_bounds__(kDownThreads) void ffn_down_kernel(FfnArgs p) {
+// part size).  A missing expert also takes the plain loop.  THREADS = 1024 or 768: the launcher
+// takes 12 wavefronts per workgroup when that deals the rows out evenly and 16 do not (H = 6144
+// over 256 workgroups: two rows per wavefront instead of two for one half and one for the other).
+template <bool BF16, int UN, int THREADS>
+__global__ __launch_bounds__(THREADS) void ffn_down_kernel(FfnArgs p) {
   extern __shared__ float4 as4[];  // a[j][F] of the activated experts
   const int b = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63, wave = wave_index();
@@ -224,7 +226,7 @@ __global__ __launch_bounds__(kDownThreads) void ffn_down_kernel(FfnArgs p) {
   const int nch = (int)(row_bytes / kChunkBytes);
   const int F4 = p.F >> 2;
   const int H = p.H;
-  constexpr int kWaves = kDownThreads / kWave;
+  constexpr int kWaves = THREADS / kWave;
   constexpr int NV = UN > 0 ? UN : 1;
 
   const bool windowed = p.j_only >= 0;
@@ -238,7 +240,7 @@ __global__ __launch_bounds__(kDownThreads) void ffn_down_kernel(FfnArgs p) {
   // back microseconds later, and a loop of load, wait, write would cost seven such round trips.
   // The LDS writes come after the first weight loads, and the barrier behind them orders LDS only
   // (a full __syncthreads() would also wait for those weight loads).
-  constexpr int kStageA = 8;
+  constexpr int kStageA = (8192 + THREADS - 1) / THREADS;   // covers both slots of F = 16384 without the loop below
   const int nst = (windowed ? 1 : 2) * F4;
   struct StageA {   // passed by value: an array written through a captured reference ends up in scratch memory
     float4 v[kStageA];
@@ -255,15 +257,15 @@ __global__ __launch_bounds__(kDownThreads) void ffn_down_kernel(FfnArgs p) {
   auto stage_a_issue = [&]() -> StageA {
     StageA st;
 #pragma unroll
-    for (int u = 0; u < kStageA; ++u) st.v[u] = *a_src(min(tid + u * kDownThreads, nst - 1));   // unconditional: a clamped repeat is dropped below
+    for (int u = 0; u < kStageA; ++u) st.v[u] = *a_src(min(tid + u * THREADS, nst - 1));   // unconditional: a clamped repeat is dropped below
     return st;
   };
   auto stage_a_finish = [&](const StageA& st) {
     // unconditional as well (threads beyond the end rewrite the last vector with its own value):
     // under a condition the compiler would move each load down to its write again
 #pragma unroll
-    for (int u = 0; u < kStageA; ++u) *a_dst(min(tid + u * kDownThreads, nst - 1)) = st.v[u];
-    for (int i = tid + kStageA * kDownThreads; i < nst; i += kDownThreads) *a_dst(i) = *a_src(i);   // very long rows only
+    for (int u = 0; u < kStageA; ++u) *a_dst(min(tid + u * THREADS, nst - 1)) = st.v[u];
+    for (int i = tid + kStageA * THREADS; i < nst; i += THREADS) *a_dst(i) = *a_src(i);   // very long rows only
     lds_barrier();
   };
   const StageA sta = stage_a_issue();
@@ -485,13 +487,18 @@ static hipError_t allow_big_lds(K kernel) {
   return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024);
 }
 
+template <bool BF16, int THREADS>
+static hipError_t init_down_t() {
+  hipError_t e;
+  if ((e = allow_big_lds(ffn_down_kernel<BF16, 7, THREADS>)) != hipSuccess) return e;
+  if ((e = allow_big_lds(ffn_down_kernel<BF16, 8, THREADS>)) != hipSuccess) return e;
+  if ((e = allow_big_lds(ffn_down_kernel<BF16, 4, THREADS>)) != hipSuccess) return e;
+  return allow_big_lds(ffn_down_kernel<BF16, 0, THREADS>);
+}
 template <bool BF16>
 static hipError_t init_down() {
-  hipError_t e;
-  if ((e = allow_big_lds(ffn_down_kernel<BF16, 7>)) != hipSuccess) return e;
-  if ((e = allow_big_lds(ffn_down_kernel<BF16, 8>)) != hipSuccess) return e;
-  if ((e = allow_big_lds(ffn_down_kernel<BF16, 4>)) != hipSuccess) return e;
-  return allow_big_lds(ffn_down_kernel<BF16, 0>);
+  const hipError_t e = init_down_t<BF16, kDownThreads>();
+  return e != hipSuccess ? e : init_down_t<BF16, 768>();
 }
 
 hipError_t ffn_kernels_init(int dtype) {
@@ -519,13 +526,23 @@ hipError_t launch_ffn_gateup(const FfnArgs& p, int dtype, const LaunchCfg& lc, h
   return hipGetLastError();
 }
 
-template <bool BF16>
+template <bool BF16, int THREADS>
 static void launch_down_t(const FfnArgs& p, int nch, dim3 grid, size_t lds, hipStream_t s, const KernelTiming& t) {
-  dim3 block(kDownThreads);
-  if (nch % 7 == 0) launch_kernel(ffn_down_kernel<BF16, 7>, grid, block, lds, s, t, p);
-  else if (nch % 8 == 0) launch_kernel(ffn_down_kernel<BF16, 8>, grid, block, lds, s, t, p);
-  else if (nch % 4 == 0) launch_kernel(ffn_down_kernel<BF16, 4>, grid, block, lds, s, t, p);
-  else launch_kernel(ffn_down_kernel<BF16, 0>, grid, block, lds, s, t, p);
+  dim3 block(THREADS);
+  if (nch % 7 == 0) launch_kernel(ffn_down_kernel<BF16, 7, THREADS>, grid, block, lds, s, t, p);
+  else if (nch % 8 == 0) launch_kernel(ffn_down_kernel<BF16, 8, THREADS>, grid, block, lds, s, t, p);
+  else if (nch % 4 == 0) launch_kernel(ffn_down_kernel<BF16, 4, THREADS>, grid, block, lds, s, t, p);
+  else launch_kernel(ffn_down_kernel<BF16, 0, THREADS>, grid, block, lds, s, t, p);
+}
+
+// Wavefronts per workgroup of a down GEMV that walks `rows` rows with `blocks` workgroups, one row per
+// wavefront and pass.  A compute unit streams at the same rate with 12 as with 16 wavefronts, so the
+// launch lasts (passes x wavefronts per workgroup) row times: 16 unless 12 makes that product smaller
+// (H = 6144 over 256 workgroups: 2 x 12 against 2 x 16, the second pass of 16 being half empty).
+int down_waves_per_workgroup(int rows, int blocks) {
+  if (rows < blocks * 16) return 16;
+  auto passes = [&](int w) { return (rows + blocks * w - 1) / (blocks * w); };
+  return passes(12) * 12 < passes(16) * 16 ? 12 : 16;
 }
 
 hipError_t launch_ffn_down(const FfnArgs& p, int dtype, const LaunchCfg& lc, hipStream_t s) {
@@ -534,8 +551,14 @@ hipError_t launch_ffn_down(const FfnArgs& p, int dtype, const LaunchCfg& lc, hip
   dim3 grid(lc.down_blocks, p.B);
   if (p.j_only >= 0) grid.x = std::max(1, std::min(lc.down_blocks, (p.r1 - p.r0 + 15) / (kDownThreads / kWave)));
   const size_t lds = (size_t)2 * p.F * sizeof(float);
-  if (bf16) launch_down_t<true>(p, nch, grid, lds, s, lc.timing);
-  else launch_down_t<false>(p, nch, grid, lds, s, lc.timing);
+  const bool twelve = p.j_only < 0 && down_waves_per_workgroup(p.H, (int)grid.x) == 12;
+  if (bf16) {
+    if (twelve) launch_down_t<true, 768>(p, nch, grid, lds, s, lc.timing);
+    else launch_down_t<true, kDownThreads>(p, nch, grid, lds, s, lc.timing);
+  } else {
+    if (twelve) launch_down_t<false, 768>(p, nch, grid, lds, s, lc.timing);
+    else launch_down_t<false, kDownThreads>(p, nch, grid, lds, s, lc.timing);
+  }
   return hipGetLastError();
 }
 

@@ -387,6 +387,7 @@ struct QRow {
   QGroup<BITS> g[PB];
 };
 
+// (THREADS = 1024 or 768: 12 wavefronts per workgroup when that deals the rows out evenly and 16 do not.)
 // One wavefront per output element y[h]; a wavefront streams its rows through four register
 // buffers (the unit in flight is one block of 64 groups of a row: 36 bytes per lane with 4-bit
 // codes).  The intermediate vectors a_j of the activated experts (halves, written by the
@@ -394,8 +395,8 @@ struct QRow {
 // with the two sums per group that the dequantisation needs, so that the weight stream is the only
 // traffic that grows with the number of rows; a lane reads its group's 64 values back with eight
 // conflict-free 16-byte reads per block.
-template <int BITS, int NBLK>
-__global__ __launch_bounds__(kQDownThreads) void ffn_down_quant_kernel(FfnArgs p) {
+template <int BITS, int NBLK, int THREADS>
+__global__ __launch_bounds__(THREADS) void ffn_down_quant_kernel(FfnArgs p) {
   extern __shared__ uint4 smem[];   // a[jj][NBLK*8*64] vectors of 8 halves, then sums[jj][NBLK*64]
   const int b = blockIdx.y;
   const int tid = threadIdx.x, lane = tid & 63, wave = wave_index();
@@ -403,7 +404,7 @@ __global__ __launch_bounds__(kQDownThreads) void ffn_down_quant_kernel(FfnArgs p
   const size_t rb = q_row_bytes<BITS>(F);
   const int G = F >> 6;
   const QConsts<BITS> kc = q_consts<BITS>();
-  constexpr int kWaves = kQDownThreads / kWave;
+  constexpr int kWaves = THREADS / kWave;
   constexpr int kAVecs = NBLK * 8 * 64;          // 16-byte vectors of one expert's a_j
   constexpr int PB = 1;                          // blocks per piece
   constexpr int NP = NBLK / PB;                  // pieces per row
@@ -419,7 +420,7 @@ __global__ __launch_bounds__(kQDownThreads) void ffn_down_quant_kernel(FfnArgs p
   // arrives within 2 us.  The LDS writes come after the first weight requests.
   const uint4* ag = reinterpret_cast<const uint4*>(p.a + (size_t)b * 2 * p.a_stride);
   const int S4 = (int)(p.a_stride >> 2);      // 16-byte vectors per (token, expert) of the scratch
-  constexpr int kStage = (2 * kAVecs + kQDownThreads - 1) / kQDownThreads;
+  constexpr int kStage = (2 * kAVecs + THREADS - 1) / THREADS;
   struct StageA {
     uint4 v[kStage];
   };
@@ -427,7 +428,7 @@ __global__ __launch_bounds__(kQDownThreads) void ffn_down_quant_kernel(FfnArgs p
     StageA st;
 #pragma unroll
     for (int u = 0; u < kStage; ++u) {
-      const int i = min(tid + u * kQDownThreads, 2 * kAVecs - 1);
+      const int i = min(tid + u * THREADS, 2 * kAVecs - 1);
       const int jj = i >= kAVecs ? 1 : 0;
       st.v[u] = ag[(size_t)jj * S4 + (i - jj * kAVecs)];
     }
@@ -465,7 +466,7 @@ __global__ __launch_bounds__(kQDownThreads) void ffn_down_quant_kernel(FfnArgs p
     for (int u = 0; u < kStage; ++u) {
       // vector i of a slot belongs to group (i / 512) * 64 + i % 64; groups beyond the row's G do not
       // exist (the scratch vector holds old values there) and are staged as zeros
-      const int i = min(tid + u * kQDownThreads, 2 * kAVecs - 1);
+      const int i = min(tid + u * THREADS, 2 * kAVecs - 1);
       const int iv = i >= kAVecs ? i - kAVecs : i;
       const bool real = ((iv >> 9) << 6) + (iv & 63) < G;
       as[i] = real ? st.v[u] : make_uint4(0, 0, 0, 0);
@@ -553,13 +554,18 @@ static hipError_t allow_lds(K kernel, size_t bytes) {
   return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes);
 }
 
+template <int BITS, int THREADS>
+static hipError_t quant_init_bits_t() {
+  hipError_t e;
+  if ((e = allow_lds(ffn_down_quant_kernel<BITS, 1, THREADS>, q_down_lds<BITS, 1>())) != hipSuccess) return e;
+  if ((e = allow_lds(ffn_down_quant_kernel<BITS, 2, THREADS>, q_down_lds<BITS, 2>())) != hipSuccess) return e;
+  if ((e = allow_lds(ffn_down_quant_kernel<BITS, 3, THREADS>, q_down_lds<BITS, 3>())) != hipSuccess) return e;
+  return allow_lds(ffn_down_quant_kernel<BITS, 4, THREADS>, q_down_lds<BITS, 4>());
+}
 template <int BITS>
 static hipError_t quant_init_bits() {
-  hipError_t e;
-  if ((e = allow_lds(ffn_down_quant_kernel<BITS, 1>, q_down_lds<BITS, 1>())) != hipSuccess) return e;
-  if ((e = allow_lds(ffn_down_quant_kernel<BITS, 2>, q_down_lds<BITS, 2>())) != hipSuccess) return e;
-  if ((e = allow_lds(ffn_down_quant_kernel<BITS, 3>, q_down_lds<BITS, 3>())) != hipSuccess) return e;
-  return allow_lds(ffn_down_quant_kernel<BITS, 4>, q_down_lds<BITS, 4>());
+  const hipError_t e = quant_init_bits_t<BITS, kQDownThreads>();
+  return e != hipSuccess ? e : quant_init_bits_t<BITS, 768>();
 }
 
 hipError_t quant_kernels_init(int bits) { return bits == 4 ? quant_init_bits<4>() : quant_init_bits<2>(); }
@@ -582,22 +588,30 @@ hipError_t launch_ffn_gateup_quant(const FfnArgs& p, int bits, const LaunchCfg& 
   return hipGetLastError();
 }
 
-template <int BITS>
+template <int BITS, int THREADS>
 static void launch_down_quant_t(const FfnArgs& p, int nblk, dim3 grid, hipStream_t s, const KernelTiming& t) {
-  dim3 block(kQDownThreads);
-  if (nblk == 1) launch_kernel(ffn_down_quant_kernel<BITS, 1>, grid, block, q_down_lds<BITS, 1>(), s, t, p);
-  else if (nblk == 2) launch_kernel(ffn_down_quant_kernel<BITS, 2>, grid, block, q_down_lds<BITS, 2>(), s, t, p);
-  else if (nblk == 3) launch_kernel(ffn_down_quant_kernel<BITS, 3>, grid, block, q_down_lds<BITS, 3>(), s, t, p);
-  else launch_kernel(ffn_down_quant_kernel<BITS, 4>, grid, block, q_down_lds<BITS, 4>(), s, t, p);
+  dim3 block(THREADS);
+  if (nblk == 1) launch_kernel(ffn_down_quant_kernel<BITS, 1, THREADS>, grid, block, q_down_lds<BITS, 1>(), s, t, p);
+  else if (nblk == 2) launch_kernel(ffn_down_quant_kernel<BITS, 2, THREADS>, grid, block, q_down_lds<BITS, 2>(), s, t, p);
+  else if (nblk == 3) launch_kernel(ffn_down_quant_kernel<BITS, 3, THREADS>, grid, block, q_down_lds<BITS, 3>(), s, t, p);
+  else launch_kernel(ffn_down_quant_kernel<BITS, 4, THREADS>, grid, block, q_down_lds<BITS, 4>(), s, t, p);
 }
 
 hipError_t launch_ffn_down_quant(const FfnArgs& p, int bits, const LaunchCfg& lc, hipStream_t s) {
   const int rows = p.j_only >= 0 ? p.r1 - p.r0 : p.H;
-  const int waves = kQDownThreads / kWave;
-  dim3 grid(std::max(1, std::min(lc.down_blocks, (rows + waves - 1) / waves)), p.B);
+  // 16 wavefronts per workgroup, or 12 if that wastes less of the last pass over the rows
+  auto blocks_for = [&](int waves) { return std::max(1, std::min(lc.down_blocks, (rows + waves - 1) / waves)); };
+  const bool twelve = p.j_only < 0 && blocks_for(12) == blocks_for(16) && down_waves_per_workgroup(rows, blocks_for(16)) == 12;
+  const int waves = twelve ? 12 : kQDownThreads / kWave;
+  dim3 grid(blocks_for(waves), p.B);
   const int nblk = ((p.F >> 6) + 63) >> 6;     // F <= 16384: at most 4 blocks of 64 groups
-  if (bits == 4) launch_down_quant_t<4>(p, nblk, grid, s, lc.timing);
-  else launch_down_quant_t<2>(p, nblk, grid, s, lc.timing);
+  if (bits == 4) {
+    if (twelve) launch_down_quant_t<4, 768>(p, nblk, grid, s, lc.timing);
+    else launch_down_quant_t<4, kQDownThreads>(p, nblk, grid, s, lc.timing);
+  } else {
+    if (twelve) launch_down_quant_t<2, 768>(p, nblk, grid, s, lc.timing);
+    else launch_down_quant_t<2, kQDownThreads>(p, nblk, grid, s, lc.timing);
+  }
   return hipGetLastError();
 }
 

@@ -136,6 +136,7 @@ hipError_t launch_gate(const GateArgs& a, bool bf16, int routers, hipStream_t s,
 hipError_t launch_norm_gate(const GateArgs& a, const NormArgs& n, bool bf16, hipStream_t s, const KernelTiming& t = KernelTiming{});
 hipError_t launch_ffn_gateup(const FfnArgs& p, int dtype, const LaunchCfg& lc, hipStream_t s);
 hipError_t launch_ffn_down(const FfnArgs& p, int dtype, const LaunchCfg& lc, hipStream_t s);
+int down_waves_per_workgroup(int rows, int blocks);   // 16, or 12 if that deals the rows out more evenly
 hipError_t ffn_kernels_init(int dtype);
 hipError_t ffn_fused_init(int dtype);
 int ffn_fused_capacity(int dtype, int H, int F, int device);

@@ -215,10 +215,12 @@ __device__ __forceinline__ void grouped_gemm_tile_loop(const char* wbase, size_t
       // other half was last read two slabs ago and every wavefront has passed a barrier since
       uint4* bslab = lds + (DB == 2 ? (sc & 1) * kSlabVecs : 0);
       if constexpr (!DIRECT) {
-        if (DB == 1) __syncthreads();
+        // both barriers order LDS only: a full __syncthreads() would also wait for the weight loads of the
+        // next slab, which are already in flight, and with that undo the double buffering
+        if (DB == 1) lds_barrier();
 #pragma unroll
         for (int v = 0; v < kVecsPerThread; ++v) bslab[v * kThreads + tid] = stage.v[v];
-        __syncthreads();
+        lds_barrier();
         if (sc + 1 < nslabs) stage = fetch_operand(sc + 1);
       }
 #pragma unroll
